@@ -1,0 +1,178 @@
+/*
+ * moqe.h - C ABI of the MI355X (gfx950) MoQE hot path.
+ *
+ * MoQE (Mixture of Quantized Experts) keeps the expert weights of a top-1
+ * routed MoE FFN as weight-only, per-output-channel, linearly quantized
+ * int4 / int3 / int2 codes with fp16 scales and runs them against fp16
+ * activations (paper: abstract; Sec. 3 "Experiments"; App. A "Quantization
+ * algorithms"; App. B "MoE architecture"; App. C on fp16 channel scales).
+ *
+ * Conventions shared by every call
+ *   - Every pointer is a DEVICE pointer unless its comment says "host".
+ *   - The caller owns every buffer.  The library allocates nothing, keeps no
+ *     state between calls, never synchronises and never frees: each call
+ *     validates its arguments on the host, enqueues kernels on `stream`
+ *     (a hipStream_t passed as void*, NULL = the null stream) and returns.
+ *   - Device buffers must be 16-byte aligned (MOQE_ERR_ALIGN otherwise).
+ *   - Argument errors are reported before anything is launched, so a failed
+ *     call leaves all outputs untouched.  A failed launch returns
+ *     MOQE_ERR_HIP; moqe_last_hip_error() gives the runtime's message.
+ *   - T = 0 (no tokens) is valid and a no-op apart from seg_offsets = 0.
+ *   - moqe_f16 is the IEEE binary16 bit pattern.
+ *
+ * Supported shapes: bits in {2,3,4}; N a multiple of 16; K a multiple of
+ * 32 (int4), 64 (int2), 128 (int3) and, when K/32 exceeds the chunk length
+ * SC (4 steps for int4, 8 for int2/int3), K/32 a multiple of SC.  The FFN
+ * additionally needs K = 32 * KS * R with KS in {2,4,8,16,24,32} and
+ * R in {1,2,4} for both of its contractions (K = d and K = f).
+ *
+ * Packed layout of one [K,N] code matrix (K*N*bits/8 bytes, no padding; the
+ * paper's Table 2 size column fixes the density, the arrangement is ours):
+ *   column tile c = n / 16, j = n % 16; step s = k / 32, row group
+ *   g = (k % 32) / 8, i = k % 8; slot l = 16 g + j; SC = min(SCmax, K/32);
+ *   chunk p = s / SC, s' = s % SC, m = 8 s' + i.  Chunks are stored column
+ *   tile major: chunk (c, p) starts at byte (c * K/(32 SC) + p) * 64 SC bits.
+ *   Stored field value u = q + 2^(bits-1) (offset binary).
+ *   bits 2,4: the chunk is 64 slots of SC*bits bytes; inside a slot, 32/bits
+ *     codes fill a little-endian 32-bit word: word = m / (32/bits),
+ *     t = m % (32/bits), bit position = 16 (t & 1) + bits (t >> 1).
+ *   bits 3: the chunk is a 2-bit plane (u & 3, arranged as for bits = 2)
+ *     followed by a 1-bit plane (u >> 2): 64 slots of SC bytes, word = m / 32,
+ *     t = m % 32, bit position = 16 (t & 1) + (t >> 1).
+ *   A slot is what one lane of a 64-wide wavefront loads (16 bytes at full SC)
+ *   and is already in the operand order of the 16x16x32 fp16 MFMA.
+ *   A stack of E matrices is E such strings back to back.
+ */
+#ifndef MOQE_H
+#define MOQE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef uint16_t moqe_f16;
+
+typedef enum {
+  MOQE_OK = 0,
+  MOQE_ERR_NULL = 1,      /* a required pointer is NULL */
+  MOQE_ERR_BITS = 2,      /* bits not in {2,3,4} */
+  MOQE_ERR_SHAPE = 3,     /* a dimension is negative, zero where it may not be, or unsupported */
+  MOQE_ERR_ALIGN = 4,     /* a device pointer is not 16-byte aligned */
+  MOQE_ERR_WORKSPACE = 5, /* workspace_bytes is smaller than the matching *_workspace_bytes() */
+  MOQE_ERR_HIP = 6        /* the HIP runtime refused a launch */
+} moqe_status;
+
+/* Human-readable name of a status; static storage, never NULL. */
+const char* moqe_status_string(int status);
+/* Message of the last HIP error seen by this thread's calls; static storage. */
+const char* moqe_last_hip_error(void);
+/* ABI version, currently 1. */
+int moqe_version(void);
+
+/* Bytes of one packed [K,N] matrix = K*N*bits/8 (Table 2: exactly `bits` bits
+ * per expert weight).  Returns 0 for an unsupported (bits, K, N). Host only. */
+size_t moqe_packed_bytes(int bits, int64_t K, int64_t N);
+/* MOQE_OK if (bits, K, N) can be packed, else the status a call would return. */
+int moqe_check_matrix(int bits, int64_t K, int64_t N);
+/* MOQE_OK if a layer with these dimensions can be run by moqe_expert_ffn. */
+int moqe_check_layer(int bits, int64_t E, int64_t d, int64_t f);
+
+/* Scratch sizes (host, pure).  Always > 0 so a caller may allocate blindly.
+ * The scratch needs no initialisation. */
+size_t moqe_route_workspace_bytes(int64_t T, int64_t E);
+size_t moqe_ffn_workspace_bytes(int64_t T, int64_t E, int64_t d, int64_t f);
+
+/*
+ * Offline round-to-nearest quantization and bit packing of a stack of E
+ * matrices (App. A "Linear quantization with absolute maximum"; scales in
+ * half precision per App. C).
+ *   w          [E,K,N] fp32, N contiguous.  A channel is a column (one of the
+ *              N outputs of y = x A); the maximum runs over the K rows.
+ *   scales_out [E,N]: s = 2 max|A_:,n| / (2^bits - 1) computed in fp64 and
+ *              rounded UP to fp16 (so that |a - q s| <= s/2 for every entry);
+ *              an all-zero channel gets s = 0 and codes 0.
+ *   codes_out  E * moqe_packed_bytes(bits,K,N) bytes, layout above, with
+ *              q = clamp(rint(a / s), -2^(bits-1), 2^(bits-1)-1), the division
+ *              and the ties-to-even rounding done in fp64 on the stored scale.
+ * Non-finite weights or a scale beyond fp16's range are undefined input.
+ */
+moqe_status moqe_quantize(const float* w, int64_t E, int64_t K, int64_t N, int bits,
+                          void* codes_out, moqe_f16* scales_out, void* stream);
+
+/* Inverse of the packing, for tests and tools: q_out [E,K,N] int8 codes. */
+moqe_status moqe_unpack(const void* codes, int64_t E, int64_t K, int64_t N, int bits,
+                        int8_t* q_out, void* stream);
+
+/*
+ * Top-1 learned gating and dispatch bookkeeping (App. B "MoE architecture":
+ * top-1 gating as in Switch; no capacity limit, jitter or dropout at inference).
+ *   x [T,d] fp16, w_gate [d,E] fp16 (E contiguous); logits = x w_gate in fp32.
+ *   expert_idx [T]  lowest index attaining the row maximum
+ *   gate       [T]  fp32 softmax probability of that expert
+ *   seg_offsets[E+1] exclusive prefix sum of the per-expert token counts,
+ *                   seg_offsets[E] = T
+ *   perm       [T]  sorted position -> token id; tokens of one expert keep
+ *                   ascending order (stable), so the result is unique
+ * 1 <= E <= 1024, d >= 1 and a multiple of 8, T >= 0.
+ */
+moqe_status moqe_route(const moqe_f16* x, const moqe_f16* w_gate, int64_t T, int64_t d, int64_t E,
+                       int32_t* expert_idx, float* gate, int32_t* seg_offsets, int32_t* perm,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* Same, starting from given fp32 logits [T,E] (E contiguous). */
+moqe_status moqe_route_logits(const float* logits, int64_t T, int64_t E,
+                              int32_t* expert_idx, float* gate, int32_t* seg_offsets, int32_t* perm,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+/* One MoE layer's quantized experts.  The struct itself lives in HOST memory;
+ * its pointers are device pointers. codesX: E packed matrices, scalesX and
+ * biasX: [E, out] fp16.  Matrix 1 is [d,f] (K = d), matrix 2 is [f,d] (K = f). */
+typedef struct {
+  int bits;
+  int64_t E, d, f;
+  const void* codes1;
+  const moqe_f16* scales1;
+  const moqe_f16* bias1;
+  const void* codes2;
+  const moqe_f16* scales2;
+  const moqe_f16* bias2;
+} moqe_layer;
+
+/*
+ * Expert FFN with dequantization on the fly (Sec. 2.1: the two-layer
+ * Transformer FFN; App. A: A' = Q s) and the gate-weighted combine:
+ *   for token t with e = expert_idx[t]:
+ *     h = max(0, x_t (Q1_e s1_e) + b1_e)        (fp32 accumulate, h kept in fp16)
+ *     y_t = gate[t] * (h (Q2_e s2_e) + b2_e)    (+ residual_t if given), stored fp16
+ * expert_idx, gate, seg_offsets, perm are as moqe_route produces them (any
+ * consistent routing is accepted; seg_offsets and perm alone drive the
+ * dispatch).  residual may be NULL; y may alias residual; y must not alias x
+ * unless x == residual.
+ */
+moqe_status moqe_expert_ffn(const moqe_layer* layer /* host */, const moqe_f16* x, int64_t T,
+                            const int32_t* expert_idx, const float* gate,
+                            const int32_t* seg_offsets, const int32_t* perm,
+                            const moqe_f16* residual, moqe_f16* y,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The two contractions of moqe_expert_ffn as separate calls, for callers that
+ * time them or put other work between them.  h is fp16 [T,f] with rows in
+ * sorted-token order (row i belongs to token perm[i]); moqe_expert_ffn keeps it
+ * in its workspace.
+ *   ffn1: h = max(0, x (Q1 s1) + b1)
+ *   ffn2: y_t = gate[t] * (h (Q2 s2) + b2) (+ residual_t)
+ */
+moqe_status moqe_expert_ffn1(const moqe_layer* layer /* host */, const moqe_f16* x, int64_t T,
+                             const int32_t* seg_offsets, const int32_t* perm, moqe_f16* h, void* stream);
+moqe_status moqe_expert_ffn2(const moqe_layer* layer /* host */, const moqe_f16* h, int64_t T, const float* gate,
+                             const int32_t* seg_offsets, const int32_t* perm, const moqe_f16* residual,
+                             moqe_f16* y, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOQE_H */

@@ -1,0 +1,78 @@
+// Device-side helpers shared by the MoQE kernels (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef _Float16 half_t;
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t uint2_t __attribute__((ext_vector_type(2)));
+
+#define MOQE_WAVE 64
+
+// ---------------------------------------------------------------------------
+// Geometry of the packed code layout (one [K,N] matrix).  See include/moqe.h.
+// ---------------------------------------------------------------------------
+struct PackGeom {
+  int bits;
+  int K, N;
+  int S;            // 32-row steps = K / 32
+  int SC;           // steps per chunk
+  int Q;            // chunks per column tile = S / SC
+  int chunk_bytes;  // 64 * SC * bits
+  int lo_lane_bytes;  // bytes one slot owns in the main (2- or 4-bit) plane of a chunk
+  int hi_lane_bytes;  // bytes one slot owns in the 1-bit plane (int3 only, else 0)
+  int64_t matrix_bytes;
+};
+
+__host__ __device__ inline int moqe_sc_max(int bits) { return bits == 4 ? 4 : 8; }
+
+// Returns false when (bits, K, N) cannot be packed.
+__host__ __device__ inline bool moqe_make_geom(int bits, int64_t K, int64_t N, PackGeom* g) {
+  if (bits != 2 && bits != 3 && bits != 4) return false;
+  if (K <= 0 || N <= 0 || (K % 32) || (N % 16)) return false;
+  if (K > (1 << 20) || N > (1 << 20)) return false;
+  int S = (int)(K / 32);
+  int sc = moqe_sc_max(bits) < S ? moqe_sc_max(bits) : S;
+  if (S % sc) return false;
+  if (bits == 2 && (sc % 2)) return false;
+  if (bits == 3 && (sc % 4)) return false;
+  g->bits = bits;
+  g->K = (int)K;
+  g->N = (int)N;
+  g->S = S;
+  g->SC = sc;
+  g->Q = S / sc;
+  g->chunk_bytes = 64 * sc * bits;
+  g->lo_lane_bytes = (bits == 3) ? sc * 2 : sc * bits;
+  g->hi_lane_bytes = (bits == 3) ? sc : 0;
+  g->matrix_bytes = (int64_t)K * N * bits / 8;
+  return true;
+}
+
+// fp16 <-> bits
+__device__ inline half_t half_from_bits(uint16_t u) {
+  union { uint16_t u; half_t h; } c;
+  c.u = u;
+  return c.h;
+}
+__device__ inline uint16_t half_to_bits(half_t h) {
+  union { uint16_t u; half_t h; } c;
+  c.h = h;
+  return c.u;
+}
+
+// wave-level helpers (64 lanes)
+__device__ inline int lane_id() { return (int)(threadIdx.x & 63); }
+__device__ inline uint32_t uniform_u32(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ inline int uniform_i32(int v) { return (int)__builtin_amdgcn_readfirstlane((uint32_t)v); }
+
+// D = (a & mask) | orv in one VALU op.  mask is wave-uniform (SGPR).
+__device__ inline uint32_t and_or(uint32_t a, uint32_t mask_s, uint32_t orv) {
+  uint32_t r;
+  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask_s), "v"(orv));
+  return r;
+}

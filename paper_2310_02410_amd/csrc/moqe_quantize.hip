@@ -1,0 +1,148 @@
+// Offline channel-wise absmax quantization and dense bit packing
+// (paper App. A "Linear quantization with absolute maximum", App. C fp16 scales),
+// plus the inverse of the packing for tests.
+#include "moqe_dev.h"
+#include "moqe_kernels.h"
+
+namespace {
+
+// Smallest fp16 bit pattern whose value is >= v (v finite, >= 0).  One rounding,
+// toward +inf, done in exact fp64 steps (scaling by powers of two, ceil).
+__device__ inline uint16_t half_bits_round_up(double v) {
+  if (!(v > 0.0)) return 0;
+  if (v > 65504.0) return 0x7BFF;  // beyond fp16: undefined input, saturate
+  const double two24 = 16777216.0;
+  if (v < 6.103515625e-05) {  // below 2^-14: subnormal grid of 2^-24
+    double n = ceil(v * two24);
+    return (uint16_t)n;  // n == 1024 is exactly the smallest normal's pattern
+  }
+  int e = ilogb(v);  // v = f * 2^e, f in [1,2)
+  double f = scalbn(v, -e);
+  int mant = (int)ceil((f - 1.0) * 1024.0);
+  if (mant == 1024) {
+    mant = 0;
+    e += 1;
+  }
+  int be = e + 15;
+  if (be >= 31) return 0x7BFF;
+  return (uint16_t)((be << 10) | mant);
+}
+
+__device__ inline int quantize_one(float w, double s, int lo, int hi) {
+  if (!(s > 0.0)) return 0;
+  double r = rint((double)w / s);  // IEEE fp64 divide, ties to even
+  r = r < (double)lo ? (double)lo : r;
+  r = r > (double)hi ? (double)hi : r;
+  return (int)r;
+}
+
+// One thread per (expert, channel): s = 2 max|A_:,n| / (2^b - 1), stored fp16 rounded up.
+__global__ __launch_bounds__(256) void scale_kernel(const float* __restrict__ w, int64_t E, int K, int N, int bits,
+                                                     uint16_t* __restrict__ scales) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= E * N) return;
+  int64_t e = idx / N;
+  int n = (int)(idx % N);
+  const float* col = w + e * (int64_t)K * N + n;
+  float m = 0.0f;
+  for (int k = 0; k < K; ++k) m = fmaxf(m, fabsf(col[(int64_t)k * N]));
+  double s64 = (2.0 * (double)m) / (double)((1 << bits) - 1);
+  scales[idx] = half_bits_round_up(s64);
+}
+
+// One thread per packed 32-bit word.
+__global__ __launch_bounds__(256) void pack_kernel(const float* __restrict__ w, const uint16_t* __restrict__ scales,
+                                                    PackGeom g, int64_t E, uint32_t* __restrict__ codes) {
+  const int64_t words_per_matrix = g.matrix_bytes / 4;
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= E * words_per_matrix) return;
+  int64_t e = idx / words_per_matrix;
+  int64_t D = idx % words_per_matrix;
+  const int chunk_words = g.chunk_bytes / 4;
+  int ci = (int)(D / chunk_words);
+  int r = (int)(D % chunk_words);
+  int c = ci / g.Q, p = ci % g.Q;
+  int fbits = g.bits, vshift = 0, lane_words = g.lo_lane_bytes / 4;
+  if (g.bits == 3) {
+    fbits = 2;
+    int lo_words = 64 * lane_words;
+    if (r >= lo_words) {
+      r -= lo_words;
+      fbits = 1;
+      vshift = 2;
+      lane_words = g.hi_lane_bytes / 4;
+    }
+  }
+  const int vmask = (1 << fbits) - 1;
+  int slot = r / lane_words, word = r % lane_words;
+  int grp = slot / 16, j = slot % 16;
+  int n = 16 * c + j;
+  const int per = 32 / fbits;
+  const int z = 1 << (g.bits - 1);
+  const int lo = -z, hi = z - 1;
+  double s = (double)(float)half_from_bits(scales[e * g.N + n]);
+  const float* wm = w + e * (int64_t)g.K * g.N;
+  uint32_t val = 0;
+  for (int t = 0; t < per; ++t) {
+    int m = word * per + t;
+    int s1 = m >> 3, i = m & 7;
+    int k = 32 * (p * g.SC + s1) + 8 * grp + i;
+    int q = quantize_one(wm[(int64_t)k * g.N + n], s, lo, hi);
+    uint32_t u = (uint32_t)(q + z);
+    val |= ((u >> vshift) & vmask) << (16 * (t & 1) + fbits * (t >> 1));
+  }
+  codes[idx] = val;
+}
+
+// One thread per code: packed layout -> int8 [E,K,N].
+__global__ __launch_bounds__(256) void unpack_kernel(const uint32_t* __restrict__ codes, PackGeom g, int64_t E,
+                                                      int8_t* __restrict__ q_out) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t per_matrix = (int64_t)g.K * g.N;
+  if (idx >= E * per_matrix) return;
+  int64_t e = idx / per_matrix;
+  int64_t rem = idx % per_matrix;
+  int k = (int)(rem / g.N), n = (int)(rem % g.N);
+  int c = n / 16, j = n % 16;
+  int s = k / 32, grp = (k % 32) / 8, i = k % 8;
+  int slot = 16 * grp + j;
+  int p = s / g.SC, s1 = s % g.SC;
+  int m = 8 * s1 + i;
+  const uint32_t* base = codes + e * (g.matrix_bytes / 4) + (int64_t)(c * g.Q + p) * (g.chunk_bytes / 4);
+  const int z = 1 << (g.bits - 1);
+  uint32_t u;
+  if (g.bits != 3) {
+    int per = 32 / g.bits;
+    int word = m / per, t = m % per;
+    uint32_t d = base[slot * (g.lo_lane_bytes / 4) + word];
+    u = (d >> (16 * (t & 1) + g.bits * (t >> 1))) & ((1u << g.bits) - 1);
+  } else {
+    int word = m / 16, t = m % 16;
+    uint32_t d = base[slot * (g.lo_lane_bytes / 4) + word];
+    u = (d >> (16 * (t & 1) + 2 * (t >> 1))) & 3u;
+    int hword = m / 32, ht = m % 32;
+    uint32_t hd = base[64 * (g.lo_lane_bytes / 4) + slot * (g.hi_lane_bytes / 4) + hword];
+    u |= ((hd >> (16 * (ht & 1) + (ht >> 1))) & 1u) << 2;
+  }
+  q_out[idx] = (int8_t)((int)u - z);
+}
+
+}  // namespace
+
+hipError_t moqe_launch_quantize(const float* w, int64_t E, const PackGeom& g, void* codes, uint16_t* scales,
+                                hipStream_t stream) {
+  int64_t nch = E * g.N;
+  hipLaunchKernelGGL(scale_kernel, dim3((unsigned)((nch + 255) / 256)), dim3(256), 0, stream, w, E, g.K, g.N, g.bits,
+                     scales);
+  int64_t words = E * (g.matrix_bytes / 4);
+  hipLaunchKernelGGL(pack_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, stream, w, scales, g, E,
+                     (uint32_t*)codes);
+  return hipGetLastError();
+}
+
+hipError_t moqe_launch_unpack(const void* codes, int64_t E, const PackGeom& g, int8_t* q_out, hipStream_t stream) {
+  int64_t n = E * (int64_t)g.K * g.N;
+  hipLaunchKernelGGL(unpack_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, (const uint32_t*)codes, g,
+                     E, q_out);
+  return hipGetLastError();
+}

@@ -1,0 +1,260 @@
+// Top-1 gating and dispatch bookkeeping (paper App. B "MoE architecture": top-1
+// learned gating as in Switch).  Two kernels:
+//   route_score_kernel    logits = x W_g (fp32), wavefront-level argmax with
+//                         lowest-index tie break, gate = softmax probability
+//   route_segments_kernel per-expert histogram, exclusive scan into contiguous
+//                         expert segments, stable token permutation
+// Everything is deterministic: no atomics decide an order anywhere.
+#include "moqe_dev.h"
+#include "moqe_kernels.h"
+
+namespace {
+
+constexpr int SCORE_THREADS = 256;
+constexpr int SEG_THREADS = 1024;
+constexpr int SEG_LDS_INTS = 8192;
+
+// Wave-level top-1 over one row of logits held in LDS or global memory.
+// Returns through lane 0 semantics: every lane gets the same (idx, gate).
+__device__ inline void wave_pick(const float* row, int E, int* idx_out, float* gate_out) {
+  const int lane = lane_id();
+  float best = -INFINITY;
+  int bidx = 0x7fffffff;
+  for (int e = lane; e < E; e += 64) {
+    float v = row[e];
+    if (v > best) {  // ascending e: strict > keeps the lowest index
+      best = v;
+      bidx = e;
+    }
+  }
+  for (int off = 32; off >= 1; off >>= 1) {
+    float ov = __shfl_xor(best, off, 64);
+    int oi = __shfl_xor(bidx, off, 64);
+    bool take = (ov > best) || (ov == best && oi < bidx);
+    best = take ? ov : best;
+    bidx = take ? oi : bidx;
+  }
+  float sum = 0.0f;
+  for (int e = lane; e < E; e += 64) sum += expf(row[e] - best);
+  for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, 64);
+  *idx_out = bidx;
+  *gate_out = 1.0f / sum;
+}
+
+// Block = 256 threads, TB tokens.  Thread (e_l, kp): partial logit of expert
+// e_l over the kp-th slice of d for each of the TB tokens.
+template <int TB>
+__global__ __launch_bounds__(SCORE_THREADS) void route_score_kernel(const half_t* __restrict__ x,
+                                                                     const half_t* __restrict__ wg, int T, int d,
+                                                                     int E, int EP, int* __restrict__ expert_idx,
+                                                                     float* __restrict__ gate) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  // layout: xs [TB][d] half | red [256][TB] float | logit [TB][E] float
+  half_t* xs = (half_t*)smem;
+  float* red = (float*)(smem + (((size_t)TB * d * 2 + 15) & ~(size_t)15));
+  float* logit = red + SCORE_THREADS * TB;
+
+  const int tid = threadIdx.x;
+  const int t0 = blockIdx.x * TB;
+  const int nt = min(TB, T - t0);
+
+  // stage the token rows (16 B per thread step; d is a multiple of 8)
+  const int vec_per_row = d / 8;
+  for (int v = tid; v < TB * vec_per_row; v += SCORE_THREADS) {
+    int tb = v / vec_per_row, c = v % vec_per_row;
+    uint4_t val = {0, 0, 0, 0};
+    if (tb < nt) val = *(const uint4_t*)(x + (int64_t)(t0 + tb) * d + c * 8);
+    *(uint4_t*)(xs + tb * d + c * 8) = val;
+  }
+  __syncthreads();
+
+  const int KP = SCORE_THREADS / EP;  // k slices
+  const int e_l = tid % EP;
+  const int kp = tid / EP;
+  const int kchunk = (d + KP - 1) / KP;
+  const int k_begin = min(d, kp * kchunk);
+  const int k_end = min(d, k_begin + kchunk);
+
+  for (int eg = 0; eg < E; eg += EP) {
+    const int e = eg + e_l;
+    float acc[TB];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) acc[tb] = 0.0f;
+    if (e < E) {
+#pragma unroll 4
+      for (int k = k_begin; k < k_end; ++k) {
+        float wv = (float)wg[(int64_t)k * E + e];
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) acc[tb] = fmaf((float)xs[tb * d + k], wv, acc[tb]);
+      }
+    }
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) red[tid * TB + tb] = acc[tb];
+    __syncthreads();
+    // thread (e_l, tb') sums the KP slices in a fixed order
+    for (int o = tid; o < EP * TB; o += SCORE_THREADS) {
+      int el = o % EP, tb = o / EP;
+      if (eg + el < E) {
+        float s = 0.0f;
+        for (int p = 0; p < KP; ++p) s += red[(p * EP + el) * TB + tb];
+        logit[tb * E + eg + el] = s;
+      }
+    }
+    __syncthreads();
+  }
+
+  const int wave = tid / 64;
+  for (int tb = wave; tb < nt; tb += SCORE_THREADS / 64) {
+    int idx;
+    float g;
+    wave_pick(logit + tb * E, E, &idx, &g);
+    if (lane_id() == 0) {
+      expert_idx[t0 + tb] = idx;
+      gate[t0 + tb] = g;
+    }
+  }
+}
+
+// One wave per token, logits given.
+__global__ __launch_bounds__(256) void route_pick_kernel(const float* __restrict__ logits, int T, int E,
+                                                          int* __restrict__ expert_idx, float* __restrict__ gate) {
+  int t = blockIdx.x * 4 + threadIdx.x / 64;
+  if (t >= T) return;
+  int idx;
+  float g;
+  wave_pick(logits + (int64_t)t * E, E, &idx, &g);
+  if (lane_id() == 0) {
+    expert_idx[t] = idx;
+    gate[t] = g;
+  }
+}
+
+// Lanes holding the same key, as a 64-bit mask (nb = number of key bits).
+__device__ inline uint64_t match_any(int key, int nb) {
+  uint64_t m = ~0ull;
+  for (int b = 0; b < nb; ++b) {
+    bool bit = (key >> b) & 1;
+    uint64_t bb = __ballot(bit);
+    m &= bit ? bb : ~bb;
+  }
+  return m;
+}
+
+// Single block.  cnt[chunk][E] (chunks of 64 consecutive tokens) lives in LDS
+// when it fits, else in the caller's workspace.
+__global__ __launch_bounds__(SEG_THREADS) void route_segments_kernel(const int* __restrict__ expert_idx, int T, int E,
+                                                                      int* __restrict__ seg_offsets,
+                                                                      int* __restrict__ perm, int* ws_cnt) {
+  __shared__ int s_cnt[SEG_LDS_INTS];
+  __shared__ int s_off[1024 + 1];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int nwaves = SEG_THREADS / 64;
+  const int nchunks = (T + 63) / 64;
+  int* cnt = ((int64_t)nchunks * E <= SEG_LDS_INTS) ? s_cnt : ws_cnt;
+  int nb = 0;
+  while ((1 << nb) <= E) ++nb;  // keys 0..E (E = "no token")
+
+  for (int i = tid; i < nchunks * E; i += SEG_THREADS) cnt[i] = 0;
+  __syncthreads();
+
+  for (int c = wave; c < nchunks; c += nwaves) {
+    int t = c * 64 + lane;
+    bool valid = t < T;
+    int key = valid ? expert_idx[t] : E;
+    uint64_t m = match_any(key, nb);
+    bool leader = (__ffsll((long long)m) - 1) == lane;
+    if (valid && leader) cnt[c * E + key] = __popcll(m);
+  }
+  __syncthreads();
+
+  // per expert: exclusive running sum over chunks
+  for (int e = tid; e < E; e += SEG_THREADS) {
+    int run = 0;
+    for (int c = 0; c < nchunks; ++c) {
+      int v = cnt[c * E + e];
+      cnt[c * E + e] = run;
+      run += v;
+    }
+    s_off[e] = run;
+  }
+  __syncthreads();
+
+  // exclusive scan over experts (wave 0, groups of 64 with a carry)
+  if (wave == 0) {
+    int carry = 0;
+    for (int eg = 0; eg < E; eg += 64) {
+      int e = eg + lane;
+      int v = (e < E) ? s_off[e] : 0;
+      int inc = v;
+      for (int off = 1; off < 64; off <<= 1) {
+        int o = __shfl_up(inc, off, 64);
+        if (lane >= off) inc += o;
+      }
+      if (e < E) {
+        int ex = carry + inc - v;
+        s_off[e] = ex;
+        seg_offsets[e] = ex;
+      }
+      carry += __shfl(inc, 63, 64);
+    }
+    if (lane == 0) seg_offsets[E] = T;
+  }
+  __syncthreads();
+
+  for (int c = wave; c < nchunks; c += nwaves) {
+    int t = c * 64 + lane;
+    bool valid = t < T;
+    int key = valid ? expert_idx[t] : E;
+    uint64_t m = match_any(key, nb);
+    if (valid) {
+      int rank = __popcll(m & ((1ull << lane) - 1ull));
+      perm[s_off[key] + cnt[c * E + key] + rank] = t;
+    }
+  }
+}
+
+}  // namespace
+
+size_t moqe_route_ws_bytes(int64_t T, int64_t E) {
+  int64_t nchunks = (T + 63) / 64;
+  int64_t ints = nchunks * E;
+  size_t b = ints > SEG_LDS_INTS ? (size_t)ints * 4 : 0;
+  return b < 256 ? 256 : ((b + 255) & ~(size_t)255);
+}
+
+static int pow2_ceil(int v) {
+  int p = 1;
+  while (p < v) p <<= 1;
+  return p;
+}
+
+hipError_t moqe_launch_route(const uint16_t* x, const uint16_t* wg, const float* logits, int T, int d, int E,
+                             int* expert_idx, float* gate, int* seg_offsets, int* perm, void* ws,
+                             hipStream_t stream) {
+  if (T > 0) {
+    if (logits) {
+      hipLaunchKernelGGL(route_pick_kernel, dim3((T + 3) / 4), dim3(256), 0, stream, logits, T, E, expert_idx, gate);
+    } else {
+      int EP = pow2_ceil(E);
+      if (EP > SCORE_THREADS) EP = SCORE_THREADS;
+      // 8 tokens per block once there are enough tokens to fill the chip, else 1
+      if (T >= 2048) {
+        constexpr int TB = 8;
+        size_t sm = (((size_t)TB * d * 2 + 15) & ~(size_t)15) + (size_t)SCORE_THREADS * TB * 4 + (size_t)TB * E * 4;
+        hipLaunchKernelGGL(route_score_kernel<TB>, dim3((T + TB - 1) / TB), dim3(SCORE_THREADS), sm, stream,
+                           (const half_t*)x, (const half_t*)wg, T, d, E, EP, expert_idx, gate);
+      } else {
+        constexpr int TB = 1;
+        size_t sm = (((size_t)TB * d * 2 + 15) & ~(size_t)15) + (size_t)SCORE_THREADS * TB * 4 + (size_t)TB * E * 4;
+        hipLaunchKernelGGL(route_score_kernel<TB>, dim3((T + TB - 1) / TB), dim3(SCORE_THREADS), sm, stream,
+                           (const half_t*)x, (const half_t*)wg, T, d, E, EP, expert_idx, gate);
+      }
+    }
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+  }
+  hipLaunchKernelGGL(route_segments_kernel, dim3(1), dim3(SEG_THREADS), 0, stream, expert_idx, T, E, seg_offsets, perm,
+                     (int*)ws);
+  return hipGetLastError();
+}

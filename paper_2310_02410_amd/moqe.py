@@ -1,0 +1,269 @@
+"""Thin ctypes binding of libmoqe.so (the C ABI in include/moqe.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels.
+PyTorch is used for device memory and the current stream, nothing else.  There
+is no CPU fallback: if the library has not been built, loading fails loudly.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libmoqe.so")
+
+MOQE_OK = 0
+STATUS_NAMES = ("MOQE_OK", "MOQE_ERR_NULL", "MOQE_ERR_BITS", "MOQE_ERR_SHAPE", "MOQE_ERR_ALIGN",
+                "MOQE_ERR_WORKSPACE", "MOQE_ERR_HIP")
+
+EXPORTS = (
+    "moqe_status_string", "moqe_last_hip_error", "moqe_version", "moqe_packed_bytes",
+    "moqe_check_matrix", "moqe_check_layer", "moqe_route_workspace_bytes",
+    "moqe_ffn_workspace_bytes", "moqe_quantize", "moqe_unpack", "moqe_route",
+    "moqe_route_logits", "moqe_expert_ffn", "moqe_expert_ffn1", "moqe_expert_ffn2",
+)
+
+
+class MoqeError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().moqe_status_string(status).decode()
+        if status == 6:
+            msg += " (" + lib().moqe_last_hip_error().decode() + ")"
+        super().__init__(f"{where}: {msg}")
+
+
+class CLayer(ctypes.Structure):
+    """moqe_layer of include/moqe.h."""
+    _fields_ = [("bits", ctypes.c_int), ("E", ctypes.c_int64), ("d", ctypes.c_int64), ("f", ctypes.c_int64),
+                ("codes1", ctypes.c_void_p), ("scales1", ctypes.c_void_p), ("bias1", ctypes.c_void_p),
+                ("codes2", ctypes.c_void_p), ("scales2", ctypes.c_void_p), ("bias2", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library; raises if it was never built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it first (python -m paper_2310_02410_amd.build, or "
+            "__graft_entry__.build()). There is no fallback path.")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i64, sz, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t, ctypes.c_int
+    L.moqe_status_string.restype = ctypes.c_char_p
+    L.moqe_status_string.argtypes = [ci]
+    L.moqe_last_hip_error.restype = ctypes.c_char_p
+    L.moqe_last_hip_error.argtypes = []
+    L.moqe_version.restype = ci
+    L.moqe_packed_bytes.restype = sz
+    L.moqe_packed_bytes.argtypes = [ci, i64, i64]
+    L.moqe_check_matrix.restype = ci
+    L.moqe_check_matrix.argtypes = [ci, i64, i64]
+    L.moqe_check_layer.restype = ci
+    L.moqe_check_layer.argtypes = [ci, i64, i64, i64]
+    L.moqe_route_workspace_bytes.restype = sz
+    L.moqe_route_workspace_bytes.argtypes = [i64, i64]
+    L.moqe_ffn_workspace_bytes.restype = sz
+    L.moqe_ffn_workspace_bytes.argtypes = [i64, i64, i64, i64]
+    L.moqe_quantize.restype = ci
+    L.moqe_quantize.argtypes = [vp, i64, i64, i64, ci, vp, vp, vp]
+    L.moqe_unpack.restype = ci
+    L.moqe_unpack.argtypes = [vp, i64, i64, i64, ci, vp, vp]
+    L.moqe_route.restype = ci
+    L.moqe_route.argtypes = [vp, vp, i64, i64, i64, vp, vp, vp, vp, vp, sz, vp]
+    L.moqe_route_logits.restype = ci
+    L.moqe_route_logits.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, sz, vp]
+    L.moqe_expert_ffn.restype = ci
+    L.moqe_expert_ffn.argtypes = [ctypes.POINTER(CLayer), vp, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.moqe_expert_ffn1.restype = ci
+    L.moqe_expert_ffn1.argtypes = [ctypes.POINTER(CLayer), vp, i64, vp, vp, vp, vp]
+    L.moqe_expert_ffn2.restype = ci
+    L.moqe_expert_ffn2.argtypes = [ctypes.POINTER(CLayer), vp, i64, vp, vp, vp, vp, vp, vp]
+    _lib = L
+    return L
+
+
+def _check(status: int, where: str) -> None:
+    if status != MOQE_OK:
+        raise MoqeError(status, where)
+
+
+def _stream(stream=None) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+def _ptr(t) -> int:
+    return 0 if t is None else t.data_ptr()
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> torch.Tensor:
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous {dtype} device tensor")
+    return t
+
+
+# ---------------------------------------------------------------------------
+# pure host queries
+# ---------------------------------------------------------------------------
+
+def moqe_packed_bytes(bits: int, K: int, N: int) -> int:
+    return lib().moqe_packed_bytes(bits, K, N)
+
+
+def moqe_route_workspace_bytes(T: int, E: int) -> int:
+    return lib().moqe_route_workspace_bytes(T, E)
+
+
+def moqe_ffn_workspace_bytes(T: int, E: int, d: int, f: int) -> int:
+    return lib().moqe_ffn_workspace_bytes(T, E, d, f)
+
+
+# ---------------------------------------------------------------------------
+# the three calls
+# ---------------------------------------------------------------------------
+
+def moqe_quantize(w: torch.Tensor, bits: int, stream=None):
+    """w fp32 [E,K,N] -> (codes uint8 [E, K*N*bits/8], scales fp16 [E,N])."""
+    _dev(w, torch.float32, "w")
+    E, K, N = w.shape
+    nbytes = moqe_packed_bytes(bits, K, N)
+    if nbytes == 0:
+        _check(lib().moqe_check_matrix(bits, K, N) or 3, "moqe_quantize")
+    codes = torch.empty((E, nbytes), dtype=torch.uint8, device=w.device)
+    scales = torch.empty((E, N), dtype=torch.float16, device=w.device)
+    _check(lib().moqe_quantize(w.data_ptr(), E, K, N, bits, codes.data_ptr(), scales.data_ptr(), _stream(stream)),
+           "moqe_quantize")
+    return codes, scales
+
+
+def moqe_unpack(codes: torch.Tensor, bits: int, K: int, N: int, stream=None) -> torch.Tensor:
+    """codes uint8 [E, K*N*bits/8] -> int8 [E,K,N]."""
+    _dev(codes, torch.uint8, "codes")
+    E = codes.shape[0]
+    q = torch.empty((E, K, N), dtype=torch.int8, device=codes.device)
+    _check(lib().moqe_unpack(codes.data_ptr(), E, K, N, bits, q.data_ptr(), _stream(stream)), "moqe_unpack")
+    return q
+
+
+@dataclass
+class Route:
+    expert_idx: torch.Tensor   # int32 [T]
+    gate: torch.Tensor         # fp32 [T]
+    seg_offsets: torch.Tensor  # int32 [E+1]
+    perm: torch.Tensor         # int32 [T]
+
+
+def alloc_route(T: int, E: int, device) -> tuple:
+    r = Route(torch.empty(max(T, 1), dtype=torch.int32, device=device)[:T],
+              torch.empty(max(T, 1), dtype=torch.float32, device=device)[:T],
+              torch.empty(E + 1, dtype=torch.int32, device=device),
+              torch.empty(max(T, 1), dtype=torch.int32, device=device)[:T])
+    ws = torch.empty(moqe_route_workspace_bytes(T, E), dtype=torch.uint8, device=device)
+    return r, ws
+
+
+def moqe_route(x: torch.Tensor, w_gate: torch.Tensor, out: Route = None, workspace=None, stream=None) -> Route:
+    """Top-1 gating of x fp16 [T,d] with w_gate fp16 [d,E]."""
+    _dev(x, torch.float16, "x")
+    _dev(w_gate, torch.float16, "w_gate")
+    T, d = x.shape
+    E = w_gate.shape[1]
+    if out is None or workspace is None:
+        out, workspace = alloc_route(T, E, x.device)
+    _check(lib().moqe_route(x.data_ptr(), w_gate.data_ptr(), T, d, E, out.expert_idx.data_ptr(),
+                            out.gate.data_ptr(), out.seg_offsets.data_ptr(), out.perm.data_ptr(),
+                            workspace.data_ptr(), workspace.numel(), _stream(stream)), "moqe_route")
+    return out
+
+
+def moqe_route_logits(logits: torch.Tensor, out: Route = None, workspace=None, stream=None) -> Route:
+    """Top-1 gating from given fp32 logits [T,E]."""
+    _dev(logits, torch.float32, "logits")
+    T, E = logits.shape
+    if out is None or workspace is None:
+        out, workspace = alloc_route(T, E, logits.device)
+    _check(lib().moqe_route_logits(logits.data_ptr(), T, E, out.expert_idx.data_ptr(), out.gate.data_ptr(),
+                                   out.seg_offsets.data_ptr(), out.perm.data_ptr(), workspace.data_ptr(),
+                                   workspace.numel(), _stream(stream)), "moqe_route_logits")
+    return out
+
+
+@dataclass
+class QuantLayer:
+    """Device buffers of one quantized MoE layer plus its moqe_layer struct."""
+    bits: int
+    E: int
+    d: int
+    f: int
+    codes1: torch.Tensor
+    scales1: torch.Tensor
+    bias1: torch.Tensor
+    codes2: torch.Tensor
+    scales2: torch.Tensor
+    bias2: torch.Tensor
+    w_gate: torch.Tensor = None
+
+    def c_struct(self) -> CLayer:
+        return CLayer(self.bits, self.E, self.d, self.f, self.codes1.data_ptr(), self.scales1.data_ptr(),
+                      self.bias1.data_ptr(), self.codes2.data_ptr(), self.scales2.data_ptr(),
+                      self.bias2.data_ptr())
+
+    def code_bytes(self) -> int:
+        return self.codes1.numel() + self.codes2.numel()
+
+
+def quantize_layer(w1: torch.Tensor, b1: torch.Tensor, w2: torch.Tensor, b2: torch.Tensor, bits: int,
+                   w_gate: torch.Tensor = None) -> QuantLayer:
+    """Quantize fp32 w1 [E,d,f], w2 [E,f,d] on the device; biases fp16 [E,f], [E,d]."""
+    E, d, f = w1.shape
+    _check(lib().moqe_check_layer(bits, E, d, f), "quantize_layer")
+    c1, s1 = moqe_quantize(w1, bits)
+    c2, s2 = moqe_quantize(w2, bits)
+    return QuantLayer(bits, E, d, f, c1, s1, _dev(b1, torch.float16, "b1"), c2, s2,
+                      _dev(b2, torch.float16, "b2"), w_gate)
+
+
+def moqe_expert_ffn(layer: QuantLayer, x: torch.Tensor, route: Route, residual: torch.Tensor = None,
+                    out: torch.Tensor = None, workspace: torch.Tensor = None, stream=None) -> torch.Tensor:
+    """FFN1 + bias + ReLU, FFN2 + bias, gate-weighted combine (+ residual) -> fp16 [T,d]."""
+    _dev(x, torch.float16, "x")
+    T, d = x.shape
+    if d != layer.d:
+        raise ValueError("x has the wrong width")
+    if out is None:
+        out = torch.empty_like(x)
+    if workspace is None:
+        workspace = torch.empty(moqe_ffn_workspace_bytes(T, layer.E, layer.d, layer.f), dtype=torch.uint8,
+                                device=x.device)
+    cl = layer.c_struct()
+    _check(lib().moqe_expert_ffn(ctypes.byref(cl), x.data_ptr(), T, _ptr(route.expert_idx), _ptr(route.gate),
+                                 route.seg_offsets.data_ptr(), _ptr(route.perm), _ptr(residual), out.data_ptr(),
+                                 workspace.data_ptr(), workspace.numel(), _stream(stream)), "moqe_expert_ffn")
+    return out
+
+
+def moqe_expert_ffn1(layer: QuantLayer, x: torch.Tensor, route: Route, h: torch.Tensor, stream=None) -> torch.Tensor:
+    """h = relu(x W1' + b1) into fp16 [T,f], rows in sorted-token order."""
+    cl = layer.c_struct()
+    _check(lib().moqe_expert_ffn1(ctypes.byref(cl), x.data_ptr(), x.shape[0], route.seg_offsets.data_ptr(),
+                                  _ptr(route.perm), h.data_ptr(), _stream(stream)), "moqe_expert_ffn1")
+    return h
+
+
+def moqe_expert_ffn2(layer: QuantLayer, h: torch.Tensor, route: Route, out: torch.Tensor,
+                     residual: torch.Tensor = None, stream=None) -> torch.Tensor:
+    """y_t = gate_t (h W2' + b2) (+ residual) into fp16 [T,d], token order."""
+    cl = layer.c_struct()
+    _check(lib().moqe_expert_ffn2(ctypes.byref(cl), h.data_ptr(), h.shape[0], _ptr(route.gate),
+                                  route.seg_offsets.data_ptr(), _ptr(route.perm), _ptr(residual), out.data_ptr(),
+                                  _stream(stream)), "moqe_expert_ffn2")
+    return out

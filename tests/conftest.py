@@ -21,3 +21,12 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(scope="session", autouse=True)
+def _built_library():
+    """Tests load the library that is built; they build it only when none is there."""
+    from paper_2310_02410_amd import build, moqe
+    if not os.path.exists(moqe.LIB_PATH):
+        build.build_library()
+    yield

@@ -1,0 +1,136 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol include/moqe.h declares, and rejects bad arguments before launching."""
+
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2310_02410_amd import moqe
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "moqe.h")
+
+pytestmark = pytest.mark.skipif(not os.path.exists(moqe.LIB_PATH), reason="libmoqe.so not built")
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(moqe_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported():
+    L = ctypes.CDLL(moqe.LIB_PATH)
+    names = declared_functions()
+    assert len(names) >= 13
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(moqe.EXPORTS) == names
+
+
+def test_version_and_strings():
+    L = moqe.lib()
+    assert L.moqe_version() == 1
+    assert L.moqe_status_string(0) == b"MOQE_OK"
+    for s in range(1, 7):
+        assert L.moqe_status_string(s).decode().startswith(moqe.STATUS_NAMES[s])
+    assert L.moqe_status_string(99) == b"unknown status"
+
+
+@pytest.mark.parametrize("bits", (2, 3, 4))
+def test_packed_bytes_density(bits):
+    # Table 2's size column: exactly `bits` bits per expert weight
+    for K, N in ((1024, 4096), (4096, 1024), (768, 3072), (256, 64)):
+        assert moqe.moqe_packed_bytes(bits, K, N) == K * N * bits // 8
+    assert moqe.moqe_packed_bytes(4, 64, 256) == 64 * 256 // 2
+
+
+def test_shape_rules():
+    L = moqe.lib()
+    assert L.moqe_check_matrix(5, 1024, 1024) == 2
+    assert L.moqe_check_matrix(4, 48, 16) == 3       # K not a multiple of 32
+    assert L.moqe_check_matrix(4, 64, 24) == 3       # N not a multiple of 16
+    assert L.moqe_check_matrix(2, 32, 16) == 3       # int2 needs K % 64
+    assert L.moqe_check_matrix(3, 64, 16) == 3       # int3 needs K % 128
+    assert L.moqe_check_matrix(4, 160, 16) == 3      # 5 steps, chunk of 4
+    assert L.moqe_check_matrix(4, 64, 256) == 0
+    assert L.moqe_check_matrix(3, 768, 3072) == 0
+    assert moqe.moqe_packed_bytes(2, 32, 16) == 0
+    assert L.moqe_check_layer(4, 4, 64, 256) == 0
+    assert L.moqe_check_layer(2, 32, 1024, 4096) == 0
+    assert L.moqe_check_layer(3, 128, 768, 3072) == 0
+    assert L.moqe_check_layer(4, 0, 64, 256) == 3
+    assert L.moqe_check_layer(4, 4, 96 * 32 * 5, 256) == 3   # K/32 = 480: no supported split
+
+
+def test_workspace_sizes():
+    assert moqe.moqe_ffn_workspace_bytes(24, 32, 1024, 4096) == 24 * 4096 * 2
+    assert moqe.moqe_ffn_workspace_bytes(0, 32, 1024, 4096) == 256
+    assert moqe.moqe_route_workspace_bytes(24, 32) == 256
+    assert moqe.moqe_route_workspace_bytes(1 << 20, 128) >= (1 << 20) // 64 * 128 * 4
+
+
+P = 0x10000  # a fake, aligned, non-NULL device address; never dereferenced on the host
+
+
+def test_quantize_error_paths():
+    L = moqe.lib()
+    assert L.moqe_quantize(0, 1, 64, 16, 4, P, P, None) == 1
+    assert L.moqe_quantize(P, 1, 64, 16, 7, P, P, None) == 2
+    assert L.moqe_quantize(P, 1, 48, 16, 4, P, P, None) == 3
+    assert L.moqe_quantize(P, 0, 64, 16, 4, P, P, None) == 3
+    assert L.moqe_quantize(P + 4, 1, 64, 16, 4, P, P, None) == 4
+    assert L.moqe_unpack(P, 1, 64, 16, 4, 0, None) == 1
+    assert L.moqe_unpack(P, 1, 64, 16, 1, P, None) == 2
+    assert L.moqe_unpack(P, 1, 64, 20, 4, P, None) == 3
+
+
+def test_route_error_paths():
+    L = moqe.lib()
+    assert L.moqe_route(0, P, 8, 64, 4, P, P, P, P, P, 256, None) == 1
+    assert L.moqe_route(P, P, 8, 64, 4, P, 0, P, P, P, 256, None) == 1
+    assert L.moqe_route(P, P, 8, 64, 4, P, P, 0, P, P, 256, None) == 1
+    assert L.moqe_route(P, P, -1, 64, 4, P, P, P, P, P, 256, None) == 3
+    assert L.moqe_route(P, P, 8, 60, 4, P, P, P, P, P, 256, None) == 3
+    assert L.moqe_route(P, P, 8, 64, 0, P, P, P, P, P, 256, None) == 3
+    assert L.moqe_route(P, P, 8, 64, 2000, P, P, P, P, P, 256, None) == 3
+    assert L.moqe_route(P, P + 2, 8, 64, 4, P, P, P, P, P, 256, None) == 4
+    assert L.moqe_route(P, P, 8, 64, 4, P, P, P, P, P, 16, None) == 5
+    assert L.moqe_route(P, P, 1 << 20, 64, 128, P, P, P, P, P, 256, None) == 5
+    assert L.moqe_route_logits(0, 8, 4, P, P, P, P, P, 256, None) == 1
+    assert L.moqe_route_logits(P, 8, 4, P, P, P, P, P, 0, None) == 5
+
+
+def test_expert_ffn_error_paths():
+    L = moqe.lib()
+
+    def layer(**kw):
+        base = dict(bits=4, E=4, d=64, f=256, codes1=P, scales1=P, bias1=P, codes2=P, scales2=P, bias2=P)
+        base.update(kw)
+        return moqe.CLayer(*[base[k] for k, _ in moqe.CLayer._fields_])
+
+    def call(lay, x=P, T=8, idx=P, gate=P, seg=P, perm=P, res=None, y=P, ws=P, wsb=1 << 20):
+        return L.moqe_expert_ffn(ctypes.byref(lay) if lay is not None else None, x, T, idx, gate, seg, perm, res, y,
+                                 ws, wsb, None)
+
+    assert call(None) == 1
+    assert call(layer(codes2=0)) == 1
+    assert call(layer(), x=0) == 1
+    assert call(layer(), y=0) == 1
+    assert call(layer(bits=8)) == 2
+    assert call(layer(d=48)) == 3
+    assert call(layer(E=0)) == 3
+    assert call(layer(), T=-2) == 3
+    assert call(layer(scales1=P + 8)) == 4
+    assert call(layer(), res=P + 2) == 4
+    assert call(layer(), wsb=100) == 5
+    assert call(layer(), T=0) == 0          # no tokens: valid no-op, nothing launched
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(moqe, "_lib", None)
+    monkeypatch.setattr(moqe, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        moqe.lib()

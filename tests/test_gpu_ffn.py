@@ -1,0 +1,98 @@
+"""GPU parity of moqe_expert_ffn against the oracle (Sec. 2.1 expert FFN with
+App. A dequantization): max|err| <= 2e-3 max|ref| on the [T,d] output."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import moqe_oracle as O
+from paper_2310_02410_amd import moqe, workloads as W
+from tests.helpers import (FFN_TOL, assert_route_equal, dev, ffn_error, gpu_quantize_layer, make_route,
+                           oracle_layer_output, route_to_numpy)
+
+pytestmark = pytest.mark.gpu
+
+
+def _layer_parity(wl, bits, residual=False, forced=None):
+    layer, x = W.make_layer(wl), W.make_tokens(wl)
+    ql = gpu_quantize_layer(layer, bits)
+    xd = dev(x)
+    if forced is None:
+        r = moqe.moqe_route(xd, ql.w_gate)
+        idx, gate, offs, perm = route_to_numpy(r)
+        assert_route_equal((idx, gate, offs, perm), O.route(x, layer["w_gate"]), wl.T, wl.E)
+    else:
+        idx, gate = forced
+        r = make_route(idx, gate, wl.E)
+    y = moqe.moqe_expert_ffn(ql, xd, r, residual=xd if residual else None)
+    torch.cuda.synchronize()
+    ref = oracle_layer_output(x, layer, bits, idx, gate.astype(np.float64), residual=residual)
+    err = ffn_error(y.cpu().numpy(), ref)
+    assert err <= FFN_TOL, f"{wl.name} int{bits}: max|err|/max|ref| = {err:.3e}"
+    return err
+
+
+def test_config0():
+    _layer_parity(W.CONFIGS["c0"], 4)
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("T", (1, 37, 150))
+def test_small_layer(bits, T):
+    # d=128 (one wave slice of 4 steps), f=256 (8 steps); T=150 over 8 experts gives
+    # segments longer than one 16-token tile with ragged tails
+    _layer_parity(W.small(T=T), bits)
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+def test_split_k_shapes(bits):
+    # d=512 -> 16 steps, f=2048 -> 16 steps x 4 waves; d=768/f=3072 -> 24 steps (x4)
+    _layer_parity(W.small(E=4, d=512, f=2048, T=40, seed=21), bits)
+    _layer_parity(W.small(E=3, d=768, f=3072, T=21, seed=22), bits)
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+def test_residual_fused(bits):
+    _layer_parity(W.small(T=50, seed=23), bits, residual=True)
+
+
+@pytest.mark.parametrize("bits", (4, 2))
+def test_forced_routes(bits):
+    wl = W.small(E=8, d=128, f=256, T=40, seed=24)
+    rng = np.random.default_rng(1)
+    # everything to one expert (others empty), gate values arbitrary
+    _layer_parity(wl, bits, forced=(np.full(40, 5, np.int32), rng.uniform(0.1, 1.0, 40).astype(np.float32)))
+    # last expert only gets the last token
+    idx = np.zeros(40, np.int32)
+    idx[-1] = 7
+    _layer_parity(wl, bits, forced=(idx, np.ones(40, np.float32)))
+
+
+def test_zero_input_closed_form():
+    # x = 0 => y = g (max(0, b1) W2' + b2): FFN2 and the biases alone
+    wl = W.small(E=4, d=128, f=256, T=9, seed=25)
+    layer = W.make_layer(wl)
+    ql = gpu_quantize_layer(layer, 4)
+    x = np.zeros((9, 128), np.float16)
+    idx = np.arange(9, dtype=np.int32) % 4
+    g = np.linspace(0.2, 1.0, 9).astype(np.float32)
+    y = moqe.moqe_expert_ffn(ql, dev(x), make_route(idx, g, 4)).cpu().numpy()
+    ref = oracle_layer_output(x, layer, 4, idx, g.astype(np.float64))
+    assert ffn_error(y, ref) <= FFN_TOL
+
+
+@pytest.mark.parametrize("name,bits", (("c1", 4), ("c2", 3), ("c2", 2)))
+def test_decode_configs_full_size(name, bits):
+    """Benchmark decode layers at full size: E=32, d=1024, f=4096, T=24."""
+    _layer_parity(W.CONFIGS[name], bits)
+
+
+def test_deterministic_output():
+    wl = W.small(E=8, d=512, f=2048, T=33, seed=26)
+    layer, x = W.make_layer(wl), W.make_tokens(wl)
+    ql = gpu_quantize_layer(layer, 2)
+    xd = dev(x)
+    r = moqe.moqe_route(xd, ql.w_gate)
+    a = moqe.moqe_expert_ffn(ql, xd, r).cpu().numpy()
+    b = moqe.moqe_expert_ffn(ql, xd, r).cpu().numpy()
+    assert np.array_equal(a.view(np.uint16), b.view(np.uint16))

@@ -1,0 +1,72 @@
+"""GPU parity of moqe_quantize / moqe_unpack against the oracle: packed codes and
+scale bit patterns must be identical (App. A quantizer, App. C fp16 scales)."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import moqe_oracle as O
+from paper_2310_02410_amd import moqe, workloads as W
+from tests.helpers import dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _check(w, bits):
+    E, K, N = w.shape
+    codes, scales = moqe.moqe_quantize(dev(w), bits)
+    q_ref, s_ref = O.quantize(w, bits)
+    torch.cuda.synchronize()
+    assert np.array_equal(scales.cpu().numpy().view(np.uint16), s_ref.view(np.uint16)), "scales differ"
+    q_gpu = moqe.moqe_unpack(codes, bits, K, N).cpu().numpy()
+    assert np.array_equal(q_gpu, q_ref), "codes differ"
+    assert np.array_equal(codes.cpu().numpy(), O.pack(q_ref, bits)), "packed bytes differ"
+
+
+def _weights(E, K, N, seed, outliers=True):
+    rng = np.random.default_rng(seed)
+    w = (rng.standard_normal((E, K, N)) * 0.02).astype(np.float32)
+    if outliers:
+        m = rng.random((E, K, N)) < 0.002
+        w[m] = np.float32(0.16) * rng.choice([-1.0, 1.0], size=int(m.sum())).astype(np.float32)
+    return w
+
+
+@pytest.mark.parametrize("bits,K,N", [
+    (4, 32, 16), (4, 64, 256), (4, 256, 64), (4, 96, 48), (4, 1024, 80),
+    (2, 64, 16), (2, 192, 32), (2, 256, 64), (2, 1024, 48),
+    (3, 128, 16), (3, 256, 64), (3, 768, 48), (3, 1024, 32),
+])
+def test_small_shapes(bits, K, N):
+    _check(_weights(3, K, N, K + N + bits), bits)
+
+
+@pytest.mark.parametrize("bits", (2, 3, 4))
+def test_special_channels(bits):
+    w = _weights(2, 256, 32, 77)
+    w[0, :, 0] = 0.0                      # all-zero channel
+    w[0, :, 1] = 0.0
+    w[0, 5, 1] = 1e-9                     # scale below the fp16 subnormal step
+    w[1, :, 2] = 0.0
+    top = {2: 1.5, 3: 3.5, 4: 7.5}[bits]  # exact ties with an exactly representable scale
+    w[1, 0, 2], w[1, 1, 2], w[1, 2, 2], w[1, 3, 2] = top, -top, 0.5, -0.5   # scale is exactly 1
+    if bits > 2:
+        w[1, 4, 2], w[1, 5, 2] = 2.5, -1.5
+    w[1, :, 3] = np.float32(2.0 ** -14)   # scale near the normal/subnormal border
+    w[1, :, 4] = np.float32(60000.0) * (2 ** bits - 1) / 2 / 2   # large scale, still in range
+    _check(w, bits)
+
+
+def test_config0_layer():
+    layer = W.make_layer(W.CONFIGS["c0"])
+    _check(layer["w1"], 4)
+    _check(layer["w2"], 4)
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+def test_full_size_experts(bits):
+    # four experts of the benchmark shape (d_model 1024, d_ff 4096), planted outliers
+    wl = W.small("q", E=4, d=1024, f=4096, seed=1)
+    layer = W.make_layer(wl)
+    _check(layer["w1"], bits)
+    _check(layer["w2"], bits)

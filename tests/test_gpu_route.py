@@ -1,0 +1,68 @@
+"""GPU parity of moqe_route / moqe_route_logits against the oracle (App. B top-1
+gating): expert indices, segment offsets and the permutation are bit-exact."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import moqe_oracle as O
+from paper_2310_02410_amd import moqe, workloads as W
+from tests.helpers import assert_route_equal, dev, route_to_numpy
+
+pytestmark = pytest.mark.gpu
+
+
+def _route_case(wl):
+    layer, x = W.make_layer(wl), W.make_tokens(wl)
+    got = route_to_numpy(moqe.moqe_route(dev(x), dev(layer["w_gate"])))
+    torch.cuda.synchronize()
+    assert_route_equal(got, O.route(x, layer["w_gate"]), wl.T, wl.E)
+    return got
+
+
+@pytest.mark.parametrize("name", ("c0", "c1", "c3"))
+def test_benchmark_configs(name):
+    wl = W.CONFIGS[name]
+    wl = W.small(name, E=wl.E, d=wl.d, f=32, T=wl.T, routing=wl.routing, n_empty=wl.n_empty, seed=wl.seed)
+    got = _route_case(wl)
+    if name == "c3":
+        counts = np.diff(got[2])
+        assert counts.max() > 300 and (counts == 0).sum() >= 4
+
+
+@pytest.mark.parametrize("T,d,E", [(1, 64, 4), (37, 128, 8), (65, 64, 1), (130, 256, 128), (700, 64, 100),
+                                   (4096, 1024, 32), (5000, 128, 8), (20000, 64, 256)])
+def test_shapes(T, d, E):
+    _route_case(W.small("r", E=E, d=d, f=32, T=T, seed=T + E))
+
+
+def test_empty_batch():
+    x = torch.empty((1, 64), dtype=torch.float16, device="cuda")[:0]
+    wg = dev(W.make_layer(W.small("r", E=8, d=64, f=32))["w_gate"])
+    r = moqe.moqe_route(x, wg)
+    torch.cuda.synchronize()
+    assert r.seg_offsets.cpu().tolist() == [0] * 9
+
+
+def test_logits_with_exact_ties_and_forced_loads():
+    rng = np.random.default_rng(5)
+    T, E = 300, 32
+    l = rng.integers(-4, 5, size=(T, E)).astype(np.float32) * 0.5   # many exact ties
+    l[:40] = 0.0                                                     # all tied: expert 0, gate 1/E
+    l[40:80, 7] = 9.0                                                # forced to expert 7
+    got = route_to_numpy(moqe.moqe_route_logits(dev(l)))
+    torch.cuda.synchronize()
+    ref = O.route_from_logits(l)
+    assert_route_equal(got, ref, T, E)
+    assert np.all(got[0][:40] == 0) and np.allclose(got[1][:40], 1.0 / E, rtol=1e-6)
+    assert np.all(got[0][40:80] == 7)
+
+
+def test_deterministic():
+    wl = W.small("r", E=32, d=1024, f=32, T=1536, routing="zipf", n_empty=4)
+    layer, x = W.make_layer(wl), W.make_tokens(wl)
+    xd, gd = dev(x), dev(layer["w_gate"])
+    a = route_to_numpy(moqe.moqe_route(xd, gd))
+    b = route_to_numpy(moqe.moqe_route(xd, gd))
+    for u, v in zip(a, b):
+        assert np.array_equal(u, v)
