@@ -23,6 +23,9 @@ def build_library(verbose: bool = False, extra=()) -> str:
     """Compile every HIP source into paper_2310_02410_amd/libmoqe.so (always recompiles)."""
     cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           # keep the four words of an unpacked MFMA fragment as scalar ops: the SLP vectorizer
+           # would turn (a & mask) | magic into vector ops that no longer select v_and_or_b32
+           "-fno-slp-vectorize",
            "-Wno-unused-command-line-argument",
            "-I", os.path.join(os.path.dirname(PKG), "include"), *extra,
            *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB + ".tmp"]

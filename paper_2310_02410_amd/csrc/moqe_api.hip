@@ -33,6 +33,10 @@ int num_cus() {
   return cache[dev];
 }
 
+#ifdef MOQE_PHASE_TRACE
+long long* g_trace = nullptr;  // debug builds only: set through moqe_debug_set_trace
+#endif
+
 constexpr int64_t MAX_TOKENS = 1 << 22;
 constexpr int64_t MAX_EXPERTS = 1024;
 
@@ -58,6 +62,10 @@ const char* moqe_status_string(int status) {
 const char* moqe_last_hip_error(void) { return g_hip_error; }
 
 int moqe_version(void) { return 1; }
+
+#ifdef MOQE_PHASE_TRACE
+void moqe_debug_set_trace(long long* p) { g_trace = p; }
+#endif
 
 int moqe_check_matrix(int bits, int64_t K, int64_t N) {
   if (bits != 2 && bits != 3 && bits != 4) return MOQE_ERR_BITS;
@@ -171,6 +179,9 @@ static void base_args(FfnArgs* a, const moqe_layer* L, int64_t T, const int32_t*
   a->T = (int)T;
   a->min_tokens = 1;
   a->max_tokens = INT_MAX;
+#ifdef MOQE_PHASE_TRACE
+  a->trace = g_trace;
+#endif
 }
 
 moqe_status moqe_expert_ffn1(const moqe_layer* L, const moqe_f16* x, int64_t T, const int32_t* seg_offsets,

@@ -70,9 +70,14 @@ __device__ inline int lane_id() { return (int)(threadIdx.x & 63); }
 __device__ inline uint32_t uniform_u32(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ inline int uniform_i32(int v) { return (int)__builtin_amdgcn_readfirstlane((uint32_t)v); }
 
-// D = (a & mask) | orv in one VALU op.  mask is wave-uniform (SGPR).
-__device__ inline uint32_t and_or(uint32_t a, uint32_t mask_s, uint32_t orv) {
-  uint32_t r;
-  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask_s), "v"(orv));
-  return r;
+// A constant the optimizer cannot see through, kept in a scalar / vector register.
+// (a & mask) | magic then compiles to one v_and_or_b32, whose VOP3 encoding cannot
+// take literals, instead of an and plus an or with literal operands.
+__device__ inline uint32_t opaque_sgpr(uint32_t c) {
+  asm volatile("" : "+s"(c));
+  return c;
+}
+__device__ inline uint32_t opaque_vgpr(uint32_t c) {
+  asm volatile("" : "+v"(c));
+  return c;
 }

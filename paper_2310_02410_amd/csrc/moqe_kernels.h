@@ -39,6 +39,8 @@ struct FfnArgs {
   int mode;
   // expert segments with min_tokens <= n < max_tokens are handled, the rest skipped
   int min_tokens, max_tokens;
+  // debug builds (-DMOQE_PHASE_TRACE): 8 wall-clock stamps per workgroup, else unused
+  long long* trace;
 };
 
 // Register-resident dequantize + 16-token MFMA path (few tokens per expert).

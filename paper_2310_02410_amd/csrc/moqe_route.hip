@@ -115,6 +115,72 @@ __global__ __launch_bounds__(SCORE_THREADS) void route_score_kernel(const half_t
   }
 }
 
+// One token per block, for E a multiple of 8: thread (kq, eg) reads rows k = kq + KQ i of
+// W_g, eight experts (16 bytes) at a time, with all loads of a batch in flight together.
+__global__ __launch_bounds__(SCORE_THREADS) void route_score8_kernel(const half_t* __restrict__ x,
+                                                                      const half_t* __restrict__ wg, int T, int d,
+                                                                      int E, int EGP, int* __restrict__ expert_idx,
+                                                                      float* __restrict__ gate) {
+  __shared__ float red[SCORE_THREADS / 64][256];  // [wave][expert], E <= 256
+  __shared__ float logit[256];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int t = blockIdx.x;
+  const int EG = E >> 3;
+  const int KQ = SCORE_THREADS / EGP;
+  const int eg = tid % EGP, kq = tid / EGP;
+  const half_t* xr = x + (int64_t)t * d;
+  float acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = 0.0f;
+  constexpr int BATCH = 16;
+  if (eg < EG) {
+    for (int k0 = kq; k0 < d; k0 += KQ * BATCH) {
+      uint4_t w[BATCH];
+      half_t xv[BATCH];
+#pragma unroll
+      for (int i = 0; i < BATCH; ++i) {
+        const int k = k0 + i * KQ;
+        const bool ok = k < d;
+        w[i] = ok ? *(const uint4_t*)(wg + (int64_t)k * E + 8 * eg) : uint4_t{0, 0, 0, 0};
+        xv[i] = ok ? xr[k] : (half_t)0;
+      }
+#pragma unroll
+      for (int i = 0; i < BATCH; ++i) {
+        const half8_t h = __builtin_bit_cast(half8_t, w[i]);
+        const float xf = (float)xv[i];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc[q] = fmaf(xf, (float)h[q], acc[q]);
+      }
+    }
+  }
+  // EGP <= 32: lanes of a wave that share eg fold their k-slices together, then the
+  // four waves meet in LDS and are summed in a fixed order
+  for (int off = 32; off >= EGP; off >>= 1) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) acc[q] += __shfl_xor(acc[q], off, 64);
+  }
+  if (lane < EGP && eg < EG) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) red[wave][eg * 8 + q] = acc[q];
+  }
+  __syncthreads();
+  for (int e = tid; e < E; e += SCORE_THREADS) {
+    float sum = 0.0f;
+    for (int w = 0; w < SCORE_THREADS / 64; ++w) sum += red[w][e];
+    logit[e] = sum;
+  }
+  __syncthreads();
+  if (wave == 0) {
+    int idx;
+    float g;
+    wave_pick(logit, E, &idx, &g);
+    if (lane == 0) {
+      expert_idx[t] = idx;
+      gate[t] = g;
+    }
+  }
+}
+
 // One wave per token, logits given.
 __global__ __launch_bounds__(256) void route_pick_kernel(const float* __restrict__ logits, int T, int E,
                                                           int* __restrict__ expert_idx, float* __restrict__ gate) {
@@ -149,13 +215,14 @@ __global__ __launch_bounds__(SEG_THREADS) void route_segments_kernel(const int* 
   __shared__ int s_off[1024 + 1];
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int nwaves = SEG_THREADS / 64;
+  const int nthreads = (int)blockDim.x;
+  const int nwaves = nthreads / 64;
   const int nchunks = (T + 63) / 64;
   int* cnt = ((int64_t)nchunks * E <= SEG_LDS_INTS) ? s_cnt : ws_cnt;
   int nb = 0;
   while ((1 << nb) <= E) ++nb;  // keys 0..E (E = "no token")
 
-  for (int i = tid; i < nchunks * E; i += SEG_THREADS) cnt[i] = 0;
+  for (int i = tid; i < nchunks * E; i += nthreads) cnt[i] = 0;
   __syncthreads();
 
   for (int c = wave; c < nchunks; c += nwaves) {
@@ -169,7 +236,7 @@ __global__ __launch_bounds__(SEG_THREADS) void route_segments_kernel(const int* 
   __syncthreads();
 
   // per expert: exclusive running sum over chunks
-  for (int e = tid; e < E; e += SEG_THREADS) {
+  for (int e = tid; e < E; e += nthreads) {
     int run = 0;
     for (int c = 0; c < nchunks; ++c) {
       int v = cnt[c * E + e];
@@ -244,6 +311,10 @@ hipError_t moqe_launch_route(const uint16_t* x, const uint16_t* wg, const float*
         size_t sm = (((size_t)TB * d * 2 + 15) & ~(size_t)15) + (size_t)SCORE_THREADS * TB * 4 + (size_t)TB * E * 4;
         hipLaunchKernelGGL(route_score_kernel<TB>, dim3((T + TB - 1) / TB), dim3(SCORE_THREADS), sm, stream,
                            (const half_t*)x, (const half_t*)wg, T, d, E, EP, expert_idx, gate);
+      } else if ((E % 8) == 0 && E <= 256) {
+        int EGP = pow2_ceil(E / 8);
+        hipLaunchKernelGGL(route_score8_kernel, dim3(T), dim3(SCORE_THREADS), 0, stream, (const half_t*)x,
+                           (const half_t*)wg, T, d, E, EGP, expert_idx, gate);
       } else {
         constexpr int TB = 1;
         size_t sm = (((size_t)TB * d * 2 + 15) & ~(size_t)15) + (size_t)SCORE_THREADS * TB * 4 + (size_t)TB * E * 4;
@@ -254,7 +325,9 @@ hipError_t moqe_launch_route(const uint16_t* x, const uint16_t* wg, const float*
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
   }
-  hipLaunchKernelGGL(route_segments_kernel, dim3(1), dim3(SEG_THREADS), 0, stream, expert_idx, T, E, seg_offsets, perm,
+  // one wave per 64-token chunk, up to the full block
+  const int seg_threads = T <= 64 ? 64 : T <= 256 ? 256 : SEG_THREADS;
+  hipLaunchKernelGGL(route_segments_kernel, dim3(1), dim3(seg_threads), 0, stream, expert_idx, T, E, seg_offsets, perm,
                      (int*)ws);
   return hipGetLastError();
 }
