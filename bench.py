@@ -1,9 +1,9 @@
 #!/usr/bin/env python3
 """Benchmark of the MoQE hot path on one MI355X.
 
-A step is one pass of the whole hot path over one batch: moqe_route (top-1 gating,
-histogram, scan, permutation) followed by moqe_expert_ffn (FFN1 + bias + ReLU,
-FFN2 + bias, gate-weighted combine) on one MoE layer of the decode configuration
+A step is one pass of the whole hot path over one batch: moqe_moe_layer, i.e. top-1
+gating, histogram, scan, permutation, then FFN1 + bias + ReLU, FFN2 + bias and the
+gate-weighted combine (one kernel launch) on one MoE layer of the decode configuration
 (E=32 experts, d_model 1024, d_ff 4096, batch of 24 tokens, int4 experts).
 Consecutive steps use different layer copies (own weights, own router) so that the
 packed weights of a step are not left in the 256 MB last-level cache by the
@@ -52,10 +52,11 @@ def parse():
 
 
 def algorithmic_bytes(seg_offsets, bits, d, f, T):
-    """Bytes the method must move for one layer-step, split per FFN launch.
+    """Bytes the method must move for one layer-step, split per contraction.
     Per active expert: packed codes + fp16 scales + fp16 biases of the matrix;
     plus the fp16 activations entering and leaving the layer (x in FFN1, y in
-    FFN2).  The hidden activations h are not counted."""
+    FFN2).  The hidden activations h are not counted; the caller adds the router
+    weights (2 d E)."""
     counts = np.diff(np.asarray(seg_offsets))
     active = int((counts > 0).sum())
     ffn1 = active * (d * f * bits // 8 + 2 * f + 2 * f) + 2 * T * d
@@ -105,8 +106,8 @@ def main():
     x = dev(x_host)
 
     L = moqe.lib()
-    route, route_ws = moqe.alloc_route(T, E, x.device)
-    ffn_ws = torch.empty(moqe.moqe_ffn_workspace_bytes(T, E, d, f), dtype=torch.uint8, device=x.device)
+    route, _ = moqe.alloc_route(T, E, x.device)
+    ws = moqe.alloc_workspace(moqe.moqe_layer_workspace_bytes(T, E, d, f), x.device)
     y = torch.empty_like(x)
 
     def make_step(qls):
@@ -116,47 +117,47 @@ def main():
         xp, yp = x.data_ptr(), y.data_ptr()
         ip, gp, sp, pp = (route.expert_idx.data_ptr(), route.gate.data_ptr(), route.seg_offsets.data_ptr(),
                           route.perm.data_ptr())
-        rws, rwsn, fws, fwsn = route_ws.data_ptr(), route_ws.numel(), ffn_ws.data_ptr(), ffn_ws.numel()
+        wsp, wsn = ws.data_ptr(), ws.numel()
 
         def step(i, stream):
             k = i % len(qls)
-            st = L.moqe_route(xp, gates[k], T, d, E, ip, gp, sp, pp, rws, rwsn, stream)
-            st |= L.moqe_expert_ffn(refs[k], xp, T, ip, gp, sp, pp, None, yp, fws, fwsn, stream)
+            st = L.moqe_moe_layer(refs[k], gates[k], xp, T, ip, gp, sp, pp, None, yp, wsp, wsn, stream)
             if st:
-                raise RuntimeError(f"moqe call failed with status {st}")
-
-        def ffn_halves(i, stream, ev):
-            k = i % len(qls)
-            st = L.moqe_route(xp, gates[k], T, d, E, ip, gp, sp, pp, rws, rwsn, stream)
-            ev[0].record()
-            st |= L.moqe_expert_ffn1(refs[k], xp, T, sp, pp, fws, stream)
-            ev[1].record()
-            st |= L.moqe_expert_ffn2(refs[k], fws, T, gp, sp, pp, None, yp, stream)
-            ev[2].record()
-            if st:
-                raise RuntimeError(f"moqe call failed with status {st}")
+                raise RuntimeError(f"moqe_moe_layer failed with status {st}")
 
         step.keep = (structs, refs)
-        return step, ffn_halves
+        return step
 
     def time_steps(run, steps, warmup):
+        """(wall ms per step with a sync on both sides, HIP-event ms per step on the launch stream)"""
         for i in range(warmup):
             run(i)
         torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         t = time.perf_counter()
+        e0.record()
         for i in range(steps):
             run(warmup + i)
+        e1.record()
         torch.cuda.synchronize()
-        return (time.perf_counter() - t) * 1e3 / steps
+        return (time.perf_counter() - t) * 1e3 / steps, e0.elapsed_time(e1) / steps
 
     results = {}
     for b in bit_list:
         qls = layers[b]
-        step, ffn_halves = make_step(qls)
+        step = make_step(qls)
         stream = torch.cuda.current_stream().cuda_stream
-        eager_ms = time_steps(lambda i: step(i, stream), args.steps, args.warmup)
+        # realised routing of every layer copy -> algorithmic bytes of its step
+        ab = []
+        for k in range(len(qls)):
+            step(k, stream)
+            torch.cuda.synchronize()
+            ab.append(algorithmic_bytes(route.seg_offsets.cpu().numpy(), b, d, f, T))
+        if moqe.workspace_error(ws):
+            raise RuntimeError("a phase wait timed out: results invalid")
+        eager_ms, eager_ev_ms = time_steps(lambda i: step(i, stream), args.steps, args.warmup)
 
-        graph_ms = None
+        graph_ms = graph_ev_ms = None
         if not args.no_graph:
             side = torch.cuda.Stream()
             graphs = []
@@ -167,40 +168,25 @@ def main():
                         step(k, torch.cuda.current_stream().cuda_stream)
                     graphs.append(g)
             torch.cuda.synchronize()
-            graph_ms = time_steps(lambda i: graphs[i % len(graphs)].replay(), args.steps, args.warmup)
+            graph_ms, graph_ev_ms = time_steps(lambda i: graphs[i % len(graphs)].replay(), args.steps, args.warmup)
+        if moqe.workspace_error(ws):
+            raise RuntimeError("a phase wait timed out: results invalid")
 
-        # ---- per-kernel time of the dominant kernel (HIP events on the launch stream) ----
-        n_ev = min(args.steps, 200)
-        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n_ev)]
-        segs = []
-        for i in range(8):
-            step(i, stream)
-        torch.cuda.synchronize()
-        for i in range(n_ev):
-            ffn_halves(i, stream, evs[i])
-            if i < len(qls):
-                torch.cuda.synchronize()
-                segs.append(route.seg_offsets.cpu().numpy().copy())
-        torch.cuda.synchronize()
-        t1 = np.array([e[0].elapsed_time(e[1]) for e in evs]) * 1e-3
-        t2 = np.array([e[1].elapsed_time(e[2]) for e in evs]) * 1e-3
-        ab = [algorithmic_bytes(s, b, d, f, T) for s in segs]
-        by1 = np.array([ab[i % len(qls)][1] for i in range(n_ev)], dtype=np.float64)
-        by2 = np.array([ab[i % len(qls)][2] for i in range(n_ev)], dtype=np.float64)
-        launches = 2 * n_ev
-        kern_s = float((t1.sum() + t2.sum()) / launches)
-        kern_bytes = float((by1.sum() + by2.sum()) / launches)
-        achieved = kern_bytes / kern_s / 1e9
+        # One step is one launch of the decode kernel (router, FFN1 and FFN2 are its phases), so
+        # the kernel's average duration is the event time per step of the eager loop.
+        layer_bytes = float(np.mean([a[1] + a[2] for a in ab])) + 2 * d * E
+        kern_s = eager_ev_ms * 1e-3
+        achieved = layer_bytes / kern_s / 1e9
         best_ms = min(eager_ms, graph_ms) if graph_ms is not None else eager_ms
         results[b] = dict(
             ms_per_step=best_ms, eager_ms=eager_ms, graph_ms=graph_ms, tokens_per_s=T / (best_ms * 1e-3),
-            active_experts=float(np.mean([a[0] for a in ab])), layer_bytes=float(np.mean([a[1] + a[2] for a in ab])),
-            kernel_us=kern_s * 1e6, kernel_bytes=kern_bytes, achieved_gbs=achieved,
-            ffn1_us=float(t1.mean() * 1e6), ffn2_us=float(t2.mean() * 1e6),
-            step_gbs=float(np.mean([a[1] + a[2] for a in ab])) / (best_ms * 1e-3) / 1e9)
-        print(f"[bench] int{b}: eager {eager_ms * 1e3:.1f} us/step, graph "
-              f"{(graph_ms or float('nan')) * 1e3:.1f} us/step, ffn kernels {t1.mean() * 1e6:.1f} + {t2.mean() * 1e6:.1f} us, "
-              f"{achieved:.0f} GB/s", file=sys.stderr, flush=True)
+            active_experts=float(np.mean([a[0] for a in ab])), layer_bytes=layer_bytes,
+            kernel_us=kern_s * 1e6, kernel_bytes=layer_bytes, achieved_gbs=achieved,
+            eager_event_ms=eager_ev_ms, graph_event_ms=graph_ev_ms,
+            step_gbs=layer_bytes / (best_ms * 1e-3) / 1e9)
+        print(f"[bench] int{b}: eager {eager_ms * 1e3:.1f} us/step (events {eager_ev_ms * 1e3:.1f}), graph "
+              f"{(graph_ms or float('nan')) * 1e3:.1f} us/step, {achieved:.0f} GB/s over {layer_bytes / 1e6:.1f} MB",
+              file=sys.stderr, flush=True)
 
     # ---- CPU oracle on the host cores: bounded sample of the same workload ----
     cpu = None
@@ -244,9 +230,8 @@ def main():
                    "step_gb_per_s": r["step_gbs"]},
         "roofline": {"bound": "hbm", "achieved": r["achieved_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": r["achieved_gbs"] / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(args.bits),
-                     "kernel": "ffn_decode_kernel<%d,32>" % args.bits, "avg_kernel_us": r["kernel_us"],
-                     "algorithmic_bytes_per_launch": r["kernel_bytes"],
-                     "ffn1_us": r["ffn1_us"], "ffn2_us": r["ffn2_us"]},
+                     "kernel": "moe_decode_kernel<%d,32>" % args.bits, "avg_kernel_us": r["kernel_us"],
+                     "algorithmic_bytes_per_launch": r["kernel_bytes"]},
         "cpu_baseline": cpu,
     }
     if len(results) > 1:

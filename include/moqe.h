@@ -72,6 +72,16 @@ const char* moqe_last_hip_error(void);
 /* ABI version, currently 1. */
 int moqe_version(void);
 
+/* How moqe_expert_ffn and moqe_moe_layer issue their work (a process-wide setting, for
+ * tuning and tests; results are identical in every mode):
+ *   AUTO      moqe_moe_layer uses one launch for router + FFN1 + FFN2 when the shapes allow
+ *             it, moqe_expert_ffn one launch per contraction
+ *   SEPARATE  always one launch per step of the path
+ *   FUSED     one launch for as much as the shapes allow (moqe_expert_ffn: FFN1 + FFN2)
+ * Returns the previous mode, or -1 (and changes nothing) for an unknown mode. */
+enum { MOQE_LAUNCH_AUTO = 0, MOQE_LAUNCH_SEPARATE = 1, MOQE_LAUNCH_FUSED = 2 };
+int moqe_set_launch_mode(int mode);
+
 /* Bytes of one packed [K,N] matrix = K*N*bits/8 (Table 2: exactly `bits` bits
  * per expert weight).  Returns 0 for an unsupported (bits, K, N). Host only. */
 size_t moqe_packed_bytes(int bits, int64_t K, int64_t N);
@@ -81,9 +91,20 @@ int moqe_check_matrix(int bits, int64_t K, int64_t N);
 int moqe_check_layer(int bits, int64_t E, int64_t d, int64_t f);
 
 /* Scratch sizes (host, pure).  Always > 0 so a caller may allocate blindly.
- * The scratch needs no initialisation. */
+ * The route scratch needs no initialisation.
+ * The FFN / layer scratch carries state from call to call: for decode-sized batches the
+ * router, FFN1 and FFN2 run as phases of one launch and hand their intermediate results
+ * over through it (a launch counter, tagged router results, two alternating buffers for
+ * the hidden activations in which zero means "not written yet").  Fill the WHOLE buffer
+ * with zero once before its first use and always pass the same (pointer, size) pair;
+ * after that any mix of calls and batch sizes may use it, one call at a time (calls that
+ * may run concurrently need scratch buffers of their own).  The 32-bit word at byte 640
+ * is an error flag: it becomes 1 and stays 1 if a wait inside a launch ever timed out
+ * (buffer not zeroed, or the device shared so that the grid was not resident); outputs
+ * are then invalid and the buffer has to be zeroed again. */
 size_t moqe_route_workspace_bytes(int64_t T, int64_t E);
 size_t moqe_ffn_workspace_bytes(int64_t T, int64_t E, int64_t d, int64_t f);
+size_t moqe_layer_workspace_bytes(int64_t T, int64_t E, int64_t d, int64_t f); /* for moqe_moe_layer */
 
 /*
  * Offline round-to-nearest quantization and bit packing of a stack of E
@@ -157,6 +178,19 @@ moqe_status moqe_expert_ffn(const moqe_layer* layer /* host */, const moqe_f16* 
                             const int32_t* seg_offsets, const int32_t* perm,
                             const moqe_f16* residual, moqe_f16* y,
                             void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * One whole MoE layer step: moqe_route followed by moqe_expert_ffn (App. B gating,
+ * Sec. 2.1 FFN) with the same outputs as the two calls.  For decode-sized batches
+ * (T <= 64, E a multiple of 8 and <= 256, d and f giving the same wave slice length)
+ * the router, FFN1 and FFN2 run as phases of ONE kernel launch; otherwise the calls
+ * are issued one after the other.  expert_idx, gate, seg_offsets, perm are outputs.
+ * workspace: moqe_layer_workspace_bytes(T, E, d, f), head zeroed as described above.
+ */
+moqe_status moqe_moe_layer(const moqe_layer* layer /* host */, const moqe_f16* w_gate, const moqe_f16* x,
+                           int64_t T, int32_t* expert_idx, float* gate, int32_t* seg_offsets, int32_t* perm,
+                           const moqe_f16* residual, moqe_f16* y,
+                           void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * The two contractions of moqe_expert_ffn as separate calls, for callers that

@@ -2,6 +2,7 @@
 // Every error is detected before the first launch, so the error paths can be
 // exercised without a GPU.
 #include <limits.h>
+#include <atomic>
 #include <stdio.h>
 #include <string.h>
 
@@ -42,6 +43,8 @@ constexpr int64_t MAX_EXPERTS = 1024;
 
 size_t round256(size_t b) { return b < 256 ? 256 : ((b + 255) & ~(size_t)255); }
 
+std::atomic<int> g_launch_mode{MOQE_LAUNCH_AUTO};
+
 }  // namespace
 
 extern "C" {
@@ -62,6 +65,11 @@ const char* moqe_status_string(int status) {
 const char* moqe_last_hip_error(void) { return g_hip_error; }
 
 int moqe_version(void) { return 1; }
+
+int moqe_set_launch_mode(int mode) {
+  if (mode != MOQE_LAUNCH_AUTO && mode != MOQE_LAUNCH_SEPARATE && mode != MOQE_LAUNCH_FUSED) return -1;
+  return g_launch_mode.exchange(mode);
+}
 
 #ifdef MOQE_PHASE_TRACE
 void moqe_debug_set_trace(long long* p) { g_trace = p; }
@@ -93,11 +101,22 @@ size_t moqe_route_workspace_bytes(int64_t T, int64_t E) {
   return moqe_route_ws_bytes(T, E);
 }
 
+// FFN / layer workspace: [sync words 1024][router results 1024][h buffer 0][h buffer 1]
+// (CHAIN_H_BYTES each, at fixed offsets whatever T is: they carry state from launch to
+// launch), then plain h [T,f] fp16 for the launches that run one contraction each.
+constexpr size_t WS_HEAD = 2048;
+constexpr size_t CHAIN_H_BYTES = 1 << 20;
+
 size_t moqe_ffn_workspace_bytes(int64_t T, int64_t E, int64_t d, int64_t f) {
   (void)E;
   (void)d;
-  if (T < 0 || f < 0) return 256;
-  return round256((size_t)T * (size_t)f * 2);  // h: fp16 [T, f] in sorted-token order
+  size_t base = WS_HEAD + 2 * CHAIN_H_BYTES;
+  if (T < 0 || f < 0) return base;
+  return base + round256((size_t)T * (size_t)f * 2);
+}
+
+size_t moqe_layer_workspace_bytes(int64_t T, int64_t E, int64_t d, int64_t f) {
+  return moqe_ffn_workspace_bytes(T, E, d, f) + moqe_route_workspace_bytes(T, E);
 }
 
 moqe_status moqe_quantize(const float* w, int64_t E, int64_t K, int64_t N, int bits, void* codes_out,
@@ -158,6 +177,11 @@ moqe_status moqe_route_logits(const float* logits, int64_t T, int64_t E, int32_t
                       workspace_bytes, stream);
 }
 
+// ---------------------------------------------------------------------------
+// expert FFN
+// ---------------------------------------------------------------------------
+
+
 static moqe_status check_layer_ptrs(const moqe_layer* L) {
   if (!L) return MOQE_ERR_NULL;
   if (!L->codes1 || !L->scales1 || !L->bias1 || !L->codes2 || !L->scales2 || !L->bias2) return MOQE_ERR_NULL;
@@ -170,13 +194,17 @@ static moqe_status check_layer_ptrs(const moqe_layer* L) {
   return MOQE_OK;
 }
 
-static void base_args(FfnArgs* a, const moqe_layer* L, int64_t T, const int32_t* seg_offsets, const int32_t* perm) {
+// Fills the launch description shared by every FFN entry point; phases are added by the caller.
+static void base_args(DecodeArgs* a, const moqe_layer* L, int64_t T, const int32_t* expert_idx, const float* gate,
+                      const int32_t* seg_offsets, const int32_t* perm) {
   memset(a, 0, sizeof(*a));
   a->bits = L->bits;
   a->E = (int)L->E;
-  a->seg_offsets = seg_offsets;
-  a->perm = perm;
   a->T = (int)T;
+  a->expert_idx = (int*)expert_idx;
+  a->gate = (float*)gate;
+  a->seg_offsets = (int*)seg_offsets;
+  a->perm = (int*)perm;
   a->min_tokens = 1;
   a->max_tokens = INT_MAX;
 #ifdef MOQE_PHASE_TRACE
@@ -184,26 +212,51 @@ static void base_args(FfnArgs* a, const moqe_layer* L, int64_t T, const int32_t*
 #endif
 }
 
+static void set_ffn1(DecodeArgs* a, const moqe_layer* L, const moqe_f16* x, moqe_f16* h, int* ksteps) {
+  PhaseArgs& p = a->ph[0];
+  p.codes = (const uint32_t*)L->codes1;
+  p.scales = L->scales1;
+  p.bias = L->bias1;
+  p.K = (int)L->d;
+  p.N = (int)L->f;
+  moqe_pick_ksplit(L->bits, p.K, ksteps, &p.ksplit);
+  p.mode = 0;
+  p.a = x;
+  p.out = h;
+  p.residual = nullptr;
+}
+
+static void set_ffn2(DecodeArgs* a, const moqe_layer* L, const moqe_f16* h, const moqe_f16* residual, moqe_f16* y,
+                     int* ksteps) {
+  PhaseArgs& p = a->ph[1];
+  p.codes = (const uint32_t*)L->codes2;
+  p.scales = L->scales2;
+  p.bias = L->bias2;
+  p.K = (int)L->f;
+  p.N = (int)L->d;
+  moqe_pick_ksplit(L->bits, p.K, ksteps, &p.ksplit);
+  p.mode = 1;
+  p.a = h;
+  p.out = y;
+  p.residual = residual;
+}
+
+// Unit counts are 32-bit inside the kernel.
+static bool units_fit(int64_t T, int64_t E, int64_t N) { return ((T + 15) / 16 + E) * (N / 16) < (1ll << 31); }
+
 moqe_status moqe_expert_ffn1(const moqe_layer* L, const moqe_f16* x, int64_t T, const int32_t* seg_offsets,
                              const int32_t* perm, moqe_f16* h, void* stream) {
   if (!L || !x || !seg_offsets || !perm || !h) return MOQE_ERR_NULL;
   moqe_status st = check_layer_ptrs(L);
   if (st != MOQE_OK) return st;
-  if (T < 0 || T > MAX_TOKENS) return MOQE_ERR_SHAPE;
+  if (T < 0 || T > MAX_TOKENS || !units_fit(T, L->E, L->f)) return MOQE_ERR_SHAPE;
   if (!aligned16(x) || !aligned16(seg_offsets) || !aligned16(perm) || !aligned16(h)) return MOQE_ERR_ALIGN;
   if (T == 0) return MOQE_OK;
-  FfnArgs a;
-  base_args(&a, L, T, seg_offsets, perm);
-  a.codes = (const uint32_t*)L->codes1;
-  a.scales = L->scales1;
-  a.bias = L->bias1;
-  a.K = (int)L->d;
-  a.N = (int)L->f;
-  moqe_pick_ksplit(a.bits, a.K, &a.ksteps, &a.ksplit);
-  a.a = x;
-  a.h_out = h;
-  a.mode = 0;
-  hipError_t e = moqe_launch_ffn_decode(a, num_cus(), (hipStream_t)stream);
+  DecodeArgs a;
+  base_args(&a, L, T, nullptr, nullptr, seg_offsets, perm);
+  set_ffn1(&a, L, x, h, &a.ksteps);
+  a.phase_mask = 2;
+  hipError_t e = moqe_launch_decode(a, num_cus(), (hipStream_t)stream);
   return e == hipSuccess ? MOQE_OK : hip_fail(e);
 }
 
@@ -213,25 +266,91 @@ moqe_status moqe_expert_ffn2(const moqe_layer* L, const moqe_f16* h, int64_t T, 
   if (!L || !h || !gate || !seg_offsets || !perm || !y) return MOQE_ERR_NULL;
   moqe_status st = check_layer_ptrs(L);
   if (st != MOQE_OK) return st;
-  if (T < 0 || T > MAX_TOKENS) return MOQE_ERR_SHAPE;
+  if (T < 0 || T > MAX_TOKENS || !units_fit(T, L->E, L->d)) return MOQE_ERR_SHAPE;
   if (!aligned16(h) || !aligned16(gate) || !aligned16(seg_offsets) || !aligned16(perm) || !aligned16(y) ||
       (residual && !aligned16(residual)))
     return MOQE_ERR_ALIGN;
   if (T == 0) return MOQE_OK;
-  FfnArgs a;
-  base_args(&a, L, T, seg_offsets, perm);
-  a.gate = gate;
-  a.codes = (const uint32_t*)L->codes2;
-  a.scales = L->scales2;
-  a.bias = L->bias2;
-  a.K = (int)L->f;
-  a.N = (int)L->d;
-  moqe_pick_ksplit(a.bits, a.K, &a.ksteps, &a.ksplit);
-  a.a = h;
-  a.y_out = y;
-  a.residual = residual;
-  a.mode = 1;
-  hipError_t e = moqe_launch_ffn_decode(a, num_cus(), (hipStream_t)stream);
+  DecodeArgs a;
+  base_args(&a, L, T, nullptr, gate, seg_offsets, perm);
+  set_ffn2(&a, L, h, residual, y, &a.ksteps);
+  a.phase_mask = 4;
+  hipError_t e = moqe_launch_decode(a, num_cus(), (hipStream_t)stream);
+  return e == hipSuccess ? MOQE_OK : hip_fail(e);
+}
+
+// Runs FFN1 and FFN2 (and, with w_gate, the router in front of them).  One launch when both
+// contractions use the same wave slice length (and the router fits the kernel's own), else
+// one launch per phase.
+static moqe_status run_layer(const moqe_layer* L, const moqe_f16* w_gate, const moqe_f16* x, int64_t T,
+                             int32_t* expert_idx, float* gate, int32_t* seg_offsets, int32_t* perm,
+                             const moqe_f16* residual, moqe_f16* y, void* workspace, size_t workspace_bytes,
+                             void* stream) {
+  moqe_status st = check_layer_ptrs(L);
+  if (st != MOQE_OK) return st;
+  if (T < 0 || T > MAX_TOKENS || !units_fit(T, L->E, L->f) || !units_fit(T, L->E, L->d)) return MOQE_ERR_SHAPE;
+  if (!aligned16(x) || !aligned16(expert_idx) || !aligned16(gate) || !aligned16(seg_offsets) || !aligned16(perm) ||
+      !aligned16(y) || !aligned16(workspace) || (residual && !aligned16(residual)) ||
+      (w_gate && !aligned16(w_gate)))
+    return MOQE_ERR_ALIGN;
+  const size_t ffn_bytes = moqe_ffn_workspace_bytes(T, L->E, L->d, L->f);
+  const size_t need = w_gate ? moqe_layer_workspace_bytes(T, L->E, L->d, L->f) : ffn_bytes;
+  if (workspace_bytes < need) return MOQE_ERR_WORKSPACE;
+  const size_t h_bytes = (size_t)T * (size_t)L->f * 2;
+  unsigned* sync = (unsigned*)workspace;
+  moqe_f16* h_chain = (moqe_f16*)((char*)workspace + WS_HEAD);
+  moqe_f16* h_plain = (moqe_f16*)((char*)workspace + WS_HEAD + 2 * CHAIN_H_BYTES);
+  void* route_ws = (char*)workspace + ffn_bytes;
+
+  if (T == 0) {
+    if (!w_gate) return MOQE_OK;
+    return moqe_route(x, w_gate, T, L->d, L->E, expert_idx, gate, seg_offsets, perm, route_ws,
+                      workspace_bytes - ffn_bytes, stream);
+  }
+
+  DecodeArgs a;
+  base_args(&a, L, T, expert_idx, gate, seg_offsets, perm);
+  int ks1 = 0, ks2 = 0;
+  set_ffn1(&a, L, x, h_plain, &ks1);
+  set_ffn2(&a, L, h_plain, residual, y, &ks2);
+  // one launch for both contractions when they share the wave slice length and h fits the
+  // chained buffers; the router joins when it fits the kernel's own
+  const int launch_mode = g_launch_mode.load();
+  const bool can_chain = ks1 == ks2 && h_bytes <= CHAIN_H_BYTES;
+  const bool can_fuse_route = w_gate && can_chain && moqe_decode_can_route(T, L->d, L->E);
+  // Measured on the decode workload: the single launch wins when it also replaces the two
+  // router launches; for the contractions alone two launches are as fast or faster.
+  const bool chain = launch_mode == MOQE_LAUNCH_FUSED ? can_chain
+                   : launch_mode == MOQE_LAUNCH_SEPARATE ? false : can_fuse_route;
+  const bool fuse_route = chain && can_fuse_route;
+
+  if (w_gate && !fuse_route) {
+    st = moqe_route(x, w_gate, T, L->d, L->E, expert_idx, gate, seg_offsets, perm, route_ws,
+                    workspace_bytes - ffn_bytes, stream);
+    if (st != MOQE_OK) return st;
+  }
+  hipError_t e;
+  if (chain) {
+    a.ksteps = ks1;
+    a.phase_mask = fuse_route ? 7 : 6;
+    a.x = x;
+    a.w_gate = w_gate;
+    a.d_route = (int)L->d;
+    a.sync = sync;
+    a.route_entries = (unsigned long long*)((char*)workspace + 1024);
+    a.h_base = h_chain;
+    a.h_stride = CHAIN_H_BYTES / 2;
+    a.h_bytes = (unsigned)h_bytes;
+    e = moqe_launch_decode(a, num_cus(), (hipStream_t)stream);
+    return e == hipSuccess ? MOQE_OK : hip_fail(e);
+  }
+  a.ksteps = ks1;
+  a.phase_mask = 2;
+  e = moqe_launch_decode(a, num_cus(), (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e);
+  a.ksteps = ks2;
+  a.phase_mask = 4;
+  e = moqe_launch_decode(a, num_cus(), (hipStream_t)stream);
   return e == hipSuccess ? MOQE_OK : hip_fail(e);
 }
 
@@ -240,19 +359,17 @@ moqe_status moqe_expert_ffn(const moqe_layer* L, const moqe_f16* x, int64_t T, c
                             const moqe_f16* residual, moqe_f16* y, void* workspace, size_t workspace_bytes,
                             void* stream) {
   if (!L || !x || !expert_idx || !gate || !seg_offsets || !perm || !y || !workspace) return MOQE_ERR_NULL;
-  moqe_status st = check_layer_ptrs(L);
-  if (st != MOQE_OK) return st;
-  if (T < 0 || T > MAX_TOKENS) return MOQE_ERR_SHAPE;
-  if (!aligned16(x) || !aligned16(expert_idx) || !aligned16(gate) || !aligned16(seg_offsets) || !aligned16(perm) ||
-      !aligned16(y) || !aligned16(workspace) || (residual && !aligned16(residual)))
-    return MOQE_ERR_ALIGN;
-  if (workspace_bytes < moqe_ffn_workspace_bytes(T, L->E, L->d, L->f)) return MOQE_ERR_WORKSPACE;
-  if (T == 0) return MOQE_OK;
-  // FFN1: h = relu(x W1' + b1), rows in sorted-token order (the workspace)
-  st = moqe_expert_ffn1(L, x, T, seg_offsets, perm, (moqe_f16*)workspace, stream);
-  if (st != MOQE_OK) return st;
-  // FFN2 + bias, gate-weighted combine (+ residual), scattered back to token order
-  return moqe_expert_ffn2(L, (const moqe_f16*)workspace, T, gate, seg_offsets, perm, residual, y, stream);
+  return run_layer(L, nullptr, x, T, (int32_t*)expert_idx, (float*)gate, (int32_t*)seg_offsets, (int32_t*)perm,
+                   residual, y, workspace, workspace_bytes, stream);
+}
+
+moqe_status moqe_moe_layer(const moqe_layer* L, const moqe_f16* w_gate, const moqe_f16* x, int64_t T,
+                           int32_t* expert_idx, float* gate, int32_t* seg_offsets, int32_t* perm,
+                           const moqe_f16* residual, moqe_f16* y, void* workspace, size_t workspace_bytes,
+                           void* stream) {
+  if (!L || !w_gate || !x || !expert_idx || !gate || !seg_offsets || !perm || !y || !workspace) return MOQE_ERR_NULL;
+  return run_layer(L, w_gate, x, T, expert_idx, gate, seg_offsets, perm, residual, y, workspace, workspace_bytes,
+                   stream);
 }
 
 }  // extern "C"

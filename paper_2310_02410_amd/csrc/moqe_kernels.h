@@ -18,32 +18,53 @@ hipError_t moqe_launch_route(const uint16_t* x, const uint16_t* wg, const float*
                              int* expert_idx, float* gate, int* seg_offsets, int* perm, void* ws, hipStream_t stream);
 
 // One contraction of the expert FFN over the routed segments.
-struct FfnArgs {
-  // weights of this contraction: K inputs -> N outputs, E experts
+struct PhaseArgs {
+  // weights of this contraction: K inputs -> N outputs
   const uint32_t* codes;
   const uint16_t* scales;  // [E,N] fp16
   const uint16_t* bias;    // [E,N] fp16
-  int bits, E, K, N;
-  int ksteps;  // 32-row steps one wave keeps in registers
+  int K, N;
   int ksplit;  // waves sharing one output tile along K (K = 32 * ksteps * ksplit)
-  // routing
-  const int* seg_offsets;  // [E+1]
-  const int* perm;         // [T] sorted position -> token
-  const float* gate;       // [T] by token
-  int T;
-  // operands
-  const uint16_t* a;  // mode 0: x [T,K] by token; mode 1: h [T,K] by sorted position
-  uint16_t* h_out;    // mode 0: relu(a W + b) -> [T,N] by sorted position
-  uint16_t* y_out;    // mode 1: gate * (a W + b) (+ residual) -> [T,N] by token
+  int mode;    // 0: rows of `a` by token through perm, out = relu(.) by sorted position
+               // 1: rows of `a` by sorted position, out = gate * (.) (+ residual) by token
+  const uint16_t* a;
+  uint16_t* out;
   const uint16_t* residual;  // mode 1, may be NULL
-  int mode;
+};
+
+// One launch of the decode-step kernel: any of router / FFN1 / FFN2, in that order.
+struct DecodeArgs {
+  int bits, ksteps;  // 32-row steps one wave keeps in registers (same for both contractions)
+  int E, T;
+  int phase_mask;  // bit 0: router, bit 1: FFN1 (ph[0]), bit 2: FFN2 (ph[1])
+  // router inputs (bit 0): x [T,d_route], w_gate [d_route,E]
+  const uint16_t* x;
+  const uint16_t* w_gate;
+  int d_route;
+  // routing tables: written by the router phase, read otherwise
+  int* expert_idx;   // [T]
+  float* gate;       // [T] by token (may be NULL when only FFN1 runs)
+  int* seg_offsets;  // [E+1]
+  int* perm;         // [T] sorted position -> token
+  PhaseArgs ph[2];
   // expert segments with min_tokens <= n < max_tokens are handled, the rest skipped
   int min_tokens, max_tokens;
-  // debug builds (-DMOQE_PHASE_TRACE): 8 wall-clock stamps per workgroup, else unused
+  // Multi-phase launches.  sync: 1024 bytes, zero before the first launch: launch epoch,
+  // start counter, error flag (one word per 128-byte line).  route_entries: two 64-bit words
+  // per token for the router phase.  h_base: two buffers of h_stride fp16 elements each,
+  // zero before the first launch; FFN1 fills one (ph[0].out / ph[1].a are then ignored).
+  unsigned* sync;
+  unsigned long long* route_entries;
+  uint16_t* h_base;
+  size_t h_stride;
+  unsigned h_bytes;  // bytes of h this launch writes (T * f * 2)
+  // debug builds (-DMOQE_PHASE_TRACE): 16 wall-clock stamps per workgroup, else unused
   long long* trace;
 };
 
 // Register-resident dequantize + 16-token MFMA path (few tokens per expert).
-hipError_t moqe_launch_ffn_decode(const FfnArgs& a, int num_cus, hipStream_t stream);
+hipError_t moqe_launch_decode(const DecodeArgs& a, int num_cus, hipStream_t stream);
 // Picks (ksteps, ksplit) for a contraction length K; false if unsupported.
 bool moqe_pick_ksplit(int bits, int64_t K, int* ksteps, int* ksplit);
+// Whether the decode kernel's own router phase can serve these sizes.
+bool moqe_decode_can_route(int64_t T, int64_t d, int64_t E);

@@ -1,0 +1,151 @@
+// Register-level unpacking of the packed 2/3/4-bit codes into fp16 MFMA fragments
+// (device only).  One lane's slot of the packed layout is already in the operand order
+// of v_mfma_f32_16x16x32_f16: lane (g, j) supplies, per 32-row step, the 8 codes
+// k = 32 s + 8 g + 0..7 of output channel j, two per 32-bit register (k even in the low
+// half).  A code field is turned into an fp16 number by OR-ing an exponent pattern onto
+// the masked bits: with exponent 2^e the field bits sit in the mantissa and the value
+// reads base + u (or base + 4 u' for the int3 high plane).  Fields that leave their
+// base in the value are corrected after the K-sum: sum_k a_k (base_k + u_k) minus
+// sum_k a_k (base_k + zero point), the second sum coming from bias_frag().
+#pragma once
+
+#include "moqe_dev.h"
+
+__device__ inline half8_t frag_from_words(uint32_t r0, uint32_t r1, uint32_t r2, uint32_t r3) {
+  uint4_t v = {r0, r1, r2, r3};
+  return __builtin_bit_cast(half8_t, v);
+}
+
+__device__ inline uint32_t pk_sub(uint32_t v, float c) {
+  half2_t h = __builtin_bit_cast(half2_t, v);
+  half2_t k = {(half_t)c, (half_t)c};
+  h = h - k;
+  return __builtin_bit_cast(uint32_t, h);
+}
+
+__device__ inline half8_t const_frag(float c0, float c1, float c2, float c3) {
+  half8_t v = {(half_t)c0, (half_t)c0, (half_t)c1, (half_t)c1, (half_t)c2, (half_t)c2, (half_t)c3, (half_t)c3};
+  return v;
+}
+
+// Masks (scalar registers) and fp16 exponent patterns (vector registers; base << 16 | base
+// with a zero mantissa) of the unpack sequences, created once per kernel.
+template <int BITS>
+struct UnpackConsts {
+  uint32_t m_000f, m_00f0;                  // int4 nibble masks
+  uint32_t m_0030, m_00c0, m_0300;          // 2-bit field masks at bits 4, 6, 8
+  uint32_t m_0040, m_0080, m_0100, m_0200;  // single-bit masks at bits 6..9 (int3 high plane)
+  uint32_t x1024, x64, x32, x16, x8, x4;    // exponent patterns
+  __device__ inline void init() {
+    if (BITS == 4) {
+      m_000f = opaque_sgpr(0x000F000Fu);
+      m_00f0 = opaque_sgpr(0x00F000F0u);
+      x1024 = opaque_vgpr(0x64006400u);
+      x64 = opaque_vgpr(0x54005400u);
+    } else {
+      m_0030 = opaque_sgpr(0x00300030u);
+      m_00c0 = opaque_sgpr(0x00C000C0u);
+      m_0300 = opaque_sgpr(0x03000300u);
+      x64 = opaque_vgpr(0x54005400u);
+      x16 = opaque_vgpr(0x4C004C00u);
+      x4 = opaque_vgpr(0x44004400u);
+    }
+    if (BITS == 3) {
+      m_0040 = opaque_sgpr(0x00400040u);
+      m_0080 = opaque_sgpr(0x00800080u);
+      m_0100 = opaque_sgpr(0x01000100u);
+      m_0200 = opaque_sgpr(0x02000200u);
+      x32 = opaque_vgpr(0x50005000u);
+      x8 = opaque_vgpr(0x48004800u);
+    }
+  }
+};
+
+// ---- int4: one word per step; word bit position of code i (i = k % 8): 16 (i & 1) + 4 (i >> 1).
+// Nibbles at bits 0-3 get base 1024 and are made exact with a packed subtract (a bias that
+// large would cost accuracy if carried through the K-sum); nibbles at bits 4-7 keep base 64
+// and their 64 + 8 is removed after the K-sum like the int2 fields.
+template <class C>
+__device__ inline half8_t unpack4(uint32_t d, const C& c) {
+  uint32_t d8 = d >> 8;
+  uint32_t r0 = pk_sub((d & c.m_000f) | c.x1024, 1032.0f);
+  uint32_t r1 = (d & c.m_00f0) | c.x64;
+  uint32_t r2 = pk_sub((d8 & c.m_000f) | c.x1024, 1032.0f);
+  uint32_t r3 = (d8 & c.m_00f0) | c.x64;
+  return frag_from_words(r0, r1, r2, r3);
+}
+
+// ---- int2: one word per two steps.  Fields are left with their exponent bias
+// (value = base + u); the bias and the zero point are removed after the K-sum
+// through bias_frag(): sum_k a_k (base_k + u_k) - sum_k a_k (base_k + 2).
+// even step: fields at bits 0,2,4,6 of each half; odd step: bits 8,10,12,14.
+template <int PARITY, class C>
+__device__ inline half8_t unpack2(uint32_t d, const C& c) {
+  if (PARITY == 0) {
+    uint32_t dl = d << 4;
+    uint32_t r0 = (dl & c.m_0030) | c.x64;  // bits 0-1 -> 4-5
+    uint32_t r1 = (dl & c.m_00c0) | c.x16;  // bits 2-3 -> 6-7
+    uint32_t r2 = (d & c.m_0030) | c.x64;   // bits 4-5
+    uint32_t r3 = (d & c.m_00c0) | c.x16;   // bits 6-7
+    return frag_from_words(r0, r1, r2, r3);
+  } else {
+    uint32_t dr = d >> 6;
+    uint32_t r0 = (d & c.m_0300) | c.x4;    // bits 8-9
+    uint32_t r1 = (dr & c.m_0030) | c.x64;  // bits 10-11 -> 4-5
+    uint32_t r2 = (dr & c.m_00c0) | c.x16;  // bits 12-13 -> 6-7
+    uint32_t r3 = (dr & c.m_0300) | c.x4;   // bits 14-15 -> 8-9
+    return frag_from_words(r0, r1, r2, r3);
+  }
+}
+
+// ---- int3 high plane: one word per four steps, one bit per code, worth 4.
+// step ss (0..3) owns bits 4 ss .. 4 ss + 3 of each half; they are moved to
+// mantissa bits 6..9 where, with bases 64, 32, 16, 8, a set bit adds exactly 4.
+template <int SS, class C>
+__device__ inline half8_t unpack1x4(uint32_t d, const C& c) {
+  uint32_t v = SS == 0 ? (d << 6) : SS == 1 ? (d << 2) : SS == 2 ? (d >> 2) : (d >> 6);
+  uint32_t r0 = (v & c.m_0040) | c.x64;
+  uint32_t r1 = (v & c.m_0080) | c.x32;
+  uint32_t r2 = (v & c.m_0100) | c.x16;
+  uint32_t r3 = (v & c.m_0200) | c.x8;
+  return frag_from_words(r0, r1, r2, r3);
+}
+
+// Constant B fragment holding, per code position, the amount the unpacked value
+// exceeds the signed code: exponent bias(es) + zero point.
+template <int BITS>
+__device__ inline half8_t bias_frag(int parity) {
+  if (BITS == 4) return const_frag(0, 72, 0, 72);
+  if (BITS == 2) return parity == 0 ? const_frag(66, 18, 66, 18) : const_frag(6, 66, 18, 6);
+  // int3: low-plane bias + high-plane bias + zero point 4
+  return parity == 0 ? const_frag(64 + 64 + 4, 16 + 32 + 4, 64 + 16 + 4, 16 + 8 + 4)
+                     : const_frag(4 + 64 + 4, 64 + 32 + 4, 16 + 16 + 4, 4 + 8 + 4);
+}
+
+template <int BITS, int KSTEPS>
+struct Shape {
+  static constexpr int SCMAX = BITS == 4 ? 4 : 8;
+  static constexpr int SC = KSTEPS < SCMAX ? KSTEPS : SCMAX;  // steps per chunk
+  static constexpr int NCH = KSTEPS / SC;                     // chunks per wave slice
+  static constexpr int LO_BITS = BITS == 3 ? 2 : BITS;
+  static constexpr int LW = SC * LO_BITS / 4;                 // main-plane words per lane per chunk
+  static constexpr int HW = BITS == 3 ? SC / 4 : 0;           // 1-bit-plane words per lane per chunk
+  static constexpr int CHUNK_WORDS = 16 * SC * BITS;          // 64 * SC * BITS / 4
+  static_assert(KSTEPS % SC == 0, "slice must hold whole chunks");
+  static_assert(LW >= 1, "lane owns at least a word");
+  static_assert(BITS != 3 || HW >= 1, "int3 needs 4 steps per chunk");
+};
+
+template <int N>
+__device__ inline void load_words(const uint32_t* p, uint32_t* dst) {
+  if (N == 4) {
+    uint4_t v = __builtin_nontemporal_load((const uint4_t*)p);
+    dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+  } else if (N == 2) {
+    uint2_t v = __builtin_nontemporal_load((const uint2_t*)p);
+    dst[0] = v.x; dst[1] = v.y;
+  } else {
+    dst[0] = __builtin_nontemporal_load(p);
+  }
+}
+

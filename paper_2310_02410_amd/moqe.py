@@ -25,7 +25,10 @@ EXPORTS = (
     "moqe_check_matrix", "moqe_check_layer", "moqe_route_workspace_bytes",
     "moqe_ffn_workspace_bytes", "moqe_quantize", "moqe_unpack", "moqe_route",
     "moqe_route_logits", "moqe_expert_ffn", "moqe_expert_ffn1", "moqe_expert_ffn2",
+    "moqe_layer_workspace_bytes", "moqe_moe_layer", "moqe_set_launch_mode",
 )
+
+LAUNCH_AUTO, LAUNCH_SEPARATE, LAUNCH_FUSED = 0, 1, 2
 
 
 class MoqeError(RuntimeError):
@@ -63,6 +66,8 @@ def lib() -> ctypes.CDLL:
     L.moqe_last_hip_error.restype = ctypes.c_char_p
     L.moqe_last_hip_error.argtypes = []
     L.moqe_version.restype = ci
+    L.moqe_set_launch_mode.restype = ci
+    L.moqe_set_launch_mode.argtypes = [ci]
     L.moqe_packed_bytes.restype = sz
     L.moqe_packed_bytes.argtypes = [ci, i64, i64]
     L.moqe_check_matrix.restype = ci
@@ -73,6 +78,10 @@ def lib() -> ctypes.CDLL:
     L.moqe_route_workspace_bytes.argtypes = [i64, i64]
     L.moqe_ffn_workspace_bytes.restype = sz
     L.moqe_ffn_workspace_bytes.argtypes = [i64, i64, i64, i64]
+    L.moqe_layer_workspace_bytes.restype = sz
+    L.moqe_layer_workspace_bytes.argtypes = [i64, i64, i64, i64]
+    L.moqe_moe_layer.restype = ci
+    L.moqe_moe_layer.argtypes = [ctypes.POINTER(CLayer), vp, vp, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.moqe_quantize.restype = ci
     L.moqe_quantize.argtypes = [vp, i64, i64, i64, ci, vp, vp, vp]
     L.moqe_unpack.restype = ci
@@ -125,6 +134,23 @@ def moqe_route_workspace_bytes(T: int, E: int) -> int:
 
 def moqe_ffn_workspace_bytes(T: int, E: int, d: int, f: int) -> int:
     return lib().moqe_ffn_workspace_bytes(T, E, d, f)
+
+
+def moqe_layer_workspace_bytes(T: int, E: int, d: int, f: int) -> int:
+    return lib().moqe_layer_workspace_bytes(T, E, d, f)
+
+
+def moqe_set_launch_mode(mode: int) -> int:
+    """Process-wide launch policy (LAUNCH_AUTO / LAUNCH_SEPARATE / LAUNCH_FUSED); returns the old one."""
+    old = lib().moqe_set_launch_mode(mode)
+    if old < 0:
+        raise ValueError(f"unknown launch mode {mode}")
+    return old
+
+
+def alloc_workspace(nbytes: int, device) -> torch.Tensor:
+    """FFN / layer scratch: its head holds the inter-phase counters and must start zeroed."""
+    return torch.zeros(nbytes, dtype=torch.uint8, device=device)
 
 
 # ---------------------------------------------------------------------------
@@ -242,8 +268,7 @@ def moqe_expert_ffn(layer: QuantLayer, x: torch.Tensor, route: Route, residual: 
     if out is None:
         out = torch.empty_like(x)
     if workspace is None:
-        workspace = torch.empty(moqe_ffn_workspace_bytes(T, layer.E, layer.d, layer.f), dtype=torch.uint8,
-                                device=x.device)
+        workspace = alloc_workspace(moqe_ffn_workspace_bytes(T, layer.E, layer.d, layer.f), x.device)
     cl = layer.c_struct()
     _check(lib().moqe_expert_ffn(ctypes.byref(cl), x.data_ptr(), T, _ptr(route.expert_idx), _ptr(route.gate),
                                  route.seg_offsets.data_ptr(), _ptr(route.perm), _ptr(residual), out.data_ptr(),
@@ -267,3 +292,30 @@ def moqe_expert_ffn2(layer: QuantLayer, h: torch.Tensor, route: Route, out: torc
                                   route.seg_offsets.data_ptr(), _ptr(route.perm), _ptr(residual), out.data_ptr(),
                                   _stream(stream)), "moqe_expert_ffn2")
     return out
+
+
+def moqe_moe_layer(layer: QuantLayer, x: torch.Tensor, residual: torch.Tensor = None, out: torch.Tensor = None,
+                   route: Route = None, workspace: torch.Tensor = None, stream=None):
+    """Route with layer.w_gate, then the expert FFN: one call (one launch for decode-sized
+    batches).  Returns (y fp16 [T,d], Route)."""
+    _dev(x, torch.float16, "x")
+    T, d = x.shape
+    if layer.w_gate is None:
+        raise ValueError("layer has no router weights")
+    if out is None:
+        out = torch.empty_like(x)
+    if route is None:
+        route, _ = alloc_route(T, layer.E, x.device)
+    if workspace is None:
+        workspace = alloc_workspace(moqe_layer_workspace_bytes(T, layer.E, layer.d, layer.f), x.device)
+    cl = layer.c_struct()
+    _check(lib().moqe_moe_layer(ctypes.byref(cl), layer.w_gate.data_ptr(), x.data_ptr(), T, _ptr(route.expert_idx),
+                                _ptr(route.gate), route.seg_offsets.data_ptr(), _ptr(route.perm), _ptr(residual),
+                                out.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream(stream)),
+           "moqe_moe_layer")
+    return out, route
+
+
+def workspace_error(workspace: torch.Tensor) -> bool:
+    """True if a phase wait of a call using this FFN / layer scratch ever timed out."""
+    return bool(workspace[640:644].view(torch.int32).item() != 0)

@@ -33,6 +33,9 @@ def test_every_declared_symbol_is_exported():
 def test_version_and_strings():
     L = moqe.lib()
     assert L.moqe_version() == 1
+    assert L.moqe_set_launch_mode(99) == -1
+    old = L.moqe_set_launch_mode(moqe.LAUNCH_SEPARATE)
+    assert L.moqe_set_launch_mode(old) == moqe.LAUNCH_SEPARATE
     assert L.moqe_status_string(0) == b"MOQE_OK"
     for s in range(1, 7):
         assert L.moqe_status_string(s).decode().startswith(moqe.STATUS_NAMES[s])
@@ -66,8 +69,11 @@ def test_shape_rules():
 
 
 def test_workspace_sizes():
-    assert moqe.moqe_ffn_workspace_bytes(24, 32, 1024, 4096) == 24 * 4096 * 2
-    assert moqe.moqe_ffn_workspace_bytes(0, 32, 1024, 4096) == 256
+    head = 2048 + 2 * (1 << 20)       # counters, router results, the two chained h buffers
+    assert moqe.moqe_ffn_workspace_bytes(24, 32, 1024, 4096) == head + 24 * 4096 * 2
+    assert moqe.moqe_ffn_workspace_bytes(0, 32, 1024, 4096) == head + 256
+    assert moqe.moqe_ffn_workspace_bytes(4096, 32, 1024, 4096) == head + 4096 * 4096 * 2
+    assert moqe.moqe_layer_workspace_bytes(24, 32, 1024, 4096) == head + 24 * 4096 * 2 + 256
     assert moqe.moqe_route_workspace_bytes(24, 32) == 256
     assert moqe.moqe_route_workspace_bytes(1 << 20, 128) >= (1 << 20) // 64 * 128 * 4
 
@@ -111,7 +117,7 @@ def test_expert_ffn_error_paths():
         base.update(kw)
         return moqe.CLayer(*[base[k] for k, _ in moqe.CLayer._fields_])
 
-    def call(lay, x=P, T=8, idx=P, gate=P, seg=P, perm=P, res=None, y=P, ws=P, wsb=1 << 20):
+    def call(lay, x=P, T=8, idx=P, gate=P, seg=P, perm=P, res=None, y=P, ws=P, wsb=1 << 24):
         return L.moqe_expert_ffn(ctypes.byref(lay) if lay is not None else None, x, T, idx, gate, seg, perm, res, y,
                                  ws, wsb, None)
 
@@ -125,8 +131,22 @@ def test_expert_ffn_error_paths():
     assert call(layer(), T=-2) == 3
     assert call(layer(scales1=P + 8)) == 4
     assert call(layer(), res=P + 2) == 4
-    assert call(layer(), wsb=100) == 5
+    assert call(layer(), wsb=1 << 20) == 5
     assert call(layer(), T=0) == 0          # no tokens: valid no-op, nothing launched
+
+    def fused(lay, wg=P, x=P, T=8, idx=P, gate=P, seg=P, perm=P, res=None, y=P, ws=P, wsb=1 << 24):
+        return L.moqe_moe_layer(ctypes.byref(lay) if lay is not None else None, wg, x, T, idx, gate, seg, perm, res,
+                                y, ws, wsb, None)
+
+    assert fused(None) == 1
+    assert fused(layer(), wg=0) == 1
+    assert fused(layer(), seg=0) == 1
+    assert fused(layer(bits=5)) == 2
+    assert fused(layer(f=100)) == 3
+    assert fused(layer(), wg=P + 2) == 4
+    assert fused(layer(), wsb=moqe.moqe_ffn_workspace_bytes(8, 4, 64, 256)) == 5   # route scratch missing
+    assert L.moqe_expert_ffn1(ctypes.byref(layer()), P, 8, P, P, 0, None) == 1
+    assert L.moqe_expert_ffn2(ctypes.byref(layer()), P, 8, P, P, P, None, P + 4, None) == 4
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):

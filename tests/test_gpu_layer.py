@@ -1,0 +1,149 @@
+"""GPU parity of moqe_moe_layer (router + expert FFN in one call, one launch for
+decode-sized batches) against the oracle and against the separate calls."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import moqe_oracle as O
+from paper_2310_02410_amd import moqe, workloads as W
+from tests.helpers import (FFN_TOL, assert_route_equal, dev, ffn_error, gpu_quantize_layer, oracle_layer_output,
+                           route_to_numpy)
+
+pytestmark = pytest.mark.gpu
+
+
+def _layer_case(wl, bits, residual=False, repeats=1):
+    layer, x = W.make_layer(wl), W.make_tokens(wl)
+    ql = gpu_quantize_layer(layer, bits)
+    xd = dev(x)
+    ws = moqe.alloc_workspace(moqe.moqe_layer_workspace_bytes(wl.T, wl.E, wl.d, wl.f), xd.device)
+    for _ in range(repeats):
+        y, r = moqe.moqe_moe_layer(ql, xd, residual=xd if residual else None, workspace=ws)
+    torch.cuda.synchronize()
+    assert not moqe.workspace_error(ws), "a phase wait timed out"
+    got = route_to_numpy(r)
+    assert_route_equal(got, O.route(x, layer["w_gate"]), wl.T, wl.E)
+    ref = oracle_layer_output(x, layer, bits, got[0], got[1].astype(np.float64), residual=residual)
+    err = ffn_error(y.cpu().numpy(), ref)
+    assert err <= FFN_TOL, f"{wl.name} int{bits}: {err:.3e}"
+    # identical to the separate calls, bit for bit
+    r2 = moqe.moqe_route(xd, ql.w_gate)
+    y2 = moqe.moqe_expert_ffn(ql, xd, r2, residual=xd if residual else None)
+    assert np.array_equal(y.cpu().numpy().view(np.uint16), y2.cpu().numpy().view(np.uint16))
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("T", (1, 24, 64))
+def test_fused_small_layer(bits, T):
+    # d=512, f=2048: 16 steps per wave for both contractions -> router, FFN1, FFN2 in one launch
+    _layer_case(W.small(E=8, d=512, f=2048, T=T, seed=31 + T), bits, repeats=3)
+
+
+@pytest.mark.parametrize("bits", (4, 2))
+def test_fused_residual(bits):
+    _layer_case(W.small(E=16, d=512, f=2048, T=24, seed=41), bits, residual=True)
+
+
+@pytest.fixture
+def launch_mode():
+    """Sets the process-wide launch policy for one test and restores it afterwards."""
+    saved = []
+
+    def set_mode(mode):
+        saved.append(moqe.moqe_set_launch_mode(mode))
+
+    yield set_mode
+    if saved:
+        moqe.moqe_set_launch_mode(saved[0])
+
+
+@pytest.mark.parametrize("mode", (moqe.LAUNCH_SEPARATE, moqe.LAUNCH_FUSED))
+@pytest.mark.parametrize("bits", (4, 3, 2))
+def test_forced_launch_modes(launch_mode, mode, bits):
+    """Every launch policy gives the oracle's result; FUSED also chains FFN1 and FFN2 inside
+    moqe_expert_ffn, which the comparison with the separate calls in _layer_case exercises."""
+    launch_mode(mode)
+    _layer_case(W.small(E=8, d=512, f=2048, T=24, seed=61), bits, repeats=3)
+    _layer_case(W.small(E=16, d=512, f=2048, T=150, seed=62), bits, residual=True, repeats=2)
+
+
+def test_launch_modes_agree_bit_for_bit(launch_mode):
+    wl = W.small(E=8, d=512, f=2048, T=33, seed=63)
+    layer, x = W.make_layer(wl), W.make_tokens(wl)
+    ql = gpu_quantize_layer(layer, 4)
+    xd = dev(x)
+    ws = moqe.alloc_workspace(moqe.moqe_layer_workspace_bytes(wl.T, wl.E, wl.d, wl.f), xd.device)
+    outs = []
+    for mode in (moqe.LAUNCH_AUTO, moqe.LAUNCH_SEPARATE, moqe.LAUNCH_FUSED, moqe.LAUNCH_AUTO):
+        launch_mode(mode)
+        y, r = moqe.moqe_moe_layer(ql, xd, workspace=ws)
+        y2 = moqe.moqe_expert_ffn(ql, xd, r, workspace=ws)
+        torch.cuda.synchronize()
+        outs += [y.cpu().numpy().view(np.uint16), y2.cpu().numpy().view(np.uint16)]
+    assert not moqe.workspace_error(ws)
+    for o in outs[1:]:
+        assert np.array_equal(o, outs[0])
+
+
+def test_unfused_fallbacks():
+    _layer_case(W.CONFIGS["c0"], 4)                              # E=4: router kernel pair, 2 and 8 steps
+    _layer_case(W.small(E=8, d=128, f=256, T=100, seed=43), 4)   # T > 64
+    _layer_case(W.small(E=8, d=512, f=2048, T=200, seed=44), 2)  # fused FFN, separate router
+
+
+@pytest.mark.parametrize("name,bits", (("c1", 4), ("c2", 3), ("c2", 2)))
+def test_decode_configs_full_size(name, bits):
+    _layer_case(W.CONFIGS[name], bits, repeats=2)
+
+
+def test_graph_replay_matches_eager():
+    """Capture one layer step in a HIP graph and replay it between eager work."""
+    wl = W.small(E=16, d=512, f=2048, T=24, seed=45)
+    layer, x = W.make_layer(wl), W.make_tokens(wl)
+    ql = gpu_quantize_layer(layer, 4)
+    xd = dev(x)
+    ws = moqe.alloc_workspace(moqe.moqe_layer_workspace_bytes(wl.T, wl.E, wl.d, wl.f), xd.device)
+    route, _ = moqe.alloc_route(wl.T, wl.E, xd.device)
+    y = torch.empty_like(xd)
+    y_eager, _ = moqe.moqe_moe_layer(ql, xd, workspace=ws)
+    torch.cuda.synchronize()
+    ref = y_eager.cpu().numpy().view(np.uint16).copy()
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            moqe.moqe_moe_layer(ql, xd, out=y, route=route, workspace=ws)
+    torch.cuda.synchronize()
+    for i in range(4):
+        y.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(y.cpu().numpy().view(np.uint16), ref), f"replay {i} differs"
+        moqe.moqe_moe_layer(ql, xd, workspace=ws)      # eager work between replays
+        torch.cuda.synchronize()
+    assert not moqe.workspace_error(ws)
+
+
+@pytest.mark.parametrize("mode", (moqe.LAUNCH_AUTO, moqe.LAUNCH_FUSED))
+def test_one_workspace_serves_changing_batch_sizes(launch_mode, mode):
+    """The scratch carries state between launches (epoch, h buffers): batches of different
+    sizes, chained and unchained, must be able to share it in any order."""
+    E, d, f = 8, 512, 2048
+    big = W.small(E=E, d=d, f=f, T=300, seed=51)
+    layer = W.make_layer(big)
+    ql = gpu_quantize_layer(layer, 2)
+    oq = O.quantize_layer(layer, 2)
+    x_all = W.make_tokens(big)
+    launch_mode(mode)
+    ws = moqe.alloc_workspace(moqe.moqe_layer_workspace_bytes(300, E, d, f), "cuda")
+    for T in (24, 64, 1, 300, 7, 64, 24, 300, 24):
+        x = np.ascontiguousarray(x_all[:T])
+        xd = dev(x)
+        y, r = moqe.moqe_moe_layer(ql, xd, workspace=ws)
+        torch.cuda.synchronize()
+        assert not moqe.workspace_error(ws)
+        got = route_to_numpy(r)
+        assert_route_equal(got, O.route(x, layer["w_gate"]), T, E)
+        ref = oracle_layer_output(x, layer, 2, got[0], got[1].astype(np.float64), qlayer=oq)
+        assert ffn_error(y.cpu().numpy(), ref) <= FFN_TOL, f"T={T}"
