@@ -46,7 +46,10 @@ def parse():
     ap.add_argument("--copies", type=int, default=8, help="independent layer copies cycled through")
     ap.add_argument("--other-bits", action="store_true", help="also time the other two bit widths")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-steps", type=int, default=3)
+    ap.add_argument("--cpu-steps", type=int, default=8)
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="also run three plain device-to-device copies of this size first: under "
+                         "rocprofv3 --pmc they give the counter reading of a known amount of traffic")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches only")
     return ap.parse_args()
 
@@ -104,6 +107,14 @@ def main():
         print(f"[bench] layer copy {i + 1}/{args.copies} ready ({time.time() - t0:.0f}s)", file=sys.stderr, flush=True)
     x_host = W.make_tokens(wl)
     x = dev(x_host)
+
+    if args.copy_calibration > 0:
+        src = torch.full((args.copy_calibration << 20,), 7, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     L = moqe.lib()
     route, _ = moqe.alloc_route(T, E, x.device)

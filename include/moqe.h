@@ -74,10 +74,11 @@ int moqe_version(void);
 
 /* How moqe_expert_ffn and moqe_moe_layer issue their work (a process-wide setting, for
  * tuning and tests; results are identical in every mode):
- *   AUTO      moqe_moe_layer uses one launch for router + FFN1 + FFN2 when the shapes allow
- *             it, moqe_expert_ffn one launch per contraction
- *   SEPARATE  always one launch per step of the path
- *   FUSED     one launch for as much as the shapes allow (moqe_expert_ffn: FFN1 + FFN2)
+ *   AUTO      whatever measured fastest on the decode workload (currently SEPARATE)
+ *   SEPARATE  one launch per step of the path (router scores, router tables, FFN1, FFN2)
+ *   FUSED     one launch for as much as the shapes allow: FFN1 + FFN2 when both contractions
+ *             use the same wave slice length and h fits the chained buffers (T*f*2 <= 1 MiB),
+ *             plus the router in moqe_moe_layer when T <= 64, E <= 256 and E % 8 == 0
  * Returns the previous mode, or -1 (and changes nothing) for an unknown mode. */
 enum { MOQE_LAUNCH_AUTO = 0, MOQE_LAUNCH_SEPARATE = 1, MOQE_LAUNCH_FUSED = 2 };
 int moqe_set_launch_mode(int mode);
@@ -92,7 +93,7 @@ int moqe_check_layer(int bits, int64_t E, int64_t d, int64_t f);
 
 /* Scratch sizes (host, pure).  Always > 0 so a caller may allocate blindly.
  * The route scratch needs no initialisation.
- * The FFN / layer scratch carries state from call to call: for decode-sized batches the
+ * The FFN / layer scratch carries state from call to call: in FUSED launch mode the
  * router, FFN1 and FFN2 run as phases of one launch and hand their intermediate results
  * over through it (a launch counter, tagged router results, two alternating buffers for
  * the hidden activations in which zero means "not written yet").  Fill the WHOLE buffer
@@ -181,10 +182,8 @@ moqe_status moqe_expert_ffn(const moqe_layer* layer /* host */, const moqe_f16* 
 
 /*
  * One whole MoE layer step: moqe_route followed by moqe_expert_ffn (App. B gating,
- * Sec. 2.1 FFN) with the same outputs as the two calls.  For decode-sized batches
- * (T <= 64, E a multiple of 8 and <= 256, d and f giving the same wave slice length)
- * the router, FFN1 and FFN2 run as phases of ONE kernel launch; otherwise the calls
- * are issued one after the other.  expert_idx, gate, seg_offsets, perm are outputs.
+ * Sec. 2.1 FFN) with the same outputs as the two calls; how many launches it takes is
+ * governed by moqe_set_launch_mode.  expert_idx, gate, seg_offsets, perm are outputs.
  * workspace: moqe_layer_workspace_bytes(T, E, d, f), head zeroed as described above.
  */
 moqe_status moqe_moe_layer(const moqe_layer* layer /* host */, const moqe_f16* w_gate, const moqe_f16* x,

@@ -242,7 +242,7 @@ static void set_ffn2(DecodeArgs* a, const moqe_layer* L, const moqe_f16* h, cons
 }
 
 // Unit counts are 32-bit inside the kernel.
-static bool units_fit(int64_t T, int64_t E, int64_t N) { return ((T + 15) / 16 + E) * (N / 16) < (1ll << 31); }
+static bool units_fit(int64_t T, int64_t E, int64_t N) { return ((T + 3) / 4 + E) * (N / 16) < (1ll << 31); }
 
 moqe_status moqe_expert_ffn1(const moqe_layer* L, const moqe_f16* x, int64_t T, const int32_t* seg_offsets,
                              const int32_t* perm, moqe_f16* h, void* stream) {
@@ -318,10 +318,10 @@ static moqe_status run_layer(const moqe_layer* L, const moqe_f16* w_gate, const 
   const int launch_mode = g_launch_mode.load();
   const bool can_chain = ks1 == ks2 && h_bytes <= CHAIN_H_BYTES;
   const bool can_fuse_route = w_gate && can_chain && moqe_decode_can_route(T, L->d, L->E);
-  // Measured on the decode workload: the single launch wins when it also replaces the two
-  // router launches; for the contractions alone two launches are as fast or faster.
-  const bool chain = launch_mode == MOQE_LAUNCH_FUSED ? can_chain
-                   : launch_mode == MOQE_LAUNCH_SEPARATE ? false : can_fuse_route;
+  // Measured on the decode workload, one launch per step of the path is as fast as the
+  // single launch or faster (the phases of the single launch wait for each other through
+  // memory, which costs about what the extra launches cost), so AUTO takes separate launches.
+  const bool chain = launch_mode == MOQE_LAUNCH_FUSED && can_chain;
   const bool fuse_route = chain && can_fuse_route;
 
   if (w_gate && !fuse_route) {

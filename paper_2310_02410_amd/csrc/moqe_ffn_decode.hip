@@ -7,12 +7,14 @@
 // multiplies the finished K-sum because it does not depend on k; App. B top-1 gating).
 //
 // Work decomposition of one contraction
-//   pair  = (expert e, tile of 16 routed tokens of e)       P pairs, found on device
+//   pair  = (expert e, tile of 4 routed tokens of e)        P pairs, found on device
 //   unit  = (pair, column tile of 16 output channels)       U = P * N/16
-//   team  = `ksplit` waves of a workgroup sharing one unit along K; each wave keeps its
-//           K-slice (32*KSTEPS rows) of the 16 token rows in registers as MFMA A-fragments
-//           and streams the unit's packed codes with 16-byte loads, two units in flight,
-//           refilled chunk by chunk as they are consumed.
+//   team  = `ksplit` waves of a workgroup sharing one unit along K; each wave parks its
+//           K-slice (32*KSTEPS columns) of the pair's token rows in LDS, reads one MFMA
+//           A-fragment per step from there (rows 4..15 of the fragment come from a row of
+//           zeros) and streams the unit's packed codes with 16-byte loads, two units in
+//           flight, refilled chunk by chunk as they are consumed.  Keeping the rows out of
+//           the register file is what lets three waves share a SIMD without spilling.
 //   Units are split evenly over the persistent grid; inside a workgroup the teams take
 //   them round-robin.  Codes go straight from registers into v_mfma_f32_16x16x32_f16 as
 //   the B operand (16 channels x 32 rows); see moqe_unpack.h.
@@ -35,7 +37,7 @@
 #endif
 
 #ifndef MOQE_MIN_WAVES
-#define MOQE_MIN_WAVES 2  // waves per SIMD the register budget is sized for
+#define MOQE_MIN_WAVES 3  // waves per SIMD the register and LDS budgets are sized for
 #endif
 
 namespace {
@@ -43,7 +45,8 @@ namespace {
 constexpr int WG_THREADS = 256;
 constexpr int WG_WAVES = 4;
 constexpr int MAX_E = 1024;
-constexpr int LDS_TOKENS = 1024;       // perm and gate are staged in LDS up to this many tokens
+constexpr int LDS_TOKENS = 256;         // perm and gate are staged in LDS up to this many tokens
+constexpr int TILE_ROWS = 4;            // token rows of a pair (the MFMA's other 12 rows are zero)
 constexpr int FUSED_ROUTE_TOKENS = 64;  // the in-kernel router handles one wave of tokens
 constexpr unsigned SPIN_LIMIT = 1u << 18;
 // Sync words of the workspace head: launch epoch, start counter, bytes of h the last writer
@@ -62,8 +65,10 @@ struct UnitBuf {
 // except sc/bi, which belong to the lane's output channel).
 struct UnitMeta {
   int pair, col, e;
-  uint16_t sc, bi;  // fp16 scale and bias of the lane's channel, untouched until the epilogue
-  bool active;
+  const uint32_t* cp;  // first packed word of this wave's K-slice of the unit
+  uint16_t sc, bi;     // fp16 scale and bias of the lane's channel, untouched until the epilogue
+  bool active;         // an inactive unit has cp == nullptr and loads nothing
+  int phase;
 };
 
 // Lanes holding the same key, as a 64-bit mask (nb = number of key bits).
@@ -110,19 +115,25 @@ __global__ __launch_bounds__(WG_THREADS, MOQE_MIN_WAVES) void moe_decode_kernel(
   const int phase_mask = PM ? PM : A.phase_mask;
   using S = Shape<BITS, KSTEPS>;
   using Buf = UnitBuf<BITS, KSTEPS>;
-  constexpr int STAGE_ROWS = 4;               // pairs with at most this many rows stage them in LDS
   constexpr int ROW_PIECES = KSTEPS * 4 + 4;  // 16-byte pieces per staged row slice, padded by 64 bytes
+  constexpr int ZERO_ROW = WG_WAVES * TILE_ROWS;
 
   __shared__ int s_seg[MAX_E + 1];  // seg_offsets
-  __shared__ int s_incl[MAX_E];     // inclusive prefix of token tiles per expert (E > 64 only)
   __shared__ int s_perm[LDS_TOKENS];
   __shared__ float s_gate[LDS_TOKENS];
-  __shared__ float4_t s_red[2][WG_WAVES][64];
-  __shared__ uint4_t s_x[WG_WAVES][STAGE_ROWS][ROW_PIECES];
-  __shared__ float s_route[WG_WAVES + 1][256];  // router: per-wave partial logits, then the logits
-  constexpr int STASH_UNITS = 4;                // finished units a wave parks before writing them out
-  __shared__ float4_t s_out[WG_WAVES][STASH_UNITS][64];
+  __shared__ float4_t s_red[2][WG_WAVES][16];
+  // token rows: TILE_ROWS per wave, then one row of zeros for the unused rows of a fragment
+  __shared__ uint4_t s_x[WG_WAVES * TILE_ROWS + 1][ROW_PIECES];
+  // router: per-wave partial logits, then the logits; afterwards (E > 64 only) the inclusive
+  // prefix of token tiles per expert
+  __shared__ float4_t s_multi[(WG_WAVES + 1) * 256 / 4];
+  float(*const s_route)[256] = reinterpret_cast<float(*)[256]>(s_multi);
+  int* const s_incl = reinterpret_cast<int*>(s_multi);
+  static_assert(sizeof(s_multi) >= MAX_E * sizeof(int), "prefix table does not fit");
+  constexpr int STASH_UNITS = 4;  // finished units a wave parks before writing them out
+  __shared__ float4_t s_out[WG_WAVES][STASH_UNITS][16];
   __shared__ int s_ometa[WG_WAVES][STASH_UNITS][4];
+  __shared__ int s_share[2][4];  // per contraction: this workgroup's first unit, end, iterations
 
   STAMP(0);
   UnpackConsts<BITS> uc;
@@ -322,7 +333,7 @@ __global__ __launch_bounds__(WG_THREADS, MOQE_MIN_WAVES) void moe_decode_kernel(
   if (small_e) {
     if (lane < E) {
       const int n = s_seg[lane + 1] - s_seg[lane];
-      my_tiles = (n >= A.min_tokens && n < A.max_tokens) ? (n + 15) >> 4 : 0;
+      my_tiles = (n >= A.min_tokens && n < A.max_tokens) ? (n + TILE_ROWS - 1) / TILE_ROWS : 0;
     }
     my_incl = my_tiles;
     for (int off = 1; off < 64; off <<= 1) {
@@ -338,7 +349,7 @@ __global__ __launch_bounds__(WG_THREADS, MOQE_MIN_WAVES) void moe_decode_kernel(
         int v = 0;
         if (e < E) {
           const int n = s_seg[e + 1] - s_seg[e];
-          v = (n >= A.min_tokens && n < A.max_tokens) ? (n + 15) >> 4 : 0;
+          v = (n >= A.min_tokens && n < A.max_tokens) ? (n + TILE_ROWS - 1) / TILE_ROWS : 0;
         }
         for (int off = 1; off < 64; off <<= 1) {
           const int o = __shfl_up(v, off, 64);
@@ -365,9 +376,69 @@ __global__ __launch_bounds__(WG_THREADS, MOQE_MIN_WAVES) void moe_decode_kernel(
     return uniform_i32(lo);
   };
 
-  half8_t xf[KSTEPS];
-  const uint32_t lane_lo = (uint32_t)lane * S::LW, lane_hi = 64u * S::LW + (uint32_t)lane * S::HW;
+  // the row of zeros, and this workgroup's share of each contraction's units
+  for (int q = tid; q < ROW_PIECES; q += WG_THREADS) s_x[ZERO_ROW][q] = uint4_t{0, 0, 0, 0};
+  if (tid < 2) {
+    const int teams = WG_WAVES / max(1, A.ph[tid].ksplit);
+    const int U = P * (A.ph[tid].N >> 4);
+    const int ubase = U / G, urem = U - ubase * G;
+    const int u_begin = bid * ubase + min(bid, urem);
+    const int u_end = u_begin + ubase + (bid < urem ? 1 : 0);
+    s_share[tid][0] = u_begin;
+    s_share[tid][1] = u_end;
+    s_share[tid][2] = (phase_mask & (2 << tid)) ? (u_end - u_begin + teams - 1) / teams : 0;
+  }
+  __syncthreads();
+
   int par = 0;
+
+  // ---- the stream of units ----
+  // Unit `it` of contraction `phz` as this wave sees it.  (Fetching a wave's first FFN2 units
+  // while it still works on FFN1 was tried and lost: FFN2 cannot start before the slowest
+  // FFN1 unit of its pair has delivered h, and the early FFN2 requests queue in front of
+  // other waves' FFN1 requests.)
+  auto make_meta = [&](int phz, int it) -> UnitMeta {
+    UnitMeta m;
+    m.active = false;
+    m.pair = 0; m.col = 0; m.e = 0; m.sc = 0; m.bi = 0; m.cp = nullptr;
+    m.phase = phz;
+    const PhaseArgs& p = A.ph[phz];
+    const int ksplit = p.ksplit, N = p.N, K = p.K;
+    const int teams = WG_WAVES / ksplit, team = wave / ksplit, ks = wave % ksplit;
+    const int u = uniform_i32(s_share[m.phase][0]) + it * teams + team;
+    m.active = (it < uniform_i32(s_share[m.phase][2])) && (u < uniform_i32(s_share[m.phase][1]));
+    const half_t *scales = nullptr, *bias = nullptr;
+    if (m.active) {
+      const int CT = N >> 4;
+      m.pair = u / CT;
+      m.col = u - m.pair * CT;
+      m.e = expert_of(m.pair);
+      scales = (const half_t*)p.scales + (int64_t)m.e * N;
+      bias = (const half_t*)p.bias + (int64_t)m.e * N;
+      const int Q = K / (32 * S::SC);  // chunks per column tile
+      const int64_t matrix_words = (int64_t)K * N * BITS / 32;
+      m.cp = p.codes + (int64_t)m.e * matrix_words + ((int64_t)m.col * Q + ks * S::NCH) * S::CHUNK_WORDS;
+    }
+    // issued whether or not the unit exists (an empty descriptor loads nothing)
+    const uint32_t ch_off = (uint32_t)(16 * m.col + j) * 2u;
+    const uint32_t row_bytes = m.active ? (uint32_t)N * 2u : 0u;
+    m.sc = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(make_rsrc(scales, row_bytes), ch_off, 0, 0);
+    m.bi = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(make_rsrc(bias, row_bytes), ch_off, 0, 0);
+    return m;
+  };
+  constexpr uint32_t UNIT_BYTES = S::NCH * S::CHUNK_WORDS * 4;
+  const uint32_t lane_lo = (uint32_t)lane * S::LW * 4, lane_hi = (64u * S::LW + (uint32_t)lane * S::HW) * 4;
+  auto unit_rsrc = [&](const UnitMeta& m) -> rsrc_t { return make_rsrc(m.cp, m.active ? UNIT_BYTES : 0u); };
+  auto issue_chunk = [&](Buf& b, rsrc_t r, int ch) {
+    load_words<S::LW>(r, lane_lo + ch * S::CHUNK_WORDS * 4, &b.lo[ch * S::LW]);
+    if constexpr (BITS == 3) load_words<S::HW>(r, lane_hi + ch * S::CHUNK_WORDS * 4, &b.hi[ch * S::HW]);
+  };
+  auto issue_unit = [&](Buf& b, const UnitMeta& m) {
+    const rsrc_t r = unit_rsrc(m);
+#pragma unroll
+    for (int ch = 0; ch < S::NCH; ++ch) issue_chunk(b, r, ch);
+  };
+  Buf bufA, bufB;  // two register buffers, refilled chunk by chunk
 
   // =========================== the contractions ===========================
   for (int phase = 0; phase < 2; ++phase) {
@@ -379,55 +450,17 @@ __global__ __launch_bounds__(WG_THREADS, MOQE_MIN_WAVES) void moe_decode_kernel(
     const bool consumes_h = chained && phase == 1;  // input rows are written by workgroups of this launch
     const uint16_t* const a_rows = consumes_h ? h_cur : ph.a;
     uint16_t* const out_rows = produces_h ? h_cur : ph.out;
-
-    // ---- this workgroup's share of the units, teams take them round-robin ----
-    const int CT = N >> 4;
-    const int U = P * CT;
-    const int teams = WG_WAVES / ksplit;
-    const int team = wave / ksplit;
     const int ks = wave % ksplit;
-    const int ubase = U / G, urem = U - ubase * G;
-    const int u_begin = bid * ubase + min(bid, urem);
-    const int u_end = u_begin + ubase + (bid < urem ? 1 : 0);
-    const int nloop = (u_end - u_begin + teams - 1) / teams;
-    const int Q = K / (32 * S::SC);  // chunks per column tile
-    const int64_t matrix_words = (int64_t)K * N * BITS / 32;
-
-    auto make_meta = [&](int it) -> UnitMeta {
-      UnitMeta m;
-      const int u = u_begin + it * teams + team;
-      m.active = (it < nloop) && (u < u_end);
-      m.pair = 0; m.col = 0; m.e = 0; m.sc = 0; m.bi = 0;
-      if (m.active) {
-        m.pair = u / CT;
-        m.col = u - m.pair * CT;
-        m.e = expert_of(m.pair);
-        const uint32_t ch_off = (uint32_t)(16 * m.col + j);
-        m.sc = (ph.scales + (int64_t)m.e * N)[ch_off];
-        m.bi = (ph.bias + (int64_t)m.e * N)[ch_off];
-      }
-      return m;
-    };
-    auto chunk_ptr = [&](const UnitMeta& m) -> const uint32_t* {
-      return ph.codes + (int64_t)m.e * matrix_words + ((int64_t)m.col * Q + ks * S::NCH) * S::CHUNK_WORDS;
-    };
-    auto issue_chunk = [&](Buf& b, const uint32_t* cp, int ch) {
-      load_words<S::LW>(cp + lane_lo, &b.lo[ch * S::LW]);
-      if constexpr (BITS == 3) load_words<S::HW>(cp + lane_hi, &b.hi[ch * S::HW]);
-    };
-    auto issue_unit = [&](Buf& b, const UnitMeta& m) {
-      if (m.active) {
-        const uint32_t* cp = chunk_ptr(m);
-#pragma unroll
-        for (int ch = 0; ch < S::NCH; ++ch) issue_chunk(b, cp + ch * S::CHUNK_WORDS, ch);
-      }
-    };
+    const int nl = uniform_i32(s_share[phase][2]);
 
     // ---- per-pair state: the 16 token rows of this wave's K-slice as A fragments ----
     float4_t corr = {0, 0, 0, 0};
     int cur_pair = -1;
     int rows_valid = 0, row0 = 0;
     int n_stash = 0;  // outputs parked in LDS by this wave
+
+    // This lane's A-fragment of step s is afrag[4 * s]: row j of the patch, or the zero row.
+    const uint4_t* afrag = &s_x[ZERO_ROW][grp];
 
     auto load_pair = [&](int p, int e, auto&& between) {
       cur_pair = p;
@@ -440,80 +473,50 @@ __global__ __launch_bounds__(WG_THREADS, MOQE_MIN_WAVES) void moe_decode_kernel(
       const int m = p - first;
       const int seg0 = s_seg[e];
       const int n_e = s_seg[e + 1] - seg0;
-      row0 = seg0 + 16 * m;
-      rows_valid = min(16, n_e - 16 * m);
-      // lane (grp, j) holds row j, k = 32 s + 8 grp .. +7 of this wave's slice
-      const bool av = j < rows_valid;
-      const half8_t zero = {0, 0, 0, 0, 0, 0, 0, 0};
+      row0 = seg0 + TILE_ROWS * m;
+      rows_valid = min(TILE_ROWS, n_e - TILE_ROWS * m);
       const int64_t slice = (int64_t)ks * KSTEPS * 32;
       // Rows produced earlier in this launch (h) are read past the caches and are complete
       // only once no half of them is zero; their values are stored plus one.
       const bool coherent = mode == 1;
+      // Each row's slice comes in with full-width coalesced loads (16 bytes per lane) and is
+      // parked in this wave's LDS patch.
+      uint4_t(*patch)[ROW_PIECES] = &s_x[wave * TILE_ROWS];
+      constexpr int PIECES = KSTEPS * 4;       // 16-byte pieces per row slice
+      constexpr int NPL = (PIECES + 63) / 64;  // pieces per lane and row
+      __builtin_amdgcn_wave_barrier();         // earlier fragment reads of the patch are done
       for (unsigned it = 0;; ++it) {
         bool missing = false;
-        if (rows_valid <= STAGE_ROWS) {
-          // Few rows (the decode case): fetch each row's slice with full-width coalesced loads
-          // (16 bytes per lane), park it in this wave's LDS patch and pick the fragments from
-          // there: 2 loads per row instead of one sparse load per step.
-          uint4_t* patch = &s_x[wave][0][0];
-          constexpr int PIECES = KSTEPS * 4;         // 16-byte pieces per row slice
-          constexpr int NPL = (PIECES + 63) / 64;    // pieces per lane and row
-          uint4_t tmp[STAGE_ROWS * NPL];
+        uint4_t tmp[TILE_ROWS * NPL];
 #pragma unroll
-          for (int r = 0; r < STAGE_ROWS; ++r) {
-            if (r < rows_valid) {
-              const int arow = mode == 0 ? (lds_tokens ? s_perm[row0 + r] : A.perm[row0 + r]) : (row0 + r);
-              const uint4_t* src = (const uint4_t*)((const half_t*)a_rows + (int64_t)arow * K + slice);
+        for (int r = 0; r < TILE_ROWS; ++r) {
+          if (r < rows_valid) {
+            const int arow = mode == 0 ? (lds_tokens ? s_perm[row0 + r] : A.perm[row0 + r]) : (row0 + r);
+            const uint4_t* src = (const uint4_t*)((const half_t*)a_rows + (int64_t)arow * K + slice);
 #pragma unroll
-              for (int i = 0; i < NPL; ++i) {
-                const int q = 64 * i + lane;
-                if (q < PIECES) tmp[r * NPL + i] = coherent ? load16_coherent(src + q) : src[q];
-              }
+            for (int i = 0; i < NPL; ++i) {
+              const int q = 64 * i + lane;
+              if (q < PIECES) tmp[r * NPL + i] = coherent ? load16_coherent(src + q) : src[q];
             }
           }
-          if (it == 0) between();  // requests that should queue right behind the rows
+        }
+        if (it == 0) between();  // requests that should queue right behind the rows
 #pragma unroll
-          for (int r = 0; r < STAGE_ROWS; ++r) {
-            if (r < rows_valid) {
+        for (int r = 0; r < TILE_ROWS; ++r) {
+          if (r < rows_valid) {
 #pragma unroll
-              for (int i = 0; i < NPL; ++i) {
-                const int q = 64 * i + lane;
-                if (q < PIECES) {
-                  uint4_t v = tmp[r * NPL + i];
-                  if (consumes_h) {
-                    missing |= has_zero_half(v.x) | has_zero_half(v.y) | has_zero_half(v.z) | has_zero_half(v.w);
-                    v -= uint4_t{0x00010001u, 0x00010001u, 0x00010001u, 0x00010001u};
-                  }
-                  patch[r * ROW_PIECES + q] = v;
+            for (int i = 0; i < NPL; ++i) {
+              const int q = 64 * i + lane;
+              if (q < PIECES) {
+                uint4_t v = tmp[r * NPL + i];
+                if (consumes_h) {
+                  missing |= has_zero_half(v.x) | has_zero_half(v.y) | has_zero_half(v.z) | has_zero_half(v.w);
+                  v -= uint4_t{0x00010001u, 0x00010001u, 0x00010001u, 0x00010001u};
                 }
+                patch[r][q] = v;
               }
             }
           }
-          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-          __builtin_amdgcn_wave_barrier();
-          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-          for (int s = 0; s < KSTEPS; ++s)
-            xf[s] = av ? __builtin_bit_cast(half8_t, patch[j * ROW_PIECES + 4 * s + grp]) : zero;
-          __builtin_amdgcn_wave_barrier();  // the patch may be rewritten by the next pair
-        } else {
-          int64_t arow = 0;
-          if (av) arow = mode == 0 ? (lds_tokens ? s_perm[row0 + j] : A.perm[row0 + j]) : (row0 + j);
-          const half_t* ap = (const half_t*)a_rows + arow * K + slice + 8 * grp;
-#pragma unroll
-          for (int s = 0; s < KSTEPS; ++s) {
-            const uint4_t* sp = (const uint4_t*)(ap + 32 * s);
-            uint4_t v = {0, 0, 0, 0};
-            if (av) {
-              v = coherent ? load16_coherent(sp) : *sp;
-              if (consumes_h) {
-                missing |= has_zero_half(v.x) | has_zero_half(v.y) | has_zero_half(v.z) | has_zero_half(v.w);
-                v -= uint4_t{0x00010001u, 0x00010001u, 0x00010001u, 0x00010001u};
-              }
-            }
-            xf[s] = __builtin_bit_cast(half8_t, v);
-          }
-          if (it == 0) between();
         }
         if (!consumes_h || !__any(missing)) break;
         if (it > SPIN_LIMIT || load_coherent(&A.sync[SY_ERR]) != 0u) {
@@ -522,12 +525,20 @@ __global__ __launch_bounds__(WG_THREADS, MOQE_MIN_WAVES) void moe_decode_kernel(
         }
         __builtin_amdgcn_s_sleep(8);
       }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      // lane (grp, j) reads row j, k = 32 s + 8 grp .. +7 of this wave's slice
+      afrag = j < rows_valid ? &patch[j][grp] : &s_x[ZERO_ROW][grp];
       // bias + zero point carried by the unpacked values, summed against the rows
       float4_t c0 = {0, 0, 0, 0}, c1 = {0, 0, 0, 0};
 #pragma unroll
       for (int s = 0; s < KSTEPS; s += 2) {
-        c0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf[s], bias_frag<BITS>(0), c0, 0, 0, 0);
-        if (s + 1 < KSTEPS) c1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf[s + 1], bias_frag<BITS>(1), c1, 0, 0, 0);
+        c0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, afrag[4 * s]), bias_frag<BITS>(0), c0,
+                                                    0, 0, 0);
+        if (s + 1 < KSTEPS)
+          c1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, afrag[4 * s + 4]), bias_frag<BITS>(1),
+                                                      c1, 0, 0, 0);
       }
       corr = c0 + c1;
     };
@@ -536,9 +547,10 @@ __global__ __launch_bounds__(WG_THREADS, MOQE_MIN_WAVES) void moe_decode_kernel(
     // same registers are refilled with the matching chunk of unit `nx` (two units ahead).
     auto compute_unit = [&](Buf& b, const UnitMeta& m, const UnitMeta& nx) {
       float4_t acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
+      const rsrc_t nr = unit_rsrc(nx);
       if (m.active) {
         if (m.pair != cur_pair) load_pair(m.pair, m.e, [] {});
-        const uint32_t* nbase = nx.active ? chunk_ptr(nx) : nullptr;
+
 #pragma unroll
         for (int ch = 0; ch < S::NCH; ++ch) {
 #ifdef MOQE_DBG_NOCOMPUTE
@@ -563,28 +575,31 @@ __global__ __launch_bounds__(WG_THREADS, MOQE_MIN_WAVES) void moe_decode_kernel(
             }
             // one accumulator suffices when a step's unpack outlasts the MFMA; int3 issues two
             // MFMAs per step and alternates between two
-            acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf[s], w, acc0, 0, 0, 0);
+            const half8_t a = __builtin_bit_cast(half8_t, afrag[4 * s]);
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, w, acc0, 0, 0, 0);
             if constexpr (BITS == 3) {
               const uint32_t hd = b.hi[ch * S::HW + (s1 >> 2)];
               const half8_t wh = (s1 & 3) == 0 ? unpack1x4<0>(hd, uc) : (s1 & 3) == 1 ? unpack1x4<1>(hd, uc)
                                : (s1 & 3) == 2 ? unpack1x4<2>(hd, uc) : unpack1x4<3>(hd, uc);
-              acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf[s], wh, acc1, 0, 0, 0);
+              acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, wh, acc1, 0, 0, 0);
             }
           }
           // the chunk's words are consumed: refill the same registers two units ahead
-          if (nx.active) issue_chunk(b, nbase + ch * S::CHUNK_WORDS, ch);
+          issue_chunk(b, nr, ch);
         }
       } else {
-        issue_unit(b, nx);
+#pragma unroll
+        for (int ch = 0; ch < S::NCH; ++ch) issue_chunk(b, nr, ch);
       }
       return acc0 + acc1 - corr;
     };
 
     auto finish_unit = [&](const UnitMeta& m, float4_t part) {
+      // the pair's rows are rows 0..3 of the MFMA tile: lanes 0..15 hold them, one channel each
       if (ksplit > 1) {
-        s_red[par][wave][lane] = part;
+        if (lane < 16) s_red[par][wave][lane] = part;
         __syncthreads();
-        if (ks == 0) {
+        if (ks == 0 && lane < 16) {
           for (int q = 1; q < ksplit; ++q) part = part + s_red[par][wave + q][lane];
         }
         par ^= 1;
@@ -600,7 +615,7 @@ __global__ __launch_bounds__(WG_THREADS, MOQE_MIN_WAVES) void moe_decode_kernel(
         o4[r] = o;
       }
       // park the result; it is written out by flush_outputs()
-      s_out[wave][n_stash][lane] = o4;
+      if (lane < 16) s_out[wave][n_stash][lane] = o4;
       if (lane == 0) {
         s_ometa[wave][n_stash][0] = row0;
         s_ometa[wave][n_stash][1] = rows_valid;
@@ -617,26 +632,24 @@ __global__ __launch_bounds__(WG_THREADS, MOQE_MIN_WAVES) void moe_decode_kernel(
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
       for (int u = 0; u < n_stash; ++u) {
-        const float4_t o4 = s_out[wave][u][lane];
+        // lane (grp, j): row grp of the tile, channel j
+        const float o = reinterpret_cast<const float*>(&s_out[wave][u][j])[grp];
         const int u_row0 = s_ometa[wave][u][0], u_rows = s_ometa[wave][u][1];
         const int col = 16 * s_ometa[wave][u][2] + j;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          if (4 * grp + r < u_rows) {
-            const int srow = u_row0 + 4 * grp + r;
-            if (mode == 0) {
-              const uint16_t hb = half_to_bits((half_t)o4[r]);
-              if (produces_h)
-                store_coherent(&out_rows[(int64_t)srow * N + col], (uint16_t)(hb + 1u));
-              else
-                out_rows[(int64_t)srow * N + col] = hb;
-            } else {
-              const int tk = lds_tokens ? s_perm[srow] : A.perm[srow];
-              float v = (lds_tokens ? s_gate[tk] : A.gate[tk]) * o4[r];
-              const int64_t at = (int64_t)tk * N + col;
-              if (ph.residual) v += (float)((const half_t*)ph.residual)[at];
-              ((half_t*)out_rows)[at] = (half_t)v;
-            }
+        if (grp < u_rows) {
+          const int srow = u_row0 + grp;
+          if (mode == 0) {
+            const uint16_t hb = half_to_bits((half_t)o);
+            if (produces_h)
+              store_coherent(&out_rows[(int64_t)srow * N + col], (uint16_t)(hb + 1u));
+            else
+              out_rows[(int64_t)srow * N + col] = hb;
+          } else {
+            const int tk = lds_tokens ? s_perm[srow] : A.perm[srow];
+            float v = (lds_tokens ? s_gate[tk] : A.gate[tk]) * o;
+            const int64_t at = (int64_t)tk * N + col;
+            if (ph.residual) v += (float)((const half_t*)ph.residual)[at];
+            ((half_t*)out_rows)[at] = (half_t)v;
           }
         }
       }
@@ -644,14 +657,12 @@ __global__ __launch_bounds__(WG_THREADS, MOQE_MIN_WAVES) void moe_decode_kernel(
       n_stash = 0;
     };
 
-    // ---- stream of units: two register buffers, refilled chunk by chunk ----
-    Buf bufA, bufB;
-    UnitMeta m0 = make_meta(0), m1 = make_meta(1);
     // Order of the first requests.  Rows that are already in memory (x) go out before the
     // bulk weight loads: a CU's requests come back in order, so rows asked for after 16 KiB
     // of weights per wave would only arrive behind them.  Rows that are still being
     // produced by this launch (h) are asked for last: the weights do not depend on them and
     // stream in while they are awaited.
+    UnitMeta m0 = make_meta(phase, 0), m1 = make_meta(phase, 1);
     if (!consumes_h && m0.active) {
       load_pair(m0.pair, m0.e, [&] {
         issue_unit(bufA, m0);
@@ -662,15 +673,15 @@ __global__ __launch_bounds__(WG_THREADS, MOQE_MIN_WAVES) void moe_decode_kernel(
       issue_unit(bufB, m1);
     }
     STAMP(stamp_base);
-    for (int it = 0; it < nloop; it += 2) {
+    for (int it = 0; it < nl; it += 2) {
       {
-        const UnitMeta n0 = make_meta(it + 2);
+        const UnitMeta n0 = make_meta(phase, it + 2);
         const float4_t part = compute_unit(bufA, m0, n0);
         finish_unit(m0, part);
         m0 = n0;
       }
-      if (it + 1 < nloop) {
-        const UnitMeta n1 = make_meta(it + 3);
+      {
+        const UnitMeta n1 = make_meta(phase, it + 3);
         const float4_t part = compute_unit(bufB, m1, n1);
         finish_unit(m1, part);
         m1 = n1;
@@ -713,14 +724,15 @@ __global__ __launch_bounds__(WG_THREADS, MOQE_MIN_WAVES) void moe_decode_kernel(
 template <int BITS, int KSTEPS, int PM>
 hipError_t launch_mask(const DecodeArgs& a, int num_cus, hipStream_t stream) {
   // Persistent grid: every workgroup must be resident at once (phases meet at grid-wide
-  // counters), so the grid is what the occupancy query says fits, at most two per CU.
+  // counters), so the grid is what the occupancy query says fits, at most MOQE_MIN_WAVES
+  // workgroups (of four waves: one wave per SIMD each) per CU.
   static int per_cu = 0;
   if (per_cu == 0) {
     int n = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, moe_decode_kernel<BITS, KSTEPS, PM>, WG_THREADS, 0) != hipSuccess ||
         n < 1)
       n = 1;
-    per_cu = n > 2 ? 2 : n;
+    per_cu = n > MOQE_MIN_WAVES ? MOQE_MIN_WAVES : n;
   }
   hipLaunchKernelGGL((moe_decode_kernel<BITS, KSTEPS, PM>), dim3(per_cu * num_cus), dim3(WG_THREADS), 0, stream, a);
   return hipGetLastError();

@@ -149,3 +149,26 @@ __device__ inline void load_words(const uint32_t* p, uint32_t* dst) {
   }
 }
 
+
+// The same through a buffer descriptor: a load beyond the descriptor's size returns zero
+// and touches no memory, so a wave can issue the loads of a unit it may not have without a
+// branch.  Branch-free load sequences matter here: loads return in order under one counter,
+// and only for straight-line code does the compiler know how many younger loads may still be
+// in flight when it waits for an older one.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ inline rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+template <int N>
+__device__ inline void load_words(rsrc_t r, uint32_t byte_off, uint32_t* dst) {
+  constexpr int NT = 2;  // streamed once: no reuse worth caching
+  if (N == 4) {
+    uint4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, NT);
+    dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+  } else if (N == 2) {
+    uint2_t v = __builtin_amdgcn_raw_buffer_load_b64(r, byte_off, 0, NT);
+    dst[0] = v.x; dst[1] = v.y;
+  } else {
+    dst[0] = __builtin_amdgcn_raw_buffer_load_b32(r, byte_off, 0, NT);
+  }
+}

@@ -1,5 +1,6 @@
-"""GPU parity of moqe_moe_layer (router + expert FFN in one call, one launch for
-decode-sized batches) against the oracle and against the separate calls."""
+"""GPU parity of moqe_moe_layer (router + expert FFN in one call) against the oracle and
+against the separate calls, in every launch mode: one launch per step of the path, and one
+launch whose phases hand their results over through the workspace."""
 
 import numpy as np
 import pytest
@@ -11,6 +12,19 @@ from tests.helpers import (FFN_TOL, assert_route_equal, dev, ffn_error, gpu_quan
                            route_to_numpy)
 
 pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture
+def launch_mode():
+    """Sets the process-wide launch policy for one test and restores it afterwards."""
+    saved = []
+
+    def set_mode(mode):
+        saved.append(moqe.moqe_set_launch_mode(mode))
+
+    yield set_mode
+    if saved:
+        moqe.moqe_set_launch_mode(saved[0])
 
 
 def _layer_case(wl, bits, residual=False, repeats=1):
@@ -35,27 +49,16 @@ def _layer_case(wl, bits, residual=False, repeats=1):
 
 @pytest.mark.parametrize("bits", (4, 3, 2))
 @pytest.mark.parametrize("T", (1, 24, 64))
-def test_fused_small_layer(bits, T):
+def test_fused_small_layer(launch_mode, bits, T):
     # d=512, f=2048: 16 steps per wave for both contractions -> router, FFN1, FFN2 in one launch
+    launch_mode(moqe.LAUNCH_FUSED)
     _layer_case(W.small(E=8, d=512, f=2048, T=T, seed=31 + T), bits, repeats=3)
 
 
 @pytest.mark.parametrize("bits", (4, 2))
-def test_fused_residual(bits):
+def test_fused_residual(launch_mode, bits):
+    launch_mode(moqe.LAUNCH_FUSED)
     _layer_case(W.small(E=16, d=512, f=2048, T=24, seed=41), bits, residual=True)
-
-
-@pytest.fixture
-def launch_mode():
-    """Sets the process-wide launch policy for one test and restores it afterwards."""
-    saved = []
-
-    def set_mode(mode):
-        saved.append(moqe.moqe_set_launch_mode(mode))
-
-    yield set_mode
-    if saved:
-        moqe.moqe_set_launch_mode(saved[0])
 
 
 @pytest.mark.parametrize("mode", (moqe.LAUNCH_SEPARATE, moqe.LAUNCH_FUSED))
@@ -86,19 +89,24 @@ def test_launch_modes_agree_bit_for_bit(launch_mode):
         assert np.array_equal(o, outs[0])
 
 
-def test_unfused_fallbacks():
+def test_unfused_fallbacks(launch_mode):
+    launch_mode(moqe.LAUNCH_FUSED)
     _layer_case(W.CONFIGS["c0"], 4)                              # E=4: router kernel pair, 2 and 8 steps
     _layer_case(W.small(E=8, d=128, f=256, T=100, seed=43), 4)   # T > 64
     _layer_case(W.small(E=8, d=512, f=2048, T=200, seed=44), 2)  # fused FFN, separate router
 
 
+@pytest.mark.parametrize("mode", (moqe.LAUNCH_AUTO, moqe.LAUNCH_FUSED))
 @pytest.mark.parametrize("name,bits", (("c1", 4), ("c2", 3), ("c2", 2)))
-def test_decode_configs_full_size(name, bits):
+def test_decode_configs_full_size(launch_mode, mode, name, bits):
+    launch_mode(mode)
     _layer_case(W.CONFIGS[name], bits, repeats=2)
 
 
-def test_graph_replay_matches_eager():
+@pytest.mark.parametrize("mode", (moqe.LAUNCH_AUTO, moqe.LAUNCH_FUSED))
+def test_graph_replay_matches_eager(launch_mode, mode):
     """Capture one layer step in a HIP graph and replay it between eager work."""
+    launch_mode(mode)
     wl = W.small(E=16, d=512, f=2048, T=24, seed=45)
     layer, x = W.make_layer(wl), W.make_tokens(wl)
     ql = gpu_quantize_layer(layer, 4)
