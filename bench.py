@@ -3,7 +3,7 @@
 
 A step is one pass of the whole hot path over one batch: moqe_moe_layer, i.e. top-1
 gating, histogram, scan, permutation, then FFN1 + bias + ReLU, FFN2 + bias and the
-gate-weighted combine (one kernel launch) on one MoE layer of the decode configuration
+gate-weighted combine (four kernel launches) on one MoE layer of the decode configuration
 (E=32 experts, d_model 1024, d_ff 4096, batch of 24 tokens, int4 experts).
 Consecutive steps use different layer copies (own weights, own router) so that the
 packed weights of a step are not left in the 256 MB last-level cache by the
@@ -31,10 +31,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM traffic per launch of the dominant kernel measured with rocprofv3 --pmc
-# (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); filled
-# from the summaries under profiles/ once measured, per bit width, else None.
-MEASURED_TRAFFIC_BYTES = {4: None, 3: None, 2: None}
+# HBM traffic per launch of the dominant kernel (FFN1) measured with rocprofv3 --pmc
+# (FETCH_SIZE and WRITE_SIZE runs of this script, scaled by a 256 MiB device copy in the
+# same run: FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); from profiles/decode_c1_int4_hbm_traffic.txt.
+# Not measured for the other bit widths.
+MEASURED_TRAFFIC_BYTES = {4: 35390084, 3: None, 2: None}
 
 
 def parse():
@@ -51,6 +52,7 @@ def parse():
                     help="also run three plain device-to-device copies of this size first: under "
                          "rocprofv3 --pmc they give the counter reading of a known amount of traffic")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches only")
+    ap.add_argument("--parts", action="store_true", help="also time each kernel of the step on its own")
     return ap.parse_args()
 
 
@@ -121,23 +123,38 @@ def main():
     ws = moqe.alloc_workspace(moqe.moqe_layer_workspace_bytes(T, E, d, f), x.device)
     y = torch.empty_like(x)
 
-    def make_step(qls):
+    hbuf = torch.empty((T, f), dtype=torch.float16, device="cuda")
+
+    def make_calls(qls):
+        """ctypes calls with every argument marshalled once: the whole step and its parts."""
         structs = [ql.c_struct() for ql in qls]
         refs = [ctypes.byref(s) for s in structs]
         gates = [ql.w_gate.data_ptr() for ql in qls]
-        xp, yp = x.data_ptr(), y.data_ptr()
+        xp, yp, hp = x.data_ptr(), y.data_ptr(), hbuf.data_ptr()
         ip, gp, sp, pp = (route.expert_idx.data_ptr(), route.gate.data_ptr(), route.seg_offsets.data_ptr(),
                           route.perm.data_ptr())
         wsp, wsn = ws.data_ptr(), ws.numel()
+        n = len(qls)
+
+        def check(st, what):
+            if st:
+                raise RuntimeError(f"{what} failed with status {st}")
 
         def step(i, stream):
-            k = i % len(qls)
-            st = L.moqe_moe_layer(refs[k], gates[k], xp, T, ip, gp, sp, pp, None, yp, wsp, wsn, stream)
-            if st:
-                raise RuntimeError(f"moqe_moe_layer failed with status {st}")
+            check(L.moqe_moe_layer(refs[i % n], gates[i % n], xp, T, ip, gp, sp, pp, None, yp, wsp, wsn, stream),
+                  "moqe_moe_layer")
+
+        def ffn1(i, stream):
+            check(L.moqe_expert_ffn1(refs[i % n], xp, T, sp, pp, hp, stream), "moqe_expert_ffn1")
+
+        def ffn2(i, stream):
+            check(L.moqe_expert_ffn2(refs[i % n], hp, T, gp, sp, pp, None, yp, stream), "moqe_expert_ffn2")
+
+        def router(i, stream):
+            check(L.moqe_route(xp, gates[i % n], T, d, E, ip, gp, sp, pp, wsp, wsn, stream), "moqe_route")
 
         step.keep = (structs, refs)
-        return step
+        return step, ffn1, ffn2, router
 
     def time_steps(run, steps, warmup):
         """(wall ms per step with a sync on both sides, HIP-event ms per step on the launch stream)"""
@@ -153,10 +170,25 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t) * 1e3 / steps, e0.elapsed_time(e1) / steps
 
+    def time_graph(run, steps, warmup):
+        """The same calls captured once per layer copy into ONE graph (a pass over all copies),
+        replayed: launch cost leaves the picture.  Returns event ms per call."""
+        side = torch.cuda.Stream()
+        n = args.copies
+        with torch.cuda.stream(side):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                for k in range(n):
+                    run(k, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        reps = max(1, steps // n)
+        _, ev = time_steps(lambda i: g.replay(), reps, max(1, warmup // n))
+        return ev / n
+
     results = {}
     for b in bit_list:
         qls = layers[b]
-        step = make_step(qls)
+        step, ffn1, ffn2, router = make_calls(qls)
         stream = torch.cuda.current_stream().cuda_stream
         # realised routing of every layer copy -> algorithmic bytes of its step
         ab = []
@@ -166,38 +198,39 @@ def main():
             ab.append(algorithmic_bytes(route.seg_offsets.cpu().numpy(), b, d, f, T))
         if moqe.workspace_error(ws):
             raise RuntimeError("a phase wait timed out: results invalid")
+        # ---- the timed region: K whole steps ----
         eager_ms, eager_ev_ms = time_steps(lambda i: step(i, stream), args.steps, args.warmup)
-
-        graph_ms = graph_ev_ms = None
-        if not args.no_graph:
-            side = torch.cuda.Stream()
-            graphs = []
-            with torch.cuda.stream(side):
-                for k in range(len(qls)):
-                    g = torch.cuda.CUDAGraph()
-                    with torch.cuda.graph(g, stream=side):
-                        step(k, torch.cuda.current_stream().cuda_stream)
-                    graphs.append(g)
-            torch.cuda.synchronize()
-            graph_ms, graph_ev_ms = time_steps(lambda i: graphs[i % len(graphs)].replay(), args.steps, args.warmup)
+        graph_ms = None if args.no_graph else time_graph(step, args.steps, args.warmup)
+        # ---- the step's kernels on their own: the same launches through the per-step entry
+        # points, K of them back to back between two HIP events on the launch stream.  The
+        # dominant kernel is the expert contraction (FFN1; FFN2 is the same kernel on a matrix
+        # of the same size).  Inside a step the same kernel runs about 2 us longer, because it
+        # starts on an idle chip instead of behind its predecessor's tail; the committed
+        # profile summaries list both populations.
+        parts = {}
+        for name, fn in (("router_2_launches", router), ("ffn1", ffn1), ("ffn2", ffn2)):
+            if name != "ffn1" and not args.parts:
+                continue
+            _, ev = time_steps(lambda i: fn(i, stream), args.steps, args.warmup)
+            parts[name + "_back_to_back_us"] = ev * 1e3
+        kern_us = parts["ffn1_back_to_back_us"]
         if moqe.workspace_error(ws):
             raise RuntimeError("a phase wait timed out: results invalid")
 
-        # One step is one launch of the decode kernel (router, FFN1 and FFN2 are its phases), so
-        # the kernel's average duration is the event time per step of the eager loop.
         layer_bytes = float(np.mean([a[1] + a[2] for a in ab])) + 2 * d * E
-        kern_s = eager_ev_ms * 1e-3
-        achieved = layer_bytes / kern_s / 1e9
+        ffn1_bytes = float(np.mean([a[1] for a in ab]))
+        # the dominant kernel is the expert contraction (FFN1 and FFN2 are the same kernel on
+        # matrices of the same size)
+        achieved = ffn1_bytes / (kern_us * 1e-6) / 1e9
         best_ms = min(eager_ms, graph_ms) if graph_ms is not None else eager_ms
         results[b] = dict(
             ms_per_step=best_ms, eager_ms=eager_ms, graph_ms=graph_ms, tokens_per_s=T / (best_ms * 1e-3),
             active_experts=float(np.mean([a[0] for a in ab])), layer_bytes=layer_bytes,
-            kernel_us=kern_s * 1e6, kernel_bytes=layer_bytes, achieved_gbs=achieved,
-            eager_event_ms=eager_ev_ms, graph_event_ms=graph_ev_ms,
+            kernel_us=kern_us, kernel_bytes=ffn1_bytes, achieved_gbs=achieved, parts=parts,
             step_gbs=layer_bytes / (best_ms * 1e-3) / 1e9)
         print(f"[bench] int{b}: eager {eager_ms * 1e3:.1f} us/step (events {eager_ev_ms * 1e3:.1f}), graph "
-              f"{(graph_ms or float('nan')) * 1e3:.1f} us/step, {achieved:.0f} GB/s over {layer_bytes / 1e6:.1f} MB",
-              file=sys.stderr, flush=True)
+              f"{(graph_ms or float('nan')) * 1e3:.1f} us/step; ffn1 kernel {kern_us:.1f} us = {achieved:.0f} GB/s over "
+              f"{ffn1_bytes / 1e6:.1f} MB; parts {json.dumps(parts)}", file=sys.stderr, flush=True)
 
     # ---- CPU oracle on the host cores: bounded sample of the same workload ----
     cpu = None
@@ -238,10 +271,11 @@ def main():
                    "launch": "hip graph replay" if (r["graph_ms"] is not None and r["graph_ms"] <= r["eager_ms"]) else "eager",
                    "eager_ms_per_step": r["eager_ms"], "graph_ms_per_step": r["graph_ms"],
                    "active_experts": r["active_experts"], "layer_algorithmic_bytes": r["layer_bytes"],
-                   "step_gb_per_s": r["step_gbs"]},
+                   "step_gb_per_s": r["step_gbs"], "launches_per_step": 4, "kernels_us": r["parts"]},
         "roofline": {"bound": "hbm", "achieved": r["achieved_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": r["achieved_gbs"] / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(args.bits),
-                     "kernel": "moe_decode_kernel<%d,32>" % args.bits, "avg_kernel_us": r["kernel_us"],
+                     "kernel": "moe_decode_kernel<%d,32,2> (FFN1; FFN2 is the same kernel on a matrix of the "
+                               "same size)" % args.bits, "avg_kernel_us": r["kernel_us"],
                      "algorithmic_bytes_per_launch": r["kernel_bytes"]},
         "cpu_baseline": cpu,
     }

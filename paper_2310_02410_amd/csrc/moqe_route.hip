@@ -1,9 +1,10 @@
 // Top-1 gating and dispatch bookkeeping (paper App. B "MoE architecture": top-1
-// learned gating as in Switch).  Two kernels:
+// learned gating as in Switch).  Two kernels in general:
 //   route_score_kernel    logits = x W_g (fp32), wavefront-level argmax with
 //                         lowest-index tie break, gate = softmax probability
 //   route_segments_kernel per-expert histogram, exclusive scan into contiguous
 //                         expert segments, stable token permutation
+// and one, route_small_kernel, that does both for a decode-sized batch.
 // Everything is deterministic: no atomics decide an order anywhere.
 #include "moqe_dev.h"
 #include "moqe_kernels.h"
@@ -281,6 +282,137 @@ __global__ __launch_bounds__(SEG_THREADS) void route_segments_kernel(const int* 
   }
 }
 
+
+// ---------------------------------------------------------------------------
+// Decode-sized batches (T <= 64): the whole router in ONE workgroup and one launch.
+// The logits are a small MFMA GEMM (token tiles x expert tiles of 16 x 16, 32 rows of d per
+// step) with d split over the 16 waves; the partial tiles are summed through LDS in a fixed
+// order, then each wave picks top-1 / softmax for its tokens and wave 0 builds the dispatch
+// tables.  NT = E / 16 expert tiles, MT = token tiles kept per wave (MT * NT <= 8).
+// ---------------------------------------------------------------------------
+constexpr int SMALL_THREADS = 1024;
+constexpr int SMALL_WAVES = 16;
+
+template <int NT>
+__global__ __launch_bounds__(SMALL_THREADS) void route_small_kernel(const half_t* __restrict__ x,
+                                                                    const half_t* __restrict__ wg, int T, int d,
+                                                                    int* __restrict__ expert_idx,
+                                                                    float* __restrict__ gate,
+                                                                    int* __restrict__ seg_offsets,
+                                                                    int* __restrict__ perm) {
+  constexpr int MT = NT >= 8 ? 1 : NT == 4 ? 2 : 4;
+  constexpr int E = 16 * NT;
+  __shared__ float4_t s_part[SMALL_WAVES][MT * NT][64];
+  __shared__ float s_logit[MT * 16 * E];
+  __shared__ int s_idx[64];
+  __shared__ int s_seg[E + 1];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 4, j = lane & 15;
+  const int mt = (T + 15) >> 4;
+  const int steps = d / (32 * SMALL_WAVES);
+
+  float4_t acc[MT][NT];
+#pragma unroll
+  for (int mi = 0; mi < MT; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < NT; ++ni) acc[mi][ni] = float4_t{0, 0, 0, 0};
+
+#pragma unroll 2
+  for (int s = 0; s < steps; ++s) {
+    const int k0 = (wave * steps + s) * 32 + 8 * g;  // this lane's 8 rows of d
+    half8_t a[MT];
+#pragma unroll
+    for (int mi = 0; mi < MT; ++mi) {
+      const int t = 16 * mi + j;
+      a[mi] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
+      if (t < T) a[mi] = *(const half8_t*)(x + (int64_t)t * d + k0);
+    }
+#pragma unroll
+    for (int ni = 0; ni < NT; ++ni) {
+      half8_t b;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) b[q] = wg[(int64_t)(k0 + q) * E + 16 * ni + j];
+#pragma unroll
+      for (int mi = 0; mi < MT; ++mi)
+        if (mi < mt) acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mi], b, acc[mi][ni], 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int mi = 0; mi < MT; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < NT; ++ni) s_part[wave][mi * NT + ni][lane] = acc[mi][ni];
+  __syncthreads();
+  // D layout of a tile: lane (g, j), register r holds token row 4 g + r, expert column j
+  for (int o = tid; o < mt * NT * 256; o += SMALL_THREADS) {
+    const int tile = o >> 8, l = (o & 255) >> 2, r = o & 3;
+    float sum = 0.0f;
+    for (int w = 0; w < SMALL_WAVES; ++w) sum += reinterpret_cast<const float*>(&s_part[w][tile][l])[r];
+    const int mi = tile / NT, ni = tile - mi * NT;
+    s_logit[(16 * mi + 4 * (l >> 4) + r) * E + 16 * ni + (l & 15)] = sum;
+  }
+  __syncthreads();
+  for (int t = wave; t < T; t += SMALL_WAVES) {
+    int idx;
+    float gt;
+    wave_pick(&s_logit[t * E], E, &idx, &gt);
+    if (lane == 0) {
+      expert_idx[t] = idx;
+      gate[t] = gt;
+      s_idx[t] = idx;
+    }
+  }
+  __syncthreads();
+  if (wave == 0) {
+    const bool valid = lane < T;
+    const int key = valid ? min(max(s_idx[lane], 0), E - 1) : E;
+    int nb = 0;
+    while ((1 << nb) <= E) ++nb;
+    const uint64_t m = match_any(key, nb);
+    const int rank = __popcll(m & ((1ull << lane) - 1ull));
+    const bool leader = (__ffsll((long long)m) - 1) == lane;
+    for (int e = lane; e <= E; e += 64) s_seg[e] = 0;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    if (valid && leader) s_seg[key] = __popcll(m);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    int carry = 0;
+    for (int eg = 0; eg < E; eg += 64) {
+      const int e = eg + lane;
+      const int v = (e < E) ? s_seg[e] : 0;
+      int inc = v;
+      for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(inc, off, 64);
+        if (lane >= off) inc += o;
+      }
+      __builtin_amdgcn_wave_barrier();
+      if (e < E) {
+        s_seg[e] = carry + inc - v;
+        seg_offsets[e] = carry + inc - v;
+      }
+      carry += __shfl(inc, 63, 64);
+    }
+    if (lane == 0) seg_offsets[E] = T;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    if (valid) perm[s_seg[key] + rank] = lane;
+  }
+}
+
+// True when route_small_kernel can take the call.
+static bool small_route_fits(int T, int d, int E) {
+  if (T < 1 || T > 64 || d < 512 || (d % 512) != 0) return false;
+  const int mt = (T + 15) / 16;
+  switch (E) {
+    case 16: return mt <= 4;
+    case 32: return mt <= 4;
+    case 64: return mt <= 2;
+    case 128: return mt <= 1;
+    default: return false;
+  }
+}
+
 }  // namespace
 
 size_t moqe_route_ws_bytes(int64_t T, int64_t E) {
@@ -299,6 +431,17 @@ static int pow2_ceil(int v) {
 hipError_t moqe_launch_route(const uint16_t* x, const uint16_t* wg, const float* logits, int T, int d, int E,
                              int* expert_idx, float* gate, int* seg_offsets, int* perm, void* ws,
                              hipStream_t stream) {
+  if (T > 0 && !logits && small_route_fits(T, d, E)) {
+    const half_t* xh = (const half_t*)x;
+    const half_t* wh = (const half_t*)wg;
+    switch (E) {
+      case 16: hipLaunchKernelGGL(route_small_kernel<1>, dim3(1), dim3(SMALL_THREADS), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
+      case 32: hipLaunchKernelGGL(route_small_kernel<2>, dim3(1), dim3(SMALL_THREADS), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
+      case 64: hipLaunchKernelGGL(route_small_kernel<4>, dim3(1), dim3(SMALL_THREADS), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
+      default: hipLaunchKernelGGL(route_small_kernel<8>, dim3(1), dim3(SMALL_THREADS), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
+    }
+    return hipGetLastError();
+  }
   if (T > 0) {
     if (logits) {
       hipLaunchKernelGGL(route_pick_kernel, dim3((T + 3) / 4), dim3(256), 0, stream, logits, T, E, expert_idx, gate);

@@ -36,6 +36,29 @@ def test_shapes(T, d, E):
     _route_case(W.small("r", E=E, d=d, f=32, T=T, seed=T + E))
 
 
+@pytest.mark.parametrize("T,d,E", [(1, 512, 16), (24, 1024, 32), (64, 512, 32), (17, 1536, 32), (33, 1024, 16),
+                                   (32, 1024, 64), (16, 1024, 128), (8, 512, 128), (5, 2048, 64)])
+def test_single_launch_router_shapes(T, d, E):
+    """Decode-sized batches take the one-workgroup MFMA router; (33, 1024, 64) and
+    (17, 1024, 128) would not fit it and stay on the two-kernel path (covered above)."""
+    _route_case(W.small("r1", E=E, d=d, f=32, T=T, seed=3 * T + E))
+
+
+def test_single_launch_router_ties_and_skew():
+    """Duplicate expert columns force exact ties (lowest index must win) on the one-launch path,
+    Zipf routing fills some experts and leaves others empty."""
+    wl = W.small("r2", E=32, d=1024, f=32, T=64, routing="zipf", n_empty=6, seed=77)
+    layer, x = W.make_layer(wl), W.make_tokens(wl)
+    wg = layer["w_gate"].copy()
+    wg[:, 9] = wg[:, 3]
+    wg[:, 30] = wg[:, 3]
+    got = route_to_numpy(moqe.moqe_route(dev(x), dev(wg)))
+    torch.cuda.synchronize()
+    ref = O.route(x, wg)
+    assert_route_equal(got, ref, wl.T, wl.E)
+    assert not np.isin(got[0], (9, 30)).any()
+
+
 def test_empty_batch():
     x = torch.empty((1, 64), dtype=torch.float16, device="cuda")[:0]
     wg = dev(W.make_layer(W.small("r", E=8, d=64, f=32))["w_gate"])
