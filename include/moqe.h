@@ -83,6 +83,16 @@ int moqe_version(void);
 enum { MOQE_LAUNCH_AUTO = 0, MOQE_LAUNCH_SEPARATE = 1, MOQE_LAUNCH_FUSED = 2 };
 int moqe_set_launch_mode(int mode);
 
+/* Path choice inside the expert FFN (process-wide, for tuning and tests; results are within
+ * the same tolerance either way): expert segments with at least n tokens are computed by the
+ * tiled MFMA kernel (token rows staged in LDS, 64-token tiles), smaller ones by the
+ * dequantize-in-register decode kernel.  Default MOQE_PREFILL_MIN_TOKENS_DEFAULT; a huge n
+ * switches the tiled kernel off.  The tiled kernel needs K a multiple of 128 (int4) or 256
+ * (int2, int3); other layers use the decode kernel throughout.  Launch mode FUSED uses the
+ * decode kernel for everything it chains.  Returns the previous n, or -1 for n < 1. */
+#define MOQE_PREFILL_MIN_TOKENS_DEFAULT 17
+int moqe_set_prefill_min_tokens(int n);
+
 /* Bytes of one packed [K,N] matrix = K*N*bits/8 (Table 2: exactly `bits` bits
  * per expert weight).  Returns 0 for an unsupported (bits, K, N). Host only. */
 size_t moqe_packed_bytes(int bits, int64_t K, int64_t N);

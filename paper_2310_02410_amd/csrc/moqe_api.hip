@@ -44,6 +44,10 @@ constexpr int64_t MAX_EXPERTS = 1024;
 size_t round256(size_t b) { return b < 256 ? 256 : ((b + 255) & ~(size_t)255); }
 
 std::atomic<int> g_launch_mode{MOQE_LAUNCH_AUTO};
+// Expert segments with at least this many tokens go to the tiled MFMA kernel.  The decode
+// kernel re-streams an expert's weights once per 4 tokens; from a handful of such passes on,
+// one pass of the tiled kernel (64-token tiles) is cheaper.
+std::atomic<int> g_prefill_min{MOQE_PREFILL_MIN_TOKENS_DEFAULT};
 
 }  // namespace
 
@@ -65,6 +69,11 @@ const char* moqe_status_string(int status) {
 const char* moqe_last_hip_error(void) { return g_hip_error; }
 
 int moqe_version(void) { return 1; }
+
+int moqe_set_prefill_min_tokens(int n) {
+  if (n < 1) return -1;
+  return g_prefill_min.exchange(n);
+}
 
 int moqe_set_launch_mode(int mode) {
   if (mode != MOQE_LAUNCH_AUTO && mode != MOQE_LAUNCH_SEPARATE && mode != MOQE_LAUNCH_FUSED) return -1;
@@ -241,6 +250,39 @@ static void set_ffn2(DecodeArgs* a, const moqe_layer* L, const moqe_f16* h, cons
   p.residual = residual;
 }
 
+// One contraction as its own launch(es): the decode kernel takes the small segments, the
+// tiled MFMA kernel the large ones (none can exist when T is below the threshold).
+static hipError_t launch_contraction(DecodeArgs& a, int phase, int ksteps, hipStream_t stream) {
+  const PhaseArgs& p = a.ph[phase];
+  const int pmin = g_prefill_min.load();
+  const bool split = a.T >= pmin && moqe_prefill_supported(a.bits, p.K, p.N);
+  a.ksteps = ksteps;
+  a.phase_mask = 2 << phase;
+  a.min_tokens = 1;
+  a.max_tokens = split ? pmin : INT_MAX;
+  hipError_t e = moqe_launch_decode(a, num_cus(), stream);
+  if (e != hipSuccess || !split) return e;
+  PrefillArgs q;
+  memset(&q, 0, sizeof(q));
+  q.bits = a.bits;
+  q.E = a.E;
+  q.T = a.T;
+  q.K = p.K;
+  q.N = p.N;
+  q.mode = p.mode;
+  q.min_tokens = pmin;
+  q.codes = p.codes;
+  q.scales = p.scales;
+  q.bias = p.bias;
+  q.a = p.a;
+  q.out = p.out;
+  q.residual = p.residual;
+  q.seg_offsets = a.seg_offsets;
+  q.perm = a.perm;
+  q.gate = a.gate;
+  return moqe_launch_prefill(q, stream);
+}
+
 // Unit counts are 32-bit inside the kernel.
 static bool units_fit(int64_t T, int64_t E, int64_t N) { return ((T + 3) / 4 + E) * (N / 16) < (1ll << 31); }
 
@@ -254,9 +296,9 @@ moqe_status moqe_expert_ffn1(const moqe_layer* L, const moqe_f16* x, int64_t T, 
   if (T == 0) return MOQE_OK;
   DecodeArgs a;
   base_args(&a, L, T, nullptr, nullptr, seg_offsets, perm);
-  set_ffn1(&a, L, x, h, &a.ksteps);
-  a.phase_mask = 2;
-  hipError_t e = moqe_launch_decode(a, num_cus(), (hipStream_t)stream);
+  int ks = 0;
+  set_ffn1(&a, L, x, h, &ks);
+  hipError_t e = launch_contraction(a, 0, ks, (hipStream_t)stream);
   return e == hipSuccess ? MOQE_OK : hip_fail(e);
 }
 
@@ -273,9 +315,9 @@ moqe_status moqe_expert_ffn2(const moqe_layer* L, const moqe_f16* h, int64_t T, 
   if (T == 0) return MOQE_OK;
   DecodeArgs a;
   base_args(&a, L, T, nullptr, gate, seg_offsets, perm);
-  set_ffn2(&a, L, h, residual, y, &a.ksteps);
-  a.phase_mask = 4;
-  hipError_t e = moqe_launch_decode(a, num_cus(), (hipStream_t)stream);
+  int ks = 0;
+  set_ffn2(&a, L, h, residual, y, &ks);
+  hipError_t e = launch_contraction(a, 1, ks, (hipStream_t)stream);
   return e == hipSuccess ? MOQE_OK : hip_fail(e);
 }
 
@@ -344,13 +386,9 @@ static moqe_status run_layer(const moqe_layer* L, const moqe_f16* w_gate, const 
     e = moqe_launch_decode(a, num_cus(), (hipStream_t)stream);
     return e == hipSuccess ? MOQE_OK : hip_fail(e);
   }
-  a.ksteps = ks1;
-  a.phase_mask = 2;
-  e = moqe_launch_decode(a, num_cus(), (hipStream_t)stream);
+  e = launch_contraction(a, 0, ks1, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e);
-  a.ksteps = ks2;
-  a.phase_mask = 4;
-  e = moqe_launch_decode(a, num_cus(), (hipStream_t)stream);
+  e = launch_contraction(a, 1, ks2, (hipStream_t)stream);
   return e == hipSuccess ? MOQE_OK : hip_fail(e);
 }
 

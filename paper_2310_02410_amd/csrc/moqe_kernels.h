@@ -62,7 +62,28 @@ struct DecodeArgs {
   long long* trace;
 };
 
-// Register-resident dequantize + 16-token MFMA path (few tokens per expert).
+// One contraction over the expert segments with at least min_tokens tokens: tiled MFMA
+// contraction with the token rows staged in LDS (many tokens per expert).
+struct PrefillArgs {
+  int bits, E, T;
+  int K, N;
+  int mode;  // as in PhaseArgs
+  int min_tokens;
+  int n_cblocks;  // set by the launcher
+  const uint32_t* codes;
+  const uint16_t* scales;
+  const uint16_t* bias;
+  const uint16_t* a;
+  uint16_t* out;
+  const uint16_t* residual;
+  const int* seg_offsets;
+  const int* perm;
+  const float* gate;
+};
+bool moqe_prefill_supported(int bits, int64_t K, int64_t N);
+hipError_t moqe_launch_prefill(const PrefillArgs& a, hipStream_t stream);
+
+// Dequantize-in-register path for few tokens per expert (tiles of 4 tokens).
 hipError_t moqe_launch_decode(const DecodeArgs& a, int num_cus, hipStream_t stream);
 // Picks (ksteps, ksplit) for a contraction length K; false if unsupported.
 bool moqe_pick_ksplit(int bits, int64_t K, int* ksteps, int* ksplit);

@@ -26,6 +26,7 @@ EXPORTS = (
     "moqe_ffn_workspace_bytes", "moqe_quantize", "moqe_unpack", "moqe_route",
     "moqe_route_logits", "moqe_expert_ffn", "moqe_expert_ffn1", "moqe_expert_ffn2",
     "moqe_layer_workspace_bytes", "moqe_moe_layer", "moqe_set_launch_mode",
+    "moqe_set_prefill_min_tokens",
 )
 
 LAUNCH_AUTO, LAUNCH_SEPARATE, LAUNCH_FUSED = 0, 1, 2
@@ -68,6 +69,8 @@ def lib() -> ctypes.CDLL:
     L.moqe_version.restype = ci
     L.moqe_set_launch_mode.restype = ci
     L.moqe_set_launch_mode.argtypes = [ci]
+    L.moqe_set_prefill_min_tokens.restype = ci
+    L.moqe_set_prefill_min_tokens.argtypes = [ci]
     L.moqe_packed_bytes.restype = sz
     L.moqe_packed_bytes.argtypes = [ci, i64, i64]
     L.moqe_check_matrix.restype = ci
@@ -145,6 +148,14 @@ def moqe_set_launch_mode(mode: int) -> int:
     old = lib().moqe_set_launch_mode(mode)
     if old < 0:
         raise ValueError(f"unknown launch mode {mode}")
+    return old
+
+
+def moqe_set_prefill_min_tokens(n: int) -> int:
+    """Process-wide: expert segments with at least n tokens take the tiled MFMA kernel; returns the old n."""
+    old = lib().moqe_set_prefill_min_tokens(n)
+    if old < 0:
+        raise ValueError(f"bad threshold {n}")
     return old
 
 

@@ -102,9 +102,11 @@ def _calibrate_bias(p_target: np.ndarray, sigma_logit: float, seed: int) -> np.n
     return beta
 
 
-def make_layer(wl: Workload, layer: int = 0) -> dict:
+def make_layer(wl: Workload, layer: int = 0, zipf_gate: bool = False) -> dict:
     """One MoE layer: fp32 'w1' [E,d,f], 'w2' [E,f,d]; fp16 'b1' [E,f], 'b2' [E,d];
-    fp16 'w_gate' [d,E]."""
+    fp16 'w_gate' [d,E].  With zipf_gate a uniform-routing workload also gets
+    'w_gate_zipf': the same router with the Zipf bias row (4 experts empty), so that one
+    set of expert weights serves both load shapes."""
     rng = np.random.default_rng([wl.seed, 1000 + layer])
     E, d, f = wl.E, wl.d, wl.f
     w1 = np.empty((E, d, f), dtype=np.float32)
@@ -128,12 +130,19 @@ def make_layer(wl: Workload, layer: int = 0) -> dict:
         b2[e] = (rng.standard_normal(d) * SIGMA_B).astype(np.float16)
 
     wg = np.clip(np.rint(rng.standard_normal((d, E)) * SIGMA_W * 512.0), -96, 96) / 512.0
+    out = dict(w1=w1, b1=b1, w2=w2, b2=b2)
     if wl.routing == "zipf":
         p = zipf_probs(E, wl.zipf_s, wl.n_empty, rng)
         wg[0, :] = _calibrate_bias(p, SIGMA_W * np.sqrt(d - 1.0), wl.seed * 131 + layer)
     elif wl.routing != "uniform":
         raise ValueError(f"unknown routing {wl.routing!r}")
-    return dict(w1=w1, b1=b1, w2=w2, b2=b2, w_gate=wg.astype(np.float16))
+    elif zipf_gate:
+        p = zipf_probs(E, wl.zipf_s, 4, rng)
+        wz = wg.copy()
+        wz[0, :] = _calibrate_bias(p, SIGMA_W * np.sqrt(d - 1.0), wl.seed * 131 + layer)
+        out["w_gate_zipf"] = wz.astype(np.float16)
+    out["w_gate"] = wg.astype(np.float16)
+    return out
 
 
 def make_tokens(wl: Workload) -> np.ndarray:

@@ -1,0 +1,112 @@
+"""GPU parity of the many-token path of moqe_expert_ffn (tiled MFMA kernel, token rows staged
+in LDS) against the oracle, alone and beside the decode kernel (per-segment path choice)."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import moqe_oracle as O
+from paper_2310_02410_amd import moqe, workloads as W
+from tests.helpers import (FFN_TOL, assert_route_equal, dev, ffn_error, gpu_quantize_layer, make_route,
+                           oracle_layer_output, route_to_numpy)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture
+def prefill_min():
+    """Sets the segment-size threshold of the path choice for one test and restores it."""
+    saved = []
+
+    def set_min(n):
+        saved.append(moqe.moqe_set_prefill_min_tokens(n))
+
+    yield set_min
+    if saved:
+        moqe.moqe_set_prefill_min_tokens(saved[0])
+
+
+def _parity(wl, bits, residual=False, forced=None, layer=None):
+    layer = W.make_layer(wl) if layer is None else layer
+    x = W.make_tokens(wl)
+    ql = gpu_quantize_layer(layer, bits)
+    xd = dev(x)
+    if forced is None:
+        r = moqe.moqe_route(xd, ql.w_gate)
+        idx, gate, offs, perm = route_to_numpy(r)
+        assert_route_equal((idx, gate, offs, perm), O.route(x, layer["w_gate"]), wl.T, wl.E)
+    else:
+        idx, gate = forced
+        r = make_route(idx, gate, wl.E)
+    y = moqe.moqe_expert_ffn(ql, xd, r, residual=xd if residual else None)
+    torch.cuda.synchronize()
+    ref = oracle_layer_output(x, layer, bits, idx, np.asarray(gate, dtype=np.float64), residual=residual)
+    err = ffn_error(y.cpu().numpy(), ref)
+    assert err <= FFN_TOL, f"{wl.name} int{bits}: max|err|/max|ref| = {err:.3e}"
+    return np.bincount(idx, minlength=wl.E)
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("T", (1, 37, 150, 700))
+def test_every_segment_through_the_tiled_kernel(prefill_min, bits, T):
+    # threshold 1: also one-token segments take 64-token tiles (ragged in every way);
+    # d=256, f=512: one and two K blocks for int2/int3, two and four for int4
+    prefill_min(1)
+    _parity(W.small(E=8, d=256, f=512, T=T, seed=70 + T), bits)
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+def test_tiled_kernel_residual_and_odd_widths(prefill_min, bits):
+    prefill_min(1)
+    _parity(W.small(E=4, d=512, f=1024, T=90, seed=81), bits, residual=True)
+    _parity(W.small(E=3, d=768, f=256, T=33, seed=83), bits)
+    if bits != 3:
+        # FFN2 with N = 64 channels: half a column block, two waves have nothing to load
+        # (FFN1 has K = 64, too short for the tiled kernel: decode kernel)
+        _parity(W.small(E=3, d=64, f=256, T=70, seed=82), bits)
+
+
+@pytest.mark.parametrize("bits", (4, 2))
+def test_forced_segment_sizes(prefill_min, bits):
+    """Segments of exactly 16, 17, 63, 64, 65 and 200 tokens at the default threshold (17): the
+    first goes to the decode kernel, the others to the tiled one, with full and ragged tiles."""
+    wl = W.small(E=8, d=256, f=512, T=16 + 17 + 63 + 64 + 65 + 200, seed=84)
+    sizes = (16, 17, 63, 64, 65, 200, 0, 0)
+    idx = np.concatenate([np.full(n, e) for e, n in enumerate(sizes)])
+    rng = np.random.default_rng(84)
+    rng.shuffle(idx)
+    gate = rng.uniform(0.2, 1.0, size=idx.size).astype(np.float32)
+    counts = _parity(wl, bits, forced=(idx, gate))
+    assert tuple(counts) == sizes
+
+
+def test_mixed_paths_under_zipf_load():
+    """Zipf load at the default threshold: large segments go to the tiled kernel, small ones
+    to the decode kernel, some experts stay empty; both kernels write disjoint rows of h and y."""
+    wl = W.small(E=16, d=256, f=512, T=500, routing="zipf", n_empty=3, seed=85)
+    for bits in (4, 3, 2):
+        counts = _parity(wl, bits, residual=True)
+    assert (counts >= 17).any() and ((counts > 0) & (counts < 17)).any() and (counts == 0).sum() >= 3
+
+
+def test_threshold_does_not_change_results_beyond_tolerance(prefill_min):
+    wl = W.small(E=8, d=256, f=512, T=300, seed=86)
+    layer, x = W.make_layer(wl), W.make_tokens(wl)
+    ql = gpu_quantize_layer(layer, 4)
+    xd = dev(x)
+    r = moqe.moqe_route(xd, ql.w_gate)
+    outs = []
+    for n in (1, 17, 1 << 30):
+        prefill_min(n)
+        outs.append(moqe.moqe_expert_ffn(ql, xd, r).cpu().numpy().astype(np.float64))
+    scale = np.abs(outs[2]).max()
+    assert np.abs(outs[0] - outs[2]).max() <= 2 * FFN_TOL * scale
+    assert np.abs(outs[1] - outs[2]).max() <= 2 * FFN_TOL * scale
+
+
+def test_config3_full_size():
+    """Config 3: T=1536, Zipf(1.1) load over 32 experts (largest segment several hundred
+    tokens, four experts empty), int4; every output compared."""
+    wl = W.CONFIGS["c3"]
+    counts = _parity(wl, 4)
+    assert counts.max() > 300 and (counts == 0).sum() >= 4
