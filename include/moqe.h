@@ -90,7 +90,7 @@ int moqe_set_launch_mode(int mode);
  * switches the tiled kernel off.  The tiled kernel needs K a multiple of 128 (int4) or 256
  * (int2, int3); other layers use the decode kernel throughout.  Launch mode FUSED uses the
  * decode kernel for everything it chains.  Returns the previous n, or -1 for n < 1. */
-#define MOQE_PREFILL_MIN_TOKENS_DEFAULT 17
+#define MOQE_PREFILL_MIN_TOKENS_DEFAULT 5
 int moqe_set_prefill_min_tokens(int n);
 
 /* Bytes of one packed [K,N] matrix = K*N*bits/8 (Table 2: exactly `bits` bits

@@ -7,9 +7,12 @@
 // Work decomposition
 //   pair = (expert e, tile of 64 of its tokens), found on device from seg_offsets; only
 //          experts with at least min_tokens tokens have pairs (the decode kernel takes the rest)
-//   workgroup = (pair, block of 8 column tiles = 128 output channels), 4 waves as
-//          2 token halves x 2 channel halves: a wave owns 32 tokens x 64 channels,
-//          2 x 4 accumulator tiles of v_mfma_f32_16x16x32_f16
+//   workgroup = (pair, block of output channels), 4 waves, two shapes:
+//          WM = 1: 256 channels, every wave owns all 64 tokens x 64 channels (4 x 4 accumulator
+//                  tiles of v_mfma_f32_16x16x32_f16) - wide matrices (FFN1)
+//          WM = 2: 128 channels, 2 token halves x 2 channel halves, a wave owns 32 tokens x 64
+//                  channels (2 x 4 tiles) - narrow matrices (FFN2), so that the grid still
+//                  fills the chip
 //   K runs in blocks of one packed chunk (128 rows for int4, 256 for int2/int3):
 //     - the block's 64 token rows are staged in LDS (double buffered, loaded one block ahead
 //       through registers) and every wave reads its A fragments from there;
@@ -17,9 +20,11 @@
 //       (the packed layout is already in B-operand order), one block ahead, and dequantizes in
 //       registers: the unpack of one B fragment is amortized over the 2 token tiles, and the
 //       fragment never has to travel through LDS because no other wave needs it.
-//   The exponent / zero-point offsets the unpack leaves in the values are removed after the
-//   K-sum through one extra MFMA per token tile and step against a constant fragment, the
-//   scale multiplies the finished sum (see moqe_unpack.h).
+//   The unpack brings every field down to the signed code exactly (one packed subtract per
+//   register more than the decode kernel's unpack, which leaves exponent and zero-point offsets
+//   in the K-sum and removes them afterwards: over a whole K of all-positive activations that
+//   costs accuracy, and here the unpack is shared by several token tiles anyway).  The scale
+//   multiplies the finished sum (see moqe_unpack.h).
 #include "moqe_dev.h"
 #include "moqe_kernels.h"
 #include "moqe_unpack.h"
@@ -28,13 +33,14 @@ namespace {
 
 constexpr int PF_THREADS = 256;
 constexpr int PF_TILE_M = 64;   // tokens per workgroup
-constexpr int PF_TILE_CT = 8;   // column tiles (of 16 channels) per workgroup
-constexpr int PF_MT = 2;        // token tiles per wave
-constexpr int PF_NT = 4;        // column tiles per wave
+constexpr int PF_NT = 4;        // column tiles (of 16 channels) per wave
 constexpr int PF_MAX_E = 1024;
 
-template <int BITS>
+template <int BITS, int WM>
 __global__ __launch_bounds__(PF_THREADS, 2) void moe_prefill_kernel(PrefillArgs A) {
+  constexpr int WN = 4 / WM;                 // waves side by side along the channels
+  constexpr int PF_MT = PF_TILE_M / 16 / WM;  // token tiles per wave
+  constexpr int PF_TILE_CT = WN * PF_NT;      // column tiles per workgroup
   constexpr int SC = BITS == 4 ? 4 : 8;       // steps of 32 rows per K block (= one packed chunk)
   constexpr int KC = 32 * SC;                 // rows of K per block
   constexpr int LO_BITS = BITS == 3 ? 2 : BITS;
@@ -50,7 +56,7 @@ __global__ __launch_bounds__(PF_THREADS, 2) void moe_prefill_kernel(PrefillArgs 
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = uniform_i32(tid >> 6);
-  const int wm = wave & 1, wn = wave >> 1;
+  const int wm = wave % WM, wn = wave / WM;
   const int g = lane >> 4, j = lane & 15;
   const int E = A.E, K = A.K, N = A.N;
 
@@ -89,11 +95,11 @@ __global__ __launch_bounds__(PF_THREADS, 2) void moe_prefill_kernel(PrefillArgs 
   const int row0 = seg0 + PF_TILE_M * (p - first);
   const int rows = min(PF_TILE_M, n_e - PF_TILE_M * (p - first));
 
-  // element offset of each token row in `a` (-1: no such row, reads as zero)
+  // element offset of each token row in `a`; the rows a ragged tile lacks repeat its last row
+  // (their results are never stored)
   if (tid < PF_TILE_M) {
-    long long off = -1;
-    if (tid < rows) off = (long long)(A.mode == 0 ? A.perm[row0 + tid] : row0 + tid) * K;
-    s_rowoff[tid] = off;
+    const int r = min(tid, rows - 1);
+    s_rowoff[tid] = (long long)(A.mode == 0 ? A.perm[row0 + r] : row0 + r) * K;
   }
   __syncthreads();
 
@@ -129,9 +135,7 @@ __global__ __launch_bounds__(PF_THREADS, 2) void moe_prefill_kernel(PrefillArgs 
     for (int i = 0; i < NP; ++i) {
       const int q = tid + PF_THREADS * i;
       const int row = q / (KC / 8), pc = q % (KC / 8);
-      const long long off = s_rowoff[row];
-      a_next[i] = uint4_t{0, 0, 0, 0};
-      if (off >= 0) a_next[i] = *(const uint4_t*)((const half_t*)A.a + off + (int64_t)kb * KC + pc * 8);
+      a_next[i] = *(const uint4_t*)((const half_t*)A.a + s_rowoff[row] + (int64_t)kb * KC + pc * 8);
     }
   };
   auto store_a = [&](int buf) {
@@ -143,10 +147,8 @@ __global__ __launch_bounds__(PF_THREADS, 2) void moe_prefill_kernel(PrefillArgs 
   };
 
   float4_t acc[PF_MT][PF_NT];
-  float4_t corr[PF_MT];
 #pragma unroll
   for (int mi = 0; mi < PF_MT; ++mi) {
-    corr[mi] = float4_t{0, 0, 0, 0};
 #pragma unroll
     for (int ni = 0; ni < PF_NT; ++ni) acc[mi][ni] = float4_t{0, 0, 0, 0};
   }
@@ -157,32 +159,24 @@ __global__ __launch_bounds__(PF_THREADS, 2) void moe_prefill_kernel(PrefillArgs 
       half8_t a[PF_MT];
 #pragma unroll
       for (int mi = 0; mi < PF_MT; ++mi)
-        a[mi] = __builtin_bit_cast(half8_t, s_a[abuf][32 * wm + 16 * mi + j][4 * s + g]);
+        a[mi] = __builtin_bit_cast(half8_t, s_a[abuf][16 * PF_MT * wm + 16 * mi + j][4 * s + g]);
 #pragma unroll
       for (int ni = 0; ni < PF_NT; ++ni) {
         half8_t w;
         if constexpr (BITS == 4) {
-          w = unpack4(b_lo[bbuf][ni][s], uc);
-        } else {
+          w = unpack4_exact(b_lo[bbuf][ni][s], uc);
+        } else if constexpr (BITS == 2) {
           const uint32_t d = b_lo[bbuf][ni][s >> 1];
-          w = (s & 1) ? unpack2<1>(d, uc) : unpack2<0>(d, uc);
+          w = (s & 1) ? unpack2_exact<1>(d, uc) : unpack2_exact<0>(d, uc);
+        } else {
+          const uint32_t d = b_lo[bbuf][ni][s >> 1], hd = b_hi[bbuf][ni][s >> 2];
+          w = (s & 3) == 0 ? unpack3_exact<0>(d, hd, uc) : (s & 3) == 1 ? unpack3_exact<1>(d, hd, uc)
+            : (s & 3) == 2 ? unpack3_exact<2>(d, hd, uc) : unpack3_exact<3>(d, hd, uc);
         }
 #pragma unroll
         for (int mi = 0; mi < PF_MT; ++mi)
           acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mi], w, acc[mi][ni], 0, 0, 0);
-        if constexpr (BITS == 3) {
-          const uint32_t hd = b_hi[bbuf][ni][s >> 2];
-          const half8_t wh = (s & 3) == 0 ? unpack1x4<0>(hd, uc) : (s & 3) == 1 ? unpack1x4<1>(hd, uc)
-                           : (s & 3) == 2 ? unpack1x4<2>(hd, uc) : unpack1x4<3>(hd, uc);
-#pragma unroll
-          for (int mi = 0; mi < PF_MT; ++mi)
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mi], wh, acc[mi][ni], 0, 0, 0);
-        }
       }
-      // what the unpacked values carry besides the code: exponent bias and zero point
-#pragma unroll
-      for (int mi = 0; mi < PF_MT; ++mi)
-        corr[mi] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mi], bias_frag<BITS>(s & 1), corr[mi], 0, 0, 0);
     }
   };
 
@@ -225,9 +219,9 @@ __global__ __launch_bounds__(PF_THREADS, 2) void moe_prefill_kernel(PrefillArgs 
     for (int mi = 0; mi < PF_MT; ++mi) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const int row = 32 * wm + 16 * mi + 4 * g + r;
+        const int row = 16 * PF_MT * wm + 16 * mi + 4 * g + r;
         if (row >= rows) continue;
-        float o = fmaf(acc[mi][ni][r] - corr[mi][r], sc, bi);
+        float o = fmaf(acc[mi][ni][r], sc, bi);
         const int srow = row0 + row;
         if (A.mode == 0) {
           o = fmaxf(o, 0.0f);
@@ -251,19 +245,27 @@ bool moqe_prefill_supported(int bits, int64_t K, int64_t N) {
   return (bits == 2 || bits == 3 || bits == 4) && K >= kc && (K % kc) == 0 && N >= 16 && (N % 16) == 0;
 }
 
-hipError_t moqe_launch_prefill(const PrefillArgs& a, hipStream_t stream) {
+template <int BITS>
+static void launch_bits(const PrefillArgs& a, int64_t pairs, hipStream_t stream) {
+  // Only the 128-channel workgroup shape is launched.  The 256-channel shape (WM = 1: 4 x 4
+  // accumulator tiles per wave) does not fit 256 registers without spilling and measured
+  // slower on the 4096-token stack (112 vs 84 us for FFN1).
   PrefillArgs args = a;
-  args.n_cblocks = (a.N / 16 + PF_TILE_CT - 1) / PF_TILE_CT;
+  args.n_cblocks = (a.N / 16 + 7) / 8;
+  hipLaunchKernelGGL((moe_prefill_kernel<BITS, 2>), dim3((unsigned)(pairs * args.n_cblocks)), dim3(PF_THREADS), 0,
+                     stream, args);
+}
+
+hipError_t moqe_launch_prefill(const PrefillArgs& a, hipStream_t stream) {
   // upper bound on the number of (expert, 64-token tile) pairs
   const int64_t with_pairs = a.min_tokens > 0 ? a.T / a.min_tokens : a.E;
   const int64_t pairs = a.T / PF_TILE_M + (with_pairs < a.E ? with_pairs : a.E);
-  const int64_t grid = pairs * args.n_cblocks;
-  if (grid <= 0) return hipSuccess;
-  if (grid >= (1ll << 31)) return hipErrorInvalidValue;
+  if (pairs <= 0) return hipSuccess;
+  if (pairs * ((a.N / 16 + 7) / 8) >= (1ll << 31)) return hipErrorInvalidValue;
   switch (a.bits) {
-    case 4: hipLaunchKernelGGL(moe_prefill_kernel<4>, dim3((unsigned)grid), dim3(PF_THREADS), 0, stream, args); break;
-    case 3: hipLaunchKernelGGL(moe_prefill_kernel<3>, dim3((unsigned)grid), dim3(PF_THREADS), 0, stream, args); break;
-    case 2: hipLaunchKernelGGL(moe_prefill_kernel<2>, dim3((unsigned)grid), dim3(PF_THREADS), 0, stream, args); break;
+    case 4: launch_bits<4>(a, pairs, stream); break;
+    case 3: launch_bits<3>(a, pairs, stream); break;
+    case 2: launch_bits<2>(a, pairs, stream); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

@@ -111,6 +111,62 @@ __device__ inline half8_t unpack1x4(uint32_t d, const C& c) {
   return frag_from_words(r0, r1, r2, r3);
 }
 
+// ---- exact variants: every field is brought down to the signed code q = u - 2^(b-1) with a
+// packed subtract, at one more VALU operation per register.  Used where the unpack is
+// amortized over several token tiles and K is long: leaving the offsets in the K-sum costs
+// accuracy when the activations are all positive (h after ReLU), because the offset term then
+// grows like K while the signal grows like sqrt(K).
+__device__ inline uint32_t pk_add(uint32_t a, uint32_t b) {
+  half2_t x = __builtin_bit_cast(half2_t, a), y = __builtin_bit_cast(half2_t, b);
+  x = x + y;
+  return __builtin_bit_cast(uint32_t, x);
+}
+
+template <class C>
+__device__ inline half8_t unpack4_exact(uint32_t d, const C& c) {
+  uint32_t d8 = d >> 8;
+  uint32_t r0 = pk_sub((d & c.m_000f) | c.x1024, 1032.0f);
+  uint32_t r1 = pk_sub((d & c.m_00f0) | c.x64, 72.0f);
+  uint32_t r2 = pk_sub((d8 & c.m_000f) | c.x1024, 1032.0f);
+  uint32_t r3 = pk_sub((d8 & c.m_00f0) | c.x64, 72.0f);
+  return frag_from_words(r0, r1, r2, r3);
+}
+
+template <int PARITY, class C>
+__device__ inline half8_t unpack2_exact(uint32_t d, const C& c) {
+  if (PARITY == 0) {
+    uint32_t dl = d << 4;
+    uint32_t r0 = pk_sub((dl & c.m_0030) | c.x64, 66.0f);
+    uint32_t r1 = pk_sub((dl & c.m_00c0) | c.x16, 18.0f);
+    uint32_t r2 = pk_sub((d & c.m_0030) | c.x64, 66.0f);
+    uint32_t r3 = pk_sub((d & c.m_00c0) | c.x16, 18.0f);
+    return frag_from_words(r0, r1, r2, r3);
+  } else {
+    uint32_t dr = d >> 6;
+    uint32_t r0 = pk_sub((d & c.m_0300) | c.x4, 6.0f);
+    uint32_t r1 = pk_sub((dr & c.m_0030) | c.x64, 66.0f);
+    uint32_t r2 = pk_sub((dr & c.m_00c0) | c.x16, 18.0f);
+    uint32_t r3 = pk_sub((dr & c.m_0300) | c.x4, 6.0f);
+    return frag_from_words(r0, r1, r2, r3);
+  }
+}
+
+// int3, step SS (0..3) of a group of four: low plane word dl (two steps per word, the step's
+// parity is SS & 1), high plane word dh (four steps per word).  The two planes are added while
+// they still carry their exponent offsets (the sums stay below 256, where fp16 still holds
+// every integer), then one subtract removes both offsets and the zero point 4.
+template <int SS, class C>
+__device__ inline half8_t unpack3_exact(uint32_t dl, uint32_t dh, const C& c) {
+  const half8_t lo = unpack2<SS & 1>(dl, c);
+  const half8_t hi = unpack1x4<SS>(dh, c);
+  const uint4_t l = __builtin_bit_cast(uint4_t, lo), h = __builtin_bit_cast(uint4_t, hi);
+  if ((SS & 1) == 0)
+    return frag_from_words(pk_sub(pk_add(l.x, h.x), 132.0f), pk_sub(pk_add(l.y, h.y), 52.0f),
+                           pk_sub(pk_add(l.z, h.z), 84.0f), pk_sub(pk_add(l.w, h.w), 28.0f));
+  return frag_from_words(pk_sub(pk_add(l.x, h.x), 72.0f), pk_sub(pk_add(l.y, h.y), 100.0f),
+                         pk_sub(pk_add(l.z, h.z), 36.0f), pk_sub(pk_add(l.w, h.w), 16.0f));
+}
+
 // Constant B fragment holding, per code position, the amount the unpacked value
 // exceeds the signed code: exponent bias(es) + zero point.
 template <int BITS>

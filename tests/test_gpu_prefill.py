@@ -68,10 +68,10 @@ def test_tiled_kernel_residual_and_odd_widths(prefill_min, bits):
 
 @pytest.mark.parametrize("bits", (4, 2))
 def test_forced_segment_sizes(prefill_min, bits):
-    """Segments of exactly 16, 17, 63, 64, 65 and 200 tokens at the default threshold (17): the
+    """Segments of exactly 4, 5, 63, 64, 65 and 200 tokens at the default threshold (5): the
     first goes to the decode kernel, the others to the tiled one, with full and ragged tiles."""
-    wl = W.small(E=8, d=256, f=512, T=16 + 17 + 63 + 64 + 65 + 200, seed=84)
-    sizes = (16, 17, 63, 64, 65, 200, 0, 0)
+    wl = W.small(E=8, d=256, f=512, T=4 + 5 + 63 + 64 + 65 + 200, seed=84)
+    sizes = (4, 5, 63, 64, 65, 200, 0, 0)
     idx = np.concatenate([np.full(n, e) for e, n in enumerate(sizes)])
     rng = np.random.default_rng(84)
     rng.shuffle(idx)
@@ -83,10 +83,10 @@ def test_forced_segment_sizes(prefill_min, bits):
 def test_mixed_paths_under_zipf_load():
     """Zipf load at the default threshold: large segments go to the tiled kernel, small ones
     to the decode kernel, some experts stay empty; both kernels write disjoint rows of h and y."""
-    wl = W.small(E=16, d=256, f=512, T=500, routing="zipf", n_empty=3, seed=85)
+    wl = W.small(E=16, d=256, f=512, T=200, routing="zipf", n_empty=3, seed=85)
     for bits in (4, 3, 2):
         counts = _parity(wl, bits, residual=True)
-    assert (counts >= 17).any() and ((counts > 0) & (counts < 17)).any() and (counts == 0).sum() >= 3
+    assert (counts >= 5).any() and ((counts > 0) & (counts < 5)).any() and (counts == 0).sum() >= 3
 
 
 def test_threshold_does_not_change_results_beyond_tolerance(prefill_min):
@@ -96,7 +96,7 @@ def test_threshold_does_not_change_results_beyond_tolerance(prefill_min):
     xd = dev(x)
     r = moqe.moqe_route(xd, ql.w_gate)
     outs = []
-    for n in (1, 17, 1 << 30):
+    for n in (1, 5, 1 << 30):
         prefill_min(n)
         outs.append(moqe.moqe_expert_ffn(ql, xd, r).cpu().numpy().astype(np.float64))
     scale = np.abs(outs[2]).max()
