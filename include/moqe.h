@@ -84,14 +84,17 @@ enum { MOQE_LAUNCH_AUTO = 0, MOQE_LAUNCH_SEPARATE = 1, MOQE_LAUNCH_FUSED = 2 };
 int moqe_set_launch_mode(int mode);
 
 /* Path choice inside the expert FFN (process-wide, for tuning and tests; results are within
- * the same tolerance either way): expert segments with at least n tokens are computed by the
- * tiled MFMA kernel (token rows staged in LDS, 64-token tiles), smaller ones by the
- * dequantize-in-register decode kernel.  Default MOQE_PREFILL_MIN_TOKENS_DEFAULT; a huge n
+ * the same tolerance either way): in a batch of at least min_batch_tokens tokens, expert
+ * segments with at least min_segment_tokens tokens are computed by the tiled MFMA kernel (token
+ * rows staged in LDS, 64-token tiles), all other segments by the dequantize-in-register decode
+ * kernel.  Smaller batches do not launch the tiled kernel at all (a decode step would pay a
+ * launch for segments that almost never exist).  Defaults below; a huge min_batch_tokens
  * switches the tiled kernel off.  The tiled kernel needs K a multiple of 128 (int4) or 256
  * (int2, int3); other layers use the decode kernel throughout.  Launch mode FUSED uses the
- * decode kernel for everything it chains.  Returns the previous n, or -1 for n < 1. */
-#define MOQE_PREFILL_MIN_TOKENS_DEFAULT 5
-int moqe_set_prefill_min_tokens(int n);
+ * decode kernel for everything it chains.  Returns 0, or -1 (nothing changed) if a value < 1. */
+#define MOQE_PREFILL_MIN_SEGMENT_DEFAULT 5
+#define MOQE_PREFILL_MIN_BATCH_DEFAULT 65
+int moqe_set_prefill_policy(int min_segment_tokens, int min_batch_tokens);
 
 /* Bytes of one packed [K,N] matrix = K*N*bits/8 (Table 2: exactly `bits` bits
  * per expert weight).  Returns 0 for an unsupported (bits, K, N). Host only. */

@@ -47,7 +47,8 @@ std::atomic<int> g_launch_mode{MOQE_LAUNCH_AUTO};
 // Expert segments with at least this many tokens go to the tiled MFMA kernel.  The decode
 // kernel re-streams an expert's weights once per 4 tokens; from a handful of such passes on,
 // one pass of the tiled kernel (64-token tiles) is cheaper.
-std::atomic<int> g_prefill_min{MOQE_PREFILL_MIN_TOKENS_DEFAULT};
+std::atomic<int> g_prefill_min{MOQE_PREFILL_MIN_SEGMENT_DEFAULT};
+std::atomic<int> g_prefill_batch{MOQE_PREFILL_MIN_BATCH_DEFAULT};
 
 }  // namespace
 
@@ -70,9 +71,11 @@ const char* moqe_last_hip_error(void) { return g_hip_error; }
 
 int moqe_version(void) { return 1; }
 
-int moqe_set_prefill_min_tokens(int n) {
-  if (n < 1) return -1;
-  return g_prefill_min.exchange(n);
+int moqe_set_prefill_policy(int min_segment_tokens, int min_batch_tokens) {
+  if (min_segment_tokens < 1 || min_batch_tokens < 1) return -1;
+  g_prefill_min.store(min_segment_tokens);
+  g_prefill_batch.store(min_batch_tokens);
+  return 0;
 }
 
 int moqe_set_launch_mode(int mode) {
@@ -255,7 +258,7 @@ static void set_ffn2(DecodeArgs* a, const moqe_layer* L, const moqe_f16* h, cons
 static hipError_t launch_contraction(DecodeArgs& a, int phase, int ksteps, hipStream_t stream) {
   const PhaseArgs& p = a.ph[phase];
   const int pmin = g_prefill_min.load();
-  const bool split = a.T >= pmin && moqe_prefill_supported(a.bits, p.K, p.N);
+  const bool split = a.T >= pmin && a.T >= g_prefill_batch.load() && moqe_prefill_supported(a.bits, p.K, p.N);
   a.ksteps = ksteps;
   a.phase_mask = 2 << phase;
   a.min_tokens = 1;

@@ -318,7 +318,6 @@ __global__ __launch_bounds__(SMALL_THREADS) void route_small_kernel(const half_t
 #pragma unroll
     for (int ni = 0; ni < NT; ++ni) acc[mi][ni] = float4_t{0, 0, 0, 0};
 
-#pragma unroll 2
   for (int s = 0; s < steps; ++s) {
     const int k0 = (wave * steps + s) * 32 + 8 * g;  // this lane's 8 rows of d
     half8_t a[MT];

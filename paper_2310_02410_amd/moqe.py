@@ -26,7 +26,7 @@ EXPORTS = (
     "moqe_ffn_workspace_bytes", "moqe_quantize", "moqe_unpack", "moqe_route",
     "moqe_route_logits", "moqe_expert_ffn", "moqe_expert_ffn1", "moqe_expert_ffn2",
     "moqe_layer_workspace_bytes", "moqe_moe_layer", "moqe_set_launch_mode",
-    "moqe_set_prefill_min_tokens",
+    "moqe_set_prefill_policy",
 )
 
 LAUNCH_AUTO, LAUNCH_SEPARATE, LAUNCH_FUSED = 0, 1, 2
@@ -69,8 +69,8 @@ def lib() -> ctypes.CDLL:
     L.moqe_version.restype = ci
     L.moqe_set_launch_mode.restype = ci
     L.moqe_set_launch_mode.argtypes = [ci]
-    L.moqe_set_prefill_min_tokens.restype = ci
-    L.moqe_set_prefill_min_tokens.argtypes = [ci]
+    L.moqe_set_prefill_policy.restype = ci
+    L.moqe_set_prefill_policy.argtypes = [ci, ci]
     L.moqe_packed_bytes.restype = sz
     L.moqe_packed_bytes.argtypes = [ci, i64, i64]
     L.moqe_check_matrix.restype = ci
@@ -151,12 +151,15 @@ def moqe_set_launch_mode(mode: int) -> int:
     return old
 
 
-def moqe_set_prefill_min_tokens(n: int) -> int:
-    """Process-wide: expert segments with at least n tokens take the tiled MFMA kernel; returns the old n."""
-    old = lib().moqe_set_prefill_min_tokens(n)
-    if old < 0:
-        raise ValueError(f"bad threshold {n}")
-    return old
+PREFILL_MIN_SEGMENT_DEFAULT, PREFILL_MIN_BATCH_DEFAULT = 5, 65
+
+
+def moqe_set_prefill_policy(min_segment_tokens: int = PREFILL_MIN_SEGMENT_DEFAULT,
+                            min_batch_tokens: int = PREFILL_MIN_BATCH_DEFAULT) -> None:
+    """Process-wide path choice: in batches of at least min_batch_tokens, expert segments with at
+    least min_segment_tokens tokens take the tiled MFMA kernel.  No arguments: the defaults."""
+    if lib().moqe_set_prefill_policy(min_segment_tokens, min_batch_tokens) != 0:
+        raise ValueError("thresholds must be >= 1")
 
 
 def alloc_workspace(nbytes: int, device) -> torch.Tensor:

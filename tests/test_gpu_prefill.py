@@ -15,15 +15,14 @@ pytestmark = pytest.mark.gpu
 
 @pytest.fixture
 def prefill_min():
-    """Sets the segment-size threshold of the path choice for one test and restores it."""
-    saved = []
+    """Sets the path-choice thresholds for one test (any batch size may use the tiled kernel)
+    and restores the defaults afterwards."""
 
     def set_min(n):
-        saved.append(moqe.moqe_set_prefill_min_tokens(n))
+        moqe.moqe_set_prefill_policy(n, 1)
 
     yield set_min
-    if saved:
-        moqe.moqe_set_prefill_min_tokens(saved[0])
+    moqe.moqe_set_prefill_policy()
 
 
 def _parity(wl, bits, residual=False, forced=None, layer=None):
@@ -67,8 +66,8 @@ def test_tiled_kernel_residual_and_odd_widths(prefill_min, bits):
 
 
 @pytest.mark.parametrize("bits", (4, 2))
-def test_forced_segment_sizes(prefill_min, bits):
-    """Segments of exactly 4, 5, 63, 64, 65 and 200 tokens at the default threshold (5): the
+def test_forced_segment_sizes(bits):
+    """Segments of exactly 4, 5, 63, 64, 65 and 200 tokens at the default thresholds: the
     first goes to the decode kernel, the others to the tiled one, with full and ragged tiles."""
     wl = W.small(E=8, d=256, f=512, T=4 + 5 + 63 + 64 + 65 + 200, seed=84)
     sizes = (4, 5, 63, 64, 65, 200, 0, 0)
@@ -81,7 +80,7 @@ def test_forced_segment_sizes(prefill_min, bits):
 
 
 def test_mixed_paths_under_zipf_load():
-    """Zipf load at the default threshold: large segments go to the tiled kernel, small ones
+    """Zipf load at the default thresholds: large segments go to the tiled kernel, small ones
     to the decode kernel, some experts stay empty; both kernels write disjoint rows of h and y."""
     wl = W.small(E=16, d=256, f=512, T=200, routing="zipf", n_empty=3, seed=85)
     for bits in (4, 3, 2):
@@ -96,7 +95,7 @@ def test_threshold_does_not_change_results_beyond_tolerance(prefill_min):
     xd = dev(x)
     r = moqe.moqe_route(xd, ql.w_gate)
     outs = []
-    for n in (1, 5, 1 << 30):
+    for n in (1, 5, 1 << 20):
         prefill_min(n)
         outs.append(moqe.moqe_expert_ffn(ql, xd, r).cpu().numpy().astype(np.float64))
     scale = np.abs(outs[2]).max()
