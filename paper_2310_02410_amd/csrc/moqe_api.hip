@@ -283,7 +283,7 @@ static hipError_t launch_contraction(DecodeArgs& a, int phase, int ksteps, hipSt
   q.seg_offsets = a.seg_offsets;
   q.perm = a.perm;
   q.gate = a.gate;
-  return moqe_launch_prefill(q, stream);
+  return moqe_launch_prefill(q, num_cus(), stream);
 }
 
 // Unit counts are 32-bit inside the kernel.

@@ -13,13 +13,17 @@
 //          WM = 2: 128 channels, 2 token halves x 2 channel halves, a wave owns 32 tokens x 64
 //                  channels (2 x 4 tiles) - narrow matrices (FFN2), so that the grid still
 //                  fills the chip
-//   K runs in blocks of one packed chunk (128 rows for int4, 256 for int2/int3):
+//   The grid is persistent (3 workgroups per compute unit); a workgroup walks over its tiles.
+//   K runs in staged blocks of 128 rows:
 //     - the block's 64 token rows are staged in LDS (double buffered, loaded one block ahead
 //       through registers) and every wave reads its A fragments from there;
-//     - each wave loads the chunk of each of its 4 column tiles with one 16-byte load per lane
-//       (the packed layout is already in B-operand order), one block ahead, and dequantizes in
-//       registers: the unpack of one B fragment is amortized over the 2 token tiles, and the
-//       fragment never has to travel through LDS because no other wave needs it.
+//     - each wave loads the packed chunk (128 rows for int4, 256 for int2/int3) of each of its
+//       4 column tiles with one 16-byte load per lane (the packed layout is already in B-operand
+//       order), one chunk ahead, and dequantizes in registers: the unpack of one B fragment is
+//       amortized over the wave's token tiles, and the fragment never has to travel through LDS
+//       because no other wave needs it;
+//     - the stream of blocks runs on across tile boundaries, so a tile's first operands arrive
+//       while the previous tile's results are being written.
 //   The unpack brings every field down to the signed code exactly (one packed subtract per
 //   register more than the decode kernel's unpack, which leaves exponent and zero-point offsets
 //   in the K-sum and removes them afterwards: over a whole K of all-positive activations that
@@ -29,38 +33,48 @@
 #include "moqe_kernels.h"
 #include "moqe_unpack.h"
 
+#include <type_traits>
+
 namespace {
 
 constexpr int PF_THREADS = 256;
-constexpr int PF_TILE_M = 64;   // tokens per workgroup
-constexpr int PF_NT = 4;        // column tiles (of 16 channels) per wave
+constexpr int PF_TILE_M = 64;    // tokens per workgroup tile
+constexpr int PF_NT = 4;         // column tiles (of 16 channels) per wave
+constexpr int PF_KB = 128;       // rows of K staged in LDS at a time
+constexpr int PF_WG_PER_CU = 3;  // persistent workgroups per compute unit
 constexpr int PF_MAX_E = 1024;
 
+struct PfTile {
+  int e, cb, row0, rows;
+  bool valid;
+};
+
 template <int BITS, int WM>
-__global__ __launch_bounds__(PF_THREADS, 2) void moe_prefill_kernel(PrefillArgs A) {
-  constexpr int WN = 4 / WM;                 // waves side by side along the channels
+__global__ __launch_bounds__(PF_THREADS, PF_WG_PER_CU) void moe_prefill_kernel(PrefillArgs A) {
+  constexpr int WN = 4 / WM;                  // waves side by side along the channels
   constexpr int PF_MT = PF_TILE_M / 16 / WM;  // token tiles per wave
-  constexpr int PF_TILE_CT = WN * PF_NT;      // column tiles per workgroup
-  constexpr int SC = BITS == 4 ? 4 : 8;       // steps of 32 rows per K block (= one packed chunk)
-  constexpr int KC = 32 * SC;                 // rows of K per block
+  constexpr int PF_TILE_CT = WN * PF_NT;      // column tiles per workgroup tile
+  constexpr int SC = BITS == 4 ? 4 : 8;       // steps of 32 rows per packed chunk
+  constexpr int SUB = SC / 4;                 // staged K blocks per packed chunk
   constexpr int LO_BITS = BITS == 3 ? 2 : BITS;
   constexpr int LW = SC * LO_BITS / 4;        // main-plane words per lane per chunk (4)
   constexpr int HW = BITS == 3 ? SC / 4 : 0;  // 1-bit-plane words per lane per chunk
   constexpr int CHUNK_BYTES = 64 * SC * BITS;
-  constexpr int ROW_PIECES = KC / 8 + 4;      // 16-byte pieces per staged row: data + 64 bytes of padding
-  constexpr int NP = PF_TILE_M * (KC / 8) / PF_THREADS;  // pieces each thread moves per block
+  constexpr int ROW_PIECES = PF_KB / 8 + 4;   // 16-byte pieces per staged row: data + 64 bytes of padding
+  constexpr int NP = PF_TILE_M * (PF_KB / 8) / PF_THREADS;  // pieces each thread moves per block
 
   __shared__ uint4_t s_a[2][PF_TILE_M][ROW_PIECES];
   __shared__ int s_incl[PF_MAX_E];
-  __shared__ long long s_rowoff[PF_TILE_M];
+  __shared__ long long s_rowoff[2][PF_TILE_M];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = uniform_i32(tid >> 6);
   const int wm = wave % WM, wn = wave / WM;
   const int g = lane >> 4, j = lane & 15;
   const int E = A.E, K = A.K, N = A.N;
+  const int G = (int)gridDim.x, bid = (int)blockIdx.x;
 
-  // ---- which pair is this workgroup's?  inclusive prefix of token tiles per expert ----
+  // ---- inclusive prefix of token tiles per expert: pair index -> expert ----
   if (wave == 0) {
     int carry = 0;
     for (int eg = 0; eg < E; eg += 64) {
@@ -79,87 +93,94 @@ __global__ __launch_bounds__(PF_THREADS, 2) void moe_prefill_kernel(PrefillArgs 
     }
   }
   __syncthreads();
-  const int P = s_incl[E - 1];
-  const int p = (int)(blockIdx.x / (unsigned)A.n_cblocks);
-  const int cb = (int)(blockIdx.x % (unsigned)A.n_cblocks);
-  if (p >= P) return;  // the grid is an upper bound on the number of pairs
-  int lo = 0, hi = E - 1;
-  while (lo < hi) {
-    const int mid = (lo + hi) >> 1;
-    if (s_incl[mid] > p) hi = mid; else lo = mid + 1;
-  }
-  const int e = uniform_i32(lo);
-  const int first = e > 0 ? s_incl[e - 1] : 0;
-  const int seg0 = A.seg_offsets[e];
-  const int n_e = A.seg_offsets[e + 1] - seg0;
-  const int row0 = seg0 + PF_TILE_M * (p - first);
-  const int rows = min(PF_TILE_M, n_e - PF_TILE_M * (p - first));
+  const int n_tiles = s_incl[E - 1] * A.n_cblocks;
+  if (bid >= n_tiles) return;
 
-  // element offset of each token row in `a`; the rows a ragged tile lacks repeat its last row
-  // (their results are never stored)
-  if (tid < PF_TILE_M) {
-    const int r = min(tid, rows - 1);
-    s_rowoff[tid] = (long long)(A.mode == 0 ? A.perm[row0 + r] : row0 + r) * K;
-  }
-  __syncthreads();
-
+  const int CT = N >> 4;
+  const int Q = K / (32 * SC);   // packed chunks per column tile
+  const int TB = Q * SUB;        // staged blocks per tile
+  const int64_t matrix_bytes = (int64_t)K * N * BITS / 8;
+  const uint32_t lane_lo = (uint32_t)lane * LW * 4, lane_hi = (64u * LW + (uint32_t)lane * HW) * 4;
   UnpackConsts<BITS> uc;
   uc.init();
-  const int CT = N >> 4;
-  const int Q = K / KC;  // K blocks = chunks per column tile
-  const int64_t matrix_bytes = (int64_t)K * N * BITS / 8;
-  // this wave's column tiles; a tile past the matrix gets an empty descriptor and loads nothing
-  rsrc_t brs[PF_NT];
+
+  // Finds tile `tile` (pair, column block) and leaves the element offsets of its token rows in
+  // s_rowoff[slot]; the rows a ragged tile lacks repeat its last row (never stored).
+  auto setup = [&](int tile, int slot) -> PfTile {
+    PfTile t;
+    t.valid = tile < n_tiles;
+    t.e = 0; t.cb = 0; t.row0 = 0; t.rows = 1;
+    if (!t.valid) return t;
+    const int p = tile / A.n_cblocks;
+    t.cb = tile - p * A.n_cblocks;
+    int lo = 0, hi = E - 1;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (s_incl[mid] > p) hi = mid; else lo = mid + 1;
+    }
+    t.e = uniform_i32(lo);
+    const int first = t.e > 0 ? s_incl[t.e - 1] : 0;
+    const int seg0 = A.seg_offsets[t.e];
+    const int n_e = A.seg_offsets[t.e + 1] - seg0;
+    t.row0 = seg0 + PF_TILE_M * (p - first);
+    t.rows = min(PF_TILE_M, n_e - PF_TILE_M * (p - first));
+    if (tid < PF_TILE_M) {
+      const int r = t.row0 + min(tid, t.rows - 1);
+      s_rowoff[slot][tid] = (long long)(A.mode == 0 ? A.perm[r] : r) * K;
+    }
+    return t;
+  };
+  // descriptors of a tile's column tiles for this wave; past the matrix (or no tile): empty
+  auto make_brs = [&](const PfTile& t, rsrc_t (&brs)[PF_NT]) {
 #pragma unroll
-  for (int ni = 0; ni < PF_NT; ++ni) {
-    const int ct = cb * PF_TILE_CT + wn * PF_NT + ni;
-    const bool ok = ct < CT;
-    const char* base = (const char*)A.codes + (int64_t)e * matrix_bytes + (int64_t)(ok ? ct : 0) * Q * CHUNK_BYTES;
-    brs[ni] = make_rsrc(base, ok ? (uint32_t)Q * CHUNK_BYTES : 0u);
-  }
-  const uint32_t lane_lo = (uint32_t)lane * LW * 4, lane_hi = (64u * LW + (uint32_t)lane * HW) * 4;
+    for (int ni = 0; ni < PF_NT; ++ni) {
+      const int ct = t.cb * PF_TILE_CT + wn * PF_NT + ni;
+      const bool ok = t.valid && ct < CT;
+      const char* base = (const char*)A.codes + (int64_t)t.e * matrix_bytes + (int64_t)(ok ? ct : 0) * Q * CHUNK_BYTES;
+      brs[ni] = make_rsrc(base, ok ? (uint32_t)Q * CHUNK_BYTES : 0u);
+    }
+  };
 
   uint32_t b_lo[2][PF_NT][LW];
   uint32_t b_hi[2][PF_NT][HW > 0 ? HW : 1];
   uint4_t a_next[NP];
+  float4_t acc[PF_MT][PF_NT];
 
-  auto load_b = [&](int buf, int kb) {
+  auto load_b = [&](auto BUF, const rsrc_t (&brs)[PF_NT], int c) {
+    constexpr int buf = decltype(BUF)::value;
 #pragma unroll
     for (int ni = 0; ni < PF_NT; ++ni) {
-      load_words<LW>(brs[ni], (uint32_t)kb * CHUNK_BYTES + lane_lo, b_lo[buf][ni]);
-      if constexpr (BITS == 3) load_words<HW>(brs[ni], (uint32_t)kb * CHUNK_BYTES + lane_hi, b_hi[buf][ni]);
+      load_words<LW>(brs[ni], (uint32_t)c * CHUNK_BYTES + lane_lo, b_lo[buf][ni]);
+      if constexpr (BITS == 3) load_words<HW>(brs[ni], (uint32_t)c * CHUNK_BYTES + lane_hi, b_hi[buf][ni]);
     }
   };
-  auto load_a = [&](int kb) {
+  auto load_a = [&](int slot, int blk) {
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
       const int q = tid + PF_THREADS * i;
-      const int row = q / (KC / 8), pc = q % (KC / 8);
-      a_next[i] = *(const uint4_t*)((const half_t*)A.a + s_rowoff[row] + (int64_t)kb * KC + pc * 8);
+      const int row = q / (PF_KB / 8), pc = q % (PF_KB / 8);
+      a_next[i] = *(const uint4_t*)((const half_t*)A.a + s_rowoff[slot][row] + (int64_t)blk * PF_KB + pc * 8);
     }
   };
   auto store_a = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
       const int q = tid + PF_THREADS * i;
-      s_a[buf][q / (KC / 8)][q % (KC / 8)] = a_next[i];
+      s_a[buf][q / (PF_KB / 8)][q % (PF_KB / 8)] = a_next[i];
     }
   };
-
-  float4_t acc[PF_MT][PF_NT];
+  // the four steps of staged block `sub` of the chunk held in B buffer BUF
+  auto compute = [&](int abuf, auto BUF, auto SUBI) {
+    constexpr int bbuf = decltype(BUF)::value;
+    constexpr int sub = decltype(SUBI)::value;
 #pragma unroll
-  for (int mi = 0; mi < PF_MT; ++mi) {
-#pragma unroll
-    for (int ni = 0; ni < PF_NT; ++ni) acc[mi][ni] = float4_t{0, 0, 0, 0};
-  }
-
-  auto compute = [&](int abuf, int bbuf) {
-#pragma unroll
-    for (int s = 0; s < SC; ++s) {
+    for (int s4 = 0; s4 < 4; ++s4) {
+      constexpr int s0 = 4 * sub;
+      const int s = s0 + s4;  // step within the chunk (compile-time after unrolling)
       half8_t a[PF_MT];
 #pragma unroll
       for (int mi = 0; mi < PF_MT; ++mi)
-        a[mi] = __builtin_bit_cast(half8_t, s_a[abuf][16 * PF_MT * wm + 16 * mi + j][4 * s + g]);
+        a[mi] = __builtin_bit_cast(half8_t, s_a[abuf][16 * PF_MT * wm + 16 * mi + j][4 * s4 + g]);
 #pragma unroll
       for (int ni = 0; ni < PF_NT; ++ni) {
         half8_t w;
@@ -180,61 +201,93 @@ __global__ __launch_bounds__(PF_THREADS, 2) void moe_prefill_kernel(PrefillArgs 
     }
   };
 
-  // ---- K loop: block kb + 1 is fetched while block kb is multiplied ----
-  load_a(0);
-  load_b(0, 0);
+  // ---- the workgroup's tiles, as one continuous stream of staged blocks ----
+  // While block t is multiplied, block t + 1 is on its way (token rows through registers into
+  // the other LDS buffer, packed chunks into the other register buffer) - also across the end
+  // of a tile, so that the next tile's first operands arrive during this tile's epilogue.
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+  PfTile cur = setup(bid, 0);
+  __syncthreads();
+  rsrc_t cur_brs[PF_NT], nxt_brs[PF_NT];
+  make_brs(cur, cur_brs);
+  load_a(0, 0);
+  load_b(I0{}, cur_brs, 0);
   store_a(0);
   __syncthreads();
-  for (int kb = 0; kb < Q; kb += 2) {
-    // even block: A buffer 0, B buffer 0; fetch into 1
-    const bool more1 = kb + 1 < Q;
-    if (more1) {
-      load_a(kb + 1);
-      load_b(1, kb + 1);
-    }
-    compute(0, 0);
-    if (more1) store_a(1);
-    __syncthreads();
-    if (!more1) break;
-    // odd block
-    const bool more2 = kb + 2 < Q;
-    if (more2) {
-      load_a(kb + 2);
-      load_b(0, kb + 2);
-    }
-    compute(1, 1);
-    if (more2) store_a(0);
-    __syncthreads();
-  }
+  int gblk = 0;                     // blocks done so far: block t lives in LDS buffer t & 1
+  const bool cross = (Q & 1) == 0;  // with an even chunk count the chunk stream crosses tiles too
 
-  // ---- epilogue: D lane (g, j), register r = token row 4 g + r of the tile, channel j ----
+  for (int it = 0; cur.valid; ++it) {
+    const int slot = it & 1;
+    const PfTile nxt = setup(bid + (it + 1) * G, slot ^ 1);
+    __syncthreads();
+    make_brs(nxt, nxt_brs);
 #pragma unroll
-  for (int ni = 0; ni < PF_NT; ++ni) {
-    const int ct = cb * PF_TILE_CT + wn * PF_NT + ni;
-    if (ct >= CT) continue;
-    const int col = 16 * ct + j;
-    const float sc = (float)half_from_bits(A.scales[(int64_t)e * N + col]);
-    const float bi = (float)half_from_bits(A.bias[(int64_t)e * N + col]);
+    for (int mi = 0; mi < PF_MT; ++mi)
 #pragma unroll
-    for (int mi = 0; mi < PF_MT; ++mi) {
+      for (int ni = 0; ni < PF_NT; ++ni) acc[mi][ni] = float4_t{0, 0, 0, 0};
+
+    auto do_chunk = [&](int c, auto BUF) {
+      constexpr int bbuf = decltype(BUF)::value;
+      using OTHER = std::integral_constant<int, 1 - bbuf>;
+      if (c + 1 < Q) {
+        load_b(OTHER{}, cur_brs, c + 1);
+      } else if (bbuf == 1) {
+        load_b(OTHER{}, nxt_brs, 0);  // first chunk of the next tile (empty descriptors if none)
+      }
+      auto do_block = [&](auto SUBI) {
+        constexpr int sub = decltype(SUBI)::value;
+        const int blk = c * SUB + sub;
+        const bool last = blk + 1 == TB;
+        if (!last) load_a(slot, blk + 1);
+        else if (nxt.valid) load_a(slot ^ 1, 0);
+        compute(gblk & 1, BUF, SUBI);
+        if (!last || nxt.valid) store_a((gblk + 1) & 1);
+        __syncthreads();
+        ++gblk;
+      };
+      do_block(I0{});
+      if constexpr (SUB == 2) do_block(I1{});
+    };
+    for (int c = 0; c < Q; c += 2) {
+      do_chunk(c, I0{});
+      if (c + 1 < Q) do_chunk(c + 1, I1{});
+    }
+    if (!cross && nxt.valid) load_b(I0{}, nxt_brs, 0);
+
+    // ---- epilogue: D lane (g, j), register r = token row 4 g + r of the tile, channel j ----
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int row = 16 * PF_MT * wm + 16 * mi + 4 * g + r;
-        if (row >= rows) continue;
-        float o = fmaf(acc[mi][ni][r], sc, bi);
-        const int srow = row0 + row;
-        if (A.mode == 0) {
-          o = fmaxf(o, 0.0f);
-          ((half_t*)A.out)[(int64_t)srow * N + col] = (half_t)o;
-        } else {
-          const int tk = A.perm[srow];
-          float v = A.gate[tk] * o;
-          const int64_t at = (int64_t)tk * N + col;
-          if (A.residual) v += (float)((const half_t*)A.residual)[at];
-          ((half_t*)A.out)[at] = (half_t)v;
+    for (int ni = 0; ni < PF_NT; ++ni) {
+      const int ct = cur.cb * PF_TILE_CT + wn * PF_NT + ni;
+      if (ct >= CT) continue;
+      const int col = 16 * ct + j;
+      const float sc = (float)half_from_bits(A.scales[(int64_t)cur.e * N + col]);
+      const float bi = (float)half_from_bits(A.bias[(int64_t)cur.e * N + col]);
+#pragma unroll
+      for (int mi = 0; mi < PF_MT; ++mi) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int row = 16 * PF_MT * wm + 16 * mi + 4 * g + r;
+          if (row >= cur.rows) continue;
+          float o = fmaf(acc[mi][ni][r], sc, bi);
+          const int srow = cur.row0 + row;
+          if (A.mode == 0) {
+            o = fmaxf(o, 0.0f);
+            ((half_t*)A.out)[(int64_t)srow * N + col] = (half_t)o;
+          } else {
+            const int tk = A.perm[srow];
+            float v = A.gate[tk] * o;
+            const int64_t at = (int64_t)tk * N + col;
+            if (A.residual) v += (float)((const half_t*)A.residual)[at];
+            ((half_t*)A.out)[at] = (half_t)v;
+          }
         }
       }
     }
+    cur = nxt;
+#pragma unroll
+    for (int ni = 0; ni < PF_NT; ++ni) cur_brs[ni] = nxt_brs[ni];
   }
 }
 
@@ -246,26 +299,27 @@ bool moqe_prefill_supported(int bits, int64_t K, int64_t N) {
 }
 
 template <int BITS>
-static void launch_bits(const PrefillArgs& a, int64_t pairs, hipStream_t stream) {
+static void launch_bits(const PrefillArgs& a, int64_t pairs, int num_cus, hipStream_t stream) {
   // Only the 128-channel workgroup shape is launched.  The 256-channel shape (WM = 1: 4 x 4
-  // accumulator tiles per wave) does not fit 256 registers without spilling and measured
-  // slower on the 4096-token stack (112 vs 84 us for FFN1).
+  // accumulator tiles per wave) does not fit the register file without spilling and measured
+  // slower on the 4096-token stack.
   PrefillArgs args = a;
   args.n_cblocks = (a.N / 16 + 7) / 8;
-  hipLaunchKernelGGL((moe_prefill_kernel<BITS, 2>), dim3((unsigned)(pairs * args.n_cblocks)), dim3(PF_THREADS), 0,
-                     stream, args);
+  int64_t grid = pairs * args.n_cblocks;  // upper bound on the tiles
+  if (grid > (int64_t)PF_WG_PER_CU * num_cus) grid = (int64_t)PF_WG_PER_CU * num_cus;
+  hipLaunchKernelGGL((moe_prefill_kernel<BITS, 2>), dim3((unsigned)grid), dim3(PF_THREADS), 0, stream, args);
 }
 
-hipError_t moqe_launch_prefill(const PrefillArgs& a, hipStream_t stream) {
+hipError_t moqe_launch_prefill(const PrefillArgs& a, int num_cus, hipStream_t stream) {
   // upper bound on the number of (expert, 64-token tile) pairs
   const int64_t with_pairs = a.min_tokens > 0 ? a.T / a.min_tokens : a.E;
   const int64_t pairs = a.T / PF_TILE_M + (with_pairs < a.E ? with_pairs : a.E);
   if (pairs <= 0) return hipSuccess;
   if (pairs * ((a.N / 16 + 7) / 8) >= (1ll << 31)) return hipErrorInvalidValue;
   switch (a.bits) {
-    case 4: launch_bits<4>(a, pairs, stream); break;
-    case 3: launch_bits<3>(a, pairs, stream); break;
-    case 2: launch_bits<2>(a, pairs, stream); break;
+    case 4: launch_bits<4>(a, pairs, num_cus, stream); break;
+    case 3: launch_bits<3>(a, pairs, num_cus, stream); break;
+    case 2: launch_bits<2>(a, pairs, num_cus, stream); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

@@ -81,7 +81,7 @@ struct PrefillArgs {
   const float* gate;
 };
 bool moqe_prefill_supported(int bits, int64_t K, int64_t N);
-hipError_t moqe_launch_prefill(const PrefillArgs& a, hipStream_t stream);
+hipError_t moqe_launch_prefill(const PrefillArgs& a, int num_cus, hipStream_t stream);
 
 // Dequantize-in-register path for few tokens per expert (tiles of 4 tokens).
 hipError_t moqe_launch_decode(const DecodeArgs& a, int num_cus, hipStream_t stream);
