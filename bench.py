@@ -3,15 +3,19 @@
 
 A step is one pass of the whole hot path over one batch: moqe_moe_layer, i.e. top-1
 gating, histogram, scan, permutation, then FFN1 + bias + ReLU, FFN2 + bias and the
-gate-weighted combine (four kernel launches) on one MoE layer of the decode configuration
-(E=32 experts, d_model 1024, d_ff 4096, batch of 24 tokens, int4 experts).
+gate-weighted combine, on one MoE layer.  The default workload is the decode
+configuration the metric is quoted on (c1: E=32 experts, d_model 1024, d_ff 4096, batch
+of 24 tokens, int4 experts: three kernel launches per step); --workload selects the
+other configurations (c3: 1536 tokens under Zipf load; c4_*: a layer of the 12-layer
+int2 stack with the residual add, at 24 or 4096 tokens).
 Consecutive steps use different layer copies (own weights, own router) so that the
-packed weights of a step are not left in the 256 MB last-level cache by the
-previous one: the weights really come from HBM.
+packed weights of a step are not left in the 256 MB last-level cache by the previous
+one: the weights really come from HBM.
 
 Prints ONE JSON line: tokens/s (metric), ms per step, the roofline of the dominant
-kernel (algorithmic bytes / measured kernel time, against the 8 TB/s HBM peak) and
-the CPU oracle timed on the host's cores on a bounded sample of the same workload.
+kernel (algorithmic bytes or flops per launch / measured kernel time, against the
+8 TB/s HBM peak or the 2.5 PFLOP/s fp16 MFMA peak) and the CPU oracle timed on the
+host's cores on a bounded sample of the same workload.
 """
 
 from __future__ import annotations
@@ -30,12 +34,13 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_F16_PEAK_TFLOPS = 2500.0
 
-# HBM traffic per launch of the dominant kernel (FFN1) measured with rocprofv3 --pmc
+# HBM traffic per launch of the dominant kernel (FFN1 of c1) measured with rocprofv3 --pmc
 # (FETCH_SIZE and WRITE_SIZE runs of this script, scaled by a 256 MiB device copy in the
 # same run: FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); from profiles/decode_c1_int4_hbm_traffic.txt.
-# Not measured for the other bit widths.
-MEASURED_TRAFFIC_BYTES = {4: 35390084, 3: None, 2: None}
+# Not measured for the other workloads and bit widths.
+MEASURED_TRAFFIC_BYTES = {("c1", 4): 35390084}
 
 
 def parse():
@@ -43,29 +48,33 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--bits", type=int, default=4, choices=(2, 3, 4), help="bit width of the headline line")
-    ap.add_argument("--copies", type=int, default=8, help="independent layer copies cycled through")
+    ap.add_argument("--workload", default="c1",
+                    choices=("c1", "c2", "c3", "c4_T24_uniform", "c4_T24_zipf", "c4_T4096_uniform", "c4_T4096_zipf"))
+    ap.add_argument("--bits", type=int, default=None, choices=(2, 3, 4),
+                    help="bit width of the headline line (default: the workload's own)")
+    ap.add_argument("--copies", type=int, default=None, help="independent layer copies cycled through "
+                    "(default 8; 12 for the c4 stack: its 12 layers)")
     ap.add_argument("--other-bits", action="store_true", help="also time the other two bit widths")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-steps", type=int, default=8)
+    ap.add_argument("--cpu-steps", type=int, default=None, help="oracle steps timed (default 8; 1 from 512 tokens on)")
+    ap.add_argument("--no-graph", action="store_true", help="time eager launches only")
+    ap.add_argument("--parts", action="store_true", help="also time each kernel of the step on its own")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run three plain device-to-device copies of this size first: under "
                          "rocprofv3 --pmc they give the counter reading of a known amount of traffic")
-    ap.add_argument("--no-graph", action="store_true", help="time eager launches only")
-    ap.add_argument("--parts", action="store_true", help="also time each kernel of the step on its own")
     return ap.parse_args()
 
 
-def algorithmic_bytes(seg_offsets, bits, d, f, T):
+def algorithmic_bytes(seg_offsets, bits, d, f, T, residual):
     """Bytes the method must move for one layer-step, split per contraction.
     Per active expert: packed codes + fp16 scales + fp16 biases of the matrix;
     plus the fp16 activations entering and leaving the layer (x in FFN1, y in
-    FFN2).  The hidden activations h are not counted; the caller adds the router
-    weights (2 d E)."""
+    FFN2, the residual where the layer adds one).  The hidden activations h are
+    not counted; the caller adds the router weights (2 d E)."""
     counts = np.diff(np.asarray(seg_offsets))
     active = int((counts > 0).sum())
     ffn1 = active * (d * f * bits // 8 + 2 * f + 2 * f) + 2 * T * d
-    ffn2 = active * (d * f * bits // 8 + 2 * d + 2 * d) + 2 * T * d
+    ffn2 = active * (d * f * bits // 8 + 2 * d + 2 * d) + 2 * T * d + (2 * T * d if residual else 0)
     return active, ffn1, ffn2
 
 
@@ -88,15 +97,25 @@ def main():
     torch.cuda.set_device(0)
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
-    wl = W.CONFIGS["c1"]
+    variants = dict(W.CONFIGS)
+    variants.update({v.name: v for v in W.c4_variants()})
+    wl = variants[args.workload]
     E, d, f, T = wl.E, wl.d, wl.f, wl.T
-    bit_list = [args.bits] + ([b for b in (4, 3, 2) if b != args.bits] if args.other_bits else [])
+    residual = wl.layers > 1               # the stack adds the layer's output to its input
+    compute_bound = T >= 512               # the tiled MFMA kernel dominates, not the weight stream
+    bits0 = args.bits if args.bits is not None else wl.bits[0]
+    bit_list = [bits0] + ([b for b in (4, 3, 2) if b != bits0] if args.other_bits else [])
+    copies = args.copies if args.copies is not None else (12 if wl.layers > 1 else 8)
+    steps, warmup = args.steps, args.warmup
+    if compute_bound and steps == 400 and warmup == 40:
+        steps, warmup = 100, 10            # defaults sized to keep the timed work near a minute at most
+    cpu_steps = args.cpu_steps if args.cpu_steps is not None else (1 if compute_bound else 8)
 
     # ---- layer copies: generated on the host (seeded), quantized on the device ----
     t0 = time.time()
     layers = {b: [] for b in bit_list}
     layer0_host = None
-    for i in range(args.copies):
+    for i in range(copies):
         host = W.make_layer(wl, layer=i)
         if i == 0:
             layer0_host = host
@@ -106,7 +125,7 @@ def main():
             layers[b].append(moqe.quantize_layer(w1, b1, w2, b2, b, wg))
         del w1, w2
         torch.cuda.synchronize()
-        print(f"[bench] layer copy {i + 1}/{args.copies} ready ({time.time() - t0:.0f}s)", file=sys.stderr, flush=True)
+        print(f"[bench] layer copy {i + 1}/{copies} ready ({time.time() - t0:.0f}s)", file=sys.stderr, flush=True)
     x_host = W.make_tokens(wl)
     x = dev(x_host)
 
@@ -122,7 +141,6 @@ def main():
     route, _ = moqe.alloc_route(T, E, x.device)
     ws = moqe.alloc_workspace(moqe.moqe_layer_workspace_bytes(T, E, d, f), x.device)
     y = torch.empty_like(x)
-
     hbuf = torch.empty((T, f), dtype=torch.float16, device="cuda")
 
     def make_calls(qls):
@@ -131,6 +149,7 @@ def main():
         refs = [ctypes.byref(s) for s in structs]
         gates = [ql.w_gate.data_ptr() for ql in qls]
         xp, yp, hp = x.data_ptr(), y.data_ptr(), hbuf.data_ptr()
+        rp = xp if residual else None
         ip, gp, sp, pp = (route.expert_idx.data_ptr(), route.gate.data_ptr(), route.seg_offsets.data_ptr(),
                           route.perm.data_ptr())
         wsp, wsn = ws.data_ptr(), ws.numel()
@@ -141,14 +160,14 @@ def main():
                 raise RuntimeError(f"{what} failed with status {st}")
 
         def step(i, stream):
-            check(L.moqe_moe_layer(refs[i % n], gates[i % n], xp, T, ip, gp, sp, pp, None, yp, wsp, wsn, stream),
+            check(L.moqe_moe_layer(refs[i % n], gates[i % n], xp, T, ip, gp, sp, pp, rp, yp, wsp, wsn, stream),
                   "moqe_moe_layer")
 
         def ffn1(i, stream):
             check(L.moqe_expert_ffn1(refs[i % n], xp, T, sp, pp, hp, stream), "moqe_expert_ffn1")
 
         def ffn2(i, stream):
-            check(L.moqe_expert_ffn2(refs[i % n], hp, T, gp, sp, pp, None, yp, stream), "moqe_expert_ffn2")
+            check(L.moqe_expert_ffn2(refs[i % n], hp, T, gp, sp, pp, rp, yp, stream), "moqe_expert_ffn2")
 
         def router(i, stream):
             check(L.moqe_route(xp, gates[i % n], T, d, E, ip, gp, sp, pp, wsp, wsn, stream), "moqe_route")
@@ -156,34 +175,33 @@ def main():
         step.keep = (structs, refs)
         return step, ffn1, ffn2, router
 
-    def time_steps(run, steps, warmup):
+    def time_steps(run, nsteps, nwarm):
         """(wall ms per step with a sync on both sides, HIP-event ms per step on the launch stream)"""
-        for i in range(warmup):
+        for i in range(nwarm):
             run(i)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         t = time.perf_counter()
         e0.record()
-        for i in range(steps):
-            run(warmup + i)
+        for i in range(nsteps):
+            run(nwarm + i)
         e1.record()
         torch.cuda.synchronize()
-        return (time.perf_counter() - t) * 1e3 / steps, e0.elapsed_time(e1) / steps
+        return (time.perf_counter() - t) * 1e3 / nsteps, e0.elapsed_time(e1) / nsteps
 
-    def time_graph(run, steps, warmup):
+    def time_graph(run, nsteps, nwarm):
         """The same calls captured once per layer copy into ONE graph (a pass over all copies),
         replayed: launch cost leaves the picture.  Returns event ms per call."""
         side = torch.cuda.Stream()
-        n = args.copies
         with torch.cuda.stream(side):
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g, stream=side):
-                for k in range(n):
+                for k in range(copies):
                     run(k, torch.cuda.current_stream().cuda_stream)
         torch.cuda.synchronize()
-        reps = max(1, steps // n)
-        _, ev = time_steps(lambda i: g.replay(), reps, max(1, warmup // n))
-        return ev / n
+        reps = max(1, nsteps // copies)
+        _, ev = time_steps(lambda i: g.replay(), reps, max(1, nwarm // copies))
+        return ev / copies
 
     results = {}
     for b in bit_list:
@@ -195,49 +213,60 @@ def main():
         for k in range(len(qls)):
             step(k, stream)
             torch.cuda.synchronize()
-            ab.append(algorithmic_bytes(route.seg_offsets.cpu().numpy(), b, d, f, T))
+            ab.append(algorithmic_bytes(route.seg_offsets.cpu().numpy(), b, d, f, T, residual))
         if moqe.workspace_error(ws):
             raise RuntimeError("a phase wait timed out: results invalid")
         # ---- the timed region: K whole steps ----
-        eager_ms, eager_ev_ms = time_steps(lambda i: step(i, stream), args.steps, args.warmup)
-        graph_ms = None if args.no_graph else time_graph(step, args.steps, args.warmup)
+        eager_ms, eager_ev_ms = time_steps(lambda i: step(i, stream), steps, warmup)
+        graph_ms = None if args.no_graph else time_graph(step, steps, warmup)
         # ---- the step's kernels on their own: the same launches through the per-step entry
         # points, K of them back to back between two HIP events on the launch stream.  The
-        # dominant kernel is the expert contraction (FFN1; FFN2 is the same kernel on a matrix
-        # of the same size).  Inside a step the same kernel runs about 2 us longer, because it
-        # starts on an idle chip instead of behind its predecessor's tail; the committed
-        # profile summaries list both populations.
+        # dominant kernel is the expert contraction (FFN1 and FFN2 run the same kernel on
+        # matrices of the same size).  Inside a step the same kernel runs a little longer,
+        # because it starts on an idle chip instead of behind its predecessor's tail; the
+        # committed profile summaries list both populations.
         parts = {}
-        for name, fn in (("router_2_launches", router), ("ffn1", ffn1), ("ffn2", ffn2)):
-            if name != "ffn1" and not args.parts:
+        for name, fn in (("router", router), ("ffn1", ffn1), ("ffn2", ffn2)):
+            if name == "router" and not args.parts:
                 continue
-            _, ev = time_steps(lambda i: fn(i, stream), args.steps, args.warmup)
+            if name == "ffn2" and not (args.parts or compute_bound):
+                continue
+            _, ev = time_steps(lambda i: fn(i, stream), steps, warmup)
             parts[name + "_back_to_back_us"] = ev * 1e3
-        kern_us = parts["ffn1_back_to_back_us"]
         if moqe.workspace_error(ws):
             raise RuntimeError("a phase wait timed out: results invalid")
 
         layer_bytes = float(np.mean([a[1] + a[2] for a in ab])) + 2 * d * E
         ffn1_bytes = float(np.mean([a[1] for a in ab]))
-        # the dominant kernel is the expert contraction (FFN1 and FFN2 are the same kernel on
-        # matrices of the same size)
-        achieved = ffn1_bytes / (kern_us * 1e-6) / 1e9
         best_ms = min(eager_ms, graph_ms) if graph_ms is not None else eager_ms
-        results[b] = dict(
-            ms_per_step=best_ms, eager_ms=eager_ms, graph_ms=graph_ms, tokens_per_s=T / (best_ms * 1e-3),
-            active_experts=float(np.mean([a[0] for a in ab])), layer_bytes=layer_bytes,
-            kernel_us=kern_us, kernel_bytes=ffn1_bytes, achieved_gbs=achieved, parts=parts,
-            step_gbs=layer_bytes / (best_ms * 1e-3) / 1e9)
-        print(f"[bench] int{b}: eager {eager_ms * 1e3:.1f} us/step (events {eager_ev_ms * 1e3:.1f}), graph "
-              f"{(graph_ms or float('nan')) * 1e3:.1f} us/step; ffn1 kernel {kern_us:.1f} us = {achieved:.0f} GB/s over "
-              f"{ffn1_bytes / 1e6:.1f} MB; parts {json.dumps(parts)}", file=sys.stderr, flush=True)
+        res = dict(ms_per_step=best_ms, eager_ms=eager_ms, graph_ms=graph_ms, tokens_per_s=T / (best_ms * 1e-3),
+                   active_experts=float(np.mean([a[0] for a in ab])), layer_bytes=layer_bytes, parts=parts,
+                   step_gbs=layer_bytes / (best_ms * 1e-3) / 1e9, step_tflops=4.0 * T * d * f / (best_ms * 1e-3) / 1e12)
+        if compute_bound:
+            # one launch of the tiled kernel per contraction (plus a decode-kernel launch for the
+            # few small segments, part of the figure): 2 T d f flops each
+            kern_us = 0.5 * (parts["ffn1_back_to_back_us"] + parts["ffn2_back_to_back_us"])
+            flops = 2.0 * T * d * f
+            res.update(bound="mfma", kernel_us=kern_us, kernel_work=flops, achieved=flops / (kern_us * 1e-6) / 1e12,
+                       peak=MFMA_F16_PEAK_TFLOPS, unit="TFLOP/s",
+                       kernel="moe_prefill_kernel<%d,2> (FFN1 and FFN2 launches averaged; each includes the decode "
+                              "kernel's launch for segments below 5 tokens)" % b)
+        else:
+            kern_us = parts["ffn1_back_to_back_us"]
+            res.update(bound="hbm", kernel_us=kern_us, kernel_work=ffn1_bytes,
+                       achieved=ffn1_bytes / (kern_us * 1e-6) / 1e9, peak=HBM_PEAK_GBS, unit="GB/s",
+                       kernel="moe_decode_kernel<%d,32,2> (FFN1; FFN2 is the same kernel on a matrix of the same "
+                              "size)" % b)
+        results[b] = res
+        print(f"[bench] {wl.name} int{b}: eager {eager_ms * 1e3:.1f} us/step (events {eager_ev_ms * 1e3:.1f}), graph "
+              f"{(graph_ms or float('nan')) * 1e3:.1f} us/step; dominant kernel {res['kernel_us']:.1f} us = "
+              f"{res['achieved']:.0f} {res['unit']}; parts {json.dumps(parts)}", file=sys.stderr, flush=True)
 
     # ---- CPU oracle on the host cores: bounded sample of the same workload ----
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import moqe_oracle as O
-        bits = args.bits
-        ql0 = layers[bits][0]
+        ql0 = layers[bits0][0]
         c1, c2 = ql0.codes1.cpu().numpy(), ql0.codes2.cpu().numpy()
         s1, s2 = ql0.scales1.cpu().numpy(), ql0.scales2.cpu().numpy()
         cores = len(os.sched_getaffinity(0))
@@ -248,41 +277,43 @@ def main():
                 self.codes, self.scales, self.K, self.N = codes, scales, K, N
 
             def __getitem__(self, e):
-                return O.dequantize(O.unpack(self.codes[e], bits, self.K, self.N), self.scales[e])
+                return O.dequantize(O.unpack(self.codes[e], bits0, self.K, self.N), self.scales[e])
 
         t = time.perf_counter()
-        for _ in range(args.cpu_steps):
+        for _ in range(cpu_steps):
             idx, gate, offs, perm = O.route(x_host, layer0_host["w_gate"])
             O.expert_ffn(x_host, idx, gate, Lazy(c1, s1, d, f), layer0_host["b1"], Lazy(c2, s2, f, d),
-                         layer0_host["b2"])
+                         layer0_host["b2"], residual=x_host if residual else None)
         dt = time.perf_counter() - t
-        cpu = dict(value=T * args.cpu_steps / dt, unit="tokens/s", cores=cores, kind="oracle",
-                   sample=f"{args.cpu_steps} steps of route + expert FFN on layer copy 0 (T={T}, int{bits}, fp64, "
+        cpu = dict(value=T * cpu_steps / dt, unit="tokens/s", cores=cores, kind="oracle",
+                   sample=f"{cpu_steps} step(s) of route + expert FFN on layer copy 0 (T={T}, int{bits0}, fp64, "
                           f"codes unpacked per call), {dt:.1f} s")
 
-    r = results[args.bits]
+    r = results[bits0]
     out = {
-        "metric": "expert-FFN tokens/s (route + int%d expert FFN, one MoE layer step)" % args.bits,
-        "value": r["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "metric": "expert-FFN tokens/s (route + int%d expert FFN, one MoE layer step)" % bits0,
+        "value": r["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int%d weights x f16 activations, f32 accumulate" % args.bits, "data": "synthetic",
-        "config": {"workload": "c1: E=32 d_model=1024 d_ff=4096 T=24 top-1, int%d per-channel RTN experts, seed 1, "
-                               "%d layer copies cycled" % (args.bits, args.copies),
+        "dtype": "int%d weights x f16 activations, f32 accumulate" % bits0, "data": "synthetic",
+        "config": {"workload": "%s: E=%d d_model=%d d_ff=%d T=%d top-1 (%s load), int%d per-channel RTN experts%s, seed %d, "
+                               "%d layer copies cycled" % (wl.name, E, d, f, T, wl.routing, bits0,
+                                                           ", fp16 residual add" if residual else "", wl.seed, copies),
                    "launch": "hip graph replay" if (r["graph_ms"] is not None and r["graph_ms"] <= r["eager_ms"]) else "eager",
                    "eager_ms_per_step": r["eager_ms"], "graph_ms_per_step": r["graph_ms"],
                    "active_experts": r["active_experts"], "layer_algorithmic_bytes": r["layer_bytes"],
-                   "step_gb_per_s": r["step_gbs"], "launches_per_step": 4, "kernels_us": r["parts"]},
-        "roofline": {"bound": "hbm", "achieved": r["achieved_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": r["achieved_gbs"] / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(args.bits),
-                     "kernel": "moe_decode_kernel<%d,32,2> (FFN1; FFN2 is the same kernel on a matrix of the "
-                               "same size)" % args.bits, "avg_kernel_us": r["kernel_us"],
-                     "algorithmic_bytes_per_launch": r["kernel_bytes"]},
+                   "step_gb_per_s": r["step_gbs"], "step_tflop_per_s": r["step_tflops"], "kernels_us": r["parts"]},
+        "roofline": {"bound": r["bound"], "achieved": r["achieved"], "peak": r["peak"], "unit": r["unit"],
+                     "frac": r["achieved"] / r["peak"], "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, bits0)),
+                     "kernel": r["kernel"], "avg_kernel_us": r["kernel_us"],
+                     ("algorithmic_flops_per_launch" if r["bound"] == "mfma" else "algorithmic_bytes_per_launch"):
+                         r["kernel_work"]},
         "cpu_baseline": cpu,
     }
     if len(results) > 1:
         out["by_bits"] = {str(b): {"tokens_per_s": v["tokens_per_s"], "ms_per_step": v["ms_per_step"],
-                                   "kernel_gb_per_s": v["achieved_gbs"], "frac_of_peak": v["achieved_gbs"] / HBM_PEAK_GBS,
-                                   "avg_kernel_us": v["kernel_us"]} for b, v in results.items()}
+                                   "kernel_achieved": v["achieved"], "unit": v["unit"],
+                                   "frac_of_peak": v["achieved"] / v["peak"], "avg_kernel_us": v["kernel_us"]}
+                          for b, v in results.items()}
     print(json.dumps(out))
 
 
