@@ -9,14 +9,18 @@
 //          experts with at least min_tokens tokens have pairs (the decode kernel takes the rest)
 //   workgroup = (pair, block of output channels), 4 waves, two shapes:
 //          WM = 1: 256 channels, every wave owns all 64 tokens x 64 channels (4 x 4 accumulator
-//                  tiles of v_mfma_f32_16x16x32_f16) - wide matrices (FFN1)
+//                  tiles of v_mfma_f32_16x16x32_f16), 2 workgroups per compute unit - wide
+//                  matrices (FFN1)
 //          WM = 2: 128 channels, 2 token halves x 2 channel halves, a wave owns 32 tokens x 64
-//                  channels (2 x 4 tiles) - narrow matrices (FFN2), so that the grid still
-//                  fills the chip
-//   The grid is persistent (3 workgroups per compute unit); a workgroup walks over its tiles.
+//                  channels (2 x 4 tiles), 3 workgroups per compute unit - narrow matrices
+//                  (FFN2), so that the grid still fills the chip
+//   The grid is persistent; a workgroup walks over its share of the tiles.
 //   K runs in staged blocks of 128 rows:
-//     - the block's 64 token rows are staged in LDS (double buffered, loaded one block ahead
-//       through registers) and every wave reads its A fragments from there;
+//     - the block's 64 token rows are staged in LDS by loads that go from global memory
+//       straight into LDS (buffer_load ... lds, 16 bytes per lane, no registers in between),
+//       three buffers deep and two blocks ahead; a row's 16-byte pieces are stored XOR-swizzled
+//       by the row number, so that the fragment reads are conflict-free without padding; every
+//       wave reads its A fragments from there;
 //     - each wave loads the packed chunk (128 rows for int4, 256 for int2/int3) of each of its
 //       4 column tiles with one 16-byte load per lane (the packed layout is already in B-operand
 //       order), one chunk ahead, and dequantizes in registers: the unpack of one B fragment is
@@ -50,7 +54,7 @@ struct PfTile {
 };
 
 template <int BITS, int WM>
-__global__ __launch_bounds__(PF_THREADS, PF_WG_PER_CU) void moe_prefill_kernel(PrefillArgs A) {
+__global__ __launch_bounds__(PF_THREADS, WM == 1 ? 2 : PF_WG_PER_CU) void moe_prefill_kernel(PrefillArgs A) {
   constexpr int WN = 4 / WM;                  // waves side by side along the channels
   constexpr int PF_MT = PF_TILE_M / 16 / WM;  // token tiles per wave
   constexpr int PF_TILE_CT = WN * PF_NT;      // column tiles per workgroup tile
@@ -60,12 +64,14 @@ __global__ __launch_bounds__(PF_THREADS, PF_WG_PER_CU) void moe_prefill_kernel(P
   constexpr int LW = SC * LO_BITS / 4;        // main-plane words per lane per chunk (4)
   constexpr int HW = BITS == 3 ? SC / 4 : 0;  // 1-bit-plane words per lane per chunk
   constexpr int CHUNK_BYTES = 64 * SC * BITS;
-  constexpr int ROW_PIECES = PF_KB / 8 + 4;   // 16-byte pieces per staged row: data + 64 bytes of padding
-  constexpr int NP = PF_TILE_M * (PF_KB / 8) / PF_THREADS;  // pieces each thread moves per block
+  constexpr int ROW_PIECES = PF_KB / 8;       // 16-byte pieces per staged row (256 bytes, no padding)
+  constexpr int NBUF = 3;                     // staged blocks in LDS: one in use, two on their way
+  constexpr int NLD = 4;                      // LDS-direct loads per wave and block (4 rows each)
 
-  __shared__ uint4_t s_a[2][PF_TILE_M][ROW_PIECES];
+  // piece p of row r lives at s_a[.][r][p ^ (r & 15)]
+  __shared__ uint4_t s_a[NBUF][PF_TILE_M][ROW_PIECES];
   __shared__ int s_incl[PF_MAX_E];
-  __shared__ long long s_rowoff[2][PF_TILE_M];
+  __shared__ unsigned s_rowoff[2][PF_TILE_M];  // byte offset of each token row in `a`
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = uniform_i32(tid >> 6);
@@ -93,8 +99,16 @@ __global__ __launch_bounds__(PF_THREADS, PF_WG_PER_CU) void moe_prefill_kernel(P
     }
   }
   __syncthreads();
+  // Tiles are numbered pair-major (a pair's column blocks are consecutive).  Workgroups are
+  // dealt to the 8 XCDs round-robin by their index, so workgroups bid = x (mod 8) share XCD x's
+  // L2: XCD x takes the x-th eighth of the tiles, its workgroups walk through it side by side.
+  // A pair's token rows and an expert's weights are then fetched into one L2 only, and are
+  // still there when the neighbouring tiles ask for them.
   const int n_tiles = s_incl[E - 1] * A.n_cblocks;
-  if (bid >= n_tiles) return;
+  const int xcd = bid & 7, GX = G >> 3;
+  const int t_begin = (int)((int64_t)n_tiles * xcd / 8), t_end = (int)((int64_t)n_tiles * (xcd + 1) / 8);
+  const int t_first = t_begin + (bid >> 3);
+  if (t_first >= t_end) return;
 
   const int CT = N >> 4;
   const int Q = K / (32 * SC);   // packed chunks per column tile
@@ -108,7 +122,7 @@ __global__ __launch_bounds__(PF_THREADS, PF_WG_PER_CU) void moe_prefill_kernel(P
   // s_rowoff[slot]; the rows a ragged tile lacks repeat its last row (never stored).
   auto setup = [&](int tile, int slot) -> PfTile {
     PfTile t;
-    t.valid = tile < n_tiles;
+    t.valid = tile < t_end;
     t.e = 0; t.cb = 0; t.row0 = 0; t.rows = 1;
     if (!t.valid) return t;
     const int p = tile / A.n_cblocks;
@@ -126,7 +140,7 @@ __global__ __launch_bounds__(PF_THREADS, PF_WG_PER_CU) void moe_prefill_kernel(P
     t.rows = min(PF_TILE_M, n_e - PF_TILE_M * (p - first));
     if (tid < PF_TILE_M) {
       const int r = t.row0 + min(tid, t.rows - 1);
-      s_rowoff[slot][tid] = (long long)(A.mode == 0 ? A.perm[r] : r) * K;
+      s_rowoff[slot][tid] = (unsigned)(A.mode == 0 ? A.perm[r] : r) * (unsigned)K * 2u;
     }
     return t;
   };
@@ -143,7 +157,6 @@ __global__ __launch_bounds__(PF_THREADS, PF_WG_PER_CU) void moe_prefill_kernel(P
 
   uint32_t b_lo[2][PF_NT][LW];
   uint32_t b_hi[2][PF_NT][HW > 0 ? HW : 1];
-  uint4_t a_next[NP];
   float4_t acc[PF_MT][PF_NT];
 
   auto load_b = [&](auto BUF, const rsrc_t (&brs)[PF_NT], int c) {
@@ -154,21 +167,29 @@ __global__ __launch_bounds__(PF_THREADS, PF_WG_PER_CU) void moe_prefill_kernel(P
       if constexpr (BITS == 3) load_words<HW>(brs[ni], (uint32_t)c * CHUNK_BYTES + lane_hi, b_hi[buf][ni]);
     }
   };
-  auto load_a = [&](int slot, int blk) {
+
+  // Token rows: wave w stages rows 16 w .. 16 w + 15 of the tile with NLD loads of 4 rows each;
+  // lane l of load i writes LDS piece (l & 15) of row 16 w + 4 i + (l >> 4), which under the
+  // swizzle holds the row's piece (l & 15) ^ (row & 15).
+  const rsrc_t a_rsrc = make_rsrc(A.a, (uint32_t)((int64_t)A.T * K * 2));
+  auto row_offsets = [&](int slot, uint32_t (&off)[NLD]) {
 #pragma unroll
-    for (int i = 0; i < NP; ++i) {
-      const int q = tid + PF_THREADS * i;
-      const int row = q / (PF_KB / 8), pc = q % (PF_KB / 8);
-      a_next[i] = *(const uint4_t*)((const half_t*)A.a + s_rowoff[slot][row] + (int64_t)blk * PF_KB + pc * 8);
+    for (int i = 0; i < NLD; ++i) {
+      const int row = 16 * wave + 4 * i + (lane >> 4);
+      off[i] = s_rowoff[slot][row] + (uint32_t)(((lane & 15) ^ (row & 15)) * 16);
     }
   };
-  auto store_a = [&](int buf) {
+  auto load_a = [&](const uint32_t (&off)[NLD], int blk, int buf) {
 #pragma unroll
-    for (int i = 0; i < NP; ++i) {
-      const int q = tid + PF_THREADS * i;
-      s_a[buf][q / (PF_KB / 8)][q % (PF_KB / 8)] = a_next[i];
-    }
+    for (int i = 0; i < NLD; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (__attribute__((address_space(3))) void*)&s_a[buf][16 * wave + 4 * i][0],
+                                               16, off[i] + (uint32_t)blk * (PF_KB * 2), 0, 0, 0);
   };
+  // this lane's fragment piece per step of a block: logical piece 4 s + g of a row with (row & 15) == j
+  int frag_piece[4];
+#pragma unroll
+  for (int s4 = 0; s4 < 4; ++s4) frag_piece[s4] = (4 * s4 + g) ^ j;
+
   // the four steps of staged block `sub` of the chunk held in B buffer BUF
   auto compute = [&](int abuf, auto BUF, auto SUBI) {
     constexpr int bbuf = decltype(BUF)::value;
@@ -180,7 +201,7 @@ __global__ __launch_bounds__(PF_THREADS, PF_WG_PER_CU) void moe_prefill_kernel(P
       half8_t a[PF_MT];
 #pragma unroll
       for (int mi = 0; mi < PF_MT; ++mi)
-        a[mi] = __builtin_bit_cast(half8_t, s_a[abuf][16 * PF_MT * wm + 16 * mi + j][4 * s4 + g]);
+        a[mi] = __builtin_bit_cast(half8_t, s_a[abuf][16 * PF_MT * wm + 16 * mi + j][frag_piece[s4]]);
 #pragma unroll
       for (int ni = 0; ni < PF_NT; ++ni) {
         half8_t w;
@@ -202,27 +223,35 @@ __global__ __launch_bounds__(PF_THREADS, PF_WG_PER_CU) void moe_prefill_kernel(P
   };
 
   // ---- the workgroup's tiles, as one continuous stream of staged blocks ----
-  // While block t is multiplied, block t + 1 is on its way (token rows through registers into
-  // the other LDS buffer, packed chunks into the other register buffer) - also across the end
-  // of a tile, so that the next tile's first operands arrive during this tile's epilogue.
+  // While block t is multiplied, blocks t + 1 and t + 2 are on their way into the other two LDS
+  // buffers and the next packed chunk into the other register buffer - also across the end of
+  // a tile, so that the next tile's first operands arrive during this tile's epilogue.
+  // LDS-direct loads are invisible to the compiler's wait insertion: the waits on them are
+  // explicit.  Loads complete in order, so "all but the youngest NLD" means block t + 1 is in.
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
-  PfTile cur = setup(bid, 0);
+  constexpr int WAIT_ALL = 0x0F70;                 // s_waitcnt vmcnt(0)
+  constexpr int WAIT_BUT_NLD = 0x0F70 | NLD;       // s_waitcnt vmcnt(NLD)
+  PfTile cur = setup(t_first, 0);
   __syncthreads();
   rsrc_t cur_brs[PF_NT], nxt_brs[PF_NT];
+  uint32_t cur_off[NLD], nxt_off[NLD];
   make_brs(cur, cur_brs);
-  load_a(0, 0);
+  row_offsets(0, cur_off);
   load_b(I0{}, cur_brs, 0);
-  store_a(0);
+  load_a(cur_off, 0, 0);
+  load_a(cur_off, 1, 1);
+  __builtin_amdgcn_s_waitcnt(WAIT_ALL);
   __syncthreads();
-  int gblk = 0;                     // blocks done so far: block t lives in LDS buffer t & 1
+  int gb = 0;                       // blocks done so far: block t of the stream lives in buffer t % NBUF
   const bool cross = (Q & 1) == 0;  // with an even chunk count the chunk stream crosses tiles too
 
   for (int it = 0; cur.valid; ++it) {
     const int slot = it & 1;
-    const PfTile nxt = setup(bid + (it + 1) * G, slot ^ 1);
+    const PfTile nxt = setup(t_first + (it + 1) * GX, slot ^ 1);
     __syncthreads();
     make_brs(nxt, nxt_brs);
+    row_offsets(slot ^ 1, nxt_off);
 #pragma unroll
     for (int mi = 0; mi < PF_MT; ++mi)
 #pragma unroll
@@ -239,13 +268,17 @@ __global__ __launch_bounds__(PF_THREADS, PF_WG_PER_CU) void moe_prefill_kernel(P
       auto do_block = [&](auto SUBI) {
         constexpr int sub = decltype(SUBI)::value;
         const int blk = c * SUB + sub;
-        const bool last = blk + 1 == TB;
-        if (!last) load_a(slot, blk + 1);
-        else if (nxt.valid) load_a(slot ^ 1, 0);
-        compute(gblk & 1, BUF, SUBI);
-        if (!last || nxt.valid) store_a((gblk + 1) & 1);
+        // block blk + 2 of the stream: this tile's, or the next tile's first or second block
+        const int ahead = blk + 2;
+        bool issued = true;
+        if (ahead < TB) load_a(cur_off, ahead, (gb + 2) % NBUF);
+        else if (nxt.valid) load_a(nxt_off, ahead - TB, (gb + 2) % NBUF);
+        else issued = false;
+        compute(gb % NBUF, BUF, SUBI);
+        if (issued) __builtin_amdgcn_s_waitcnt(WAIT_BUT_NLD);
+        else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
         __syncthreads();
-        ++gblk;
+        ++gb;
       };
       do_block(I0{});
       if constexpr (SUB == 2) do_block(I1{});
@@ -288,6 +321,8 @@ __global__ __launch_bounds__(PF_THREADS, PF_WG_PER_CU) void moe_prefill_kernel(P
     cur = nxt;
 #pragma unroll
     for (int ni = 0; ni < PF_NT; ++ni) cur_brs[ni] = nxt_brs[ni];
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) cur_off[i] = nxt_off[i];
   }
 }
 
@@ -295,19 +330,28 @@ __global__ __launch_bounds__(PF_THREADS, PF_WG_PER_CU) void moe_prefill_kernel(P
 
 bool moqe_prefill_supported(int bits, int64_t K, int64_t N) {
   const int kc = bits == 4 ? 128 : 256;
-  return (bits == 2 || bits == 3 || bits == 4) && K >= kc && (K % kc) == 0 && N >= 16 && (N % 16) == 0;
+  return (bits == 2 || bits == 3 || bits == 4) && K >= 256 && (K % kc) == 0 && N >= 16 && (N % 16) == 0;
 }
 
 template <int BITS>
 static void launch_bits(const PrefillArgs& a, int64_t pairs, int num_cus, hipStream_t stream) {
-  // Only the 128-channel workgroup shape is launched.  The 256-channel shape (WM = 1: 4 x 4
-  // accumulator tiles per wave) does not fit the register file without spilling and measured
-  // slower on the 4096-token stack.
   PrefillArgs args = a;
-  args.n_cblocks = (a.N / 16 + 7) / 8;
+  const int CT = a.N / 16;
+  // Wide matrices (FFN1) take 64 x 256 tiles: every wave owns all 64 tokens x 64 channels, so
+  // a weight fragment is unpacked once for four token tiles and a staged block feeds twice the
+  // arithmetic; two workgroups per compute unit (the 4 x 4 accumulator tiles need the registers).
+  // Narrow ones (FFN2) take 64 x 128 tiles, three workgroups per compute unit, or the grid
+  // would not fill the chip (measured: no gain from the wide shape there).
+  const bool wide = CT >= 128;
+  const int per_cu = wide ? 2 : PF_WG_PER_CU;
+  args.n_cblocks = wide ? (CT + 15) / 16 : (CT + 7) / 8;
   int64_t grid = pairs * args.n_cblocks;  // upper bound on the tiles
-  if (grid > (int64_t)PF_WG_PER_CU * num_cus) grid = (int64_t)PF_WG_PER_CU * num_cus;
-  hipLaunchKernelGGL((moe_prefill_kernel<BITS, 2>), dim3((unsigned)grid), dim3(PF_THREADS), 0, stream, args);
+  if (grid > (int64_t)per_cu * num_cus) grid = (int64_t)per_cu * num_cus;
+  grid = grid < 8 ? 8 : (grid & ~(int64_t)7);  // a multiple of the 8 XCDs
+  if (wide)
+    hipLaunchKernelGGL((moe_prefill_kernel<BITS, 1>), dim3((unsigned)grid), dim3(PF_THREADS), 0, stream, args);
+  else
+    hipLaunchKernelGGL((moe_prefill_kernel<BITS, 2>), dim3((unsigned)grid), dim3(PF_THREADS), 0, stream, args);
 }
 
 hipError_t moqe_launch_prefill(const PrefillArgs& a, int num_cus, hipStream_t stream) {
