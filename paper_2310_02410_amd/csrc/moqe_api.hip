@@ -285,6 +285,9 @@ static hipError_t launch_contraction(DecodeArgs& a, int phase, int ksteps, hipSt
   q.seg_offsets = a.seg_offsets;
   q.perm = a.perm;
   q.gate = a.gate;
+#ifdef MOQE_PHASE_TRACE
+  q.trace = g_trace;
+#endif
   return moqe_launch_prefill(q, num_cus(), stream);
 }
 

@@ -39,6 +39,19 @@
 
 #include <type_traits>
 
+#ifdef MOQE_PHASE_TRACE
+#define PF_T0() long long pf_t = clock64()
+#define PF_ACC(i)                \
+  do {                           \
+    const long long n = clock64(); \
+    pf_sum[i] += n - pf_t;       \
+    pf_t = n;                    \
+  } while (0)
+#else
+#define PF_T0()
+#define PF_ACC(i)
+#endif
+
 namespace {
 
 constexpr int PF_THREADS = 256;
@@ -47,6 +60,13 @@ constexpr int PF_NT = 4;         // column tiles (of 16 channels) per wave
 constexpr int PF_KB = 128;       // rows of K staged in LDS at a time
 constexpr int PF_WG_PER_CU = 3;  // persistent workgroups per compute unit
 constexpr int PF_MAX_E = 1024;
+
+// Byte offsets of the four token rows a lane stages per block (members, not an array: they
+// must stay in registers; a reload from scratch in front of every load would also wait for all
+// loads in flight).
+struct PfRowOff {
+  uint32_t r0, r1, r2, r3;
+};
 
 struct PfTile {
   int e, cb, row0, rows;
@@ -172,18 +192,21 @@ __global__ __launch_bounds__(PF_THREADS, WM == 1 ? 2 : PF_WG_PER_CU) void moe_pr
   // lane l of load i writes LDS piece (l & 15) of row 16 w + 4 i + (l >> 4), which under the
   // swizzle holds the row's piece (l & 15) ^ (row & 15).
   const rsrc_t a_rsrc = make_rsrc(A.a, (uint32_t)((int64_t)A.T * K * 2));
-  auto row_offsets = [&](int slot, uint32_t (&off)[NLD]) {
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int row = 16 * wave + 4 * i + (lane >> 4);
-      off[i] = s_rowoff[slot][row] + (uint32_t)(((lane & 15) ^ (row & 15)) * 16);
-    }
+  static_assert(NLD == 4, "PfRowOff holds four rows");
+  auto row_offset = [&](int slot, int i) -> uint32_t {
+    const int row = 16 * wave + 4 * i + (lane >> 4);
+    return s_rowoff[slot][row] + (uint32_t)(((lane & 15) ^ (row & 15)) * 16);
   };
-  auto load_a = [&](const uint32_t (&off)[NLD], int blk, int buf) {
-#pragma unroll
-    for (int i = 0; i < NLD; ++i)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (__attribute__((address_space(3))) void*)&s_a[buf][16 * wave + 4 * i][0],
-                                               16, off[i] + (uint32_t)blk * (PF_KB * 2), 0, 0, 0);
+  auto row_offsets = [&](int slot) -> PfRowOff {
+    return PfRowOff{row_offset(slot, 0), row_offset(slot, 1), row_offset(slot, 2), row_offset(slot, 3)};
+  };
+  auto load_a = [&](const PfRowOff off, int blk, int buf) {
+    const uint32_t kb = (uint32_t)blk * (PF_KB * 2);
+    typedef __attribute__((address_space(3))) void* lds_ptr;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_ptr)&s_a[buf][16 * wave + 0][0], 16, off.r0 + kb, 0, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_ptr)&s_a[buf][16 * wave + 4][0], 16, off.r1 + kb, 0, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_ptr)&s_a[buf][16 * wave + 8][0], 16, off.r2 + kb, 0, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_ptr)&s_a[buf][16 * wave + 12][0], 16, off.r3 + kb, 0, 0, 0);
   };
   // this lane's fragment piece per step of a block: logical piece 4 s + g of a row with (row & 15) == j
   int frag_piece[4];
@@ -217,7 +240,7 @@ __global__ __launch_bounds__(PF_THREADS, WM == 1 ? 2 : PF_WG_PER_CU) void moe_pr
         }
 #pragma unroll
         for (int mi = 0; mi < PF_MT; ++mi)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mi], w, acc[mi][ni], 0, 0, 0);
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w, a[mi], acc[mi][ni], 0, 0, 0);
       }
     }
   };
@@ -232,12 +255,15 @@ __global__ __launch_bounds__(PF_THREADS, WM == 1 ? 2 : PF_WG_PER_CU) void moe_pr
   using I1 = std::integral_constant<int, 1>;
   constexpr int WAIT_ALL = 0x0F70;                 // s_waitcnt vmcnt(0)
   constexpr int WAIT_BUT_NLD = 0x0F70 | NLD;       // s_waitcnt vmcnt(NLD)
+#ifdef MOQE_PHASE_TRACE
+  long long pf_sum[8] = {0, 0, 0, 0, 0, 0, 0, 0};  // setup, issue, compute, wait, barrier, epilogue
+#endif
+  PF_T0();
   PfTile cur = setup(t_first, 0);
   __syncthreads();
   rsrc_t cur_brs[PF_NT], nxt_brs[PF_NT];
-  uint32_t cur_off[NLD], nxt_off[NLD];
   make_brs(cur, cur_brs);
-  row_offsets(0, cur_off);
+  PfRowOff cur_off = row_offsets(0);
   load_b(I0{}, cur_brs, 0);
   load_a(cur_off, 0, 0);
   load_a(cur_off, 1, 1);
@@ -251,7 +277,18 @@ __global__ __launch_bounds__(PF_THREADS, WM == 1 ? 2 : PF_WG_PER_CU) void moe_pr
     const PfTile nxt = setup(t_first + (it + 1) * GX, slot ^ 1);
     __syncthreads();
     make_brs(nxt, nxt_brs);
-    row_offsets(slot ^ 1, nxt_off);
+    const PfRowOff nxt_off = row_offsets(slot ^ 1);
+    // scales and biases of this tile's channels (4 per lane and column tile), asked for now and
+    // used in the epilogue, by when they have long arrived
+    uint2_t sc2[PF_NT], bi2[PF_NT];
+#pragma unroll
+    for (int ni = 0; ni < PF_NT; ++ni) {
+      const int ct = cur.cb * PF_TILE_CT + wn * PF_NT + ni;
+      const int c0 = 16 * (ct < CT ? ct : 0) + 4 * g;
+      sc2[ni] = *(const uint2_t*)(A.scales + (int64_t)cur.e * N + c0);
+      bi2[ni] = *(const uint2_t*)(A.bias + (int64_t)cur.e * N + c0);
+    }
+    PF_ACC(0);
 #pragma unroll
     for (int mi = 0; mi < PF_MT; ++mi)
 #pragma unroll
@@ -274,10 +311,14 @@ __global__ __launch_bounds__(PF_THREADS, WM == 1 ? 2 : PF_WG_PER_CU) void moe_pr
         if (ahead < TB) load_a(cur_off, ahead, (gb + 2) % NBUF);
         else if (nxt.valid) load_a(nxt_off, ahead - TB, (gb + 2) % NBUF);
         else issued = false;
+        PF_ACC(1);
         compute(gb % NBUF, BUF, SUBI);
+        PF_ACC(2);
         if (issued) __builtin_amdgcn_s_waitcnt(WAIT_BUT_NLD);
         else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
+        PF_ACC(3);
         __syncthreads();
+        PF_ACC(4);
         ++gb;
       };
       do_block(I0{});
@@ -289,41 +330,68 @@ __global__ __launch_bounds__(PF_THREADS, WM == 1 ? 2 : PF_WG_PER_CU) void moe_pr
     }
     if (!cross && nxt.valid) load_b(I0{}, nxt_brs, 0);
 
-    // ---- epilogue: D lane (g, j), register r = token row 4 g + r of the tile, channel j ----
+    // ---- epilogue ----
+    // The weights are the MFMA's first operand and the tokens its second, so the result tile is
+    // channels x tokens: lane (g, j) holds channels 4 g .. 4 g + 3 of the column tile for token
+    // j of the token tile - four neighbouring fp16 outputs, written with one 8-byte store.
 #pragma unroll
-    for (int ni = 0; ni < PF_NT; ++ni) {
-      const int ct = cur.cb * PF_TILE_CT + wn * PF_NT + ni;
-      if (ct >= CT) continue;
-      const int col = 16 * ct + j;
-      const float sc = (float)half_from_bits(A.scales[(int64_t)cur.e * N + col]);
-      const float bi = (float)half_from_bits(A.bias[(int64_t)cur.e * N + col]);
+    for (int mi = 0; mi < PF_MT; ++mi) {
+      const int row = 16 * PF_MT * wm + 16 * mi + j;
+      if (row >= cur.rows) continue;
+      const int srow = cur.row0 + row;
+      int64_t out_row;
+      float gt = 1.0f;
+      if (A.mode == 0) {
+        out_row = (int64_t)srow * N;
+      } else {
+        const int tk = A.perm[srow];
+        gt = A.gate[tk];
+        out_row = (int64_t)tk * N;
+      }
 #pragma unroll
-      for (int mi = 0; mi < PF_MT; ++mi) {
+      for (int ni = 0; ni < PF_NT; ++ni) {
+        const int ct = cur.cb * PF_TILE_CT + wn * PF_NT + ni;
+        if (ct >= CT) continue;
+        const int c0 = 16 * ct + 4 * g;
+        const half_t sc[4] = {half_from_bits((uint16_t)sc2[ni].x), half_from_bits((uint16_t)(sc2[ni].x >> 16)),
+                              half_from_bits((uint16_t)sc2[ni].y), half_from_bits((uint16_t)(sc2[ni].y >> 16))};
+        const half_t bi[4] = {half_from_bits((uint16_t)bi2[ni].x), half_from_bits((uint16_t)(bi2[ni].x >> 16)),
+                              half_from_bits((uint16_t)bi2[ni].y), half_from_bits((uint16_t)(bi2[ni].y >> 16))};
+        float o[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int row = 16 * PF_MT * wm + 16 * mi + 4 * g + r;
-          if (row >= cur.rows) continue;
-          float o = fmaf(acc[mi][ni][r], sc, bi);
-          const int srow = cur.row0 + row;
-          if (A.mode == 0) {
-            o = fmaxf(o, 0.0f);
-            ((half_t*)A.out)[(int64_t)srow * N + col] = (half_t)o;
-          } else {
-            const int tk = A.perm[srow];
-            float v = A.gate[tk] * o;
-            const int64_t at = (int64_t)tk * N + col;
-            if (A.residual) v += (float)((const half_t*)A.residual)[at];
-            ((half_t*)A.out)[at] = (half_t)v;
+        for (int r = 0; r < 4; ++r) o[r] = fmaf(acc[mi][ni][r], (float)sc[r], (float)bi[r]);
+        if (A.mode == 0) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) o[r] = fmaxf(o[r], 0.0f);
+        } else {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) o[r] *= gt;
+          if (A.residual) {
+            const uint2_t rs = *(const uint2_t*)(A.residual + out_row + c0);
+            o[0] += (float)half_from_bits((uint16_t)rs.x);
+            o[1] += (float)half_from_bits((uint16_t)(rs.x >> 16));
+            o[2] += (float)half_from_bits((uint16_t)rs.y);
+            o[3] += (float)half_from_bits((uint16_t)(rs.y >> 16));
           }
         }
+        uint2_t pk;
+        pk.x = (uint32_t)half_to_bits((half_t)o[0]) | ((uint32_t)half_to_bits((half_t)o[1]) << 16);
+        pk.y = (uint32_t)half_to_bits((half_t)o[2]) | ((uint32_t)half_to_bits((half_t)o[3]) << 16);
+        *(uint2_t*)(A.out + out_row + c0) = pk;
       }
     }
+    PF_ACC(5);
     cur = nxt;
 #pragma unroll
     for (int ni = 0; ni < PF_NT; ++ni) cur_brs[ni] = nxt_brs[ni];
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) cur_off[i] = nxt_off[i];
+    cur_off = nxt_off;
   }
+#ifdef MOQE_PHASE_TRACE
+  if (A.trace && lane == 0) {
+    for (int i = 0; i < 6; ++i) A.trace[((int64_t)bid * 4 + wave) * 8 + i] = pf_sum[i];
+    A.trace[((int64_t)bid * 4 + wave) * 8 + 6] = gb;
+  }
+#endif
 }
 
 }  // namespace

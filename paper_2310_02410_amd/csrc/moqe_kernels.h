@@ -79,6 +79,7 @@ struct PrefillArgs {
   const int* seg_offsets;
   const int* perm;
   const float* gate;
+  long long* trace;  // debug builds (-DMOQE_PHASE_TRACE): cycle sums per wave, else unused
 };
 bool moqe_prefill_supported(int bits, int64_t K, int64_t N);
 hipError_t moqe_launch_prefill(const PrefillArgs& a, int num_cus, hipStream_t stream);
