@@ -36,18 +36,58 @@ __device__ inline int quantize_one(float w, double s, int lo, int hi) {
   return (int)r;
 }
 
-// One thread per (expert, channel): s = 2 max|A_:,n| / (2^b - 1), stored fp16 rounded up.
+// s = 2 max|A_:,n| / (2^b - 1), stored fp16 rounded up.  A workgroup takes 256 neighbouring
+// channels of one expert: a lane owns 4 of them (16-byte loads, a wave reads 1 KiB per row), the
+// 4 waves split the K rows and keep 8 loads in flight each; the partial maxima meet in LDS.
 __global__ __launch_bounds__(256) void scale_kernel(const float* __restrict__ w, int64_t E, int K, int N, int bits,
                                                      uint16_t* __restrict__ scales) {
-  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= E * N) return;
-  int64_t e = idx / N;
-  int n = (int)(idx % N);
-  const float* col = w + e * (int64_t)K * N + n;
-  float m = 0.0f;
-  for (int k = 0; k < K; ++k) m = fmaxf(m, fabsf(col[(int64_t)k * N]));
-  double s64 = (2.0 * (double)m) / (double)((1 << bits) - 1);
-  scales[idx] = half_bits_round_up(s64);
+  __shared__ float4_t s_max[4][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nblocks = (N + 255) / 256;
+  const int64_t e = blockIdx.x / nblocks;
+  const int n0 = (int)(blockIdx.x % nblocks) * 256 + 4 * lane;
+  float4_t m = {0.0f, 0.0f, 0.0f, 0.0f};
+  if (n0 < N) {  // N is a multiple of 16, so the lane's 4 channels are all there
+    const float* col = w + e * (int64_t)K * N + n0;
+    const int k_begin = (int)((int64_t)K * wave / 4), k_end = (int)((int64_t)K * (wave + 1) / 4);
+    int k = k_begin;
+    for (; k + 8 <= k_end; k += 8) {
+      float4_t v[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = __builtin_nontemporal_load((const float4_t*)(col + (int64_t)(k + i) * N));
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        m.x = fmaxf(m.x, fabsf(v[i].x));
+        m.y = fmaxf(m.y, fabsf(v[i].y));
+        m.z = fmaxf(m.z, fabsf(v[i].z));
+        m.w = fmaxf(m.w, fabsf(v[i].w));
+      }
+    }
+    for (; k < k_end; ++k) {
+      const float4_t v = *(const float4_t*)(col + (int64_t)k * N);
+      m.x = fmaxf(m.x, fabsf(v.x));
+      m.y = fmaxf(m.y, fabsf(v.y));
+      m.z = fmaxf(m.z, fabsf(v.z));
+      m.w = fmaxf(m.w, fabsf(v.w));
+    }
+  }
+  s_max[wave][lane] = m;
+  __syncthreads();
+  if (wave == 0 && n0 < N) {
+    for (int q = 1; q < 4; ++q) {
+      const float4_t o = s_max[q][lane];
+      m.x = fmaxf(m.x, o.x);
+      m.y = fmaxf(m.y, o.y);
+      m.z = fmaxf(m.z, o.z);
+      m.w = fmaxf(m.w, o.w);
+    }
+    const double den = (double)((1 << bits) - 1);
+    uint16_t* out = scales + e * N + n0;
+    out[0] = half_bits_round_up((2.0 * (double)m.x) / den);
+    out[1] = half_bits_round_up((2.0 * (double)m.y) / den);
+    out[2] = half_bits_round_up((2.0 * (double)m.z) / den);
+    out[3] = half_bits_round_up((2.0 * (double)m.w) / den);
+  }
 }
 
 // One thread per packed 32-bit word.
@@ -131,9 +171,8 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint32_t* __restrict_
 
 hipError_t moqe_launch_quantize(const float* w, int64_t E, const PackGeom& g, void* codes, uint16_t* scales,
                                 hipStream_t stream) {
-  int64_t nch = E * g.N;
-  hipLaunchKernelGGL(scale_kernel, dim3((unsigned)((nch + 255) / 256)), dim3(256), 0, stream, w, E, g.K, g.N, g.bits,
-                     scales);
+  const int64_t blocks = E * ((g.N + 255) / 256);
+  hipLaunchKernelGGL(scale_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, w, E, g.K, g.N, g.bits, scales);
   int64_t words = E * (g.matrix_bytes / 4);
   hipLaunchKernelGGL(pack_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, stream, w, scales, g, E,
                      (uint32_t*)codes);
