@@ -71,6 +71,13 @@ def test_forced_launch_modes(launch_mode, mode, bits):
     _layer_case(W.small(E=16, d=512, f=2048, T=150, seed=62), bits, residual=True, repeats=2)
 
 
+@pytest.mark.parametrize("bits", (4, 3, 2))
+def test_many_small_experts_shape(bits):
+    """The paper's second model shape (App. B: 128 experts, d_model 768, d_ff 3072) at batch 24:
+    24-step wave slices, more experts than one wave has lanes, most experts empty."""
+    _layer_case(W.small(E=128, d=768, f=3072, T=24, seed=64), bits, repeats=2)
+
+
 def test_launch_modes_agree_bit_for_bit(launch_mode):
     wl = W.small(E=8, d=512, f=2048, T=33, seed=63)
     layer, x = W.make_layer(wl), W.make_tokens(wl)
