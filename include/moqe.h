@@ -90,8 +90,9 @@ int moqe_set_launch_mode(int mode);
  * kernel.  Smaller batches do not launch the tiled kernel at all (a decode step would pay a
  * launch for segments that almost never exist).  Defaults below; a huge min_batch_tokens
  * switches the tiled kernel off.  The tiled kernel needs K >= 256 and a multiple of 128 (int4)
- * or 256 (int2, int3), and T*K*2 < 2^32; other layers use the decode kernel throughout.  Launch mode FUSED uses the
- * decode kernel for everything it chains.  Returns 0, or -1 (nothing changed) if a value < 1. */
+ * or 256 (int2, int3), and T*K*2 < 2^32; other layers use the decode kernel throughout.
+ * Launch mode FUSED uses the decode kernel for everything it chains.
+ * Returns 0, or -1 (nothing changed) if a value < 1. */
 #define MOQE_PREFILL_MIN_SEGMENT_DEFAULT 5
 #define MOQE_PREFILL_MIN_BATCH_DEFAULT 65
 int moqe_set_prefill_policy(int min_segment_tokens, int min_batch_tokens);
