@@ -293,15 +293,23 @@ __global__ __launch_bounds__(SEG_THREADS) void route_segments_kernel(const int* 
 constexpr int SMALL_THREADS = 1024;
 constexpr int SMALL_WAVES = 16;
 
-template <int NT>
+// TABLES = false: the same scoring for any number of tokens (T_total), one workgroup per
+// 16 tokens, top-1 and gate only; route_segments_kernel follows.
+template <int NT, bool TABLES>
 __global__ __launch_bounds__(SMALL_THREADS) void route_small_kernel(const half_t* __restrict__ x,
-                                                                    const half_t* __restrict__ wg, int T, int d,
+                                                                    const half_t* __restrict__ wg, int T_total, int d,
                                                                     int* __restrict__ expert_idx,
                                                                     float* __restrict__ gate,
                                                                     int* __restrict__ seg_offsets,
                                                                     int* __restrict__ perm) {
-  constexpr int MT = NT >= 8 ? 1 : NT == 4 ? 2 : 4;
+  constexpr int MT = !TABLES ? 1 : NT >= 8 ? 1 : NT == 4 ? 2 : 4;
   constexpr int E = 16 * NT;
+  // this workgroup's tokens
+  const int t_base = TABLES ? 0 : (int)blockIdx.x * 16 * MT;
+  const int T = TABLES ? T_total : min(16 * MT, T_total - t_base);
+  x += (int64_t)t_base * d;
+  expert_idx += t_base;
+  gate += t_base;
   __shared__ float4_t s_part[SMALL_WAVES][MT * NT][64];
   __shared__ float s_logit[MT * 16 * E];
   __shared__ int s_idx[64];
@@ -310,7 +318,7 @@ __global__ __launch_bounds__(SMALL_THREADS) void route_small_kernel(const half_t
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 4, j = lane & 15;
   const int mt = (T + 15) >> 4;
-  const int steps = d / (32 * SMALL_WAVES);
+  const int steps = d / 32;  // 32-row steps of d, dealt round-robin to the waves
 
   float4_t acc[MT][NT];
 #pragma unroll
@@ -318,8 +326,8 @@ __global__ __launch_bounds__(SMALL_THREADS) void route_small_kernel(const half_t
 #pragma unroll
     for (int ni = 0; ni < NT; ++ni) acc[mi][ni] = float4_t{0, 0, 0, 0};
 
-  for (int s = 0; s < steps; ++s) {
-    const int k0 = (wave * steps + s) * 32 + 8 * g;  // this lane's 8 rows of d
+  for (int s = wave; s < steps; s += SMALL_WAVES) {
+    const int k0 = s * 32 + 8 * g;  // this lane's 8 rows of d
     half8_t a[MT];
 #pragma unroll
     for (int mi = 0; mi < MT; ++mi) {
@@ -361,6 +369,7 @@ __global__ __launch_bounds__(SMALL_THREADS) void route_small_kernel(const half_t
       s_idx[t] = idx;
     }
   }
+  if constexpr (!TABLES) return;
   __syncthreads();
   if (wave == 0) {
     const bool valid = lane < T;
@@ -401,7 +410,7 @@ __global__ __launch_bounds__(SMALL_THREADS) void route_small_kernel(const half_t
 
 // True when route_small_kernel can take the call.
 static bool small_route_fits(int T, int d, int E) {
-  if (T < 1 || T > 64 || d < 512 || (d % 512) != 0) return false;
+  if (T < 1 || T > 64 || d < 32 || (d % 32) != 0) return false;
   const int mt = (T + 15) / 16;
   switch (E) {
     case 16: return mt <= 4;
@@ -434,11 +443,30 @@ hipError_t moqe_launch_route(const uint16_t* x, const uint16_t* wg, const float*
     const half_t* xh = (const half_t*)x;
     const half_t* wh = (const half_t*)wg;
     switch (E) {
-      case 16: hipLaunchKernelGGL(route_small_kernel<1>, dim3(1), dim3(SMALL_THREADS), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
-      case 32: hipLaunchKernelGGL(route_small_kernel<2>, dim3(1), dim3(SMALL_THREADS), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
-      case 64: hipLaunchKernelGGL(route_small_kernel<4>, dim3(1), dim3(SMALL_THREADS), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
-      default: hipLaunchKernelGGL(route_small_kernel<8>, dim3(1), dim3(SMALL_THREADS), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
+      case 16: hipLaunchKernelGGL((route_small_kernel<1, true>), dim3(1), dim3(SMALL_THREADS), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
+      case 32: hipLaunchKernelGGL((route_small_kernel<2, true>), dim3(1), dim3(SMALL_THREADS), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
+      case 64: hipLaunchKernelGGL((route_small_kernel<4, true>), dim3(1), dim3(SMALL_THREADS), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
+      default: hipLaunchKernelGGL((route_small_kernel<8, true>), dim3(1), dim3(SMALL_THREADS), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
     }
+    return hipGetLastError();
+  }
+  if (T > 0 && !logits && d >= 32 && (d % 32) == 0 && (E == 16 || E == 32 || E == 64 || E == 128)) {
+    // more tokens than one workgroup takes: MFMA scoring, one workgroup per 16 tokens
+    const half_t* xh = (const half_t*)x;
+    const half_t* wh = (const half_t*)wg;
+    const int per_wg = 16;
+    const dim3 grid((unsigned)((T + per_wg - 1) / per_wg));
+    switch (E) {
+      case 16: hipLaunchKernelGGL((route_small_kernel<1, false>), grid, dim3(SMALL_THREADS), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
+      case 32: hipLaunchKernelGGL((route_small_kernel<2, false>), grid, dim3(SMALL_THREADS), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
+      case 64: hipLaunchKernelGGL((route_small_kernel<4, false>), grid, dim3(SMALL_THREADS), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
+      default: hipLaunchKernelGGL((route_small_kernel<8, false>), grid, dim3(SMALL_THREADS), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
+    }
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    const int seg_threads = T <= 256 ? 256 : SEG_THREADS;
+    hipLaunchKernelGGL(route_segments_kernel, dim3(1), dim3(seg_threads), 0, stream, expert_idx, T, E, seg_offsets, perm,
+                       (int*)ws);
     return hipGetLastError();
   }
   if (T > 0) {
