@@ -258,9 +258,10 @@ static void set_ffn2(DecodeArgs* a, const moqe_layer* L, const moqe_f16* h, cons
 static hipError_t launch_contraction(DecodeArgs& a, int phase, int ksteps, hipStream_t stream) {
   const PhaseArgs& p = a.ph[phase];
   const int pmin = g_prefill_min.load();
-  // (the tiled kernel addresses its input rows with 32-bit byte offsets)
+  // (the tiled kernel addresses its input rows with 32-bit byte offsets and its output rows with
+  // 32-bit element offsets)
   const bool split = a.T >= pmin && a.T >= g_prefill_batch.load() && moqe_prefill_supported(a.bits, p.K, p.N) &&
-                     (int64_t)a.T * p.K * 2 < (1ll << 32);
+                     (int64_t)a.T * p.K * 2 < (1ll << 32) && (int64_t)a.T * p.N < (1ll << 31);
   a.ksteps = ksteps;
   a.phase_mask = 2 << phase;
   a.min_tokens = 1;

@@ -60,10 +60,11 @@ constexpr int PF_NT = 4;         // column tiles (of 16 channels) per wave
 constexpr int PF_KB = 128;       // rows of K staged in LDS at a time
 constexpr int PF_WG_PER_CU = 3;  // persistent workgroups per compute unit
 constexpr int PF_MAX_E = 1024;
+constexpr int PF_SEG_LDS = 128;  // segment starts are kept in LDS for up to this many experts
 
-// Byte offsets of the four token rows a lane stages per block (members, not an array: they
-// must stay in registers; a reload from scratch in front of every load would also wait for all
-// loads in flight).
+// The four token rows a lane stages per block: first their row numbers in `a`, then their byte
+// offsets (members, not an array: they must stay in registers; a reload from scratch in front
+// of every load would also wait for all loads in flight).
 struct PfRowOff {
   uint32_t r0, r1, r2, r3;
 };
@@ -91,7 +92,7 @@ __global__ __launch_bounds__(PF_THREADS, WM == 1 ? 2 : PF_WG_PER_CU) void moe_pr
   // piece p of row r lives at s_a[.][r][p ^ (r & 15)]
   __shared__ uint4_t s_a[NBUF][PF_TILE_M][ROW_PIECES];
   __shared__ int s_incl[PF_MAX_E];
-  __shared__ unsigned s_rowoff[2][PF_TILE_M];  // byte offset of each token row in `a`
+  __shared__ int s_seg[PF_SEG_LDS];  // seg_offsets[0 .. E - 1] when E <= PF_SEG_LDS
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = uniform_i32(tid >> 6);
@@ -107,8 +108,10 @@ __global__ __launch_bounds__(PF_THREADS, WM == 1 ? 2 : PF_WG_PER_CU) void moe_pr
       const int e = eg + lane;
       int v = 0;
       if (e < E) {
-        const int n = A.seg_offsets[e + 1] - A.seg_offsets[e];
+        const int s0 = A.seg_offsets[e];
+        const int n = A.seg_offsets[e + 1] - s0;
         v = n >= A.min_tokens ? (n + PF_TILE_M - 1) / PF_TILE_M : 0;
+        if (E <= PF_SEG_LDS) s_seg[e] = s0;
       }
       for (int off = 1; off < 64; off <<= 1) {
         const int o = __shfl_up(v, off, 64);
@@ -138,9 +141,9 @@ __global__ __launch_bounds__(PF_THREADS, WM == 1 ? 2 : PF_WG_PER_CU) void moe_pr
   UnpackConsts<BITS> uc;
   uc.init();
 
-  // Finds tile `tile` (pair, column block) and leaves the element offsets of its token rows in
-  // s_rowoff[slot]; the rows a ragged tile lacks repeat its last row (never stored).
-  auto setup = [&](int tile, int slot) -> PfTile {
+  // Finds tile `tile` (pair, column block): all of it is uniform over the workgroup and, with
+  // the segment starts in LDS, needs no global read.
+  auto find = [&](int tile) -> PfTile {
     PfTile t;
     t.valid = tile < t_end;
     t.e = 0; t.cb = 0; t.row0 = 0; t.rows = 1;
@@ -154,14 +157,16 @@ __global__ __launch_bounds__(PF_THREADS, WM == 1 ? 2 : PF_WG_PER_CU) void moe_pr
     }
     t.e = uniform_i32(lo);
     const int first = t.e > 0 ? s_incl[t.e - 1] : 0;
-    const int seg0 = A.seg_offsets[t.e];
-    const int n_e = A.seg_offsets[t.e + 1] - seg0;
-    t.row0 = seg0 + PF_TILE_M * (p - first);
-    t.rows = min(PF_TILE_M, n_e - PF_TILE_M * (p - first));
-    if (tid < PF_TILE_M) {
-      const int r = t.row0 + min(tid, t.rows - 1);
-      s_rowoff[slot][tid] = (unsigned)(A.mode == 0 ? A.perm[r] : r) * (unsigned)K * 2u;
+    int seg0, seg1;
+    if (E <= PF_SEG_LDS) {
+      seg0 = s_seg[t.e];
+      seg1 = t.e + 1 < E ? s_seg[t.e + 1] : A.seg_offsets[E];
+    } else {
+      seg0 = A.seg_offsets[t.e];
+      seg1 = A.seg_offsets[t.e + 1];
     }
+    t.row0 = uniform_i32(seg0 + PF_TILE_M * (p - first));
+    t.rows = uniform_i32(min(PF_TILE_M, seg1 - seg0 - PF_TILE_M * (p - first)));
     return t;
   };
   // descriptors of a tile's column tiles for this wave; past the matrix (or no tile): empty
@@ -193,12 +198,23 @@ __global__ __launch_bounds__(PF_THREADS, WM == 1 ? 2 : PF_WG_PER_CU) void moe_pr
   // swizzle holds the row's piece (l & 15) ^ (row & 15).
   const rsrc_t a_rsrc = make_rsrc(A.a, (uint32_t)((int64_t)A.T * K * 2));
   static_assert(NLD == 4, "PfRowOff holds four rows");
-  auto row_offset = [&](int slot, int i) -> uint32_t {
-    const int row = 16 * wave + 4 * i + (lane >> 4);
-    return s_rowoff[slot][row] + (uint32_t)(((lane & 15) ^ (row & 15)) * 16);
+  // Row numbers in `a` of the four rows this lane stages for tile t (FFN1: through perm, a
+  // global read that is asked for at the start of the tile before, blocks before its first
+  // use); the rows a ragged tile lacks repeat its last row (never stored).
+  auto stage_row = [&](const PfTile& t, int i) -> uint32_t {
+    const int sr = t.row0 + min(16 * wave + 4 * i + (lane >> 4), t.rows - 1);
+    if (A.mode != 0) return (uint32_t)sr;
+    return t.valid ? (uint32_t)A.perm[sr] : 0u;
   };
-  auto row_offsets = [&](int slot) -> PfRowOff {
-    return PfRowOff{row_offset(slot, 0), row_offset(slot, 1), row_offset(slot, 2), row_offset(slot, 3)};
+  auto stage_rows = [&](const PfTile& t) -> PfRowOff {
+    return PfRowOff{stage_row(t, 0), stage_row(t, 1), stage_row(t, 2), stage_row(t, 3)};
+  };
+  auto row_offset = [&](uint32_t arow, int i) -> uint32_t {
+    const int row = 4 * i + (lane >> 4);  // 16 wave + row is the row of the tile
+    return arow * (uint32_t)K * 2u + (uint32_t)(((lane & 15) ^ (row & 15)) * 16);
+  };
+  auto row_offsets = [&](const PfRowOff r) -> PfRowOff {
+    return PfRowOff{row_offset(r.r0, 0), row_offset(r.r1, 1), row_offset(r.r2, 2), row_offset(r.r3, 3)};
   };
   auto load_a = [&](const PfRowOff off, int blk, int buf) {
     const uint32_t kb = (uint32_t)blk * (PF_KB * 2);
@@ -259,11 +275,10 @@ __global__ __launch_bounds__(PF_THREADS, WM == 1 ? 2 : PF_WG_PER_CU) void moe_pr
   long long pf_sum[8] = {0, 0, 0, 0, 0, 0, 0, 0};  // setup, issue, compute, wait, barrier, epilogue
 #endif
   PF_T0();
-  PfTile cur = setup(t_first, 0);
-  __syncthreads();
+  PfTile cur = find(t_first);
   rsrc_t cur_brs[PF_NT], nxt_brs[PF_NT];
   make_brs(cur, cur_brs);
-  PfRowOff cur_off = row_offsets(0);
+  PfRowOff cur_off = row_offsets(stage_rows(cur));
   load_b(I0{}, cur_brs, 0);
   load_a(cur_off, 0, 0);
   load_a(cur_off, 1, 1);
@@ -273,11 +288,19 @@ __global__ __launch_bounds__(PF_THREADS, WM == 1 ? 2 : PF_WG_PER_CU) void moe_pr
   const bool cross = (Q & 1) == 0;  // with an even chunk count the chunk stream crosses tiles too
 
   for (int it = 0; cur.valid; ++it) {
-    const int slot = it & 1;
-    const PfTile nxt = setup(t_first + (it + 1) * GX, slot ^ 1);
-    __syncthreads();
+    const PfTile nxt = find(t_first + (it + 1) * GX);
     make_brs(nxt, nxt_brs);
-    const PfRowOff nxt_off = row_offsets(slot ^ 1);
+    const PfRowOff nxt_rows = stage_rows(nxt);  // first needed two blocks before the tile's end
+    // FFN2 writes by token, times the token's gate: the tokens of the rows this lane writes
+    // are asked for now, their gates after the first chunk, both used in the epilogue
+    int cur_tk[PF_MT];
+    float cur_gt[PF_MT];
+#pragma unroll
+    for (int mi = 0; mi < PF_MT; ++mi) {
+      const int row = 16 * PF_MT * wm + 16 * mi + j;
+      cur_tk[mi] = (A.mode != 0 && row < cur.rows) ? A.perm[cur.row0 + row] : 0;
+      cur_gt[mi] = 1.0f;
+    }
     // scales and biases of this tile's channels (4 per lane and column tile), asked for now and
     // used in the epilogue, by when they have long arrived
     uint2_t sc2[PF_NT], bi2[PF_NT];
@@ -309,7 +332,7 @@ __global__ __launch_bounds__(PF_THREADS, WM == 1 ? 2 : PF_WG_PER_CU) void moe_pr
         const int ahead = blk + 2;
         bool issued = true;
         if (ahead < TB) load_a(cur_off, ahead, (gb + 2) % NBUF);
-        else if (nxt.valid) load_a(nxt_off, ahead - TB, (gb + 2) % NBUF);
+        else if (nxt.valid) load_a(row_offsets(nxt_rows), ahead - TB, (gb + 2) % NBUF);
         else issued = false;
         PF_ACC(1);
         compute(gb % NBUF, BUF, SUBI);
@@ -326,6 +349,10 @@ __global__ __launch_bounds__(PF_THREADS, WM == 1 ? 2 : PF_WG_PER_CU) void moe_pr
     };
     for (int c = 0; c < Q; c += 2) {
       do_chunk(c, I0{});
+      if (c == 0 && A.mode != 0) {
+#pragma unroll
+        for (int mi = 0; mi < PF_MT; ++mi) cur_gt[mi] = A.gate[cur_tk[mi]];
+      }
       if (c + 1 < Q) do_chunk(c + 1, I1{});
     }
     if (!cross && nxt.valid) load_b(I0{}, nxt_brs, 0);
@@ -334,40 +361,36 @@ __global__ __launch_bounds__(PF_THREADS, WM == 1 ? 2 : PF_WG_PER_CU) void moe_pr
     // The weights are the MFMA's first operand and the tokens its second, so the result tile is
     // channels x tokens: lane (g, j) holds channels 4 g .. 4 g + 3 of the column tile for token
     // j of the token tile - four neighbouring fp16 outputs, written with one 8-byte store.
+    // element offset of this lane's output rows (T N < 2^31: checked by the caller); -1: no row
+    int out_row[PF_MT];
 #pragma unroll
     for (int mi = 0; mi < PF_MT; ++mi) {
       const int row = 16 * PF_MT * wm + 16 * mi + j;
-      if (row >= cur.rows) continue;
-      const int srow = cur.row0 + row;
-      int64_t out_row;
-      float gt = 1.0f;
-      if (A.mode == 0) {
-        out_row = (int64_t)srow * N;
-      } else {
-        const int tk = A.perm[srow];
-        gt = A.gate[tk];
-        out_row = (int64_t)tk * N;
-      }
+      out_row[mi] = row < cur.rows ? (A.mode == 0 ? cur.row0 + row : cur_tk[mi]) * N : -1;
+    }
 #pragma unroll
-      for (int ni = 0; ni < PF_NT; ++ni) {
-        const int ct = cur.cb * PF_TILE_CT + wn * PF_NT + ni;
-        if (ct >= CT) continue;
-        const int c0 = 16 * ct + 4 * g;
-        const half_t sc[4] = {half_from_bits((uint16_t)sc2[ni].x), half_from_bits((uint16_t)(sc2[ni].x >> 16)),
-                              half_from_bits((uint16_t)sc2[ni].y), half_from_bits((uint16_t)(sc2[ni].y >> 16))};
-        const half_t bi[4] = {half_from_bits((uint16_t)bi2[ni].x), half_from_bits((uint16_t)(bi2[ni].x >> 16)),
-                              half_from_bits((uint16_t)bi2[ni].y), half_from_bits((uint16_t)(bi2[ni].y >> 16))};
+    for (int ni = 0; ni < PF_NT; ++ni) {
+      const int ct = cur.cb * PF_TILE_CT + wn * PF_NT + ni;
+      if (ct >= CT) continue;
+      const int c0 = 16 * ct + 4 * g;
+      const float sc[4] = {(float)half_from_bits((uint16_t)sc2[ni].x), (float)half_from_bits((uint16_t)(sc2[ni].x >> 16)),
+                           (float)half_from_bits((uint16_t)sc2[ni].y), (float)half_from_bits((uint16_t)(sc2[ni].y >> 16))};
+      const float bi[4] = {(float)half_from_bits((uint16_t)bi2[ni].x), (float)half_from_bits((uint16_t)(bi2[ni].x >> 16)),
+                           (float)half_from_bits((uint16_t)bi2[ni].y), (float)half_from_bits((uint16_t)(bi2[ni].y >> 16))};
+#pragma unroll
+      for (int mi = 0; mi < PF_MT; ++mi) {
+        if (out_row[mi] < 0) continue;
         float o[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) o[r] = fmaf(acc[mi][ni][r], (float)sc[r], (float)bi[r]);
+        for (int r = 0; r < 4; ++r) o[r] = fmaf(acc[mi][ni][r], sc[r], bi[r]);
         if (A.mode == 0) {
 #pragma unroll
           for (int r = 0; r < 4; ++r) o[r] = fmaxf(o[r], 0.0f);
         } else {
 #pragma unroll
-          for (int r = 0; r < 4; ++r) o[r] *= gt;
+          for (int r = 0; r < 4; ++r) o[r] *= cur_gt[mi];
           if (A.residual) {
-            const uint2_t rs = *(const uint2_t*)(A.residual + out_row + c0);
+            const uint2_t rs = *(const uint2_t*)(A.residual + out_row[mi] + c0);
             o[0] += (float)half_from_bits((uint16_t)rs.x);
             o[1] += (float)half_from_bits((uint16_t)(rs.x >> 16));
             o[2] += (float)half_from_bits((uint16_t)rs.y);
@@ -377,14 +400,14 @@ __global__ __launch_bounds__(PF_THREADS, WM == 1 ? 2 : PF_WG_PER_CU) void moe_pr
         uint2_t pk;
         pk.x = (uint32_t)half_to_bits((half_t)o[0]) | ((uint32_t)half_to_bits((half_t)o[1]) << 16);
         pk.y = (uint32_t)half_to_bits((half_t)o[2]) | ((uint32_t)half_to_bits((half_t)o[3]) << 16);
-        *(uint2_t*)(A.out + out_row + c0) = pk;
+        *(uint2_t*)(A.out + out_row[mi] + c0) = pk;
       }
     }
     PF_ACC(5);
     cur = nxt;
 #pragma unroll
     for (int ni = 0; ni < PF_NT; ++ni) cur_brs[ni] = nxt_brs[ni];
-    cur_off = nxt_off;
+    cur_off = row_offsets(nxt_rows);
   }
 #ifdef MOQE_PHASE_TRACE
   if (A.trace && lane == 0) {

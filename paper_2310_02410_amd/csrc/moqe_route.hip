@@ -4,7 +4,8 @@
 //                         lowest-index tie break, gate = softmax probability
 //   route_segments_kernel per-expert histogram, exclusive scan into contiguous
 //                         expert segments, stable token permutation
-// and one, route_small_kernel, that does both for a decode-sized batch.
+// and one, route_small_kernel, that does both for a decode-sized batch with MFMA scoring;
+// without its table step it also serves as the scoring kernel of larger batches.
 // Everything is deterministic: no atomics decide an order anywhere.
 #include "moqe_dev.h"
 #include "moqe_kernels.h"
