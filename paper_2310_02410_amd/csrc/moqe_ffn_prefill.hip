@@ -75,7 +75,7 @@ struct PfTile {
 };
 
 template <int BITS, int WM>
-__global__ __launch_bounds__(PF_THREADS, WM == 1 ? 2 : PF_WG_PER_CU) void moe_prefill_kernel(PrefillArgs A) {
+__global__ __launch_bounds__(PF_THREADS, (WM == 1 || BITS == 3) ? 2 : PF_WG_PER_CU) void moe_prefill_kernel(PrefillArgs A) {
   constexpr int WN = 4 / WM;                  // waves side by side along the channels
   constexpr int PF_MT = PF_TILE_M / 16 / WM;  // token tiles per wave
   constexpr int PF_TILE_CT = WN * PF_NT;      // column tiles per workgroup tile
@@ -434,7 +434,7 @@ static void launch_bits(const PrefillArgs& a, int64_t pairs, int num_cus, hipStr
   // Narrow ones (FFN2) take 64 x 128 tiles, three workgroups per compute unit, or the grid
   // would not fill the chip (measured: no gain from the wide shape there).
   const bool wide = CT >= 128;
-  const int per_cu = wide ? 2 : PF_WG_PER_CU;
+  const int per_cu = (wide || BITS == 3) ? 2 : PF_WG_PER_CU;
   args.n_cblocks = wide ? (CT + 15) / 16 : (CT + 7) / 8;
   int64_t grid = pairs * args.n_cblocks;  // upper bound on the tiles
   if (grid > (int64_t)per_cu * num_cus) grid = (int64_t)per_cu * num_cus;
