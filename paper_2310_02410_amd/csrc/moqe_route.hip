@@ -14,7 +14,7 @@ namespace {
 
 constexpr int SCORE_THREADS = 256;
 constexpr int SEG_THREADS = 1024;
-constexpr int SEG_LDS_INTS = 8192;
+constexpr int SEG_LDS_INTS = 9216;
 
 // Wave-level top-1 over one row of logits held in LDS or global memory.
 // Returns through lane 0 semantics: every lane gets the same (idx, gate).
@@ -208,8 +208,10 @@ __device__ inline uint64_t match_any(int key, int nb) {
   return m;
 }
 
-// Single block.  cnt[chunk][E] (chunks of 64 consecutive tokens) lives in LDS
-// when it fits, else in the caller's workspace.
+// Single block.  cnt[expert][chunk] (chunks of 64 consecutive tokens, rows of an odd length so
+// that neither a wave that walks along the chunks of one expert nor one that scatters over the
+// experts of one chunk meets bank conflicts) lives in LDS when it fits, else in the caller's
+// workspace.
 __global__ __launch_bounds__(SEG_THREADS) void route_segments_kernel(const int* __restrict__ expert_idx, int T, int E,
                                                                       int* __restrict__ seg_offsets,
                                                                       int* __restrict__ perm, int* ws_cnt) {
@@ -220,11 +222,12 @@ __global__ __launch_bounds__(SEG_THREADS) void route_segments_kernel(const int* 
   const int nthreads = (int)blockDim.x;
   const int nwaves = nthreads / 64;
   const int nchunks = (T + 63) / 64;
-  int* cnt = ((int64_t)nchunks * E <= SEG_LDS_INTS) ? s_cnt : ws_cnt;
+  const int CP = nchunks | 1;  // row length of cnt
+  int* cnt = ((int64_t)CP * E <= SEG_LDS_INTS) ? s_cnt : ws_cnt;
   int nb = 0;
   while ((1 << nb) <= E) ++nb;  // keys 0..E (E = "no token")
 
-  for (int i = tid; i < nchunks * E; i += nthreads) cnt[i] = 0;
+  for (int i = tid; i < CP * E; i += nthreads) cnt[i] = 0;
   __syncthreads();
 
   for (int c = wave; c < nchunks; c += nwaves) {
@@ -233,19 +236,25 @@ __global__ __launch_bounds__(SEG_THREADS) void route_segments_kernel(const int* 
     int key = valid ? expert_idx[t] : E;
     uint64_t m = match_any(key, nb);
     bool leader = (__ffsll((long long)m) - 1) == lane;
-    if (valid && leader) cnt[c * E + key] = __popcll(m);
+    if (valid && leader) cnt[key * CP + c] = __popcll(m);
   }
   __syncthreads();
 
-  // per expert: exclusive running sum over chunks
-  for (int e = tid; e < E; e += nthreads) {
-    int run = 0;
-    for (int c = 0; c < nchunks; ++c) {
-      int v = cnt[c * E + e];
-      cnt[c * E + e] = run;
-      run += v;
+  // per expert: exclusive running sum over chunks, a wave per expert, a lane per chunk
+  for (int e = wave; e < E; e += nwaves) {
+    int carry = 0;
+    for (int c0 = 0; c0 < nchunks; c0 += 64) {
+      const int c = c0 + lane;
+      const int v = (c < nchunks) ? cnt[e * CP + c] : 0;
+      int inc = v;
+      for (int off = 1; off < 64; off <<= 1) {
+        int o = __shfl_up(inc, off, 64);
+        if (lane >= off) inc += o;
+      }
+      if (c < nchunks) cnt[e * CP + c] = carry + inc - v;
+      carry += __shfl(inc, 63, 64);
     }
-    s_off[e] = run;
+    if (lane == 0) s_off[e] = carry;
   }
   __syncthreads();
 
@@ -278,7 +287,7 @@ __global__ __launch_bounds__(SEG_THREADS) void route_segments_kernel(const int* 
     uint64_t m = match_any(key, nb);
     if (valid) {
       int rank = __popcll(m & ((1ull << lane) - 1ull));
-      perm[s_off[key] + cnt[c * E + key] + rank] = t;
+      perm[s_off[key] + cnt[key * CP + c] + rank] = t;
     }
   }
 }
@@ -426,7 +435,7 @@ static bool small_route_fits(int T, int d, int E) {
 
 size_t moqe_route_ws_bytes(int64_t T, int64_t E) {
   int64_t nchunks = (T + 63) / 64;
-  int64_t ints = nchunks * E;
+  int64_t ints = (nchunks | 1) * E;
   size_t b = ints > SEG_LDS_INTS ? (size_t)ints * 4 : 0;
   return b < 256 ? 256 : ((b + 255) & ~(size_t)255);
 }
