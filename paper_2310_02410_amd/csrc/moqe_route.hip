@@ -298,7 +298,7 @@ __global__ __launch_bounds__(SEG_THREADS) void route_segments_kernel(const int* 
 // The logits are a small MFMA GEMM (token tiles x expert tiles of 16 x 16, 32 rows of d per
 // step) with d split over the 16 waves; the partial tiles are summed through LDS in a fixed
 // order, then each wave picks top-1 / softmax for its tokens and wave 0 builds the dispatch
-// tables.  NT = E / 16 expert tiles, MT = token tiles kept per wave (MT * NT <= 8).
+// tables.  NT = E / 16 expert tiles, MT = token tiles kept per wave (4, or 2 for 128 experts).
 // ---------------------------------------------------------------------------
 constexpr int SMALL_THREADS = 1024;
 constexpr int SMALL_WAVES = 16;
@@ -312,7 +312,7 @@ __global__ __launch_bounds__(SMALL_THREADS) void route_small_kernel(const half_t
                                                                     float* __restrict__ gate,
                                                                     int* __restrict__ seg_offsets,
                                                                     int* __restrict__ perm) {
-  constexpr int MT = !TABLES ? 1 : NT >= 8 ? 1 : NT == 4 ? 2 : 4;
+  constexpr int MT = !TABLES ? 1 : NT >= 8 ? 2 : 4;
   constexpr int E = 16 * NT;
   // this workgroup's tokens
   const int t_base = TABLES ? 0 : (int)blockIdx.x * 16 * MT;
@@ -320,7 +320,7 @@ __global__ __launch_bounds__(SMALL_THREADS) void route_small_kernel(const half_t
   x += (int64_t)t_base * d;
   expert_idx += t_base;
   gate += t_base;
-  __shared__ float4_t s_part[SMALL_WAVES][MT * NT][64];
+  __shared__ float4_t s_part[SMALL_WAVES][NT][64];  // one token tile's partial sums at a time
   __shared__ float s_logit[MT * 16 * E];
   __shared__ int s_idx[64];
   __shared__ int s_seg[E + 1];
@@ -355,20 +355,21 @@ __global__ __launch_bounds__(SMALL_THREADS) void route_small_kernel(const half_t
         if (mi < mt) acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mi], b, acc[mi][ni], 0, 0, 0);
     }
   }
-#pragma unroll
-  for (int mi = 0; mi < MT; ++mi)
-#pragma unroll
-    for (int ni = 0; ni < NT; ++ni) s_part[wave][mi * NT + ni][lane] = acc[mi][ni];
-  __syncthreads();
   // D layout of a tile: lane (g, j), register r holds token row 4 g + r, expert column j
-  for (int o = tid; o < mt * NT * 256; o += SMALL_THREADS) {
-    const int tile = o >> 8, l = (o & 255) >> 2, r = o & 3;
-    float sum = 0.0f;
-    for (int w = 0; w < SMALL_WAVES; ++w) sum += reinterpret_cast<const float*>(&s_part[w][tile][l])[r];
-    const int mi = tile / NT, ni = tile - mi * NT;
-    s_logit[(16 * mi + 4 * (l >> 4) + r) * E + 16 * ni + (l & 15)] = sum;
+#pragma unroll
+  for (int mi = 0; mi < MT; ++mi) {
+    if (mi >= mt) break;  // uniform
+#pragma unroll
+    for (int ni = 0; ni < NT; ++ni) s_part[wave][ni][lane] = acc[mi][ni];
+    __syncthreads();
+    for (int o = tid; o < NT * 256; o += SMALL_THREADS) {
+      const int ni = o >> 8, l = (o & 255) >> 2, r = o & 3;
+      float sum = 0.0f;
+      for (int w = 0; w < SMALL_WAVES; ++w) sum += reinterpret_cast<const float*>(&s_part[w][ni][l])[r];
+      s_logit[(16 * mi + 4 * (l >> 4) + r) * E + 16 * ni + (l & 15)] = sum;
+    }
+    __syncthreads();
   }
-  __syncthreads();
   for (int t = wave; t < T; t += SMALL_WAVES) {
     int idx;
     float gt;
@@ -425,8 +426,8 @@ static bool small_route_fits(int T, int d, int E) {
   switch (E) {
     case 16: return mt <= 4;
     case 32: return mt <= 4;
-    case 64: return mt <= 2;
-    case 128: return mt <= 1;
+    case 64: return mt <= 4;
+    case 128: return mt <= 2;
     default: return false;
   }
 }

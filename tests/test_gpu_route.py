@@ -38,15 +38,16 @@ def test_shapes(T, d, E):
 
 @pytest.mark.parametrize("T,d,E", [(1, 512, 16), (24, 1024, 32), (64, 512, 32), (17, 1536, 32), (33, 1024, 16),
                                    (32, 1024, 64), (16, 1024, 128), (8, 512, 128), (5, 2048, 64),
-                                   (16, 768, 128), (24, 96, 32), (3, 32, 16)])
+                                   (16, 768, 128), (24, 96, 32), (3, 32, 16), (24, 768, 128), (32, 1024, 128),
+                                   (17, 1024, 128), (33, 1024, 64), (64, 1024, 64)])
 def test_single_launch_router_shapes(T, d, E):
-    """Decode-sized batches take the one-workgroup MFMA router; (33, 1024, 64) and
-    (17, 1024, 128) would not fit it and stay on the two-kernel path (covered above)."""
+    """Decode-sized batches take the one-workgroup MFMA router: up to 64 tokens, 32 with 128
+    experts; (33, 1024, 128) does not fit it and takes the two-kernel path (covered below)."""
     _route_case(W.small("r1", E=E, d=d, f=32, T=T, seed=3 * T + E))
 
 
 @pytest.mark.parametrize("T,d,E", [(65, 512, 16), (300, 1024, 64), (1000, 512, 128), (1536, 1024, 32),
-                                   (129, 1536, 32), (4096, 768, 128), (81, 96, 16)])
+                                   (129, 1536, 32), (4096, 768, 128), (81, 96, 16), (33, 1024, 128)])
 def test_mfma_scoring_for_many_tokens(T, d, E):
     """More than 64 tokens with E in {16, 32, 64, 128} and d a multiple of 32: MFMA scoring by
     one workgroup per 16 tokens (ragged last tile), then the segment kernel."""
