@@ -60,6 +60,9 @@ constexpr int PF_NT = 4;         // column tiles (of 16 channels) per wave
 constexpr int PF_KB = 128;       // rows of K staged in LDS at a time
 constexpr int PF_WG_PER_CU = 3;  // persistent workgroups per compute unit
 constexpr int PF_MAX_E = 1024;
+// An expert's packed weights are read once per 64-token tile of that expert, by workgroups of
+// one XCD: ordinary cached loads (the decode kernel's weights are read once and stream past L2).
+constexpr int PF_B_NT = 0;
 constexpr int PF_SEG_LDS = 128;  // segment starts are kept in LDS for up to this many experts
 
 // The four token rows a lane stages per block: first their row numbers in `a`, then their byte
@@ -188,8 +191,8 @@ __global__ __launch_bounds__(PF_THREADS, (WM == 1 || BITS == 3) ? 2 : PF_WG_PER_
     constexpr int buf = decltype(BUF)::value;
 #pragma unroll
     for (int ni = 0; ni < PF_NT; ++ni) {
-      load_words<LW>(brs[ni], (uint32_t)c * CHUNK_BYTES + lane_lo, b_lo[buf][ni]);
-      if constexpr (BITS == 3) load_words<HW>(brs[ni], (uint32_t)c * CHUNK_BYTES + lane_hi, b_hi[buf][ni]);
+      load_words<LW, PF_B_NT>(brs[ni], (uint32_t)c * CHUNK_BYTES + lane_lo, b_lo[buf][ni]);
+      if constexpr (BITS == 3) load_words<HW, PF_B_NT>(brs[ni], (uint32_t)c * CHUNK_BYTES + lane_hi, b_hi[buf][ni]);
     }
   };
 

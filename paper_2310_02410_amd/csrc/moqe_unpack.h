@@ -215,9 +215,8 @@ typedef __amdgpu_buffer_rsrc_t rsrc_t;
 __device__ inline rsrc_t make_rsrc(const void* base, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
 }
-template <int N>
+template <int N, int NT = 2>  // NT = 2: streamed once, no reuse worth caching; 0: ordinary cached load
 __device__ inline void load_words(rsrc_t r, uint32_t byte_off, uint32_t* dst) {
-  constexpr int NT = 2;  // streamed once: no reuse worth caching
   if (N == 4) {
     uint4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, NT);
     dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
