@@ -56,7 +56,6 @@ namespace {
 
 constexpr int PF_THREADS = 256;
 constexpr int PF_TILE_M = 64;    // tokens per workgroup tile
-constexpr int PF_NT = 4;         // column tiles (of 16 channels) per wave
 constexpr int PF_KB = 128;       // rows of K staged in LDS at a time
 constexpr int PF_WG_PER_CU = 3;  // persistent workgroups per compute unit
 constexpr int PF_MAX_E = 1024;
@@ -77,8 +76,10 @@ struct PfTile {
   bool valid;
 };
 
-template <int BITS, int WM>
-__global__ __launch_bounds__(PF_THREADS, (WM == 1 || BITS == 3) ? 2 : PF_WG_PER_CU) void moe_prefill_kernel(PrefillArgs A) {
+// PF_NT: column tiles (of 16 channels) per wave, 4 or 2
+template <int BITS, int PF_NT>
+__global__ __launch_bounds__(PF_THREADS, PF_NT == 4 ? 2 : PF_WG_PER_CU) void moe_prefill_kernel(PrefillArgs A) {
+  constexpr int WM = 1;                       // waves along the tokens: every wave owns all 64
   constexpr int WN = 4 / WM;                  // waves side by side along the channels
   constexpr int PF_MT = PF_TILE_M / 16 / WM;  // token tiles per wave
   constexpr int PF_TILE_CT = WN * PF_NT;      // column tiles per workgroup tile
@@ -437,13 +438,13 @@ static void launch_bits(const PrefillArgs& a, int64_t pairs, int num_cus, hipStr
   // Narrow ones (FFN2) take 64 x 128 tiles, three workgroups per compute unit, or the grid
   // would not fill the chip (measured: no gain from the wide shape there).
   const bool wide = CT >= 128;
-  const int per_cu = (wide || BITS == 3) ? 2 : PF_WG_PER_CU;
+  const int per_cu = wide ? 2 : PF_WG_PER_CU;
   args.n_cblocks = wide ? (CT + 15) / 16 : (CT + 7) / 8;
   int64_t grid = pairs * args.n_cblocks;  // upper bound on the tiles
   if (grid > (int64_t)per_cu * num_cus) grid = (int64_t)per_cu * num_cus;
   grid = grid < 8 ? 8 : (grid & ~(int64_t)7);  // a multiple of the 8 XCDs
   if (wide)
-    hipLaunchKernelGGL((moe_prefill_kernel<BITS, 1>), dim3((unsigned)grid), dim3(PF_THREADS), 0, stream, args);
+    hipLaunchKernelGGL((moe_prefill_kernel<BITS, 4>), dim3((unsigned)grid), dim3(PF_THREADS), 0, stream, args);
   else
     hipLaunchKernelGGL((moe_prefill_kernel<BITS, 2>), dim3((unsigned)grid), dim3(PF_THREADS), 0, stream, args);
 }
