@@ -7,13 +7,14 @@
 // Work decomposition
 //   pair = (expert e, tile of 64 of its tokens), found on device from seg_offsets; only
 //          experts with at least min_tokens tokens have pairs (the decode kernel takes the rest)
-//   workgroup = (pair, block of output channels), 4 waves, two shapes:
-//          WM = 1: 256 channels, every wave owns all 64 tokens x 64 channels (4 x 4 accumulator
-//                  tiles of v_mfma_f32_16x16x32_f16), 2 workgroups per compute unit - wide
-//                  matrices (FFN1)
-//          WM = 2: 128 channels, 2 token halves x 2 channel halves, a wave owns 32 tokens x 64
-//                  channels (2 x 4 tiles), 3 workgroups per compute unit - narrow matrices
-//                  (FFN2), so that the grid still fills the chip
+//   workgroup = (pair, block of output channels), 4 waves side by side along the channels;
+//          every wave owns all 64 tokens of the tile, so a weight fragment is unpacked once
+//          for four token tiles.  Two shapes:
+//          PF_NT = 4: 256 channels, 64 per wave (4 x 4 accumulator tiles of
+//                  v_mfma_f32_16x16x32_f16), 2 workgroups per compute unit - launches with
+//                  enough tiles for several full rounds
+//          PF_NT = 2: 128 channels, 32 per wave (4 x 2 tiles), 3 workgroups per compute unit -
+//                  narrow matrices and smaller launches, so that the grid still fills the chip
 //   The grid is persistent; a workgroup walks over its share of the tiles.
 //   K runs in staged blocks of 128 rows:
 //     - the block's 64 token rows are staged in LDS by loads that go from global memory
@@ -22,7 +23,7 @@
 //       by the row number, so that the fragment reads are conflict-free without padding; every
 //       wave reads its A fragments from there;
 //     - each wave loads the packed chunk (128 rows for int4, 256 for int2/int3) of each of its
-//       4 column tiles with one 16-byte load per lane (the packed layout is already in B-operand
+//       column tiles with one 16-byte load per lane (the packed layout is already in B-operand
 //       order), one chunk ahead, and dequantizes in registers: the unpack of one B fragment is
 //       amortized over the wave's token tiles, and the fragment never has to travel through LDS
 //       because no other wave needs it;
@@ -79,10 +80,8 @@ struct PfTile {
 // PF_NT: column tiles (of 16 channels) per wave, 4 or 2
 template <int BITS, int PF_NT>
 __global__ __launch_bounds__(PF_THREADS, PF_NT == 4 ? 2 : PF_WG_PER_CU) void moe_prefill_kernel(PrefillArgs A) {
-  constexpr int WM = 1;                       // waves along the tokens: every wave owns all 64
-  constexpr int WN = 4 / WM;                  // waves side by side along the channels
-  constexpr int PF_MT = PF_TILE_M / 16 / WM;  // token tiles per wave
-  constexpr int PF_TILE_CT = WN * PF_NT;      // column tiles per workgroup tile
+  constexpr int PF_MT = PF_TILE_M / 16;       // token tiles per wave: all of the tile's
+  constexpr int PF_TILE_CT = 4 * PF_NT;       // column tiles per workgroup tile
   constexpr int SC = BITS == 4 ? 4 : 8;       // steps of 32 rows per packed chunk
   constexpr int SUB = SC / 4;                 // staged K blocks per packed chunk
   constexpr int LO_BITS = BITS == 3 ? 2 : BITS;
@@ -100,7 +99,7 @@ __global__ __launch_bounds__(PF_THREADS, PF_NT == 4 ? 2 : PF_WG_PER_CU) void moe
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = uniform_i32(tid >> 6);
-  const int wm = wave % WM, wn = wave / WM;
+  const int wn = wave;  // this wave's place along the channels
   const int g = lane >> 4, j = lane & 15;
   const int E = A.E, K = A.K, N = A.N;
   const int G = (int)gridDim.x, bid = (int)blockIdx.x;
@@ -229,9 +228,8 @@ __global__ __launch_bounds__(PF_THREADS, PF_NT == 4 ? 2 : PF_WG_PER_CU) void moe
     __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_ptr)&s_a[buf][16 * wave + 12][0], 16, off.r3 + kb, 0, 0, 0);
   };
   // this lane's fragment piece per step of a block: logical piece 4 s + g of a row with (row & 15) == j
-  int frag_piece[4];
-#pragma unroll
-  for (int s4 = 0; s4 < 4; ++s4) frag_piece[s4] = (4 * s4 + g) ^ j;
+  // = frag_base ^ (4 s): 4 s only has bits that g has not
+  const int frag_base = g ^ j;
 
   // the four steps of staged block `sub` of the chunk held in B buffer BUF
   auto compute = [&](int abuf, auto BUF, auto SUBI) {
@@ -244,7 +242,7 @@ __global__ __launch_bounds__(PF_THREADS, PF_NT == 4 ? 2 : PF_WG_PER_CU) void moe
       half8_t a[PF_MT];
 #pragma unroll
       for (int mi = 0; mi < PF_MT; ++mi)
-        a[mi] = __builtin_bit_cast(half8_t, s_a[abuf][16 * PF_MT * wm + 16 * mi + j][frag_piece[s4]]);
+        a[mi] = __builtin_bit_cast(half8_t, s_a[abuf][16 * mi + j][frag_base ^ (4 * s4)]);
 #pragma unroll
       for (int ni = 0; ni < PF_NT; ++ni) {
         half8_t w;
@@ -301,7 +299,7 @@ __global__ __launch_bounds__(PF_THREADS, PF_NT == 4 ? 2 : PF_WG_PER_CU) void moe
     float cur_gt[PF_MT];
 #pragma unroll
     for (int mi = 0; mi < PF_MT; ++mi) {
-      const int row = 16 * PF_MT * wm + 16 * mi + j;
+      const int row = 16 * mi + j;
       cur_tk[mi] = (A.mode != 0 && row < cur.rows) ? A.perm[cur.row0 + row] : 0;
       cur_gt[mi] = 1.0f;
     }
@@ -369,7 +367,7 @@ __global__ __launch_bounds__(PF_THREADS, PF_NT == 4 ? 2 : PF_WG_PER_CU) void moe
     int out_row[PF_MT];
 #pragma unroll
     for (int mi = 0; mi < PF_MT; ++mi) {
-      const int row = 16 * PF_MT * wm + 16 * mi + j;
+      const int row = 16 * mi + j;
       out_row[mi] = row < cur.rows ? (A.mode == 0 ? cur.row0 + row : cur_tk[mi]) * N : -1;
     }
 #pragma unroll
@@ -432,12 +430,14 @@ template <int BITS>
 static void launch_bits(const PrefillArgs& a, int64_t pairs, int num_cus, hipStream_t stream) {
   PrefillArgs args = a;
   const int CT = a.N / 16;
-  // Wide matrices (FFN1) take 64 x 256 tiles: every wave owns all 64 tokens x 64 channels, so
-  // a weight fragment is unpacked once for four token tiles and a staged block feeds twice the
-  // arithmetic; two workgroups per compute unit (the 4 x 4 accumulator tiles need the registers).
-  // Narrow ones (FFN2) take 64 x 128 tiles, three workgroups per compute unit, or the grid
-  // would not fill the chip (measured: no gain from the wide shape there).
-  const bool wide = CT >= 128;
+  // Both shapes give every wave all 64 tokens, so a weight fragment is unpacked once for four
+  // token tiles.  64 x 256 tiles (64 channels per wave, two workgroups per compute unit: the
+  // 4 x 4 accumulator tiles need the registers) halve the token-row traffic per flop; 64 x 128
+  // tiles (32 channels per wave, three workgroups per compute unit) make twice as many,
+  // half-sized tiles.  The big shape pays once a launch has at least three full rounds of its
+  // tiles (measured: +7 % at 8192 tokens, -10 % at 1536); below that the last, partly filled
+  // round costs more than the traffic saves.
+  const bool wide = CT >= 128 && pairs * ((CT + 15) / 16) >= 3ll * 2 * num_cus;
   const int per_cu = wide ? 2 : PF_WG_PER_CU;
   args.n_cblocks = wide ? (CT + 15) / 16 : (CT + 7) / 8;
   int64_t grid = pairs * args.n_cblocks;  // upper bound on the tiles
