@@ -88,14 +88,19 @@ int moqe_set_launch_mode(int mode);
  * segments with at least min_segment_tokens tokens are computed by the tiled MFMA kernel (token
  * rows staged in LDS, 64-token tiles), all other segments by the dequantize-in-register decode
  * kernel.  Smaller batches do not launch the tiled kernel at all (a decode step would pay a
- * launch for segments that almost never exist).  Defaults below; a huge min_batch_tokens
- * switches the tiled kernel off.  The tiled kernel needs K >= 256 and a multiple of 128 (int4)
- * or 256 (int2, int3), and T*K*2 < 2^32; other layers use the decode kernel throughout.
+ * launch for segments that almost never exist), and batches with at least
+ * all_tiled_tokens_per_expert tokens per expert on average (T >= that * E) do not launch the
+ * decode kernel: every segment, however small, then takes the tiled kernel (a padded tile
+ * for the rare small segment costs less than a launch).  Defaults below; a huge
+ * min_batch_tokens switches the tiled kernel off, a huge all_tiled_tokens_per_expert the
+ * second rule.  The tiled kernel needs K >= 256 and a multiple of 128 (int4) or 256 (int2,
+ * int3), T*K*2 < 2^32 and T*N < 2^31; other layers use the decode kernel throughout.
  * Launch mode FUSED uses the decode kernel for everything it chains.
  * Returns 0, or -1 (nothing changed) if a value < 1. */
 #define MOQE_PREFILL_MIN_SEGMENT_DEFAULT 5
 #define MOQE_PREFILL_MIN_BATCH_DEFAULT 65
-int moqe_set_prefill_policy(int min_segment_tokens, int min_batch_tokens);
+#define MOQE_PREFILL_ALL_TILED_DEFAULT 16
+int moqe_set_prefill_policy(int min_segment_tokens, int min_batch_tokens, int all_tiled_tokens_per_expert);
 
 /* Bytes of one packed [K,N] matrix = K*N*bits/8 (Table 2: exactly `bits` bits
  * per expert weight).  Returns 0 for an unsupported (bits, K, N). Host only. */

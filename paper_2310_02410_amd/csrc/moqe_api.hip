@@ -49,6 +49,7 @@ std::atomic<int> g_launch_mode{MOQE_LAUNCH_AUTO};
 // one pass of the tiled kernel (64-token tiles) is cheaper.
 std::atomic<int> g_prefill_min{MOQE_PREFILL_MIN_SEGMENT_DEFAULT};
 std::atomic<int> g_prefill_batch{MOQE_PREFILL_MIN_BATCH_DEFAULT};
+std::atomic<int> g_prefill_all{MOQE_PREFILL_ALL_TILED_DEFAULT};
 
 }  // namespace
 
@@ -71,10 +72,11 @@ const char* moqe_last_hip_error(void) { return g_hip_error; }
 
 int moqe_version(void) { return 1; }
 
-int moqe_set_prefill_policy(int min_segment_tokens, int min_batch_tokens) {
-  if (min_segment_tokens < 1 || min_batch_tokens < 1) return -1;
+int moqe_set_prefill_policy(int min_segment_tokens, int min_batch_tokens, int all_tiled_tokens_per_expert) {
+  if (min_segment_tokens < 1 || min_batch_tokens < 1 || all_tiled_tokens_per_expert < 1) return -1;
   g_prefill_min.store(min_segment_tokens);
   g_prefill_batch.store(min_batch_tokens);
+  g_prefill_all.store(all_tiled_tokens_per_expert);
   return 0;
 }
 
@@ -257,7 +259,8 @@ static void set_ffn2(DecodeArgs* a, const moqe_layer* L, const moqe_f16* h, cons
 // tiled MFMA kernel the large ones (none can exist when T is below the threshold).
 static hipError_t launch_contraction(DecodeArgs& a, int phase, int ksteps, hipStream_t stream) {
   const PhaseArgs& p = a.ph[phase];
-  const int pmin = g_prefill_min.load();
+  // many tokens per expert on average: everything through the tiled kernel
+  const int pmin = (int64_t)a.T >= (int64_t)g_prefill_all.load() * a.E ? 1 : g_prefill_min.load();
   // (the tiled kernel addresses its input rows with 32-bit byte offsets and its output rows with
   // 32-bit element offsets)
   const bool split = a.T >= pmin && a.T >= g_prefill_batch.load() && moqe_prefill_supported(a.bits, p.K, p.N) &&
@@ -266,8 +269,11 @@ static hipError_t launch_contraction(DecodeArgs& a, int phase, int ksteps, hipSt
   a.phase_mask = 2 << phase;
   a.min_tokens = 1;
   a.max_tokens = split ? pmin : INT_MAX;
-  hipError_t e = moqe_launch_decode(a, num_cus(), stream);
-  if (e != hipSuccess || !split) return e;
+  // (with a threshold of one token every segment is the tiled kernel's: no decode launch)
+  if (!split || pmin > 1) {
+    hipError_t e = moqe_launch_decode(a, num_cus(), stream);
+    if (e != hipSuccess || !split) return e;
+  }
   PrefillArgs q;
   memset(&q, 0, sizeof(q));
   q.bits = a.bits;

@@ -70,7 +70,7 @@ def lib() -> ctypes.CDLL:
     L.moqe_set_launch_mode.restype = ci
     L.moqe_set_launch_mode.argtypes = [ci]
     L.moqe_set_prefill_policy.restype = ci
-    L.moqe_set_prefill_policy.argtypes = [ci, ci]
+    L.moqe_set_prefill_policy.argtypes = [ci, ci, ci]
     L.moqe_packed_bytes.restype = sz
     L.moqe_packed_bytes.argtypes = [ci, i64, i64]
     L.moqe_check_matrix.restype = ci
@@ -151,14 +151,18 @@ def moqe_set_launch_mode(mode: int) -> int:
     return old
 
 
-PREFILL_MIN_SEGMENT_DEFAULT, PREFILL_MIN_BATCH_DEFAULT = 5, 65
+PREFILL_MIN_SEGMENT_DEFAULT, PREFILL_MIN_BATCH_DEFAULT, PREFILL_ALL_TILED_DEFAULT = 5, 65, 16
+PREFILL_NEVER = 2**31 - 1  # as all_tiled_tokens_per_expert: keep the decode kernel for small segments
 
 
 def moqe_set_prefill_policy(min_segment_tokens: int = PREFILL_MIN_SEGMENT_DEFAULT,
-                            min_batch_tokens: int = PREFILL_MIN_BATCH_DEFAULT) -> None:
+                            min_batch_tokens: int = PREFILL_MIN_BATCH_DEFAULT,
+                            all_tiled_tokens_per_expert: int = PREFILL_ALL_TILED_DEFAULT) -> None:
     """Process-wide path choice: in batches of at least min_batch_tokens, expert segments with at
-    least min_segment_tokens tokens take the tiled MFMA kernel.  No arguments: the defaults."""
-    if lib().moqe_set_prefill_policy(min_segment_tokens, min_batch_tokens) != 0:
+    least min_segment_tokens tokens take the tiled MFMA kernel; with at least
+    all_tiled_tokens_per_expert tokens per expert on average, all segments do.  No arguments:
+    the defaults."""
+    if lib().moqe_set_prefill_policy(min_segment_tokens, min_batch_tokens, all_tiled_tokens_per_expert) != 0:
         raise ValueError("thresholds must be >= 1")
 
 

@@ -33,8 +33,10 @@ def test_every_declared_symbol_is_exported():
 def test_version_and_strings():
     L = moqe.lib()
     assert L.moqe_version() == 1
-    assert L.moqe_set_prefill_policy(0, 65) == -1 and L.moqe_set_prefill_policy(5, 0) == -1
-    assert L.moqe_set_prefill_policy(moqe.PREFILL_MIN_SEGMENT_DEFAULT, moqe.PREFILL_MIN_BATCH_DEFAULT) == 0
+    assert L.moqe_set_prefill_policy(0, 65, 16) == -1 and L.moqe_set_prefill_policy(5, 0, 16) == -1
+    assert L.moqe_set_prefill_policy(5, 65, 0) == -1
+    assert L.moqe_set_prefill_policy(moqe.PREFILL_MIN_SEGMENT_DEFAULT, moqe.PREFILL_MIN_BATCH_DEFAULT,
+                                     moqe.PREFILL_ALL_TILED_DEFAULT) == 0
     assert L.moqe_set_launch_mode(99) == -1
     old = L.moqe_set_launch_mode(moqe.LAUNCH_SEPARATE)
     assert L.moqe_set_launch_mode(old) == moqe.LAUNCH_SEPARATE

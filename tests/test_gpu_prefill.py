@@ -15,11 +15,11 @@ pytestmark = pytest.mark.gpu
 
 @pytest.fixture
 def prefill_min():
-    """Sets the path-choice thresholds for one test (any batch size may use the tiled kernel)
-    and restores the defaults afterwards."""
+    """Sets the path-choice thresholds for one test (any batch size may use the tiled kernel,
+    segments below n tokens always take the decode kernel) and restores the defaults afterwards."""
 
     def set_min(n):
-        moqe.moqe_set_prefill_policy(n, 1)
+        moqe.moqe_set_prefill_policy(n, 1, moqe.PREFILL_NEVER)
 
     yield set_min
     moqe.moqe_set_prefill_policy()
@@ -65,10 +65,18 @@ def test_tiled_kernel_residual_and_odd_widths(prefill_min, bits):
         _parity(W.small(E=3, d=64, f=256, T=70, seed=82), bits)
 
 
+@pytest.mark.parametrize("all_tiled", (False, True))
 @pytest.mark.parametrize("bits", (4, 2))
-def test_forced_segment_sizes(bits):
-    """Segments of exactly 4, 5, 63, 64, 65 and 200 tokens at the default thresholds: the
-    first goes to the decode kernel, the others to the tiled one, with full and ragged tiles."""
+def test_forced_segment_sizes(bits, all_tiled, prefill_min):
+    """Segments of exactly 4, 5, 63, 64, 65 and 200 tokens, with full and ragged tiles.  With
+    the decode kernel kept for segments below 5 tokens the first goes there and the others to
+    the tiled kernel; at the defaults this batch has 50 tokens per expert, so all of them,
+    the 4-token one included, take the tiled kernel and no decode kernel is launched."""
+    if all_tiled:
+        moqe.moqe_set_prefill_policy()
+    else:
+        moqe.moqe_set_prefill_policy(moqe.PREFILL_MIN_SEGMENT_DEFAULT, moqe.PREFILL_MIN_BATCH_DEFAULT,
+                                     moqe.PREFILL_NEVER)
     wl = W.small(E=8, d=256, f=512, T=4 + 5 + 63 + 64 + 65 + 200, seed=84)
     sizes = (4, 5, 63, 64, 65, 200, 0, 0)
     idx = np.concatenate([np.full(n, e) for e, n in enumerate(sizes)])
