@@ -243,14 +243,14 @@ def main():
                    active_experts=float(np.mean([a[0] for a in ab])), layer_bytes=layer_bytes, parts=parts,
                    step_gbs=layer_bytes / (best_ms * 1e-3) / 1e9, step_tflops=4.0 * T * d * f / (best_ms * 1e-3) / 1e12)
         if compute_bound:
-            # one launch of the tiled kernel per contraction (plus a decode-kernel launch for the
-            # few small segments, part of the figure): 2 T d f flops each
+            # one launch of the tiled kernel per contraction: 2 T d f flops each (at these sizes,
+            # 16 or more tokens per expert, every segment takes the tiled kernel)
             kern_us = 0.5 * (parts["ffn1_back_to_back_us"] + parts["ffn2_back_to_back_us"])
             flops = 2.0 * T * d * f
             res.update(bound="mfma", kernel_us=kern_us, kernel_work=flops, achieved=flops / (kern_us * 1e-6) / 1e12,
                        peak=MFMA_F16_PEAK_TFLOPS, unit="TFLOP/s",
-                       kernel="moe_prefill_kernel<%d,2> (FFN1 and FFN2 launches averaged; each includes the decode "
-                              "kernel's launch for segments below 5 tokens)" % b)
+                       kernel="moe_prefill_kernel<%d,*> (the launches of FFN1 and FFN2, each back to back, "
+                              "averaged)" % b)
         else:
             kern_us = parts["ffn1_back_to_back_us"]
             res.update(bound="hbm", kernel_us=kern_us, kernel_work=ffn1_bytes,
