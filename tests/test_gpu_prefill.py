@@ -87,6 +87,31 @@ def test_forced_segment_sizes(bits, all_tiled, prefill_min):
     assert tuple(counts) == sizes
 
 
+@pytest.mark.parametrize("bits", (4, 2))
+def test_more_experts_than_the_kernel_keeps_segment_starts_for(prefill_min, bits):
+    """160 experts: above 128 the tiled kernel reads the segment starts from memory instead of
+    its LDS copy; threshold 1, so every non-empty segment (most of them a few tokens) is a tile."""
+    prefill_min(1)
+    counts = _parity(W.small(E=160, d=256, f=256, T=900, seed=87), bits)
+    assert (counts > 0).sum() > 128
+
+
+def test_wide_tile_shape_takes_large_launches():
+    """Enough tiles for three full rounds of 64 x 256 tiles (T = 8192 over 4 experts, N = 4096):
+    FFN1 runs the wide shape, FFN2 (N = 256) the narrow one; sampled rows against the oracle."""
+    wl = W.small(E=4, d=256, f=4096, T=8192, seed=88)
+    layer, x = W.make_layer(wl), W.make_tokens(wl)
+    ql = gpu_quantize_layer(layer, 4)
+    xd = dev(x)
+    r = moqe.moqe_route(xd, ql.w_gate)
+    idx, gate, offs, perm = route_to_numpy(r)
+    y = moqe.moqe_expert_ffn(ql, xd, r).cpu().numpy()
+    rows = np.random.default_rng(88).choice(wl.T, size=256, replace=False)
+    rows = np.concatenate([rows, perm[offs[:-1][np.diff(offs) > 0]], perm[offs[1:][np.diff(offs) > 0] - 1]])
+    ref = oracle_layer_output(x[rows], layer, 4, idx[rows], gate[rows].astype(np.float64))
+    assert ffn_error(y[rows], ref) <= FFN_TOL
+
+
 def test_mixed_paths_under_zipf_load():
     """Zipf load at the default thresholds: large segments go to the tiled kernel, small ones
     to the decode kernel, some experts stay empty; both kernels write disjoint rows of h and y."""
