@@ -227,10 +227,28 @@ __global__ __launch_bounds__(SEG_THREADS) void route_segments_kernel(const int* 
   int nb = 0;
   while ((1 << nb) <= E) ++nb;  // keys 0..E (E = "no token")
 
+  // a wave's first KEEP chunks stay in registers from the counting pass to the scatter pass
+  constexpr int KEEP = 4;
+  int keep_key[KEEP];
+  uint64_t keep_m[KEEP];
+#pragma unroll
+  for (int i = 0; i < KEEP; ++i) {
+    const int t = (wave + i * nwaves) * 64 + lane;
+    keep_key[i] = t < T ? expert_idx[t] : E;  // asked for before the table is cleared
+  }
   for (int i = tid; i < CP * E; i += nthreads) cnt[i] = 0;
   __syncthreads();
 
-  for (int c = wave; c < nchunks; c += nwaves) {
+#pragma unroll
+  for (int i = 0; i < KEEP; ++i) {
+    const int c = wave + i * nwaves;
+    const int key = keep_key[i];
+    const uint64_t m = match_any(key, nb);  // (chunks past the end: all lanes hold E, nothing written)
+    keep_m[i] = m;
+    const bool leader = (__ffsll((long long)m) - 1) == lane;
+    if (key < E && leader) cnt[key * CP + c] = __popcll(m);
+  }
+  for (int c = wave + KEEP * nwaves; c < nchunks; c += nwaves) {
     int t = c * 64 + lane;
     bool valid = t < T;
     int key = valid ? expert_idx[t] : E;
@@ -280,7 +298,16 @@ __global__ __launch_bounds__(SEG_THREADS) void route_segments_kernel(const int* 
   }
   __syncthreads();
 
-  for (int c = wave; c < nchunks; c += nwaves) {
+#pragma unroll
+  for (int i = 0; i < KEEP; ++i) {
+    const int c = wave + i * nwaves;
+    const int key = keep_key[i];
+    if (key < E) {
+      const int rank = __popcll(keep_m[i] & ((1ull << lane) - 1ull));
+      perm[s_off[key] + cnt[key * CP + c] + rank] = c * 64 + lane;
+    }
+  }
+  for (int c = wave + KEEP * nwaves; c < nchunks; c += nwaves) {
     int t = c * 64 + lane;
     bool valid = t < T;
     int key = valid ? expert_idx[t] : E;
