@@ -30,7 +30,7 @@ from __future__ import annotations
 
 import numpy as np
 
-SUPPORTED_BITS = (2, 3, 4)
+SUPPORTED_BITS = (2, 3, 4, 8)  # Table 2's quantized rows: int8, int4, int3, int2
 
 
 # --------------------------------------------------------------------------
@@ -39,7 +39,7 @@ SUPPORTED_BITS = (2, 3, 4)
 
 def code_range(bits: int) -> tuple[int, int]:
     """Two's-complement range of a b-bit code: [-(2^(b-1)), 2^(b-1)-1]."""
-    if bits not in SUPPORTED_BITS and bits not in (8,):
+    if bits not in SUPPORTED_BITS:
         raise ValueError(f"unsupported bit width {bits}")
     return -(1 << (bits - 1)), (1 << (bits - 1)) - 1
 
@@ -137,7 +137,7 @@ def steps_per_chunk(bits: int, K: int) -> int:
     if K <= 0 or K % 32:
         raise ValueError("K must be a positive multiple of 32")
     S = K // 32
-    sc = min(4 if bits == 4 else 8, S)
+    sc = min({4: 4, 8: 2}.get(bits, 8), S)  # a slot owns at most 16 bytes of a chunk's main plane
     if S % sc:
         raise ValueError("K/32 must be a multiple of the chunk length")
     if bits == 2 and sc % 2:
@@ -161,7 +161,7 @@ def code_positions(bits: int, K: int, N: int):
       slot l = 16 g + j (64 slots per tile), chunk p = s // SC, s' = s % SC,
       m = 8 s' + i  (index among the 8 SC codes a slot owns in a chunk)
       Q = K / (32 SC) chunks per column tile; chunks are stored tile-major.
-    b in {2,4}: a chunk is 64 slots x (SC b) bytes, slot-major; inside a slot
+    b in {2,4,8}: a chunk is 64 slots x (SC b) bytes, slot-major; inside a slot
       32/b codes fill one little-endian 32-bit word: word = m // (32/b),
       t = m % (32/b), half = t & 1, field = t >> 1, bit = 16 half + b field.
     b = 3: a chunk is a 2-bit plane (as b = 2, holding u & 3) followed by a
@@ -191,7 +191,7 @@ def code_positions(bits: int, K: int, N: int):
         off = base + plane_off + slot * lane_bytes + 4 * word + bit // 8
         return np.broadcast_to(off, (K, N)).copy(), np.broadcast_to(bit % 8, (K, N)).copy()
 
-    if bits in (2, 4):
+    if bits in (2, 4, 8):
         off, sh = plane(bits, sc * bits, 0)
         return [(0, (1 << bits) - 1, off, sh, bits)]
     lo_off, lo_sh = plane(2, sc * 2, 0)

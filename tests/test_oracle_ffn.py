@@ -28,7 +28,7 @@ def test_fp16_single_expert_equals_dense_ffn():
     assert np.allclose(O.dense_ffn(x, w1, layer["b1"][0], w2, layer["b2"][0]), ref, rtol=1e-12, atol=1e-15)
 
 
-@pytest.mark.parametrize("bits", (2, 3, 4))
+@pytest.mark.parametrize("bits", (2, 3, 4, 8))
 def test_every_expert_then_select(bits):
     wl, layer, x = _layer(E=3, d=32 if bits != 3 else 128, f=64 if bits != 3 else 128, T=5, seed=bits)
     ql = O.quantize_layer(layer, bits)

@@ -7,7 +7,7 @@ import pytest
 from oracle import brute
 from oracle import moqe_oracle as O
 
-BITS = (2, 3, 4)
+BITS = (2, 3, 4, 8)
 
 
 def _codes(bits, E, K, N, seed):

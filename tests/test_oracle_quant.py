@@ -10,7 +10,7 @@ from oracle import brute
 from oracle import moqe_oracle as O
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "quant_hand_examples.txt")
-BITS = (2, 3, 4)
+BITS = (2, 3, 4, 8)
 
 
 def _rows():
@@ -97,7 +97,9 @@ def test_channel_maximum_gets_an_extreme_code(bits):
 def test_power_of_two_scaling(bits):
     w = _rand((1, 64, 32), 8)
     q0, s0 = O.quantize(w, bits)
-    for j in (-3, 2, 5):
+    # (int8 scales are 17 times smaller than int4's: 2^-3 would push them into fp16's
+    # subnormal range, where the stored scale has fewer bits and the codes may change)
+    for j in ((-3, 2, 5) if bits < 8 else (-1, 2, 5)):
         q1, s1 = O.quantize(w * np.float32(2.0 ** j), bits)
         assert np.array_equal(q0, q1)
         assert np.array_equal(s1.astype(np.float64), s0.astype(np.float64) * 2.0 ** j)
