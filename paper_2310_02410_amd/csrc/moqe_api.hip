@@ -90,7 +90,7 @@ void moqe_debug_set_trace(long long* p) { g_trace = p; }
 #endif
 
 int moqe_check_matrix(int bits, int64_t K, int64_t N) {
-  if (bits != 2 && bits != 3 && bits != 4) return MOQE_ERR_BITS;
+  if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return MOQE_ERR_BITS;
   PackGeom g;
   return moqe_make_geom(bits, K, N, &g) ? MOQE_OK : MOQE_ERR_SHAPE;
 }
@@ -102,7 +102,7 @@ size_t moqe_packed_bytes(int bits, int64_t K, int64_t N) {
 }
 
 int moqe_check_layer(int bits, int64_t E, int64_t d, int64_t f) {
-  if (bits != 2 && bits != 3 && bits != 4) return MOQE_ERR_BITS;
+  if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return MOQE_ERR_BITS;
   if (E < 1 || E > MAX_EXPERTS) return MOQE_ERR_SHAPE;
   int ks, r;
   if (moqe_check_matrix(bits, d, f) != MOQE_OK || moqe_check_matrix(bits, f, d) != MOQE_OK) return MOQE_ERR_SHAPE;
@@ -136,7 +136,7 @@ size_t moqe_layer_workspace_bytes(int64_t T, int64_t E, int64_t d, int64_t f) {
 moqe_status moqe_quantize(const float* w, int64_t E, int64_t K, int64_t N, int bits, void* codes_out,
                           moqe_f16* scales_out, void* stream) {
   if (!w || !codes_out || !scales_out) return MOQE_ERR_NULL;
-  if (bits != 2 && bits != 3 && bits != 4) return MOQE_ERR_BITS;
+  if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return MOQE_ERR_BITS;
   PackGeom g;
   if (E < 1 || E > MAX_EXPERTS || !moqe_make_geom(bits, K, N, &g)) return MOQE_ERR_SHAPE;
   if (!aligned16(w) || !aligned16(codes_out) || !aligned16(scales_out)) return MOQE_ERR_ALIGN;
@@ -146,7 +146,7 @@ moqe_status moqe_quantize(const float* w, int64_t E, int64_t K, int64_t N, int b
 
 moqe_status moqe_unpack(const void* codes, int64_t E, int64_t K, int64_t N, int bits, int8_t* q_out, void* stream) {
   if (!codes || !q_out) return MOQE_ERR_NULL;
-  if (bits != 2 && bits != 3 && bits != 4) return MOQE_ERR_BITS;
+  if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return MOQE_ERR_BITS;
   PackGeom g;
   if (E < 1 || E > MAX_EXPERTS || !moqe_make_geom(bits, K, N, &g)) return MOQE_ERR_SHAPE;
   if (!aligned16(codes) || !aligned16(q_out)) return MOQE_ERR_ALIGN;
@@ -199,7 +199,7 @@ moqe_status moqe_route_logits(const float* logits, int64_t T, int64_t E, int32_t
 static moqe_status check_layer_ptrs(const moqe_layer* L) {
   if (!L) return MOQE_ERR_NULL;
   if (!L->codes1 || !L->scales1 || !L->bias1 || !L->codes2 || !L->scales2 || !L->bias2) return MOQE_ERR_NULL;
-  if (L->bits != 2 && L->bits != 3 && L->bits != 4) return MOQE_ERR_BITS;
+  if (L->bits != 2 && L->bits != 3 && L->bits != 4 && L->bits != 8) return MOQE_ERR_BITS;
   int st = moqe_check_layer(L->bits, L->E, L->d, L->f);
   if (st != MOQE_OK) return (moqe_status)st;
   if (!aligned16(L->codes1) || !aligned16(L->scales1) || !aligned16(L->bias1) || !aligned16(L->codes2) ||

@@ -23,16 +23,17 @@ struct PackGeom {
   int SC;           // steps per chunk
   int Q;            // chunks per column tile = S / SC
   int chunk_bytes;  // 64 * SC * bits
-  int lo_lane_bytes;  // bytes one slot owns in the main (2- or 4-bit) plane of a chunk
+  int lo_lane_bytes;  // bytes one slot owns in the main (2-, 4- or 8-bit) plane of a chunk
   int hi_lane_bytes;  // bytes one slot owns in the 1-bit plane (int3 only, else 0)
   int64_t matrix_bytes;
 };
 
-__host__ __device__ inline int moqe_sc_max(int bits) { return bits == 4 ? 4 : 8; }
+// (a slot owns at most 16 bytes of a chunk's main plane)
+__host__ __device__ inline int moqe_sc_max(int bits) { return bits == 8 ? 2 : bits == 4 ? 4 : 8; }
 
 // Returns false when (bits, K, N) cannot be packed.
 __host__ __device__ inline bool moqe_make_geom(int bits, int64_t K, int64_t N, PackGeom* g) {
-  if (bits != 2 && bits != 3 && bits != 4) return false;
+  if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return false;
   if (K <= 0 || N <= 0 || (K % 32) || (N % 16)) return false;
   if (K > (1 << 20) || N > (1 << 20)) return false;
   int S = (int)(K / 32);

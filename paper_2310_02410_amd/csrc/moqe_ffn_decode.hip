@@ -108,8 +108,12 @@ __device__ inline uint4_t load16_coherent(const uint4_t* p) {
 // True if any 16-bit half of the word is zero.
 __device__ inline bool has_zero_half(uint32_t v) { return ((v - 0x00010001u) & ~v & 0x80008000u) != 0u; }
 
+// Waves per SIMD the register budget is sized for: int8 holds two words per step, so its long
+// slices (two units of 2 x 24 or 2 x 32 words in flight) need the registers of two waves.
+constexpr int min_waves(int bits, int ksteps) { return (bits == 8 && ksteps > 16) ? 2 : MOQE_MIN_WAVES; }
+
 template <int BITS, int KSTEPS, int PM>
-__global__ __launch_bounds__(WG_THREADS, MOQE_MIN_WAVES) void moe_decode_kernel(DecodeArgs A) {
+__global__ __launch_bounds__(WG_THREADS, min_waves(BITS, KSTEPS)) void moe_decode_kernel(DecodeArgs A) {
   // PM != 0 fixes the phase mask at compile time (the single-contraction launches), so that
   // everything the other phases need drops out of the code
   const int phase_mask = PM ? PM : A.phase_mask;
@@ -567,7 +571,9 @@ __global__ __launch_bounds__(WG_THREADS, MOQE_MIN_WAVES) void moe_decode_kernel(
 #endif
             const int s = ch * S::SC + s1;
             half8_t w;
-            if constexpr (BITS == 4) {
+            if constexpr (BITS == 8) {
+              w = unpack8(b.lo[ch * S::LW + 2 * s1], b.lo[ch * S::LW + 2 * s1 + 1], uc);
+            } else if constexpr (BITS == 4) {
               w = unpack4(b.lo[ch * S::LW + s1], uc);
             } else {
               const uint32_t d = b.lo[ch * S::LW + (s1 >> 1)];
@@ -732,7 +738,7 @@ hipError_t launch_mask(const DecodeArgs& a, int num_cus, hipStream_t stream) {
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, moe_decode_kernel<BITS, KSTEPS, PM>, WG_THREADS, 0) != hipSuccess ||
         n < 1)
       n = 1;
-    per_cu = n > MOQE_MIN_WAVES ? MOQE_MIN_WAVES : n;
+    per_cu = n > min_waves(BITS, KSTEPS) ? min_waves(BITS, KSTEPS) : n;
   }
   hipLaunchKernelGGL((moe_decode_kernel<BITS, KSTEPS, PM>), dim3(per_cu * num_cus), dim3(WG_THREADS), 0, stream, a);
   return hipGetLastError();
@@ -765,7 +771,11 @@ hipError_t launch_bits(const DecodeArgs& a, int num_cus, hipStream_t stream) {
 bool moqe_pick_ksplit(int bits, int64_t K, int* ksteps, int* ksplit) {
   PackGeom g;
   if (!moqe_make_geom(bits, K, 16, &g)) return false;
-  static const int cand[] = {32, 24, 16, 8, 4, 2};
+  // longest slice first; int8 (two words per step) prefers 16 steps, which still fit three waves
+  // per SIMD
+  static const int cand_default[] = {32, 24, 16, 8, 4, 2};
+  static const int cand_int8[] = {16, 32, 24, 8, 4, 2};
+  const int(&cand)[6] = bits == 8 ? cand_int8 : cand_default;
   for (int ks : cand) {
     if (g.S % ks) continue;
     int r = g.S / ks;
@@ -785,6 +795,7 @@ bool moqe_decode_can_route(int64_t T, int64_t d, int64_t E) {
 
 hipError_t moqe_launch_decode(const DecodeArgs& a, int num_cus, hipStream_t stream) {
   switch (a.bits) {
+    case 8: return launch_bits<8>(a, num_cus, stream);
     case 4: return launch_bits<4>(a, num_cus, stream);
     case 3: return launch_bits<3>(a, num_cus, stream);
     case 2: return launch_bits<2>(a, num_cus, stream);

@@ -33,11 +33,15 @@ __device__ inline half8_t const_frag(float c0, float c1, float c2, float c3) {
 template <int BITS>
 struct UnpackConsts {
   uint32_t m_000f, m_00f0;                  // int4 nibble masks
+  uint32_t m_00ff;                          // int8 byte mask
   uint32_t m_0030, m_00c0, m_0300;          // 2-bit field masks at bits 4, 6, 8
   uint32_t m_0040, m_0080, m_0100, m_0200;  // single-bit masks at bits 6..9 (int3 high plane)
   uint32_t x1024, x64, x32, x16, x8, x4;    // exponent patterns
   __device__ inline void init() {
-    if (BITS == 4) {
+    if (BITS == 8) {
+      m_00ff = opaque_sgpr(0x00FF00FFu);
+      x1024 = opaque_vgpr(0x64006400u);
+    } else if (BITS == 4) {
       m_000f = opaque_sgpr(0x000F000Fu);
       m_00f0 = opaque_sgpr(0x00F000F0u);
       x1024 = opaque_vgpr(0x64006400u);
@@ -72,6 +76,18 @@ __device__ inline half8_t unpack4(uint32_t d, const C& c) {
   uint32_t r1 = (d & c.m_00f0) | c.x64;
   uint32_t r2 = pk_sub((d8 & c.m_000f) | c.x1024, 1032.0f);
   uint32_t r3 = (d8 & c.m_00f0) | c.x64;
+  return frag_from_words(r0, r1, r2, r3);
+}
+
+// ---- int8: two words per step; word bit position of code i: 16 (i & 1) + 8 ((i >> 1) & 1), word
+// i >> 2.  Every byte gets base 1024: value = 1024 + u, u = q + 128; the 1152 is removed after
+// the K-sum (it is 9 to 1000 times the code, like the bases of the 2-bit fields).
+template <class C>
+__device__ inline half8_t unpack8(uint32_t d0, uint32_t d1, const C& c) {
+  uint32_t r0 = (d0 & c.m_00ff) | c.x1024;
+  uint32_t r1 = ((d0 >> 8) & c.m_00ff) | c.x1024;
+  uint32_t r2 = (d1 & c.m_00ff) | c.x1024;
+  uint32_t r3 = ((d1 >> 8) & c.m_00ff) | c.x1024;
   return frag_from_words(r0, r1, r2, r3);
 }
 
@@ -171,6 +187,7 @@ __device__ inline half8_t unpack3_exact(uint32_t dl, uint32_t dh, const C& c) {
 // exceeds the signed code: exponent bias(es) + zero point.
 template <int BITS>
 __device__ inline half8_t bias_frag(int parity) {
+  if (BITS == 8) return const_frag(1152, 1152, 1152, 1152);
   if (BITS == 4) return const_frag(0, 72, 0, 72);
   if (BITS == 2) return parity == 0 ? const_frag(66, 18, 66, 18) : const_frag(6, 66, 18, 6);
   // int3: low-plane bias + high-plane bias + zero point 4
@@ -180,7 +197,7 @@ __device__ inline half8_t bias_frag(int parity) {
 
 template <int BITS, int KSTEPS>
 struct Shape {
-  static constexpr int SCMAX = BITS == 4 ? 4 : 8;
+  static constexpr int SCMAX = BITS == 8 ? 2 : BITS == 4 ? 4 : 8;
   static constexpr int SC = KSTEPS < SCMAX ? KSTEPS : SCMAX;  // steps per chunk
   static constexpr int NCH = KSTEPS / SC;                     // chunks per wave slice
   static constexpr int LO_BITS = BITS == 3 ? 2 : BITS;

@@ -46,7 +46,7 @@ def test_version_and_strings():
     assert L.moqe_status_string(99) == b"unknown status"
 
 
-@pytest.mark.parametrize("bits", (2, 3, 4))
+@pytest.mark.parametrize("bits", (2, 3, 4, 8))
 def test_packed_bytes_density(bits):
     # Table 2's size column: exactly `bits` bits per expert weight
     for K, N in ((1024, 4096), (4096, 1024), (768, 3072), (256, 64)):
@@ -64,6 +64,8 @@ def test_shape_rules():
     assert L.moqe_check_matrix(4, 160, 16) == 3      # 5 steps, chunk of 4
     assert L.moqe_check_matrix(4, 64, 256) == 0
     assert L.moqe_check_matrix(3, 768, 3072) == 0
+    assert L.moqe_check_matrix(8, 32, 16) == 0 and L.moqe_check_matrix(8, 96, 16) == 3   # 3 steps, chunk of 2
+    assert L.moqe_check_layer(8, 32, 1024, 4096) == 0
     assert moqe.moqe_packed_bytes(2, 32, 16) == 0
     assert L.moqe_check_layer(4, 4, 64, 256) == 0
     assert L.moqe_check_layer(2, 32, 1024, 4096) == 0
@@ -129,7 +131,7 @@ def test_expert_ffn_error_paths():
     assert call(layer(codes2=0)) == 1
     assert call(layer(), x=0) == 1
     assert call(layer(), y=0) == 1
-    assert call(layer(bits=8)) == 2
+    assert call(layer(bits=5)) == 2
     assert call(layer(d=48)) == 3
     assert call(layer(E=0)) == 3
     assert call(layer(), T=-2) == 3

@@ -36,7 +36,7 @@ def test_config0():
     _layer_parity(W.CONFIGS["c0"], 4)
 
 
-@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("bits", (8, 4, 3, 2))
 @pytest.mark.parametrize("T", (1, 37, 150))
 def test_small_layer(bits, T):
     # d=128 (one wave slice of 4 steps), f=256 (8 steps); T=150 over 8 experts gives
@@ -44,14 +44,14 @@ def test_small_layer(bits, T):
     _layer_parity(W.small(T=T), bits)
 
 
-@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("bits", (8, 4, 3, 2))
 def test_split_k_shapes(bits):
     # d=512 -> 16 steps, f=2048 -> 16 steps x 4 waves; d=768/f=3072 -> 24 steps (x4)
     _layer_parity(W.small(E=4, d=512, f=2048, T=40, seed=21), bits)
     _layer_parity(W.small(E=3, d=768, f=3072, T=21, seed=22), bits)
 
 
-@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("bits", (8, 4, 3, 2))
 def test_residual_fused(bits):
     _layer_parity(W.small(T=50, seed=23), bits, residual=True)
 
@@ -81,9 +81,10 @@ def test_zero_input_closed_form():
     assert ffn_error(y, ref) <= FFN_TOL
 
 
-@pytest.mark.parametrize("name,bits", (("c1", 4), ("c2", 3), ("c2", 2)))
+@pytest.mark.parametrize("name,bits", (("c1", 8), ("c1", 4), ("c2", 3), ("c2", 2)))
 def test_decode_configs_full_size(name, bits):
-    """Benchmark decode layers at full size: E=32, d=1024, f=4096, T=24."""
+    """Benchmark decode layers at full size: E=32, d=1024, f=4096, T=24 (int8: Table 2's 8-bit
+    row on C1's layer)."""
     _layer_parity(W.CONFIGS[name], bits)
 
 

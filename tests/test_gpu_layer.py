@@ -47,7 +47,7 @@ def _layer_case(wl, bits, residual=False, repeats=1):
     assert np.array_equal(y.cpu().numpy().view(np.uint16), y2.cpu().numpy().view(np.uint16))
 
 
-@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("bits", (8, 4, 3, 2))
 @pytest.mark.parametrize("T", (1, 24, 64))
 def test_fused_small_layer(launch_mode, bits, T):
     # d=512, f=2048: 16 steps per wave for both contractions -> router, FFN1, FFN2 in one launch

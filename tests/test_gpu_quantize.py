@@ -41,14 +41,14 @@ def test_small_shapes(bits, K, N):
     _check(_weights(3, K, N, K + N + bits), bits)
 
 
-@pytest.mark.parametrize("bits", (2, 3, 4))
+@pytest.mark.parametrize("bits", (2, 3, 4, 8))
 def test_special_channels(bits):
     w = _weights(2, 256, 32, 77)
     w[0, :, 0] = 0.0                      # all-zero channel
     w[0, :, 1] = 0.0
     w[0, 5, 1] = 1e-9                     # scale below the fp16 subnormal step
     w[1, :, 2] = 0.0
-    top = {2: 1.5, 3: 3.5, 4: 7.5}[bits]  # exact ties with an exactly representable scale
+    top = {2: 1.5, 3: 3.5, 4: 7.5, 8: 127.5}[bits]  # exact ties with an exactly representable scale
     w[1, 0, 2], w[1, 1, 2], w[1, 2, 2], w[1, 3, 2] = top, -top, 0.5, -0.5   # scale is exactly 1
     if bits > 2:
         w[1, 4, 2], w[1, 5, 2] = 2.5, -1.5
