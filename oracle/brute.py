@@ -76,11 +76,11 @@ def pack_matrix(q, bits: int) -> bytes:
     (bit plane,) slot, 32-bit word, half, field -> which (k, n) sits there."""
     K, N = len(q), len(q[0])
     S = K // 32
-    sc = min({4: 4, 8: 2}.get(bits, 8), S)
+    sc = min({4: 4, 8: 2, 16: 1}.get(bits, 8), S)
     assert K % 32 == 0 and N % 16 == 0 and S % sc == 0
     out = bytearray()
-    z = 1 << (bits - 1)
-    plane_defs = [(bits, 0, (1 << bits) - 1)] if bits in (2, 4, 8) else [(2, 0, 3), (1, 2, 1)]
+    z = 0 if bits == 16 else 1 << (bits - 1)  # 16: q holds fp16 bit patterns, stored as they are
+    plane_defs = [(bits, 0, (1 << bits) - 1)] if bits in (2, 4, 8, 16) else [(2, 0, 3), (1, 2, 1)]
     for c in range(N // 16):
         for p in range(S // sc):
             for fbits, vshift, vmask in plane_defs:

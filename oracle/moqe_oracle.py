@@ -132,12 +132,12 @@ def model_size_ratio(expert_fraction: float, bits: int) -> float:
 
 def steps_per_chunk(bits: int, K: int) -> int:
     """SC of the layout below: 32-row steps per chunk."""
-    if bits not in SUPPORTED_BITS:
+    if bits not in SUPPORTED_BITS and bits != 16:
         raise ValueError(f"unsupported bit width {bits}")
     if K <= 0 or K % 32:
         raise ValueError("K must be a positive multiple of 32")
     S = K // 32
-    sc = min({4: 4, 8: 2}.get(bits, 8), S)  # a slot owns at most 16 bytes of a chunk's main plane
+    sc = min({4: 4, 8: 2, 16: 1}.get(bits, 8), S)  # a slot owns at most 16 bytes of a chunk's main plane
     if S % sc:
         raise ValueError("K/32 must be a multiple of the chunk length")
     if bits == 2 and sc % 2:
@@ -167,6 +167,9 @@ def code_positions(bits: int, K: int, N: int):
     b = 3: a chunk is a 2-bit plane (as b = 2, holding u & 3) followed by a
       1-bit plane (holding u >> 2): 64 slots x SC bytes, word = m // 32,
       t = m % 32, half = t & 1, field = t >> 1, bit = 16 half + field.
+    b = 16 (the unquantized half-precision path, see pack_fp16): the same rule as b in {2,4,8}
+      with u = the fp16 bit pattern; a field is a whole half of a word, returned here as its
+      low and its high byte.
     """
     sc = steps_per_chunk(bits, K)
     if N <= 0 or N % 16:
@@ -194,6 +197,9 @@ def code_positions(bits: int, K: int, N: int):
     if bits in (2, 4, 8):
         off, sh = plane(bits, sc * bits, 0)
         return [(0, (1 << bits) - 1, off, sh, bits)]
+    if bits == 16:
+        off, sh = plane(16, sc * 16, 0)
+        return [(0, 255, off, sh, 8), (8, 255, off + 1, sh, 8)]
     lo_off, lo_sh = plane(2, sc * 2, 0)
     hi_off, hi_sh = plane(1, sc, 64 * sc * 2)
     return [(0, 3, lo_off, lo_sh, 2), (2, 1, hi_off, hi_sh, 1)]
@@ -220,6 +226,44 @@ def pack(q, bits: int) -> np.ndarray:
             # fields are disjoint, so the sum of the shifted fields is their OR
             acc += np.bincount(off.ravel(), weights=v.ravel().astype(np.float64), minlength=nbytes)
         out[e] = acc.astype(np.uint8)
+    return out[0] if squeeze else out
+
+
+def pack_fp16(w) -> np.ndarray:
+    """The unquantized 16-bit path's storage: A' = fp16(A) (one rounding, to nearest even), its
+    bit patterns laid out by the same rule as the codes (code_positions with b = 16), so that
+    the fp16 and the quantized experts go through the same kernels.
+    w [E,K,N] (or [K,N]) -> uint8 [E, 2 K N]."""
+    w = np.asarray(w)
+    squeeze = w.ndim == 2
+    if squeeze:
+        w = w[None]
+    E, K, N = w.shape
+    planes = code_positions(16, K, N)
+    nbytes = 2 * K * N
+    out = np.zeros((E, nbytes), dtype=np.uint8)
+    for e in range(E):
+        u = w[e].astype(np.float16).view(np.uint16).astype(np.int64)
+        for vshift, vmask, off, sh, _ in planes:
+            out[e][off.ravel()] = ((u >> vshift) & vmask).ravel().astype(np.uint8)
+    return out[0] if squeeze else out
+
+
+def unpack_fp16(codes, K: int, N: int) -> np.ndarray:
+    """Inverse of pack_fp16: uint8 [E, 2 K N] -> fp16 [E,K,N]."""
+    codes = np.asarray(codes, dtype=np.uint8)
+    squeeze = codes.ndim == 1
+    if squeeze:
+        codes = codes[None]
+    if codes.shape[1] != 2 * K * N:
+        raise ValueError("wrong packed length")
+    planes = code_positions(16, K, N)
+    out = np.empty((codes.shape[0], K, N), dtype=np.float16)
+    for e in range(codes.shape[0]):
+        u = np.zeros((K, N), dtype=np.int64)
+        for vshift, vmask, off, sh, _ in planes:
+            u |= (codes[e][off].astype(np.int64) & vmask) << vshift
+        out[e] = u.astype(np.uint16).view(np.float16)
     return out[0] if squeeze else out
 
 

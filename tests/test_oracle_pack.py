@@ -103,7 +103,8 @@ def test_single_code_sensitivity(bits):
         assert np.all(diff & ~allowed == 0) and diff.any()
 
 
-@pytest.mark.parametrize("bits,K,N", ((4, 64, 16), (4, 256, 32), (2, 64, 16), (2, 512, 16), (3, 128, 16), (3, 512, 32)))
+@pytest.mark.parametrize("bits,K,N", ((4, 64, 16), (4, 256, 32), (2, 64, 16), (2, 512, 16), (3, 128, 16), (3, 512, 32),
+                                      (8, 32, 16), (8, 256, 32)))
 def test_matches_storage_order_enumeration(bits, K, N):
     """The oracle maps code -> position; the brute force walks positions -> code."""
     q = _codes(bits, 1, K, N, 31)[0]
@@ -132,3 +133,26 @@ def test_layout_spot_values():
     assert (lo_pl[2][0, 0], hi_pl[2][0, 0]) == (0, 1024)
     assert (hi_pl[2][96, 0], hi_pl[3][96, 0]) == (1024 + 1, 4)   # step 3 -> t=24 -> field 12
     assert (hi_pl[2][128, 0], hi_pl[3][128, 0]) == (1024 + 4, 0)  # step 4 -> word 1
+
+
+def test_fp16_storage_roundtrip_order_and_spots():
+    """The unquantized 16-bit path stores fp16(A) by the same layout rule: round trip, the
+    position -> element brute force, positions worked out by hand, and one rounding to nearest."""
+    rng = np.random.default_rng(41)
+    w = (rng.standard_normal((2, 96, 32)) * 0.02).astype(np.float32)
+    p = O.pack_fp16(w)
+    assert p.shape == (2, 96 * 32 * 2)
+    assert np.array_equal(O.unpack_fp16(p, 96, 32), w.astype(np.float16))
+    pat = w[0].astype(np.float16).view(np.uint16).astype(int).tolist()
+    assert p[0].tobytes() == brute.pack_matrix(pat, 16)
+    # K=64 (chunks of one step): slot = 16*((k%32)//8) + n%16 owns 16 bytes = 8 halves, k%8 in order
+    lo, hi = O.code_positions(16, 64, 32)
+    off = lo[2]
+    assert off[0, 0] == 0 and hi[2][0, 0] == 1      # low byte, high byte
+    assert off[1, 0] == 2 and off[7, 0] == 14
+    assert off[8, 0] == 16 * 16                     # row group 1 -> slot 16
+    assert off[32, 0] == 1024                       # step 1 -> next chunk of the column tile
+    assert off[0, 16] == 2048                       # second column tile (2 chunks of 1024 bytes each)
+    # 1 + 2^-11 lies half way between two fp16 numbers: ties to even -> 1.0
+    one = np.full((32, 16), 1.0 + 2.0 ** -11, dtype=np.float32)
+    assert np.all(O.unpack_fp16(O.pack_fp16(one), 32, 16) == np.float16(1.0))
