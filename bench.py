@@ -50,11 +50,11 @@ def parse():
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="c1",
                     choices=("c1", "c2", "c3", "c4_T24_uniform", "c4_T24_zipf", "c4_T4096_uniform", "c4_T4096_zipf"))
-    ap.add_argument("--bits", type=int, default=None, choices=(2, 3, 4, 8),
+    ap.add_argument("--bits", type=int, default=None, choices=(2, 3, 4, 8, 16),
                     help="bit width of the headline line (default: the workload's own)")
     ap.add_argument("--copies", type=int, default=None, help="independent layer copies cycled through "
                     "(default 8; 12 for the c4 stack: its 12 layers)")
-    ap.add_argument("--other-bits", action="store_true", help="also time the other bit widths (8, 4, 3, 2)")
+    ap.add_argument("--other-bits", action="store_true", help="also time the other widths (fp16, 8, 4, 3, 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=None, help="oracle steps timed (default 8; 1 from 512 tokens on)")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches only")
@@ -104,7 +104,7 @@ def main():
     residual = wl.layers > 1               # the stack adds the layer's output to its input
     compute_bound = T >= 512               # the tiled MFMA kernel dominates, not the weight stream
     bits0 = args.bits if args.bits is not None else wl.bits[0]
-    bit_list = [bits0] + ([b for b in (8, 4, 3, 2) if b != bits0] if args.other_bits else [])
+    bit_list = [bits0] + ([b for b in (16, 8, 4, 3, 2) if b != bits0] if args.other_bits else [])
     copies = args.copies if args.copies is not None else (12 if wl.layers > 1 else 8)
     steps, warmup = args.steps, args.warmup
     if compute_bound and steps == 400 and warmup == 40:

@@ -21,9 +21,13 @@
  *   - moqe_f16 is the IEEE binary16 bit pattern.
  *
  * Supported shapes: bits in {2,3,4,8} (Table 2's quantized rows; 8 bits run on the
- * dequantize-in-register kernel at every batch size); N a multiple of 16; K a multiple of
- * 32 (int8, int4), 64 (int2), 128 (int3) and, when K/32 exceeds the chunk length
- * SC (2 steps for int8, 4 for int4, 8 for int2/int3), K/32 a multiple of SC.  The FFN
+ * dequantize-in-register kernel at every batch size) and bits = 16, the unquantized
+ * baseline of the same table: moqe_quantize then stores fp16(w) (one rounding, to nearest
+ * even) in place of codes, by the layout rule below with a field = the fp16 bit pattern, and
+ * scales of 1; such layers run on the tiled kernel at every batch size (K a multiple of 128,
+ * at least 256) and moqe_unpack does not apply.  N a multiple of 16; K a multiple of
+ * 32 (fp16, int8, int4), 64 (int2), 128 (int3) and, when K/32 exceeds the chunk length
+ * SC (1 step for fp16, 2 for int8, 4 for int4, 8 for int2/int3), K/32 a multiple of SC.  The FFN
  * additionally needs K = 32 * KS * R with KS in {2,4,8,16,24,32} and
  * R in {1,2,4} for both of its contractions (K = d and K = f).
  *
@@ -34,7 +38,7 @@
  *   chunk p = s / SC, s' = s % SC, m = 8 s' + i.  Chunks are stored column
  *   tile major: chunk (c, p) starts at byte (c * K/(32 SC) + p) * 64 SC bits.
  *   Stored field value u = q + 2^(bits-1) (offset binary).
- *   bits 2,4,8: the chunk is 64 slots of SC*bits bytes; inside a slot, 32/bits
+ *   bits 2,4,8,16: the chunk is 64 slots of SC*bits bytes; inside a slot, 32/bits
  *     codes fill a little-endian 32-bit word: word = m / (32/bits),
  *     t = m % (32/bits), bit position = 16 (t & 1) + bits (t >> 1).
  *   bits 3: the chunk is a 2-bit plane (u & 3, arranged as for bits = 2)

@@ -89,8 +89,11 @@ int moqe_set_launch_mode(int mode) {
 void moqe_debug_set_trace(long long* p) { g_trace = p; }
 #endif
 
+// 2, 3, 4, 8: quantized codes; 16: unquantized fp16 weights (the paper's baseline row)
+static bool valid_bits(int bits) { return bits == 2 || bits == 3 || bits == 4 || bits == 8 || bits == 16; }
+
 int moqe_check_matrix(int bits, int64_t K, int64_t N) {
-  if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return MOQE_ERR_BITS;
+  if (!valid_bits(bits)) return MOQE_ERR_BITS;
   PackGeom g;
   return moqe_make_geom(bits, K, N, &g) ? MOQE_OK : MOQE_ERR_SHAPE;
 }
@@ -102,10 +105,12 @@ size_t moqe_packed_bytes(int bits, int64_t K, int64_t N) {
 }
 
 int moqe_check_layer(int bits, int64_t E, int64_t d, int64_t f) {
-  if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return MOQE_ERR_BITS;
+  if (!valid_bits(bits)) return MOQE_ERR_BITS;
   if (E < 1 || E > MAX_EXPERTS) return MOQE_ERR_SHAPE;
   int ks, r;
   if (moqe_check_matrix(bits, d, f) != MOQE_OK || moqe_check_matrix(bits, f, d) != MOQE_OK) return MOQE_ERR_SHAPE;
+  // fp16 weights run on the tiled kernel only
+  if (bits == 16) return moqe_prefill_supported(bits, d, f) && moqe_prefill_supported(bits, f, d) ? MOQE_OK : MOQE_ERR_SHAPE;
   if (!moqe_pick_ksplit(bits, d, &ks, &r) || !moqe_pick_ksplit(bits, f, &ks, &r)) return MOQE_ERR_SHAPE;
   return MOQE_OK;
 }
@@ -136,7 +141,7 @@ size_t moqe_layer_workspace_bytes(int64_t T, int64_t E, int64_t d, int64_t f) {
 moqe_status moqe_quantize(const float* w, int64_t E, int64_t K, int64_t N, int bits, void* codes_out,
                           moqe_f16* scales_out, void* stream) {
   if (!w || !codes_out || !scales_out) return MOQE_ERR_NULL;
-  if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return MOQE_ERR_BITS;
+  if (!valid_bits(bits)) return MOQE_ERR_BITS;
   PackGeom g;
   if (E < 1 || E > MAX_EXPERTS || !moqe_make_geom(bits, K, N, &g)) return MOQE_ERR_SHAPE;
   if (!aligned16(w) || !aligned16(codes_out) || !aligned16(scales_out)) return MOQE_ERR_ALIGN;
@@ -146,7 +151,7 @@ moqe_status moqe_quantize(const float* w, int64_t E, int64_t K, int64_t N, int b
 
 moqe_status moqe_unpack(const void* codes, int64_t E, int64_t K, int64_t N, int bits, int8_t* q_out, void* stream) {
   if (!codes || !q_out) return MOQE_ERR_NULL;
-  if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return MOQE_ERR_BITS;
+  if (!valid_bits(bits) || bits == 16) return MOQE_ERR_BITS;  // (fp16 weights are not int8 codes)
   PackGeom g;
   if (E < 1 || E > MAX_EXPERTS || !moqe_make_geom(bits, K, N, &g)) return MOQE_ERR_SHAPE;
   if (!aligned16(codes) || !aligned16(q_out)) return MOQE_ERR_ALIGN;
@@ -199,7 +204,7 @@ moqe_status moqe_route_logits(const float* logits, int64_t T, int64_t E, int32_t
 static moqe_status check_layer_ptrs(const moqe_layer* L) {
   if (!L) return MOQE_ERR_NULL;
   if (!L->codes1 || !L->scales1 || !L->bias1 || !L->codes2 || !L->scales2 || !L->bias2) return MOQE_ERR_NULL;
-  if (L->bits != 2 && L->bits != 3 && L->bits != 4 && L->bits != 8) return MOQE_ERR_BITS;
+  if (!valid_bits(L->bits)) return MOQE_ERR_BITS;
   int st = moqe_check_layer(L->bits, L->E, L->d, L->f);
   if (st != MOQE_OK) return (moqe_status)st;
   if (!aligned16(L->codes1) || !aligned16(L->scales1) || !aligned16(L->bias1) || !aligned16(L->codes2) ||
@@ -259,12 +264,16 @@ static void set_ffn2(DecodeArgs* a, const moqe_layer* L, const moqe_f16* h, cons
 // tiled MFMA kernel the large ones (none can exist when T is below the threshold).
 static hipError_t launch_contraction(DecodeArgs& a, int phase, int ksteps, hipStream_t stream) {
   const PhaseArgs& p = a.ph[phase];
-  // many tokens per expert on average: everything through the tiled kernel
-  const int pmin = (int64_t)a.T >= (int64_t)g_prefill_all.load() * a.E ? 1 : g_prefill_min.load();
+  // many tokens per expert on average, or fp16 weights (which only the tiled kernel takes):
+  // everything through the tiled kernel
+  const bool tiled_only = a.bits == 16;
+  const int pmin = (tiled_only || (int64_t)a.T >= (int64_t)g_prefill_all.load() * a.E) ? 1 : g_prefill_min.load();
   // (the tiled kernel addresses its input rows with 32-bit byte offsets and its output rows with
   // 32-bit element offsets)
-  const bool split = a.T >= pmin && a.T >= g_prefill_batch.load() && moqe_prefill_supported(a.bits, p.K, p.N) &&
-                     (int64_t)a.T * p.K * 2 < (1ll << 32) && (int64_t)a.T * p.N < (1ll << 31);
+  const bool split = a.T >= pmin && (tiled_only || a.T >= g_prefill_batch.load()) &&
+                     moqe_prefill_supported(a.bits, p.K, p.N) && (int64_t)a.T * p.K * 2 < (1ll << 32) &&
+                     (int64_t)a.T * p.N < (1ll << 31);
+  if (tiled_only && !split) return hipErrorInvalidValue;  // (sizes are checked by the callers)
   a.ksteps = ksteps;
   a.phase_mask = 2 << phase;
   a.min_tokens = 1;
@@ -300,13 +309,18 @@ static hipError_t launch_contraction(DecodeArgs& a, int phase, int ksteps, hipSt
 
 // Unit counts are 32-bit inside the kernel.
 static bool units_fit(int64_t T, int64_t E, int64_t N) { return ((T + 3) / 4 + E) * (N / 16) < (1ll << 31); }
+// fp16 weights: the tiled kernel's 32-bit offsets must hold for both contractions
+static bool fp16_fits(const moqe_layer* L, int64_t T) {
+  const int64_t m = L->d > L->f ? L->d : L->f;
+  return L->bits != 16 || (T * m * 2 < (1ll << 32));
+}
 
 moqe_status moqe_expert_ffn1(const moqe_layer* L, const moqe_f16* x, int64_t T, const int32_t* seg_offsets,
                              const int32_t* perm, moqe_f16* h, void* stream) {
   if (!L || !x || !seg_offsets || !perm || !h) return MOQE_ERR_NULL;
   moqe_status st = check_layer_ptrs(L);
   if (st != MOQE_OK) return st;
-  if (T < 0 || T > MAX_TOKENS || !units_fit(T, L->E, L->f)) return MOQE_ERR_SHAPE;
+  if (T < 0 || T > MAX_TOKENS || !units_fit(T, L->E, L->f) || !fp16_fits(L, T)) return MOQE_ERR_SHAPE;
   if (!aligned16(x) || !aligned16(seg_offsets) || !aligned16(perm) || !aligned16(h)) return MOQE_ERR_ALIGN;
   if (T == 0) return MOQE_OK;
   DecodeArgs a;
@@ -323,7 +337,7 @@ moqe_status moqe_expert_ffn2(const moqe_layer* L, const moqe_f16* h, int64_t T, 
   if (!L || !h || !gate || !seg_offsets || !perm || !y) return MOQE_ERR_NULL;
   moqe_status st = check_layer_ptrs(L);
   if (st != MOQE_OK) return st;
-  if (T < 0 || T > MAX_TOKENS || !units_fit(T, L->E, L->d)) return MOQE_ERR_SHAPE;
+  if (T < 0 || T > MAX_TOKENS || !units_fit(T, L->E, L->d) || !fp16_fits(L, T)) return MOQE_ERR_SHAPE;
   if (!aligned16(h) || !aligned16(gate) || !aligned16(seg_offsets) || !aligned16(perm) || !aligned16(y) ||
       (residual && !aligned16(residual)))
     return MOQE_ERR_ALIGN;
@@ -345,7 +359,8 @@ static moqe_status run_layer(const moqe_layer* L, const moqe_f16* w_gate, const 
                              void* stream) {
   moqe_status st = check_layer_ptrs(L);
   if (st != MOQE_OK) return st;
-  if (T < 0 || T > MAX_TOKENS || !units_fit(T, L->E, L->f) || !units_fit(T, L->E, L->d)) return MOQE_ERR_SHAPE;
+  if (T < 0 || T > MAX_TOKENS || !units_fit(T, L->E, L->f) || !units_fit(T, L->E, L->d) || !fp16_fits(L, T))
+    return MOQE_ERR_SHAPE;
   if (!aligned16(x) || !aligned16(expert_idx) || !aligned16(gate) || !aligned16(seg_offsets) || !aligned16(perm) ||
       !aligned16(y) || !aligned16(workspace) || (residual && !aligned16(residual)) ||
       (w_gate && !aligned16(w_gate)))
@@ -373,7 +388,7 @@ static moqe_status run_layer(const moqe_layer* L, const moqe_f16* w_gate, const 
   // one launch for both contractions when they share the wave slice length and h fits the
   // chained buffers; the router joins when it fits the kernel's own
   const int launch_mode = g_launch_mode.load();
-  const bool can_chain = ks1 == ks2 && h_bytes <= CHAIN_H_BYTES;
+  const bool can_chain = L->bits != 16 && ks1 == ks2 && h_bytes <= CHAIN_H_BYTES;
   const bool can_fuse_route = w_gate && can_chain && moqe_decode_can_route(T, L->d, L->E);
   // Measured on the decode workload, one launch per step of the path is as fast as the
   // single launch or faster (the phases of the single launch wait for each other through

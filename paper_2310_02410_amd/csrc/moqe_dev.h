@@ -17,7 +17,7 @@ typedef uint32_t uint2_t __attribute__((ext_vector_type(2)));
 // Geometry of the packed code layout (one [K,N] matrix).  See include/moqe.h.
 // ---------------------------------------------------------------------------
 struct PackGeom {
-  int bits;
+  int bits;  // 16: unquantized fp16 values in place of codes (field = the fp16 bit pattern)
   int K, N;
   int S;            // 32-row steps = K / 32
   int SC;           // steps per chunk
@@ -29,11 +29,11 @@ struct PackGeom {
 };
 
 // (a slot owns at most 16 bytes of a chunk's main plane)
-__host__ __device__ inline int moqe_sc_max(int bits) { return bits == 8 ? 2 : bits == 4 ? 4 : 8; }
+__host__ __device__ inline int moqe_sc_max(int bits) { return bits == 16 ? 1 : bits == 8 ? 2 : bits == 4 ? 4 : 8; }
 
 // Returns false when (bits, K, N) cannot be packed.
 __host__ __device__ inline bool moqe_make_geom(int bits, int64_t K, int64_t N, PackGeom* g) {
-  if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return false;
+  if (bits != 2 && bits != 3 && bits != 4 && bits != 8 && bits != 16) return false;
   if (K <= 0 || N <= 0 || (K % 32) || (N % 16)) return false;
   if (K > (1 << 20) || N > (1 << 20)) return false;
   int S = (int)(K / 32);

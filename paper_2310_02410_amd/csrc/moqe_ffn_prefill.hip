@@ -79,13 +79,18 @@ struct PfTile {
 
 // PF_NT: column tiles (of 16 channels) per wave, 4 or 2
 template <int BITS, int PF_NT>
-__global__ __launch_bounds__(PF_THREADS, PF_NT == 4 ? 2 : PF_WG_PER_CU) void moe_prefill_kernel(PrefillArgs A) {
+__global__ __launch_bounds__(PF_THREADS, (PF_NT == 4 || BITS == 16) ? 2 : PF_WG_PER_CU) void moe_prefill_kernel(PrefillArgs A) {
   constexpr int PF_MT = PF_TILE_M / 16;       // token tiles per wave: all of the tile's
   constexpr int PF_TILE_CT = 4 * PF_NT;       // column tiles per workgroup tile
-  constexpr int SC = BITS == 4 ? 4 : 8;       // steps of 32 rows per packed chunk
-  constexpr int SUB = SC / 4;                 // staged K blocks per packed chunk
+  // A chunk here is what a wave fetches at a time for one column tile: one packed chunk (128
+  // rows for int4, 256 for int2 / int3), or, for unquantized fp16 weights (BITS = 16, packed
+  // chunks of 32 rows), the four packed chunks of a staged block.
+  constexpr int SC = (BITS == 4 || BITS == 16) ? 4 : 8;  // steps of 32 rows per chunk
+  constexpr int PCH = BITS == 16 ? 4 : 1;     // packed chunks per chunk
+  constexpr int SUB = SC / 4;                 // staged K blocks per chunk
   constexpr int LO_BITS = BITS == 3 ? 2 : BITS;
-  constexpr int LW = SC * LO_BITS / 4;        // main-plane words per lane per chunk (4)
+  constexpr int LWC = (SC / PCH) * LO_BITS / 4;  // main-plane words per lane per packed chunk (4)
+  constexpr int LW = LWC * PCH;               // ... per chunk
   constexpr int HW = BITS == 3 ? SC / 4 : 0;  // 1-bit-plane words per lane per chunk
   constexpr int CHUNK_BYTES = 64 * SC * BITS;
   constexpr int ROW_PIECES = PF_KB / 8;       // 16-byte pieces per staged row (256 bytes, no padding)
@@ -140,7 +145,7 @@ __global__ __launch_bounds__(PF_THREADS, PF_NT == 4 ? 2 : PF_WG_PER_CU) void moe
   const int Q = K / (32 * SC);   // packed chunks per column tile
   const int TB = Q * SUB;        // staged blocks per tile
   const int64_t matrix_bytes = (int64_t)K * N * BITS / 8;
-  const uint32_t lane_lo = (uint32_t)lane * LW * 4, lane_hi = (64u * LW + (uint32_t)lane * HW) * 4;
+  const uint32_t lane_lo = (uint32_t)lane * LWC * 4, lane_hi = (64u * LWC + (uint32_t)lane * HW) * 4;
   UnpackConsts<BITS> uc;
   uc.init();
 
@@ -191,7 +196,10 @@ __global__ __launch_bounds__(PF_THREADS, PF_NT == 4 ? 2 : PF_WG_PER_CU) void moe
     constexpr int buf = decltype(BUF)::value;
 #pragma unroll
     for (int ni = 0; ni < PF_NT; ++ni) {
-      load_words<LW, PF_B_NT>(brs[ni], (uint32_t)c * CHUNK_BYTES + lane_lo, b_lo[buf][ni]);
+#pragma unroll
+      for (int pc = 0; pc < PCH; ++pc)
+        load_words<LWC, PF_B_NT>(brs[ni], (uint32_t)c * CHUNK_BYTES + pc * (CHUNK_BYTES / PCH) + lane_lo,
+                                 &b_lo[buf][ni][LWC * pc]);
       if constexpr (BITS == 3) load_words<HW, PF_B_NT>(brs[ni], (uint32_t)c * CHUNK_BYTES + lane_hi, b_hi[buf][ni]);
     }
   };
@@ -246,7 +254,10 @@ __global__ __launch_bounds__(PF_THREADS, PF_NT == 4 ? 2 : PF_WG_PER_CU) void moe
 #pragma unroll
       for (int ni = 0; ni < PF_NT; ++ni) {
         half8_t w;
-        if constexpr (BITS == 4) {
+        if constexpr (BITS == 16) {
+          w = frag_from_words(b_lo[bbuf][ni][4 * s], b_lo[bbuf][ni][4 * s + 1], b_lo[bbuf][ni][4 * s + 2],
+                              b_lo[bbuf][ni][4 * s + 3]);
+        } else if constexpr (BITS == 4) {
           w = unpack4_exact(b_lo[bbuf][ni][s], uc);
         } else if constexpr (BITS == 2) {
           const uint32_t d = b_lo[bbuf][ni][s >> 1];
@@ -422,8 +433,8 @@ __global__ __launch_bounds__(PF_THREADS, PF_NT == 4 ? 2 : PF_WG_PER_CU) void moe
 }  // namespace
 
 bool moqe_prefill_supported(int bits, int64_t K, int64_t N) {
-  const int kc = bits == 4 ? 128 : 256;
-  return (bits == 2 || bits == 3 || bits == 4) && K >= 256 && (K % kc) == 0 && N >= 16 && (N % 16) == 0;
+  const int kc = (bits == 4 || bits == 16) ? 128 : 256;
+  return (bits == 2 || bits == 3 || bits == 4 || bits == 16) && K >= 256 && (K % kc) == 0 && N >= 16 && (N % 16) == 0;
 }
 
 template <int BITS>
@@ -437,16 +448,22 @@ static void launch_bits(const PrefillArgs& a, int64_t pairs, int num_cus, hipStr
   // half-sized tiles.  The big shape pays once a launch has at least three full rounds of its
   // tiles (measured: +7 % at 8192 tokens, -10 % at 1536); below that the last, partly filled
   // round costs more than the traffic saves.
-  const bool wide = CT >= 128 && pairs * ((CT + 15) / 16) >= 3ll * 2 * num_cus;
-  const int per_cu = wide ? 2 : PF_WG_PER_CU;
+  // (fp16 weights hold 16 words per chunk and column tile: only the narrow shape has the registers)
+  const bool wide = BITS != 16 && CT >= 128 && pairs * ((CT + 15) / 16) >= 3ll * 2 * num_cus;
+  const int per_cu = (wide || BITS == 16) ? 2 : PF_WG_PER_CU;
   args.n_cblocks = wide ? (CT + 15) / 16 : (CT + 7) / 8;
   int64_t grid = pairs * args.n_cblocks;  // upper bound on the tiles
   if (grid > (int64_t)per_cu * num_cus) grid = (int64_t)per_cu * num_cus;
   grid = grid < 8 ? 8 : (grid & ~(int64_t)7);  // a multiple of the 8 XCDs
-  if (wide)
-    hipLaunchKernelGGL((moe_prefill_kernel<BITS, 4>), dim3((unsigned)grid), dim3(PF_THREADS), 0, stream, args);
-  else
+  if constexpr (BITS != 16) {
+    if (wide) {
+      hipLaunchKernelGGL((moe_prefill_kernel<BITS, 4>), dim3((unsigned)grid), dim3(PF_THREADS), 0, stream, args);
+      return;
+    }
+  }
+  {
     hipLaunchKernelGGL((moe_prefill_kernel<BITS, 2>), dim3((unsigned)grid), dim3(PF_THREADS), 0, stream, args);
+  }
 }
 
 hipError_t moqe_launch_prefill(const PrefillArgs& a, int num_cus, hipStream_t stream) {
@@ -456,6 +473,7 @@ hipError_t moqe_launch_prefill(const PrefillArgs& a, int num_cus, hipStream_t st
   if (pairs <= 0) return hipSuccess;
   if (pairs * ((a.N / 16 + 7) / 8) >= (1ll << 31)) return hipErrorInvalidValue;
   switch (a.bits) {
+    case 16: launch_bits<16>(a, pairs, num_cus, stream); break;
     case 4: launch_bits<4>(a, pairs, num_cus, stream); break;
     case 3: launch_bits<3>(a, pairs, num_cus, stream); break;
     case 2: launch_bits<2>(a, pairs, num_cus, stream); break;

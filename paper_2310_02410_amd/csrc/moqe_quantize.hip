@@ -81,8 +81,12 @@ __global__ __launch_bounds__(256) void scale_kernel(const float* __restrict__ w,
       m.z = fmaxf(m.z, o.z);
       m.w = fmaxf(m.w, o.w);
     }
-    const double den = (double)((1 << bits) - 1);
     uint16_t* out = scales + e * N + n0;
+    if (bits == 16) {  // unquantized: the stored values are the weights themselves, scale 1
+      out[0] = out[1] = out[2] = out[3] = 0x3C00;
+      return;
+    }
+    const double den = (double)((1 << bits) - 1);
     out[0] = half_bits_round_up((2.0 * (double)m.x) / den);
     out[1] = half_bits_round_up((2.0 * (double)m.y) / den);
     out[2] = half_bits_round_up((2.0 * (double)m.z) / den);
@@ -127,8 +131,12 @@ __global__ __launch_bounds__(256) void pack_kernel(const float* __restrict__ w, 
     int m = word * per + t;
     int s1 = m >> 3, i = m & 7;
     int k = 32 * (p * g.SC + s1) + 8 * grp + i;
-    int q = quantize_one(wm[(int64_t)k * g.N + n], s, lo, hi);
-    uint32_t u = (uint32_t)(q + z);
+    uint32_t u;
+    if (g.bits == 16) {
+      u = half_to_bits((half_t)wm[(int64_t)k * g.N + n]);  // one rounding, to nearest even
+    } else {
+      u = (uint32_t)(quantize_one(wm[(int64_t)k * g.N + n], s, lo, hi) + z);
+    }
     val |= ((u >> vshift) & vmask) << (16 * (t & 1) + fbits * (t >> 1));
   }
   codes[idx] = val;

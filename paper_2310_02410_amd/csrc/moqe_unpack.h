@@ -38,6 +38,7 @@ struct UnpackConsts {
   uint32_t m_0040, m_0080, m_0100, m_0200;  // single-bit masks at bits 6..9 (int3 high plane)
   uint32_t x1024, x64, x32, x16, x8, x4;    // exponent patterns
   __device__ inline void init() {
+    if (BITS == 16) return;  // fp16 weights need no unpacking
     if (BITS == 8) {
       m_00ff = opaque_sgpr(0x00FF00FFu);
       x1024 = opaque_vgpr(0x64006400u);

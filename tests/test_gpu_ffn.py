@@ -97,3 +97,16 @@ def test_deterministic_output():
     a = moqe.moqe_expert_ffn(ql, xd, r).cpu().numpy()
     b = moqe.moqe_expert_ffn(ql, xd, r).cpu().numpy()
     assert np.array_equal(a.view(np.uint16), b.view(np.uint16))
+
+
+@pytest.mark.parametrize("T", (1, 24, 150))
+def test_fp16_experts_small(T):
+    """Unquantized fp16 experts (bits = 16) against the oracle's 16-bit path; they run on the
+    tiled kernel at every batch size."""
+    _layer_parity(W.small(E=4, d=256, f=512, T=T, seed=60 + T), 16)
+    _layer_parity(W.small(E=3, d=384, f=256, T=T, seed=61 + T), 16, residual=True)
+
+
+def test_fp16_experts_decode_config():
+    """C1's layer with fp16 experts: the baseline row of the bit-width comparison."""
+    _layer_parity(W.CONFIGS["c1"], 16)

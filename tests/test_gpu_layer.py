@@ -55,6 +55,14 @@ def test_fused_small_layer(launch_mode, bits, T):
     _layer_case(W.small(E=8, d=512, f=2048, T=T, seed=31 + T), bits, repeats=3)
 
 
+@pytest.mark.parametrize("mode", (moqe.LAUNCH_AUTO, moqe.LAUNCH_FUSED))
+def test_layer_with_fp16_experts(launch_mode, mode):
+    """bits = 16: router + tiled kernel for both contractions in every launch mode (the single
+    launch only exists for the decode kernel)."""
+    launch_mode(mode)
+    _layer_case(W.small(E=8, d=512, f=2048, T=24, seed=44), 16, residual=True, repeats=2)
+
+
 @pytest.mark.parametrize("bits", (4, 2))
 def test_fused_residual(launch_mode, bits):
     launch_mode(moqe.LAUNCH_FUSED)

@@ -36,6 +36,7 @@ def _weights(E, K, N, seed, outliers=True):
     (4, 32, 16), (4, 64, 256), (4, 256, 64), (4, 96, 48), (4, 1024, 80),
     (2, 64, 16), (2, 192, 32), (2, 256, 64), (2, 1024, 48),
     (3, 128, 16), (3, 256, 64), (3, 768, 48), (3, 1024, 32),
+    (8, 32, 16), (8, 64, 48), (8, 256, 64), (8, 1024, 32),
 ])
 def test_small_shapes(bits, K, N):
     _check(_weights(3, K, N, K + N + bits), bits)
@@ -70,3 +71,18 @@ def test_full_size_experts(bits):
     layer = W.make_layer(wl)
     _check(layer["w1"], bits)
     _check(layer["w2"], bits)
+
+
+@pytest.mark.parametrize("K,N", [(32, 16), (96, 48), (256, 64), (1024, 32)])
+def test_fp16_storage(K, N):
+    """bits = 16 (Table 2's unquantized row): the stored bytes are fp16(w), rounded once to
+    nearest even, in the oracle's layout; the scales are ones."""
+    w = _weights(3, K, N, K + N)
+    w[0, 0, 0] = 1.0 + 2.0 ** -11      # half way between two fp16 numbers: ties to even
+    w[0, 1, 0] = 1e-7                   # fp16 subnormal
+    w[0, 2, 0] = 70000.0                # beyond the fp16 range: infinity, as numpy rounds it
+    codes, scales = moqe.moqe_quantize(dev(w), 16)
+    torch.cuda.synchronize()
+    with np.errstate(over="ignore"):
+        assert np.array_equal(codes.cpu().numpy(), O.pack_fp16(w)), "stored fp16 values differ"
+    assert np.all(scales.cpu().numpy().view(np.uint16) == 0x3C00)
