@@ -78,6 +78,11 @@ def algorithmic_bytes(seg_offsets, bits, d, f, T, residual):
     return active, ffn1, ffn2
 
 
+def wname(bits):
+    """Weight format name of a bit width (16 = the unquantized baseline)."""
+    return "fp16" if bits == 16 else "int%d" % bits
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -258,7 +263,9 @@ def main():
                        kernel="moe_decode_kernel<%d,32,2> (FFN1; FFN2 is the same kernel on a matrix of the same "
                               "size)" % b)
         results[b] = res
-        print(f"[bench] {wl.name} int{b}: eager {eager_ms * 1e3:.1f} us/step (events {eager_ev_ms * 1e3:.1f}), graph "
+        if b == 16 and not compute_bound:
+            res["kernel"] = "moe_prefill_kernel<16,2> (FFN1; fp16 experts run on the tiled kernel at every batch size)"
+        print(f"[bench] {wl.name} {wname(b)}: eager {eager_ms * 1e3:.1f} us/step (events {eager_ev_ms * 1e3:.1f}), graph "
               f"{(graph_ms or float('nan')) * 1e3:.1f} us/step; dominant kernel {res['kernel_us']:.1f} us = "
               f"{res['achieved']:.0f} {res['unit']}; parts {json.dumps(parts)}", file=sys.stderr, flush=True)
 
@@ -277,6 +284,8 @@ def main():
                 self.codes, self.scales, self.K, self.N = codes, scales, K, N
 
             def __getitem__(self, e):
+                if bits0 == 16:
+                    return O.unpack_fp16(self.codes[e], self.K, self.N).astype(np.float64)
                 return O.dequantize(O.unpack(self.codes[e], bits0, self.K, self.N), self.scales[e])
 
         t = time.perf_counter()
@@ -286,17 +295,18 @@ def main():
                          layer0_host["b2"], residual=x_host if residual else None)
         dt = time.perf_counter() - t
         cpu = dict(value=T * cpu_steps / dt, unit="tokens/s", cores=cores, kind="oracle",
-                   sample=f"{cpu_steps} step(s) of route + expert FFN on layer copy 0 (T={T}, int{bits0}, fp64, "
+                   sample=f"{cpu_steps} step(s) of route + expert FFN on layer copy 0 (T={T}, {wname(bits0)}, fp64, "
                           f"codes unpacked per call), {dt:.1f} s")
 
     r = results[bits0]
     out = {
-        "metric": "expert-FFN tokens/s (route + int%d expert FFN, one MoE layer step)" % bits0,
+        "metric": "expert-FFN tokens/s (route + %s expert FFN, one MoE layer step)" % wname(bits0),
         "value": r["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int%d weights x f16 activations, f32 accumulate" % bits0, "data": "synthetic",
-        "config": {"workload": "%s: E=%d d_model=%d d_ff=%d T=%d top-1 (%s load), int%d per-channel RTN experts%s, seed %d, "
-                               "%d layer copies cycled" % (wl.name, E, d, f, T, wl.routing, bits0,
+        "dtype": "%s weights x f16 activations, f32 accumulate" % wname(bits0), "data": "synthetic",
+        "config": {"workload": "%s: E=%d d_model=%d d_ff=%d T=%d top-1 (%s load), %s experts%s, seed %d, "
+                               "%d layer copies cycled" % (wl.name, E, d, f, T, wl.routing,
+                                                           "unquantized fp16" if bits0 == 16 else "int%d per-channel RTN" % bits0,
                                                            ", fp16 residual add" if residual else "", wl.seed, copies),
                    "launch": "hip graph replay" if (r["graph_ms"] is not None and r["graph_ms"] <= r["eager_ms"]) else "eager",
                    "eager_ms_per_step": r["eager_ms"], "graph_ms_per_step": r["graph_ms"],
