@@ -20,8 +20,7 @@
  *   - T = 0 (no tokens) is valid and a no-op apart from seg_offsets = 0.
  *   - moqe_f16 is the IEEE binary16 bit pattern.
  *
- * Supported shapes: bits in {2,3,4,8} (Table 2's quantized rows; 8 bits run on the
- * dequantize-in-register kernel at every batch size) and bits = 16, the unquantized
+ * Supported shapes: bits in {2,3,4,8} (Table 2's quantized rows) and bits = 16, the unquantized
  * baseline of the same table: moqe_quantize then stores fp16(w) (one rounding, to nearest
  * even) in place of codes, by the layout rule below with a field = the fp16 bit pattern, and
  * scales of 1; such layers run on the tiled kernel at every batch size (K a multiple of 128,
@@ -98,8 +97,8 @@ int moqe_set_launch_mode(int mode);
  * decode kernel: every segment, however small, then takes the tiled kernel (a padded tile
  * for the rare small segment costs less than a launch).  Defaults below; a huge
  * min_batch_tokens switches the tiled kernel off, a huge all_tiled_tokens_per_expert the
- * second rule.  The tiled kernel needs K >= 256 and a multiple of 128 (int4) or 256 (int2,
- * int3), T*K*2 < 2^32 and T*N < 2^31; other layers use the decode kernel throughout.
+ * second rule.  The tiled kernel needs K >= 256 and a multiple of 128 (int8, int4) or 256
+ * (int2, int3), T*K*2 < 2^32 and T*N < 2^31; other layers use the decode kernel throughout.
  * Launch mode FUSED uses the decode kernel for everything it chains.
  * Returns 0, or -1 (nothing changed) if a value < 1. */
 #define MOQE_PREFILL_MIN_SEGMENT_DEFAULT 5

@@ -83,10 +83,10 @@ __global__ __launch_bounds__(PF_THREADS, (PF_NT == 4 || BITS == 16) ? 2 : PF_WG_
   constexpr int PF_MT = PF_TILE_M / 16;       // token tiles per wave: all of the tile's
   constexpr int PF_TILE_CT = 4 * PF_NT;       // column tiles per workgroup tile
   // A chunk here is what a wave fetches at a time for one column tile: one packed chunk (128
-  // rows for int4, 256 for int2 / int3), or, for unquantized fp16 weights (BITS = 16, packed
-  // chunks of 32 rows), the four packed chunks of a staged block.
-  constexpr int SC = (BITS == 4 || BITS == 16) ? 4 : 8;  // steps of 32 rows per chunk
-  constexpr int PCH = BITS == 16 ? 4 : 1;     // packed chunks per chunk
+  // rows for int4, 256 for int2 / int3) or, where packed chunks are shorter (64 rows for int8,
+  // 32 for unquantized fp16 weights, BITS = 16), the packed chunks of a staged block.
+  constexpr int SC = (BITS == 4 || BITS == 8 || BITS == 16) ? 4 : 8;  // steps of 32 rows per chunk
+  constexpr int PCH = BITS == 16 ? 4 : BITS == 8 ? 2 : 1;  // packed chunks per chunk
   constexpr int SUB = SC / 4;                 // staged K blocks per chunk
   constexpr int LO_BITS = BITS == 3 ? 2 : BITS;
   constexpr int LWC = (SC / PCH) * LO_BITS / 4;  // main-plane words per lane per packed chunk (4)
@@ -257,6 +257,8 @@ __global__ __launch_bounds__(PF_THREADS, (PF_NT == 4 || BITS == 16) ? 2 : PF_WG_
         if constexpr (BITS == 16) {
           w = frag_from_words(b_lo[bbuf][ni][4 * s], b_lo[bbuf][ni][4 * s + 1], b_lo[bbuf][ni][4 * s + 2],
                               b_lo[bbuf][ni][4 * s + 3]);
+        } else if constexpr (BITS == 8) {
+          w = unpack8_exact(b_lo[bbuf][ni][2 * s], b_lo[bbuf][ni][2 * s + 1], uc);
         } else if constexpr (BITS == 4) {
           w = unpack4_exact(b_lo[bbuf][ni][s], uc);
         } else if constexpr (BITS == 2) {
@@ -433,8 +435,8 @@ __global__ __launch_bounds__(PF_THREADS, (PF_NT == 4 || BITS == 16) ? 2 : PF_WG_
 }  // namespace
 
 bool moqe_prefill_supported(int bits, int64_t K, int64_t N) {
-  const int kc = (bits == 4 || bits == 16) ? 128 : 256;
-  return (bits == 2 || bits == 3 || bits == 4 || bits == 16) && K >= 256 && (K % kc) == 0 && N >= 16 && (N % 16) == 0;
+  const int kc = (bits == 4 || bits == 8 || bits == 16) ? 128 : 256;
+  return (bits == 2 || bits == 3 || bits == 4 || bits == 8 || bits == 16) && K >= 256 && (K % kc) == 0 && N >= 16 && (N % 16) == 0;
 }
 
 template <int BITS>
@@ -474,6 +476,7 @@ hipError_t moqe_launch_prefill(const PrefillArgs& a, int num_cus, hipStream_t st
   if (pairs * ((a.N / 16 + 7) / 8) >= (1ll << 31)) return hipErrorInvalidValue;
   switch (a.bits) {
     case 16: launch_bits<16>(a, pairs, num_cus, stream); break;
+    case 8: launch_bits<8>(a, pairs, num_cus, stream); break;
     case 4: launch_bits<4>(a, pairs, num_cus, stream); break;
     case 3: launch_bits<3>(a, pairs, num_cus, stream); break;
     case 2: launch_bits<2>(a, pairs, num_cus, stream); break;

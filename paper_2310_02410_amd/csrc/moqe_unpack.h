@@ -149,6 +149,15 @@ __device__ inline half8_t unpack4_exact(uint32_t d, const C& c) {
   return frag_from_words(r0, r1, r2, r3);
 }
 
+template <class C>
+__device__ inline half8_t unpack8_exact(uint32_t d0, uint32_t d1, const C& c) {
+  uint32_t r0 = pk_sub((d0 & c.m_00ff) | c.x1024, 1152.0f);
+  uint32_t r1 = pk_sub(((d0 >> 8) & c.m_00ff) | c.x1024, 1152.0f);
+  uint32_t r2 = pk_sub((d1 & c.m_00ff) | c.x1024, 1152.0f);
+  uint32_t r3 = pk_sub(((d1 >> 8) & c.m_00ff) | c.x1024, 1152.0f);
+  return frag_from_words(r0, r1, r2, r3);
+}
+
 template <int PARITY, class C>
 __device__ inline half8_t unpack2_exact(uint32_t d, const C& c) {
   if (PARITY == 0) {

@@ -45,7 +45,7 @@ def _parity(wl, bits, residual=False, forced=None, layer=None):
     return np.bincount(idx, minlength=wl.E)
 
 
-@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("bits", (8, 4, 3, 2))
 @pytest.mark.parametrize("T", (1, 37, 150, 700))
 def test_every_segment_through_the_tiled_kernel(prefill_min, bits, T):
     # threshold 1: also one-token segments take 64-token tiles (ragged in every way);
@@ -54,7 +54,7 @@ def test_every_segment_through_the_tiled_kernel(prefill_min, bits, T):
     _parity(W.small(E=8, d=256, f=512, T=T, seed=70 + T), bits)
 
 
-@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("bits", (8, 4, 3, 2))
 def test_tiled_kernel_residual_and_odd_widths(prefill_min, bits):
     prefill_min(1)
     _parity(W.small(E=4, d=512, f=1024, T=90, seed=81), bits, residual=True)
@@ -116,7 +116,7 @@ def test_mixed_paths_under_zipf_load():
     """Zipf load at the default thresholds: large segments go to the tiled kernel, small ones
     to the decode kernel, some experts stay empty; both kernels write disjoint rows of h and y."""
     wl = W.small(E=16, d=256, f=512, T=200, routing="zipf", n_empty=3, seed=85)
-    for bits in (4, 3, 2):
+    for bits in (8, 4, 3, 2):
         counts = _parity(wl, bits, residual=True)
     assert (counts >= 5).any() and ((counts > 0) & (counts < 5)).any() and (counts == 0).sum() >= 3
 
