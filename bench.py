@@ -49,7 +49,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="c1",
-                    choices=("c1", "c2", "c3", "c4_T24_uniform", "c4_T24_zipf", "c4_T4096_uniform", "c4_T4096_zipf"))
+                    choices=("c1", "c2", "c3", "c4_T24_uniform", "c4_T24_zipf", "c4_T4096_uniform", "c4_T4096_zipf",
+                             "n2_e128", "n2_dense"))
     ap.add_argument("--bits", type=int, default=None, choices=(2, 3, 4, 8, 16),
                     help="bit width of the headline line (default: the workload's own)")
     ap.add_argument("--copies", type=int, default=None, help="independent layer copies cycled through "
@@ -104,6 +105,7 @@ def main():
 
     variants = dict(W.CONFIGS)
     variants.update({v.name: v for v in W.c4_variants()})
+    variants.update(W.EXTRA)
     wl = variants[args.workload]
     E, d, f, T = wl.E, wl.d, wl.f, wl.T
     residual = wl.layers > 1               # the stack adds the layer's output to its input
@@ -260,7 +262,7 @@ def main():
             kern_us = parts["ffn1_back_to_back_us"]
             res.update(bound="hbm", kernel_us=kern_us, kernel_work=ffn1_bytes,
                        achieved=ffn1_bytes / (kern_us * 1e-6) / 1e9, peak=HBM_PEAK_GBS, unit="GB/s",
-                       kernel="moe_decode_kernel<%d,32,2> (FFN1; FFN2 is the same kernel on a matrix of the same "
+                       kernel="moe_decode_kernel<%d,*,2> (FFN1; FFN2 is the same kernel on a matrix of the same "
                               "size)" % b)
         results[b] = res
         if b == 16 and not compute_bound:

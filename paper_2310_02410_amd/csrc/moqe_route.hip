@@ -446,6 +446,24 @@ __global__ __launch_bounds__(SMALL_THREADS) void route_small_kernel(const half_t
   }
 }
 
+// One expert (a dense FFN run through the same calls): every token goes to expert 0 with the
+// softmax probability of a single logit, 1.
+__global__ __launch_bounds__(256) void route_single_expert_kernel(int T, int* __restrict__ expert_idx,
+                                                                   float* __restrict__ gate,
+                                                                   int* __restrict__ seg_offsets,
+                                                                   int* __restrict__ perm) {
+  const int t = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+  if (t < T) {
+    expert_idx[t] = 0;
+    gate[t] = 1.0f;
+    perm[t] = t;
+  }
+  if (t == 0) {
+    seg_offsets[0] = 0;
+    seg_offsets[1] = T;
+  }
+}
+
 // True when route_small_kernel can take the call.
 static bool small_route_fits(int T, int d, int E) {
   if (T < 1 || T > 64 || d < 32 || (d % 32) != 0) return false;
@@ -477,6 +495,12 @@ static int pow2_ceil(int v) {
 hipError_t moqe_launch_route(const uint16_t* x, const uint16_t* wg, const float* logits, int T, int d, int E,
                              int* expert_idx, float* gate, int* seg_offsets, int* perm, void* ws,
                              hipStream_t stream) {
+  if (E == 1) {
+    // (also with given logits: the argmax over one column is 0 and its softmax 1 whatever it holds)
+    hipLaunchKernelGGL(route_single_expert_kernel, dim3((unsigned)((T + 255) / 256 > 0 ? (T + 255) / 256 : 1)),
+                       dim3(256), 0, stream, T, expert_idx, gate, seg_offsets, perm);
+    return hipGetLastError();
+  }
   if (T > 0 && !logits && small_route_fits(T, d, E)) {
     const half_t* xh = (const half_t*)x;
     const half_t* wh = (const half_t*)wg;

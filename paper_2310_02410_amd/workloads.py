@@ -61,6 +61,14 @@ CONFIGS = {
 }
 
 
+# Shapes beyond the five configurations: the paper's second model (App. B: 128 experts,
+# d_model 768, d_ff 3072) and a dense FFN (one expert) run through the same calls, at batch 24.
+EXTRA = {
+    "n2_e128": Workload("n2_e128", E=128, d=768, f=3072, T=24, bits=(4,), seed=5, outlier_prob=1e-3),
+    "n2_dense": Workload("n2_dense", E=1, d=1024, f=4096, T=24, bits=(4,), seed=6, outlier_prob=1e-3),
+}
+
+
 def c4_variants():
     """Config 4 runs at T in {24, 4096} with uniform and Zipf(1.1) routing."""
     base = CONFIGS["c4"]

@@ -86,6 +86,14 @@ def test_many_small_experts_shape(bits):
     _layer_case(W.small(E=128, d=768, f=3072, T=24, seed=64), bits, repeats=2)
 
 
+@pytest.mark.parametrize("bits", (4, 2))
+def test_dense_ffn_as_one_expert(bits):
+    """E = 1: a quantized dense FFN through the same calls (every token to expert 0, gate 1),
+    at the benchmark's size and at a ragged token count."""
+    _layer_case(W.EXTRA["n2_dense"], bits, repeats=2)
+    _layer_case(W.small(E=1, d=256, f=512, T=37, seed=65), bits, residual=True)
+
+
 def test_launch_modes_agree_bit_for_bit(launch_mode):
     wl = W.small(E=8, d=512, f=2048, T=33, seed=63)
     layer, x = W.make_layer(wl), W.make_tokens(wl)
