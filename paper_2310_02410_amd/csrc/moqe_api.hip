@@ -59,7 +59,7 @@ const char* moqe_status_string(int status) {
   switch (status) {
     case MOQE_OK: return "MOQE_OK";
     case MOQE_ERR_NULL: return "MOQE_ERR_NULL: required pointer is NULL";
-    case MOQE_ERR_BITS: return "MOQE_ERR_BITS: bits must be 2, 3 or 4";
+    case MOQE_ERR_BITS: return "MOQE_ERR_BITS: bits must be 2, 3, 4, 8 or 16 (fp16 weights)";
     case MOQE_ERR_SHAPE: return "MOQE_ERR_SHAPE: unsupported dimension";
     case MOQE_ERR_ALIGN: return "MOQE_ERR_ALIGN: device pointer not 16-byte aligned";
     case MOQE_ERR_WORKSPACE: return "MOQE_ERR_WORKSPACE: workspace too small";

@@ -15,6 +15,8 @@
 //                  enough tiles for several full rounds
 //          PF_NT = 2: 128 channels, 32 per wave (4 x 2 tiles), 3 workgroups per compute unit -
 //                  narrow matrices and smaller launches, so that the grid still fills the chip
+//          PF_NT = 1: 64 channels, 16 per wave - launches with fewer 64 x 128 tiles than the
+//                  chip has places
 //   The grid is persistent; a workgroup walks over its share of the tiles.
 //   K runs in staged blocks of 128 rows:
 //     - the block's 64 token rows are staged in LDS by loads that go from global memory
@@ -77,7 +79,7 @@ struct PfTile {
   bool valid;
 };
 
-// PF_NT: column tiles (of 16 channels) per wave, 4 or 2
+// PF_NT: column tiles (of 16 channels) per wave: 4, 2 or 1
 template <int BITS, int PF_NT>
 __global__ __launch_bounds__(PF_THREADS, (PF_NT == 4 || BITS == 16) ? 2 : PF_WG_PER_CU) void moe_prefill_kernel(PrefillArgs A) {
   constexpr int PF_MT = PF_TILE_M / 16;       // token tiles per wave: all of the tile's
@@ -453,7 +455,11 @@ static void launch_bits(const PrefillArgs& a, int64_t pairs, int num_cus, hipStr
   // (fp16 weights hold 16 words per chunk and column tile: only the narrow shape has the registers)
   const bool wide = BITS != 16 && CT >= 128 && pairs * ((CT + 15) / 16) >= 3ll * 2 * num_cus;
   const int per_cu = (wide || BITS == 16) ? 2 : PF_WG_PER_CU;
-  args.n_cblocks = wide ? (CT + 15) / 16 : (CT + 7) / 8;
+  // A launch that cannot even fill the chip once with 64 x 128 tiles takes 64 x 64 ones (16
+  // channels per wave): twice the workgroups to share the weight stream (fp16 experts at batch
+  // 24, FFN2: 44.7 -> 34.2 us; no change where the launch was not short of workgroups).
+  const bool small = !wide && pairs * ((CT + 7) / 8) < (int64_t)per_cu * num_cus;
+  args.n_cblocks = wide ? (CT + 15) / 16 : small ? (CT + 3) / 4 : (CT + 7) / 8;
   int64_t grid = pairs * args.n_cblocks;  // upper bound on the tiles
   if (grid > (int64_t)per_cu * num_cus) grid = (int64_t)per_cu * num_cus;
   grid = grid < 8 ? 8 : (grid & ~(int64_t)7);  // a multiple of the 8 XCDs
@@ -463,9 +469,10 @@ static void launch_bits(const PrefillArgs& a, int64_t pairs, int num_cus, hipStr
       return;
     }
   }
-  {
+  if (small)
+    hipLaunchKernelGGL((moe_prefill_kernel<BITS, 1>), dim3((unsigned)grid), dim3(PF_THREADS), 0, stream, args);
+  else
     hipLaunchKernelGGL((moe_prefill_kernel<BITS, 2>), dim3((unsigned)grid), dim3(PF_THREADS), 0, stream, args);
-  }
 }
 
 hipError_t moqe_launch_prefill(const PrefillArgs& a, int num_cus, hipStream_t stream) {
@@ -473,7 +480,7 @@ hipError_t moqe_launch_prefill(const PrefillArgs& a, int num_cus, hipStream_t st
   const int64_t with_pairs = a.min_tokens > 0 ? a.T / a.min_tokens : a.E;
   const int64_t pairs = a.T / PF_TILE_M + (with_pairs < a.E ? with_pairs : a.E);
   if (pairs <= 0) return hipSuccess;
-  if (pairs * ((a.N / 16 + 7) / 8) >= (1ll << 31)) return hipErrorInvalidValue;
+  if (pairs * ((a.N / 16 + 3) / 4) >= (1ll << 31)) return hipErrorInvalidValue;
   switch (a.bits) {
     case 16: launch_bits<16>(a, pairs, num_cus, stream); break;
     case 8: launch_bits<8>(a, pairs, num_cus, stream); break;
