@@ -62,7 +62,7 @@ def fp16_round_up(s64) -> np.ndarray:
     return h
 
 
-def quantize(w, bits: int):
+def quantize(w, bits: int, scale_per: str = "channel"):
     """Channel-wise absmax linear quantization of a stack of matrices.
 
     w: [E, K, N] (or [K, N]); a channel is a column A_:,j, i.e. one of the N
@@ -75,7 +75,13 @@ def quantize(w, bits: int):
     clamp to the two's-complement range (A/s spans +-(2^b-1)/2, whose rounding
     has one level too many for b bits).  An all-zero channel gets s = 0 and
     codes 0.
+
+    scale_per = "tensor" is the alternative App. A names ("per the whole tensor", the
+    matrix-wise scale App. C compares against): one s = 2 max|A| / (2^b - 1) for the whole
+    matrix, returned as N equal channel scales so that everything downstream is unchanged.
     """
+    if scale_per not in ("channel", "tensor"):
+        raise ValueError("scale_per must be 'channel' or 'tensor'")
     w = np.asarray(w)
     squeeze = w.ndim == 2
     if squeeze:
@@ -89,6 +95,8 @@ def quantize(w, bits: int):
     for e in range(E):
         a = w[e].astype(np.float64)
         m = np.max(np.abs(a), axis=0)
+        if scale_per == "tensor":
+            m = np.full_like(m, m.max())
         s64 = (2.0 * m) / float((1 << bits) - 1)
         s16 = fp16_round_up(s64)
         sd = s16.astype(np.float64)

@@ -165,3 +165,32 @@ def test_more_bits_is_closer():
     w = _rand((1, 256, 64), 14, outliers=False)
     errs = [np.abs(O.dequantize(*O.quantize(w, b)) - w).mean() for b in (2, 3, 4)]
     assert errs[0] > errs[1] > errs[2]
+
+
+@pytest.mark.parametrize("bits", BITS)
+def test_tensor_wise_scale(bits):
+    """App. A's other choice of s ("per the whole tensor"): one scale from the matrix maximum.
+    Hand example: columns with maxima 3 and 1.5 share s = 2*3/(2^b - 1); invariants as for the
+    channel-wise scale; a matrix of one column is the same either way; channel-wise scales never
+    exceed the tensor's."""
+    w = np.array([[3.0, 1.5], [-1.0, -1.5], [0.4, 0.0]])
+    q, s = O.quantize(w, bits, scale_per="tensor")
+    expect = float(O.fp16_round_up(np.array(6.0 / (2 ** bits - 1))))
+    assert s.tolist() == [expect, expect]
+    assert q[0, 0] == 2 ** (bits - 1) - 1                      # the maximum takes the top code
+    assert q[0, 1] == int(np.clip(np.rint(1.5 / expect), -(2 ** (bits - 1)), 2 ** (bits - 1) - 1))
+    w = _rand((2, 64, 32), 9)
+    q, s = O.quantize(w, bits, scale_per="tensor")
+    lo, hi = O.code_range(bits)
+    assert q.min() >= lo and q.max() <= hi
+    assert np.all(s == s[:, :1])                                # one value per matrix
+    err = np.abs(w.astype(np.float64) - O.dequantize(q, s))
+    assert np.all(err <= 0.5 * s.astype(np.float64)[:, None, :] * (1 + 2.0 ** -50))
+    qc, sc = O.quantize(w, bits)
+    assert np.all(sc.astype(np.float64) <= s.astype(np.float64))
+    assert np.array_equal(s[:, 0].astype(np.float64), sc.astype(np.float64).max(axis=1))
+    q1, s1 = O.quantize(w[:, :, :1], bits, scale_per="tensor")
+    q2, s2 = O.quantize(w[:, :, :1], bits)
+    assert np.array_equal(q1, q2) and np.array_equal(s1, s2)
+    with pytest.raises(ValueError):
+        O.quantize(w, bits, scale_per="row")
