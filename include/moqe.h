@@ -146,6 +146,13 @@ size_t moqe_layer_workspace_bytes(int64_t T, int64_t E, int64_t d, int64_t f); /
  */
 moqe_status moqe_quantize(const float* w, int64_t E, int64_t K, int64_t N, int bits,
                           void* codes_out, moqe_f16* scales_out, void* stream);
+/* The same with the other choice of s that App. A names ("per the whole tensor"; the
+ * matrix-wise scale App. C compares the channel-wise one against): one
+ * s = 2 max|A| / (2^bits - 1) per [K,N] matrix, written to all N entries of its row of
+ * scales_out, so that the expert FFN calls take such a layer unchanged.  Arguments, layouts
+ * and errors as for moqe_quantize; bits = 16 has no scale to choose and is the same call. */
+moqe_status moqe_quantize_tensor_scale(const float* w, int64_t E, int64_t K, int64_t N, int bits,
+                                       void* codes_out, moqe_f16* scales_out, void* stream);
 
 /* Inverse of the packing, for tests and tools: q_out [E,K,N] int8 codes. */
 moqe_status moqe_unpack(const void* codes, int64_t E, int64_t K, int64_t N, int bits,

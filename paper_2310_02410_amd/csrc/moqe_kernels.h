@@ -8,8 +8,9 @@
 
 #include "moqe_dev.h"
 
+// tensor_scale: one scale per matrix (the largest channel scale) instead of one per channel
 hipError_t moqe_launch_quantize(const float* w, int64_t E, const PackGeom& g, void* codes, uint16_t* scales,
-                                hipStream_t stream);
+                                bool tensor_scale, hipStream_t stream);
 hipError_t moqe_launch_unpack(const void* codes, int64_t E, const PackGeom& g, int8_t* q_out, hipStream_t stream);
 
 size_t moqe_route_ws_bytes(int64_t T, int64_t E);

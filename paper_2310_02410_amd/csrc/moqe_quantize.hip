@@ -94,6 +94,24 @@ __global__ __launch_bounds__(256) void scale_kernel(const float* __restrict__ w,
   }
 }
 
+// Tensor-wise scale: every channel of a matrix gets the largest channel scale.  The fp16
+// round-up is monotone, so the largest stored channel scale is the stored scale of the matrix
+// maximum; positive fp16 numbers order like their bit patterns.  One workgroup per matrix.
+__global__ __launch_bounds__(256) void tensor_scale_kernel(uint16_t* __restrict__ scales, int N) {
+  __shared__ uint16_t s_max[256];
+  uint16_t* row = scales + (int64_t)blockIdx.x * N;
+  uint16_t m = 0;
+  for (int n = threadIdx.x; n < N; n += 256) m = row[n] > m ? row[n] : m;
+  s_max[threadIdx.x] = m;
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if ((int)threadIdx.x < off && s_max[threadIdx.x + off] > s_max[threadIdx.x]) s_max[threadIdx.x] = s_max[threadIdx.x + off];
+    __syncthreads();
+  }
+  m = s_max[0];
+  for (int n = threadIdx.x; n < N; n += 256) row[n] = m;
+}
+
 // One thread per packed 32-bit word.
 __global__ __launch_bounds__(256) void pack_kernel(const float* __restrict__ w, const uint16_t* __restrict__ scales,
                                                     PackGeom g, int64_t E, uint32_t* __restrict__ codes) {
@@ -178,9 +196,11 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint32_t* __restrict_
 }  // namespace
 
 hipError_t moqe_launch_quantize(const float* w, int64_t E, const PackGeom& g, void* codes, uint16_t* scales,
-                                hipStream_t stream) {
+                                bool tensor_scale, hipStream_t stream) {
   const int64_t blocks = E * ((g.N + 255) / 256);
   hipLaunchKernelGGL(scale_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, w, E, g.K, g.N, g.bits, scales);
+  if (tensor_scale && g.bits != 16)
+    hipLaunchKernelGGL(tensor_scale_kernel, dim3((unsigned)E), dim3(256), 0, stream, scales, g.N);
   int64_t words = E * (g.matrix_bytes / 4);
   hipLaunchKernelGGL(pack_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, stream, w, scales, g, E,
                      (uint32_t*)codes);

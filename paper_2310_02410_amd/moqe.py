@@ -26,7 +26,7 @@ EXPORTS = (
     "moqe_ffn_workspace_bytes", "moqe_quantize", "moqe_unpack", "moqe_route",
     "moqe_route_logits", "moqe_expert_ffn", "moqe_expert_ffn1", "moqe_expert_ffn2",
     "moqe_layer_workspace_bytes", "moqe_moe_layer", "moqe_set_launch_mode",
-    "moqe_set_prefill_policy",
+    "moqe_set_prefill_policy", "moqe_quantize_tensor_scale",
 )
 
 LAUNCH_AUTO, LAUNCH_SEPARATE, LAUNCH_FUSED = 0, 1, 2
@@ -87,6 +87,8 @@ def lib() -> ctypes.CDLL:
     L.moqe_moe_layer.argtypes = [ctypes.POINTER(CLayer), vp, vp, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.moqe_quantize.restype = ci
     L.moqe_quantize.argtypes = [vp, i64, i64, i64, ci, vp, vp, vp]
+    L.moqe_quantize_tensor_scale.restype = ci
+    L.moqe_quantize_tensor_scale.argtypes = [vp, i64, i64, i64, ci, vp, vp, vp]
     L.moqe_unpack.restype = ci
     L.moqe_unpack.argtypes = [vp, i64, i64, i64, ci, vp, vp]
     L.moqe_route.restype = ci
@@ -175,8 +177,9 @@ def alloc_workspace(nbytes: int, device) -> torch.Tensor:
 # the three calls
 # ---------------------------------------------------------------------------
 
-def moqe_quantize(w: torch.Tensor, bits: int, stream=None):
-    """w fp32 [E,K,N] -> (codes uint8 [E, K*N*bits/8], scales fp16 [E,N])."""
+def moqe_quantize(w: torch.Tensor, bits: int, stream=None, tensor_scale: bool = False):
+    """w fp32 [E,K,N] -> (codes uint8 [E, K*N*bits/8], scales fp16 [E,N]); tensor_scale: one scale
+    per matrix instead of one per channel."""
     _dev(w, torch.float32, "w")
     E, K, N = w.shape
     nbytes = moqe_packed_bytes(bits, K, N)
@@ -184,8 +187,8 @@ def moqe_quantize(w: torch.Tensor, bits: int, stream=None):
         _check(lib().moqe_check_matrix(bits, K, N) or 3, "moqe_quantize")
     codes = torch.empty((E, nbytes), dtype=torch.uint8, device=w.device)
     scales = torch.empty((E, N), dtype=torch.float16, device=w.device)
-    _check(lib().moqe_quantize(w.data_ptr(), E, K, N, bits, codes.data_ptr(), scales.data_ptr(), _stream(stream)),
-           "moqe_quantize")
+    fn = lib().moqe_quantize_tensor_scale if tensor_scale else lib().moqe_quantize
+    _check(fn(w.data_ptr(), E, K, N, bits, codes.data_ptr(), scales.data_ptr(), _stream(stream)), "moqe_quantize")
     return codes, scales
 
 

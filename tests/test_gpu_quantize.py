@@ -86,3 +86,30 @@ def test_fp16_storage(K, N):
     with np.errstate(over="ignore"):
         assert np.array_equal(codes.cpu().numpy(), O.pack_fp16(w)), "stored fp16 values differ"
     assert np.all(scales.cpu().numpy().view(np.uint16) == 0x3C00)
+
+
+@pytest.mark.parametrize("bits", (2, 3, 4, 8))
+def test_tensor_wise_scale(bits):
+    """moqe_quantize_tensor_scale: one scale per matrix (App. A "per the whole tensor"), codes and
+    scales identical to the oracle's; an expert FFN takes the result unchanged."""
+    w = _weights(3, 256, 48, 77 + bits)
+    codes, scales = moqe.moqe_quantize(dev(w), bits, tensor_scale=True)
+    q_ref, s_ref = O.quantize(w, bits, scale_per="tensor")
+    torch.cuda.synchronize()
+    assert np.array_equal(scales.cpu().numpy().view(np.uint16), s_ref.view(np.uint16)), "scales differ"
+    assert np.array_equal(codes.cpu().numpy(), O.pack(q_ref, bits)), "packed bytes differ"
+    # a layer quantized this way through the FFN
+    wl = W.small(E=4, d=256, f=512, T=19, seed=90 + bits)
+    layer, x = W.make_layer(wl), W.make_tokens(wl)
+    c1, s1 = moqe.moqe_quantize(dev(layer["w1"]), bits, tensor_scale=True)
+    c2, s2 = moqe.moqe_quantize(dev(layer["w2"]), bits, tensor_scale=True)
+    ql = moqe.QuantLayer(bits, wl.E, wl.d, wl.f, c1, s1, dev(layer["b1"]), c2, s2, dev(layer["b2"]), dev(layer["w_gate"]))
+    xd = dev(x)
+    r = moqe.moqe_route(xd, ql.w_gate)
+    y = moqe.moqe_expert_ffn(ql, xd, r).cpu().numpy()
+    q1, t1 = O.quantize(layer["w1"], bits, scale_per="tensor")
+    q2, t2 = O.quantize(layer["w2"], bits, scale_per="tensor")
+    idx, gate = r.expert_idx.cpu().numpy(), r.gate.cpu().numpy().astype(np.float64)
+    ref = O.expert_ffn(x, idx, gate, O.dequantize(q1, t1), layer["b1"], O.dequantize(q2, t2), layer["b2"])
+    err = np.abs(y.astype(np.float64) - ref).max() / np.abs(ref).max()
+    assert err <= 2e-3, err
