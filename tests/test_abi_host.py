@@ -66,6 +66,11 @@ def test_shape_rules():
     assert L.moqe_check_matrix(3, 768, 3072) == 0
     assert L.moqe_check_matrix(8, 32, 16) == 0 and L.moqe_check_matrix(8, 96, 16) == 3   # 3 steps, chunk of 2
     assert L.moqe_check_layer(8, 32, 1024, 4096) == 0
+    # fp16 weights: packable from K = 32 on, but as a layer only where the tiled kernel takes both
+    # contractions (K at least 256 and a multiple of 128)
+    assert L.moqe_check_matrix(16, 32, 16) == 0 and moqe.moqe_packed_bytes(16, 256, 64) == 256 * 64 * 2
+    assert L.moqe_check_layer(16, 32, 1024, 4096) == 0 and L.moqe_check_layer(16, 4, 384, 256) == 0
+    assert L.moqe_check_layer(16, 4, 64, 256) == 3 and L.moqe_check_layer(16, 4, 256, 320) == 3
     assert moqe.moqe_packed_bytes(2, 32, 16) == 0
     assert L.moqe_check_layer(4, 4, 64, 256) == 0
     assert L.moqe_check_layer(2, 32, 1024, 4096) == 0
@@ -96,6 +101,8 @@ def test_quantize_error_paths():
     assert L.moqe_quantize(P + 4, 1, 64, 16, 4, P, P, None) == 4
     assert L.moqe_unpack(P, 1, 64, 16, 4, 0, None) == 1
     assert L.moqe_unpack(P, 1, 64, 16, 1, P, None) == 2
+    assert L.moqe_unpack(P, 1, 64, 16, 16, P, None) == 2       # fp16 weights are not int8 codes
+    assert L.moqe_quantize_tensor_scale(P, 1, 64, 16, 7, P, P, None) == 2
     assert L.moqe_unpack(P, 1, 64, 20, 4, P, None) == 3
 
 
