@@ -112,6 +112,27 @@ def test_wide_tile_shape_takes_large_launches():
     assert ffn_error(y[rows], ref) <= FFN_TOL
 
 
+def test_largest_batch_the_tiled_kernel_addresses():
+    """520,000 tokens with d_ff 4096: h holds 4.26e9 bytes and 2.13e9 elements, just inside the
+    32-bit offsets of the tiled kernel (byte offsets below 2^32, element offsets below 2^31).
+    Routing tables for every token, the FFN on sampled rows - the last rows of h and y, the
+    highest addresses, among them."""
+    T = 520_000
+    wl = W.small(E=4, d=256, f=4096, T=T, seed=89)
+    layer, x = W.make_layer(wl), W.make_tokens(wl)
+    ql = gpu_quantize_layer(layer, 4)
+    xd = dev(x)
+    r = moqe.moqe_route(xd, ql.w_gate)
+    idx, gate, offs, perm = route_to_numpy(r)
+    assert_route_equal((idx, gate, offs, perm), O.route(x, layer["w_gate"]), T, wl.E)
+    y = moqe.moqe_expert_ffn(ql, xd, r)
+    torch.cuda.synchronize()
+    rows = np.random.default_rng(89).choice(T, size=192, replace=False)
+    rows = np.concatenate([rows, np.arange(T - 64, T), perm[offs[1:] - 1], perm[offs[:-1]]])
+    ref = oracle_layer_output(x[rows], layer, 4, idx[rows], gate[rows].astype(np.float64))
+    assert ffn_error(y[torch.from_numpy(rows).cuda()].cpu().numpy(), ref) <= FFN_TOL
+
+
 def test_mixed_paths_under_zipf_load():
     """Zipf load at the default thresholds: large segments go to the tiled kernel, small ones
     to the decode kernel, some experts stay empty; both kernels write disjoint rows of h and y."""
