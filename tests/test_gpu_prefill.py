@@ -133,6 +133,26 @@ def test_largest_batch_the_tiled_kernel_addresses():
     assert ffn_error(y[torch.from_numpy(rows).cuda()].cpu().numpy(), ref) <= FFN_TOL
 
 
+def test_batch_beyond_the_tiled_kernels_offsets():
+    """530,000 tokens with d_ff 4096: h has more than 2^31 elements and 2^32 bytes, which the
+    tiled kernel does not address; both contractions stay with the decode kernel (64-bit
+    offsets, token tables read from memory).  Sampled rows, the last ones among them."""
+    T = 530_000
+    wl = W.small(E=4, d=256, f=4096, T=T, seed=90)
+    layer, x = W.make_layer(wl), W.make_tokens(wl)
+    ql = gpu_quantize_layer(layer, 2)
+    xd = dev(x)
+    r = moqe.moqe_route(xd, ql.w_gate)
+    idx, gate, offs, perm = route_to_numpy(r)
+    assert_route_equal((idx, gate, offs, perm), O.route(x, layer["w_gate"]), T, wl.E)
+    y = moqe.moqe_expert_ffn(ql, xd, r)
+    torch.cuda.synchronize()
+    rows = np.random.default_rng(90).choice(T, size=192, replace=False)
+    rows = np.concatenate([rows, np.arange(T - 64, T), perm[offs[1:] - 1], perm[offs[:-1]]])
+    ref = oracle_layer_output(x[rows], layer, 2, idx[rows], gate[rows].astype(np.float64))
+    assert ffn_error(y[torch.from_numpy(rows).cuda()].cpu().numpy(), ref) <= FFN_TOL
+
+
 def test_mixed_paths_under_zipf_load():
     """Zipf load at the default thresholds: large segments go to the tiled kernel, small ones
     to the decode kernel, some experts stay empty; both kernels write disjoint rows of h and y."""
