@@ -71,6 +71,34 @@ def quantize_matrix(w, bits: int):
     return q, scales
 
 
+def log_quantize_column(col, bits: int):
+    """App. A log-scale quantization of one channel, in exact rational arithmetic and straight
+    from the printed formulas: T = clip(|a|/s, 2^(1-2^(b-1)), 1), Q = ceil(log2(2T/3)) found as
+    the smallest integer with 2^Q >= 2T/3, sign kept apart; s = smallest fp16 >= max|a|.
+    Returns (signs list[int] (1 = negative), exponents list[int], scale float)."""
+    from fractions import Fraction
+
+    m = max(abs(float(v)) for v in col)
+    _, s = smallest_half_at_least(m)
+    low = Fraction(1, 2 ** ((1 << (bits - 1)) - 1))
+    signs, expos = [], []
+    for v in col:
+        signs.append(1 if float(v) < 0 else 0)
+        if s == 0.0:
+            expos.append(None)
+            continue
+        t = abs(Fraction(float(v))) / Fraction(s)
+        t = min(Fraction(1), max(low, t))
+        target = Fraction(2, 3) * t
+        expo = 0
+        while Fraction(2) ** (expo - 1) >= target:   # 2^Q >= 2T/3 still holds one lower
+            expo -= 1
+        while Fraction(2) ** expo < target:
+            expo += 1
+        expos.append(expo)
+    return signs, expos, s
+
+
 def pack_matrix(q, bits: int) -> bytes:
     """Pack q[K][N] by enumerating the storage in order: column tile, chunk,
     (bit plane,) slot, 32-bit word, half, field -> which (k, n) sits there."""

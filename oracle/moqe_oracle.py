@@ -10,6 +10,9 @@ What it states (all arithmetic IEEE fp64 unless the paper fixes a precision):
   absolute maximum, paper App. A "Linear quantization with absolute maximum"
   (s_j = 2 max|A_:,j| / (2^b - 1), Q = int(A / s), A' = Q * s), scales kept in
   half precision as App. C says.
+* ``quantize_log`` / ``dequantize_log`` - the log-scale alternative of App. A
+  (sign bit + (b-1)-bit exponent, A' = P * s * 2^Q), which the paper compares
+  with the linear one and sets aside.
 * ``pack`` / ``unpack``          - the dense b-bit storage implied by Table 2's
   size column (exactly b bits per weight); the byte/bit position of every code
   is the layout function written out in ``code_positions``.
@@ -121,6 +124,94 @@ def dequantize(q, s) -> np.ndarray:
 def quantize_fp16(w) -> np.ndarray:
     """The unquantized 16-bit path: A' = fp16(A), returned as fp64."""
     return np.asarray(w).astype(np.float16).astype(np.float64)
+
+
+# --------------------------------------------------------------------------
+# log-scale quantizer (App. A, "log-scale quantization": the alternative the
+# paper compares with the linear one and does not adopt)
+# --------------------------------------------------------------------------
+
+LOG_BITS = (2, 3, 4)
+
+
+def log_exponent_range(bits: int) -> tuple[int, int]:
+    """Exponents Q a b-bit log code can hold: one bit is the sign, the other b-1 bits
+    count the 2^(b-1) values 1 - 2^(b-1) .. 0."""
+    if bits not in LOG_BITS:
+        raise ValueError(f"unsupported log-scale bit width {bits}")
+    return 1 - (1 << (bits - 1)), 0
+
+
+def quantize_log(w, bits: int, scale_per: str = "channel"):
+    """Log-scale quantization of a stack of matrices (App. A).
+
+    P = sign(A);  T = clip(|A| / s, 2^(1 - 2^(b-1)), 1);  Q = ceil(log2(2/3 T)).
+    Returns (q int8 [E,K,N], s fp16 [E,N]).
+
+    Readings.  The printed clip has its two bounds in the order (1, 2^(1-2^(b-1))), a lower
+    bound above the upper one; it is read as the interval [2^(1-2^(b-1)), 1], the one whose
+    ends give exactly the 2^(b-1) exponents 1 - 2^(b-1) .. 0 that b - 1 bits can count.
+    s is the first of the two choices the paper names, the absolute maximum (the MSE-optimal
+    search is another paper's algorithm), taken per output channel like the linear scale (or
+    per matrix with scale_per = "tensor") and stored in fp16 rounded upward, so that T <= 1.
+    Q = ceil(log2(2T/3)) is the smallest integer with 2^Q >= 2T/3, i.e. with
+    |A| <= 1.5 * 2^Q * s; that comparison is exact in floating point (1.5 * 2^Q * s has few
+    bits), so the exponent is decided without rounding a quotient or a logarithm.  It rounds
+    |A|/s to the nearest power of two on the linear axis (the break between 2^(Q-1) and 2^Q is
+    their mean 0.75 * 2^Q, which goes down).
+    Stored code: u = sign_bit * 2^(b-1) + (Q - (1 - 2^(b-1))), a b-bit field; it is returned
+    offset like the linear codes, q = u - 2^(b-1), so that pack() / unpack() serve both.
+    A zero weight has T below the lower bound and takes the smallest magnitude with a plus
+    sign (the format has no zero); an all-zero channel has s = 0 and decodes to zeros.
+    """
+    if scale_per not in ("channel", "tensor"):
+        raise ValueError("scale_per must be 'channel' or 'tensor'")
+    q_lo, q_hi = log_exponent_range(bits)
+    w = np.asarray(w)
+    squeeze = w.ndim == 2
+    if squeeze:
+        w = w[None]
+    if w.ndim != 3:
+        raise ValueError("w must be [E,K,N] or [K,N]")
+    E, K, N = w.shape
+    half = 1 << (bits - 1)
+    q = np.empty((E, K, N), dtype=np.int8)
+    s = np.empty((E, N), dtype=np.float16)
+    for e in range(E):
+        a = w[e].astype(np.float64)
+        m = np.max(np.abs(a), axis=0)
+        if scale_per == "tensor":
+            m = np.full_like(m, m.max())
+        s16 = fp16_round_up(m)
+        sd = s16.astype(np.float64)
+        mag = np.abs(a)
+        # smallest exponent in range whose upper break 1.5 * 2^Q * s is not below |A|
+        expo = np.full((K, N), q_hi, dtype=np.int64)
+        for cand in range(q_hi - 1, q_lo - 1, -1):
+            expo = np.where(mag <= 1.5 * 2.0 ** cand * sd[None, :], cand, expo)
+        neg = (a < 0).astype(np.int64)
+        u = neg * half + (expo - q_lo)
+        u = np.where(sd[None, :] > 0, u, 0)
+        q[e] = (u - half).astype(np.int8)
+        s[e] = s16
+    if squeeze:
+        return q[0], s[0]
+    return q, s
+
+
+def log_code_parts(q, bits: int):
+    """(negative flag, exponent Q) of stored log codes q = u - 2^(b-1)."""
+    q_lo, _ = log_exponent_range(bits)
+    half = 1 << (bits - 1)
+    u = np.asarray(q).astype(np.int64) + half
+    return u >= half, (u % half) + q_lo
+
+
+def dequantize_log(q, s, bits: int) -> np.ndarray:
+    """A' = P * s * 2^Q (App. A), exact in fp64. q [...,K,N], s [...,N]."""
+    neg, expo = log_code_parts(q, bits)
+    mag = np.asarray(s).astype(np.float64)[..., None, :] * 2.0 ** expo
+    return np.where(neg, -mag, mag)
 
 
 # --------------------------------------------------------------------------
