@@ -154,6 +154,27 @@ moqe_status moqe_quantize(const float* w, int64_t E, int64_t K, int64_t N, int b
 moqe_status moqe_quantize_tensor_scale(const float* w, int64_t E, int64_t K, int64_t N, int bits,
                                        void* codes_out, moqe_f16* scales_out, void* stream);
 
+/* The codec App. A describes beside the linear one and the paper sets aside ("Log-scale
+ * quantization"): one sign bit and a (bits-1)-bit exponent per weight,
+ *   P = sign(A),  T = clip(|A| / s, 2^(1 - 2^(bits-1)), 1),  Q = ceil(log2(2T/3)),  A' = P s 2^Q
+ * (the printed clip bounds, a lower bound of 1 above an upper bound below 1, are read as that
+ * interval: its ends give exactly the 2^(bits-1) exponents the field can count).  s is the
+ * absolute maximum of the output channel, the first of the two choices the paper names, stored
+ * in fp16 rounded toward +inf.  Q is decided as the smallest integer with |A| <= 1.5 * 2^Q * s,
+ * an exact comparison in fp64.  Stored field: u = sign_bit * 2^(bits-1) + (Q + 2^(bits-1) - 1),
+ * in the same packed layout as the linear codes (moqe_unpack returns u - 2^(bits-1)).  A zero
+ * weight takes the smallest magnitude with a plus sign (the format has no zero); a channel of
+ * zeros has s = 0.  bits must be 2, 3 or 4 (MOQE_ERR_BITS otherwise); other arguments, layouts
+ * and errors as for moqe_quantize.  This codec stops at the storage format: the expert FFN
+ * calls take linear codes only. */
+moqe_status moqe_quantize_log(const float* w, int64_t E, int64_t K, int64_t N, int bits,
+                              void* codes_out, moqe_f16* scales_out, void* stream);
+/* Dequantization of log-scale codes, A' = P s 2^Q, written as fp32 [E,K,N] (every value is
+ * exact): the exponent Q is added to the exponent field of s and the sign bit set, no multiply.
+ * w_out must be 16-byte aligned. */
+moqe_status moqe_dequantize_log(const void* codes, const moqe_f16* scales, int64_t E, int64_t K, int64_t N,
+                                int bits, float* w_out, void* stream);
+
 /* Inverse of the packing, for tests and tools: q_out [E,K,N] int8 codes. */
 moqe_status moqe_unpack(const void* codes, int64_t E, int64_t K, int64_t N, int bits,
                         int8_t* q_out, void* stream);

@@ -139,24 +139,40 @@ size_t moqe_layer_workspace_bytes(int64_t T, int64_t E, int64_t d, int64_t f) {
 }
 
 static moqe_status quantize_common(const float* w, int64_t E, int64_t K, int64_t N, int bits, void* codes_out,
-                                   moqe_f16* scales_out, bool tensor_scale, void* stream) {
+                                   moqe_f16* scales_out, bool tensor_scale, int codec, void* stream) {
   if (!w || !codes_out || !scales_out) return MOQE_ERR_NULL;
-  if (!valid_bits(bits)) return MOQE_ERR_BITS;
+  if (!valid_bits(bits) || (codec == MOQE_CODEC_LOG && bits > 4)) return MOQE_ERR_BITS;
   PackGeom g;
   if (E < 1 || E > MAX_EXPERTS || !moqe_make_geom(bits, K, N, &g)) return MOQE_ERR_SHAPE;
   if (!aligned16(w) || !aligned16(codes_out) || !aligned16(scales_out)) return MOQE_ERR_ALIGN;
-  hipError_t e = moqe_launch_quantize(w, E, g, codes_out, scales_out, tensor_scale, (hipStream_t)stream);
+  hipError_t e = moqe_launch_quantize(w, E, g, codes_out, scales_out, tensor_scale, codec, (hipStream_t)stream);
   return e == hipSuccess ? MOQE_OK : hip_fail(e);
 }
 
 moqe_status moqe_quantize(const float* w, int64_t E, int64_t K, int64_t N, int bits, void* codes_out,
                           moqe_f16* scales_out, void* stream) {
-  return quantize_common(w, E, K, N, bits, codes_out, scales_out, false, stream);
+  return quantize_common(w, E, K, N, bits, codes_out, scales_out, false, MOQE_CODEC_LINEAR, stream);
 }
 
 moqe_status moqe_quantize_tensor_scale(const float* w, int64_t E, int64_t K, int64_t N, int bits, void* codes_out,
                                        moqe_f16* scales_out, void* stream) {
-  return quantize_common(w, E, K, N, bits, codes_out, scales_out, true, stream);
+  return quantize_common(w, E, K, N, bits, codes_out, scales_out, true, MOQE_CODEC_LINEAR, stream);
+}
+
+moqe_status moqe_quantize_log(const float* w, int64_t E, int64_t K, int64_t N, int bits, void* codes_out,
+                              moqe_f16* scales_out, void* stream) {
+  return quantize_common(w, E, K, N, bits, codes_out, scales_out, false, MOQE_CODEC_LOG, stream);
+}
+
+moqe_status moqe_dequantize_log(const void* codes, const moqe_f16* scales, int64_t E, int64_t K, int64_t N, int bits,
+                                float* w_out, void* stream) {
+  if (!codes || !scales || !w_out) return MOQE_ERR_NULL;
+  if (bits != 2 && bits != 3 && bits != 4) return MOQE_ERR_BITS;
+  PackGeom g;
+  if (E < 1 || E > MAX_EXPERTS || !moqe_make_geom(bits, K, N, &g)) return MOQE_ERR_SHAPE;
+  if (!aligned16(codes) || !aligned16(scales) || !aligned16(w_out)) return MOQE_ERR_ALIGN;
+  hipError_t e = moqe_launch_dequantize_log(codes, scales, E, g, w_out, (hipStream_t)stream);
+  return e == hipSuccess ? MOQE_OK : hip_fail(e);
 }
 
 moqe_status moqe_unpack(const void* codes, int64_t E, int64_t K, int64_t N, int bits, int8_t* q_out, void* stream) {

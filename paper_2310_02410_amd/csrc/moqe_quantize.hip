@@ -1,6 +1,6 @@
 // Offline channel-wise absmax quantization and dense bit packing
-// (paper App. A "Linear quantization with absolute maximum", App. C fp16 scales),
-// plus the inverse of the packing for tests.
+// (paper App. A "Linear quantization with absolute maximum", App. C fp16 scales; also App. A's
+// "Log-scale quantization" as a second codec), plus the inverse of the packing for tests.
 #include "moqe_dev.h"
 #include "moqe_kernels.h"
 
@@ -36,11 +36,24 @@ __device__ inline int quantize_one(float w, double s, int lo, int hi) {
   return (int)r;
 }
 
-// s = 2 max|A_:,n| / (2^b - 1), stored fp16 rounded up.  A workgroup takes 256 neighbouring
+// Log-scale code of one weight (App. A): sign bit, then the exponent Q = ceil(log2(2T/3)) of
+// T = clip(|w|/s, 2^(1-2^(b-1)), 1) counted from its lowest value.  Q is the smallest integer
+// with |w| <= 1.5 * 2^Q * s; the right-hand side is exact in fp64 (s is an fp16 number), so
+// no quotient or logarithm is rounded.  The printed clip bounds are read as that interval.
+__device__ inline uint32_t log_code_one(float w, double s, int bits) {
+  if (!(s > 0.0)) return 0u;
+  const int half = 1 << (bits - 1), q_lo = 1 - half;
+  const double mag = fabs((double)w);
+  int expo = 0;
+  while (expo > q_lo && mag <= 1.5 * scalbn(s, expo - 1)) --expo;
+  return (uint32_t)((w < 0.0f ? half : 0) + (expo - q_lo));
+}
+
+// s = 2 max|A_:,n| / (2^b - 1) (log-scale codec: s = max|A_:,n|), stored fp16 rounded up.  A workgroup takes 256 neighbouring
 // channels of one expert: a lane owns 4 of them (16-byte loads, a wave reads 1 KiB per row), the
 // 4 waves split the K rows and keep 8 loads in flight each; the partial maxima meet in LDS.
 __global__ __launch_bounds__(256) void scale_kernel(const float* __restrict__ w, int64_t E, int K, int N, int bits,
-                                                     uint16_t* __restrict__ scales) {
+                                                     int codec, uint16_t* __restrict__ scales) {
   __shared__ float4_t s_max[4][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nblocks = (N + 255) / 256;
@@ -86,6 +99,13 @@ __global__ __launch_bounds__(256) void scale_kernel(const float* __restrict__ w,
       out[0] = out[1] = out[2] = out[3] = 0x3C00;
       return;
     }
+    if (codec == MOQE_CODEC_LOG) {
+      out[0] = half_bits_round_up((double)m.x);
+      out[1] = half_bits_round_up((double)m.y);
+      out[2] = half_bits_round_up((double)m.z);
+      out[3] = half_bits_round_up((double)m.w);
+      return;
+    }
     const double den = (double)((1 << bits) - 1);
     out[0] = half_bits_round_up((2.0 * (double)m.x) / den);
     out[1] = half_bits_round_up((2.0 * (double)m.y) / den);
@@ -114,7 +134,7 @@ __global__ __launch_bounds__(256) void tensor_scale_kernel(uint16_t* __restrict_
 
 // One thread per packed 32-bit word.
 __global__ __launch_bounds__(256) void pack_kernel(const float* __restrict__ w, const uint16_t* __restrict__ scales,
-                                                    PackGeom g, int64_t E, uint32_t* __restrict__ codes) {
+                                                    PackGeom g, int codec, int64_t E, uint32_t* __restrict__ codes) {
   const int64_t words_per_matrix = g.matrix_bytes / 4;
   int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= E * words_per_matrix) return;
@@ -152,6 +172,8 @@ __global__ __launch_bounds__(256) void pack_kernel(const float* __restrict__ w, 
     uint32_t u;
     if (g.bits == 16) {
       u = half_to_bits((half_t)wm[(int64_t)k * g.N + n]);  // one rounding, to nearest even
+    } else if (codec == MOQE_CODEC_LOG) {
+      u = log_code_one(wm[(int64_t)k * g.N + n], s, g.bits);
     } else {
       u = (uint32_t)(quantize_one(wm[(int64_t)k * g.N + n], s, lo, hi) + z);
     }
@@ -160,22 +182,14 @@ __global__ __launch_bounds__(256) void pack_kernel(const float* __restrict__ w, 
   codes[idx] = val;
 }
 
-// One thread per code: packed layout -> int8 [E,K,N].
-__global__ __launch_bounds__(256) void unpack_kernel(const uint32_t* __restrict__ codes, PackGeom g, int64_t E,
-                                                      int8_t* __restrict__ q_out) {
-  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t per_matrix = (int64_t)g.K * g.N;
-  if (idx >= E * per_matrix) return;
-  int64_t e = idx / per_matrix;
-  int64_t rem = idx % per_matrix;
-  int k = (int)(rem / g.N), n = (int)(rem % g.N);
+// The stored field u of code (k, n) of matrix e.
+__device__ inline uint32_t stored_field(const uint32_t* __restrict__ codes, const PackGeom& g, int64_t e, int k, int n) {
   int c = n / 16, j = n % 16;
   int s = k / 32, grp = (k % 32) / 8, i = k % 8;
   int slot = 16 * grp + j;
   int p = s / g.SC, s1 = s % g.SC;
   int m = 8 * s1 + i;
   const uint32_t* base = codes + e * (g.matrix_bytes / 4) + (int64_t)(c * g.Q + p) * (g.chunk_bytes / 4);
-  const int z = 1 << (g.bits - 1);
   uint32_t u;
   if (g.bits != 3) {
     int per = 32 / g.bits;
@@ -190,20 +204,52 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint32_t* __restrict_
     uint32_t hd = base[64 * (g.lo_lane_bytes / 4) + slot * (g.hi_lane_bytes / 4) + hword];
     u |= ((hd >> (16 * (ht & 1) + (ht >> 1))) & 1u) << 2;
   }
-  q_out[idx] = (int8_t)((int)u - z);
+  return u;
+}
+
+// One thread per code: packed layout -> int8 [E,K,N].
+__global__ __launch_bounds__(256) void unpack_kernel(const uint32_t* __restrict__ codes, PackGeom g, int64_t E,
+                                                      int8_t* __restrict__ q_out) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t per_matrix = (int64_t)g.K * g.N;
+  if (idx >= E * per_matrix) return;
+  int64_t e = idx / per_matrix;
+  int64_t rem = idx % per_matrix;
+  const uint32_t u = stored_field(codes, g, e, (int)(rem / g.N), (int)(rem % g.N));
+  q_out[idx] = (int8_t)((int)u - (1 << (g.bits - 1)));
+}
+
+// One thread per code: A' = P s 2^Q of a log-scale code as fp32, by adding Q to the exponent
+// field of s (an fp16 number is a normal fp32 number, and Q >= -7 keeps it one) and setting
+// the sign bit.  s = 0 stays 0.
+__global__ __launch_bounds__(256) void dequantize_log_kernel(const uint32_t* __restrict__ codes,
+                                                              const uint16_t* __restrict__ scales, PackGeom g,
+                                                              int64_t E, float* __restrict__ w_out) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t per_matrix = (int64_t)g.K * g.N;
+  if (idx >= E * per_matrix) return;
+  int64_t e = idx / per_matrix;
+  int64_t rem = idx % per_matrix;
+  const int n = (int)(rem % g.N);
+  const uint32_t u = stored_field(codes, g, e, (int)(rem / g.N), n);
+  const int half = 1 << (g.bits - 1);
+  const int expo = (int)(u & (uint32_t)(half - 1)) + 1 - half;  // Q <= 0
+  uint32_t v = __builtin_bit_cast(uint32_t, (float)half_from_bits(scales[e * g.N + n]));
+  if (v != 0u) v = (v - ((uint32_t)(-expo) << 23)) | ((u & (uint32_t)half) ? 0x80000000u : 0u);
+  w_out[idx] = __builtin_bit_cast(float, v);
 }
 
 }  // namespace
 
 hipError_t moqe_launch_quantize(const float* w, int64_t E, const PackGeom& g, void* codes, uint16_t* scales,
-                                bool tensor_scale, hipStream_t stream) {
+                                bool tensor_scale, int codec, hipStream_t stream) {
   const int64_t blocks = E * ((g.N + 255) / 256);
-  hipLaunchKernelGGL(scale_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, w, E, g.K, g.N, g.bits, scales);
+  hipLaunchKernelGGL(scale_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, w, E, g.K, g.N, g.bits, codec, scales);
   if (tensor_scale && g.bits != 16)
     hipLaunchKernelGGL(tensor_scale_kernel, dim3((unsigned)E), dim3(256), 0, stream, scales, g.N);
   int64_t words = E * (g.matrix_bytes / 4);
-  hipLaunchKernelGGL(pack_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, stream, w, scales, g, E,
-                     (uint32_t*)codes);
+  hipLaunchKernelGGL(pack_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, stream, w, scales, g, codec,
+                     E, (uint32_t*)codes);
   return hipGetLastError();
 }
 
@@ -211,5 +257,13 @@ hipError_t moqe_launch_unpack(const void* codes, int64_t E, const PackGeom& g, i
   int64_t n = E * (int64_t)g.K * g.N;
   hipLaunchKernelGGL(unpack_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, (const uint32_t*)codes, g,
                      E, q_out);
+  return hipGetLastError();
+}
+
+hipError_t moqe_launch_dequantize_log(const void* codes, const uint16_t* scales, int64_t E, const PackGeom& g,
+                                      float* w_out, hipStream_t stream) {
+  int64_t n = E * (int64_t)g.K * g.N;
+  hipLaunchKernelGGL(dequantize_log_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream,
+                     (const uint32_t*)codes, scales, g, E, w_out);
   return hipGetLastError();
 }

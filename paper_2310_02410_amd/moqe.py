@@ -26,7 +26,7 @@ EXPORTS = (
     "moqe_ffn_workspace_bytes", "moqe_quantize", "moqe_unpack", "moqe_route",
     "moqe_route_logits", "moqe_expert_ffn", "moqe_expert_ffn1", "moqe_expert_ffn2",
     "moqe_layer_workspace_bytes", "moqe_moe_layer", "moqe_set_launch_mode",
-    "moqe_set_prefill_policy", "moqe_quantize_tensor_scale",
+    "moqe_set_prefill_policy", "moqe_quantize_tensor_scale", "moqe_quantize_log", "moqe_dequantize_log",
 )
 
 LAUNCH_AUTO, LAUNCH_SEPARATE, LAUNCH_FUSED = 0, 1, 2
@@ -89,6 +89,10 @@ def lib() -> ctypes.CDLL:
     L.moqe_quantize.argtypes = [vp, i64, i64, i64, ci, vp, vp, vp]
     L.moqe_quantize_tensor_scale.restype = ci
     L.moqe_quantize_tensor_scale.argtypes = [vp, i64, i64, i64, ci, vp, vp, vp]
+    L.moqe_quantize_log.restype = ci
+    L.moqe_quantize_log.argtypes = [vp, i64, i64, i64, ci, vp, vp, vp]
+    L.moqe_dequantize_log.restype = ci
+    L.moqe_dequantize_log.argtypes = [vp, vp, i64, i64, i64, ci, vp, vp]
     L.moqe_unpack.restype = ci
     L.moqe_unpack.argtypes = [vp, i64, i64, i64, ci, vp, vp]
     L.moqe_route.restype = ci
@@ -190,6 +194,31 @@ def moqe_quantize(w: torch.Tensor, bits: int, stream=None, tensor_scale: bool = 
     fn = lib().moqe_quantize_tensor_scale if tensor_scale else lib().moqe_quantize
     _check(fn(w.data_ptr(), E, K, N, bits, codes.data_ptr(), scales.data_ptr(), _stream(stream)), "moqe_quantize")
     return codes, scales
+
+
+def moqe_quantize_log(w: torch.Tensor, bits: int, stream=None):
+    """Log-scale codec: w fp32 [E,K,N] -> (codes uint8 [E, K*N*bits/8], scales fp16 [E,N]); bits 2, 3 or 4."""
+    _dev(w, torch.float32, "w")
+    E, K, N = w.shape
+    nbytes = moqe_packed_bytes(bits, K, N)
+    if nbytes == 0:
+        _check(lib().moqe_check_matrix(bits, K, N) or 3, "moqe_quantize_log")
+    codes = torch.empty((E, nbytes), dtype=torch.uint8, device=w.device)
+    scales = torch.empty((E, N), dtype=torch.float16, device=w.device)
+    _check(lib().moqe_quantize_log(w.data_ptr(), E, K, N, bits, codes.data_ptr(), scales.data_ptr(), _stream(stream)),
+           "moqe_quantize_log")
+    return codes, scales
+
+
+def moqe_dequantize_log(codes: torch.Tensor, scales: torch.Tensor, bits: int, K: int, N: int, stream=None) -> torch.Tensor:
+    """Log-scale codes -> fp32 [E,K,N], A' = P s 2^Q (exact)."""
+    _dev(codes, torch.uint8, "codes")
+    _dev(scales, torch.float16, "scales")
+    E = codes.shape[0]
+    w = torch.empty((E, K, N), dtype=torch.float32, device=codes.device)
+    _check(lib().moqe_dequantize_log(codes.data_ptr(), scales.data_ptr(), E, K, N, bits, w.data_ptr(), _stream(stream)),
+           "moqe_dequantize_log")
+    return w
 
 
 def moqe_unpack(codes: torch.Tensor, bits: int, K: int, N: int, stream=None) -> torch.Tensor:

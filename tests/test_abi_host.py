@@ -104,6 +104,15 @@ def test_quantize_error_paths():
     assert L.moqe_unpack(P, 1, 64, 16, 16, P, None) == 2       # fp16 weights are not int8 codes
     assert L.moqe_quantize_tensor_scale(P, 1, 64, 16, 7, P, P, None) == 2
     assert L.moqe_unpack(P, 1, 64, 20, 4, P, None) == 3
+    # log-scale codec: 2, 3 or 4 bits only
+    assert L.moqe_quantize_log(P, 1, 64, 16, 8, P, P, None) == 2
+    assert L.moqe_quantize_log(P, 1, 64, 16, 16, P, P, None) == 2
+    assert L.moqe_quantize_log(0, 1, 64, 16, 4, P, P, None) == 1
+    assert L.moqe_quantize_log(P, 1, 48, 16, 4, P, P, None) == 3
+    assert L.moqe_dequantize_log(P, P, 1, 64, 16, 8, P, None) == 2
+    assert L.moqe_dequantize_log(P, 0, 1, 64, 16, 4, P, None) == 1
+    assert L.moqe_dequantize_log(P, P, 1, 64, 24, 4, P, None) == 3
+    assert L.moqe_dequantize_log(P, P, 1, 64, 16, 4, P + 4, None) == 4
 
 
 def test_route_error_paths():

@@ -113,3 +113,36 @@ def test_tensor_wise_scale(bits):
     ref = O.expert_ffn(x, idx, gate, O.dequantize(q1, t1), layer["b1"], O.dequantize(q2, t2), layer["b2"])
     err = np.abs(y.astype(np.float64) - ref).max() / np.abs(ref).max()
     assert err <= 2e-3, err
+
+
+@pytest.mark.parametrize("bits,K,N", [(4, 32, 16), (4, 256, 64), (4, 1024, 48), (3, 128, 16), (3, 768, 48),
+                                      (2, 64, 16), (2, 1024, 32)])
+def test_log_scale_codec(bits, K, N):
+    """moqe_quantize_log / moqe_dequantize_log (App. A "Log-scale quantization"): packed codes
+    and scale bit patterns identical to the oracle's, dequantized values equal to P s 2^Q exactly."""
+    w = _weights(3, K, N, 3 * K + N + bits)
+    w[0, :, 0] = 0.0                                   # all-zero channel: s = 0, field 0
+    w[0, 3, 1] = 0.0                                   # a zero weight: smallest magnitude, plus sign
+    w[0, 4, 1] = -0.0
+    top = np.abs(w[1, :, 2]).max()
+    w[1, 0, 2], w[1, 1, 2], w[1, 2, 2] = 1.0, 0.75, -0.375   # channel maximum 1: s = 1; values on the breaks
+    w[1, 3:, 2] *= np.float32(0.5 / max(top, 1e-6))
+    w[2, :, 3] = np.float32(2.0 ** -20)                # scale in fp16's subnormal range
+    codes, scales = moqe.moqe_quantize_log(dev(w), bits)
+    q_ref, s_ref = O.quantize_log(w, bits)
+    torch.cuda.synchronize()
+    assert np.array_equal(scales.cpu().numpy().view(np.uint16), s_ref.view(np.uint16)), "scales differ"
+    assert np.array_equal(codes.cpu().numpy(), O.pack(q_ref, bits)), "packed bytes differ"
+    assert np.array_equal(moqe.moqe_unpack(codes, bits, K, N).cpu().numpy(), q_ref)
+    d = moqe.moqe_dequantize_log(codes, scales, bits, K, N).cpu().numpy()
+    assert np.array_equal(d.astype(np.float64), O.dequantize_log(q_ref, s_ref, bits)), "dequantized values differ"
+
+
+def test_log_scale_codec_full_size_expert():
+    wl = W.small("q", E=2, d=1024, f=4096, seed=2)
+    w = W.make_layer(wl)["w1"]
+    for bits in (4, 3, 2):
+        codes, scales = moqe.moqe_quantize_log(dev(w), bits)
+        q_ref, s_ref = O.quantize_log(w, bits)
+        assert np.array_equal(scales.cpu().numpy().view(np.uint16), s_ref.view(np.uint16))
+        assert np.array_equal(codes.cpu().numpy(), O.pack(q_ref, bits))
