@@ -73,7 +73,7 @@ typedef enum {
 const char* moqe_status_string(int status);
 /* Message of the last HIP error seen by this thread's calls; static storage. */
 const char* moqe_last_hip_error(void);
-/* ABI version, currently 1. */
+/* ABI version, currently 2 (1: moqe_layer without its codec field). */
 int moqe_version(void);
 
 /* How moqe_expert_ffn and moqe_moe_layer issue their work (a process-wide setting, for
@@ -154,6 +154,10 @@ moqe_status moqe_quantize(const float* w, int64_t E, int64_t K, int64_t N, int b
 moqe_status moqe_quantize_tensor_scale(const float* w, int64_t E, int64_t K, int64_t N, int bits,
                                        void* codes_out, moqe_f16* scales_out, void* stream);
 
+/* Codec of a layer's expert weights: the linear absmax codes of moqe_quantize, or the
+ * log-scale codes of moqe_quantize_log. */
+enum { MOQE_CODEC_LINEAR = 0, MOQE_CODEC_LOG = 1 };
+
 /* The codec App. A describes beside the linear one and the paper sets aside ("Log-scale
  * quantization"): one sign bit and a (bits-1)-bit exponent per weight,
  *   P = sign(A),  T = clip(|A| / s, 2^(1 - 2^(bits-1)), 1),  Q = ceil(log2(2T/3)),  A' = P s 2^Q
@@ -165,8 +169,12 @@ moqe_status moqe_quantize_tensor_scale(const float* w, int64_t E, int64_t K, int
  * in the same packed layout as the linear codes (moqe_unpack returns u - 2^(bits-1)).  A zero
  * weight takes the smallest magnitude with a plus sign (the format has no zero); a channel of
  * zeros has s = 0.  bits must be 2, 3 or 4 (MOQE_ERR_BITS otherwise); other arguments, layouts
- * and errors as for moqe_quantize.  This codec stops at the storage format: the expert FFN
- * calls take linear codes only. */
+ * and errors as for moqe_quantize.  The expert FFN calls take a layer of such codes at 4 bits
+ * (moqe_layer.codec = MOQE_CODEC_LOG; the weights unpack to +-2^Q by exponent insert, the scale
+ * multiplies the finished sum as for linear codes); every segment then goes through the
+ * dequantize-in-register kernel, whatever the batch size.  Other widths stop at the storage
+ * format.  A layer's codec field set to MOQE_CODEC_LOG with bits != 4, or to any other
+ * value, is MOQE_ERR_BITS. */
 moqe_status moqe_quantize_log(const float* w, int64_t E, int64_t K, int64_t N, int bits,
                               void* codes_out, moqe_f16* scales_out, void* stream);
 /* Dequantization of log-scale codes, A' = P s 2^Q, written as fp32 [E,K,N] (every value is
@@ -212,6 +220,7 @@ typedef struct {
   const void* codes2;
   const moqe_f16* scales2;
   const moqe_f16* bias2;
+  int codec; /* MOQE_CODEC_LINEAR (0), or MOQE_CODEC_LOG with bits = 4: codes from moqe_quantize_log */
 } moqe_layer;
 
 /*

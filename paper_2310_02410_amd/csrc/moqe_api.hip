@@ -70,7 +70,7 @@ const char* moqe_status_string(int status) {
 
 const char* moqe_last_hip_error(void) { return g_hip_error; }
 
-int moqe_version(void) { return 1; }
+int moqe_version(void) { return 2; }
 
 int moqe_set_prefill_policy(int min_segment_tokens, int min_batch_tokens, int all_tiled_tokens_per_expert) {
   if (min_segment_tokens < 1 || min_batch_tokens < 1 || all_tiled_tokens_per_expert < 1) return -1;
@@ -231,6 +231,7 @@ static moqe_status check_layer_ptrs(const moqe_layer* L) {
   if (!L) return MOQE_ERR_NULL;
   if (!L->codes1 || !L->scales1 || !L->bias1 || !L->codes2 || !L->scales2 || !L->bias2) return MOQE_ERR_NULL;
   if (!valid_bits(L->bits)) return MOQE_ERR_BITS;
+  if (L->codec != MOQE_CODEC_LINEAR && !(L->codec == MOQE_CODEC_LOG && L->bits == 4)) return MOQE_ERR_BITS;
   int st = moqe_check_layer(L->bits, L->E, L->d, L->f);
   if (st != MOQE_OK) return (moqe_status)st;
   if (!aligned16(L->codes1) || !aligned16(L->scales1) || !aligned16(L->bias1) || !aligned16(L->codes2) ||
@@ -243,7 +244,7 @@ static moqe_status check_layer_ptrs(const moqe_layer* L) {
 static void base_args(DecodeArgs* a, const moqe_layer* L, int64_t T, const int32_t* expert_idx, const float* gate,
                       const int32_t* seg_offsets, const int32_t* perm) {
   memset(a, 0, sizeof(*a));
-  a->bits = L->bits;
+  a->bits = L->codec == MOQE_CODEC_LOG ? MOQE_LOG4 : L->bits;  // what the kernels are instantiated on
   a->E = (int)L->E;
   a->T = (int)T;
   a->expert_idx = (int*)expert_idx;

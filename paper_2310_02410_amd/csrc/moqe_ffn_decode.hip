@@ -420,7 +420,7 @@ __global__ __launch_bounds__(WG_THREADS, min_waves(BITS, KSTEPS)) void moe_decod
       scales = (const half_t*)p.scales + (int64_t)m.e * N;
       bias = (const half_t*)p.bias + (int64_t)m.e * N;
       const int Q = K / (32 * S::SC);  // chunks per column tile
-      const int64_t matrix_words = (int64_t)K * N * BITS / 32;
+      const int64_t matrix_words = (int64_t)K * N * moqe_field_bits(BITS) / 32;
       m.cp = p.codes + (int64_t)m.e * matrix_words + ((int64_t)m.col * Q + ks * S::NCH) * S::CHUNK_WORDS;
     }
     // issued whether or not the unit exists (an empty descriptor loads nothing)
@@ -535,16 +535,19 @@ __global__ __launch_bounds__(WG_THREADS, min_waves(BITS, KSTEPS)) void moe_decod
       // lane (grp, j) reads row j, k = 32 s + 8 grp .. +7 of this wave's slice
       afrag = j < rows_valid ? &patch[j][grp] : &s_x[ZERO_ROW][grp];
       // bias + zero point carried by the unpacked values, summed against the rows
-      float4_t c0 = {0, 0, 0, 0}, c1 = {0, 0, 0, 0};
+      // (log-scale codes unpack to their exact values: nothing to remove)
+      if constexpr (BITS != MOQE_LOG4) {
+        float4_t c0 = {0, 0, 0, 0}, c1 = {0, 0, 0, 0};
 #pragma unroll
-      for (int s = 0; s < KSTEPS; s += 2) {
-        c0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, afrag[4 * s]), bias_frag<BITS>(0), c0,
-                                                    0, 0, 0);
-        if (s + 1 < KSTEPS)
-          c1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, afrag[4 * s + 4]), bias_frag<BITS>(1),
-                                                      c1, 0, 0, 0);
+        for (int s = 0; s < KSTEPS; s += 2) {
+          c0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, afrag[4 * s]), bias_frag<BITS>(0), c0,
+                                                      0, 0, 0);
+          if (s + 1 < KSTEPS)
+            c1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, afrag[4 * s + 4]),
+                                                        bias_frag<BITS>(1), c1, 0, 0, 0);
+        }
+        corr = c0 + c1;
       }
-      corr = c0 + c1;
     };
 
     // Consumes the unit in `b` chunk by chunk; as soon as a chunk's words are unpacked the
@@ -575,6 +578,8 @@ __global__ __launch_bounds__(WG_THREADS, min_waves(BITS, KSTEPS)) void moe_decod
               w = unpack8(b.lo[ch * S::LW + 2 * s1], b.lo[ch * S::LW + 2 * s1 + 1], uc);
             } else if constexpr (BITS == 4) {
               w = unpack4(b.lo[ch * S::LW + s1], uc);
+            } else if constexpr (BITS == MOQE_LOG4) {
+              w = unpack4_log(b.lo[ch * S::LW + s1], uc);
             } else {
               const uint32_t d = b.lo[ch * S::LW + (s1 >> 1)];
               w = (s1 & 1) ? unpack2<1>(d, uc) : unpack2<0>(d, uc);
@@ -797,6 +802,7 @@ hipError_t moqe_launch_decode(const DecodeArgs& a, int num_cus, hipStream_t stre
   switch (a.bits) {
     case 8: return launch_bits<8>(a, num_cus, stream);
     case 4: return launch_bits<4>(a, num_cus, stream);
+    case MOQE_LOG4: return launch_bits<MOQE_LOG4>(a, num_cus, stream);
     case 3: return launch_bits<3>(a, num_cus, stream);
     case 2: return launch_bits<2>(a, num_cus, stream);
     default: return hipErrorInvalidValue;

@@ -6,11 +6,11 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include "moqe.h"
 #include "moqe_dev.h"
 
 // tensor_scale: one scale per matrix (the largest channel scale) instead of one per channel
-// codec: linear absmax codes, or the log-scale codes of App. A (sign bit + exponent)
-enum { MOQE_CODEC_LINEAR = 0, MOQE_CODEC_LOG = 1 };
+// codec: MOQE_CODEC_LINEAR or MOQE_CODEC_LOG of moqe.h
 hipError_t moqe_launch_quantize(const float* w, int64_t E, const PackGeom& g, void* codes, uint16_t* scales,
                                 bool tensor_scale, int codec, hipStream_t stream);
 hipError_t moqe_launch_dequantize_log(const void* codes, const uint16_t* scales, int64_t E, const PackGeom& g,

@@ -37,8 +37,17 @@ struct UnpackConsts {
   uint32_t m_0030, m_00c0, m_0300;          // 2-bit field masks at bits 4, 6, 8
   uint32_t m_0040, m_0080, m_0100, m_0200;  // single-bit masks at bits 6..9 (int3 high plane)
   uint32_t x1024, x64, x32, x16, x8, x4;    // exponent patterns
+  uint32_t l_e0, l_e1, l_e2, l_e3, l_s0, l_s1, l_s2, l_s3, l_one;  // log-scale codes: exponent / sign masks
   __device__ inline void init() {
     if (BITS == 16) return;  // fp16 weights need no unpacking
+    if (BITS == MOQE_LOG4) {
+      l_e0 = opaque_sgpr(0x00070007u); l_s0 = opaque_sgpr(0x00080008u);
+      l_e1 = opaque_sgpr(0x00700070u); l_s1 = opaque_sgpr(0x00800080u);
+      l_e2 = opaque_sgpr(0x07000700u); l_s2 = opaque_sgpr(0x08000800u);
+      l_e3 = opaque_sgpr(0x1C001C00u); l_s3 = opaque_sgpr(0x80008000u);
+      l_one = opaque_vgpr(0x20002000u);
+      return;
+    }
     if (BITS == 8) {
       m_00ff = opaque_sgpr(0x00FF00FFu);
       x1024 = opaque_vgpr(0x64006400u);
@@ -77,6 +86,20 @@ __device__ inline half8_t unpack4(uint32_t d, const C& c) {
   uint32_t r1 = (d & c.m_00f0) | c.x64;
   uint32_t r2 = pk_sub((d8 & c.m_000f) | c.x1024, 1032.0f);
   uint32_t r3 = (d8 & c.m_00f0) | c.x64;
+  return frag_from_words(r0, r1, r2, r3);
+}
+
+// ---- 4-bit log-scale codes (App. A: A' = P s 2^Q): same nibble positions as int4; a nibble
+// holds the exponent e = Q + 7 in its low three bits and the sign in its top bit.  The fp16
+// number +-2^Q has exponent field e + 8 and no mantissa: the three bits go to bits 10..12,
+// 0x2000 adds the 8, the sign bit goes to bit 15.  No multiply, and nothing to correct after
+// the K-sum (the value is exact; the format has no zero point).
+template <class C>
+__device__ inline half8_t unpack4_log(uint32_t d, const C& c) {
+  uint32_t r0 = (((d & c.l_e0) << 10) | c.l_one) | ((d & c.l_s0) << 12);
+  uint32_t r1 = (((d & c.l_e1) << 6) | c.l_one) | ((d & c.l_s1) << 8);
+  uint32_t r2 = (((d & c.l_e2) << 2) | c.l_one) | ((d & c.l_s2) << 4);
+  uint32_t r3 = (((d >> 2) & c.l_e3) | c.l_one) | (d & c.l_s3);
   return frag_from_words(r0, r1, r2, r3);
 }
 
@@ -207,13 +230,14 @@ __device__ inline half8_t bias_frag(int parity) {
 
 template <int BITS, int KSTEPS>
 struct Shape {
-  static constexpr int SCMAX = BITS == 8 ? 2 : BITS == 4 ? 4 : 8;
+  static constexpr int FB = moqe_field_bits(BITS);  // stored bits per code
+  static constexpr int SCMAX = FB == 8 ? 2 : FB == 4 ? 4 : 8;
   static constexpr int SC = KSTEPS < SCMAX ? KSTEPS : SCMAX;  // steps per chunk
   static constexpr int NCH = KSTEPS / SC;                     // chunks per wave slice
-  static constexpr int LO_BITS = BITS == 3 ? 2 : BITS;
+  static constexpr int LO_BITS = FB == 3 ? 2 : FB;
   static constexpr int LW = SC * LO_BITS / 4;                 // main-plane words per lane per chunk
   static constexpr int HW = BITS == 3 ? SC / 4 : 0;           // 1-bit-plane words per lane per chunk
-  static constexpr int CHUNK_WORDS = 16 * SC * BITS;          // 64 * SC * BITS / 4
+  static constexpr int CHUNK_WORDS = 16 * SC * FB;            // 64 * SC * FB / 4
   static_assert(KSTEPS % SC == 0, "slice must hold whole chunks");
   static_assert(LW >= 1, "lane owns at least a word");
   static_assert(BITS != 3 || HW >= 1, "int3 needs 4 steps per chunk");

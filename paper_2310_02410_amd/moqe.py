@@ -30,6 +30,7 @@ EXPORTS = (
 )
 
 LAUNCH_AUTO, LAUNCH_SEPARATE, LAUNCH_FUSED = 0, 1, 2
+CODEC_LINEAR, CODEC_LOG = 0, 1
 
 
 class MoqeError(RuntimeError):
@@ -45,7 +46,8 @@ class CLayer(ctypes.Structure):
     """moqe_layer of include/moqe.h."""
     _fields_ = [("bits", ctypes.c_int), ("E", ctypes.c_int64), ("d", ctypes.c_int64), ("f", ctypes.c_int64),
                 ("codes1", ctypes.c_void_p), ("scales1", ctypes.c_void_p), ("bias1", ctypes.c_void_p),
-                ("codes2", ctypes.c_void_p), ("scales2", ctypes.c_void_p), ("bias2", ctypes.c_void_p)]
+                ("codes2", ctypes.c_void_p), ("scales2", ctypes.c_void_p), ("bias2", ctypes.c_void_p),
+                ("codec", ctypes.c_int)]
 
 
 _lib = None
@@ -287,25 +289,27 @@ class QuantLayer:
     scales2: torch.Tensor
     bias2: torch.Tensor
     w_gate: torch.Tensor = None
+    codec: int = CODEC_LINEAR
 
     def c_struct(self) -> CLayer:
         return CLayer(self.bits, self.E, self.d, self.f, self.codes1.data_ptr(), self.scales1.data_ptr(),
                       self.bias1.data_ptr(), self.codes2.data_ptr(), self.scales2.data_ptr(),
-                      self.bias2.data_ptr())
+                      self.bias2.data_ptr(), self.codec)
 
     def code_bytes(self) -> int:
         return self.codes1.numel() + self.codes2.numel()
 
 
 def quantize_layer(w1: torch.Tensor, b1: torch.Tensor, w2: torch.Tensor, b2: torch.Tensor, bits: int,
-                   w_gate: torch.Tensor = None) -> QuantLayer:
+                   w_gate: torch.Tensor = None, codec: int = CODEC_LINEAR) -> QuantLayer:
     """Quantize fp32 w1 [E,d,f], w2 [E,f,d] on the device; biases fp16 [E,f], [E,d]."""
     E, d, f = w1.shape
     _check(lib().moqe_check_layer(bits, E, d, f), "quantize_layer")
-    c1, s1 = moqe_quantize(w1, bits)
-    c2, s2 = moqe_quantize(w2, bits)
+    quant = moqe_quantize_log if codec == CODEC_LOG else moqe_quantize
+    c1, s1 = quant(w1, bits)
+    c2, s2 = quant(w2, bits)
     return QuantLayer(bits, E, d, f, c1, s1, _dev(b1, torch.float16, "b1"), c2, s2,
-                      _dev(b2, torch.float16, "b2"), w_gate)
+                      _dev(b2, torch.float16, "b2"), w_gate, codec)
 
 
 def moqe_expert_ffn(layer: QuantLayer, x: torch.Tensor, route: Route, residual: torch.Tensor = None,

@@ -32,7 +32,7 @@ def test_every_declared_symbol_is_exported():
 
 def test_version_and_strings():
     L = moqe.lib()
-    assert L.moqe_version() == 1
+    assert L.moqe_version() == 2
     assert L.moqe_set_prefill_policy(0, 65, 16) == -1 and L.moqe_set_prefill_policy(5, 0, 16) == -1
     assert L.moqe_set_prefill_policy(5, 65, 0) == -1
     assert L.moqe_set_prefill_policy(moqe.PREFILL_MIN_SEGMENT_DEFAULT, moqe.PREFILL_MIN_BATCH_DEFAULT,
@@ -135,7 +135,7 @@ def test_expert_ffn_error_paths():
     L = moqe.lib()
 
     def layer(**kw):
-        base = dict(bits=4, E=4, d=64, f=256, codes1=P, scales1=P, bias1=P, codes2=P, scales2=P, bias2=P)
+        base = dict(bits=4, E=4, d=64, f=256, codes1=P, scales1=P, bias1=P, codes2=P, scales2=P, bias2=P, codec=0)
         base.update(kw)
         return moqe.CLayer(*[base[k] for k, _ in moqe.CLayer._fields_])
 
@@ -148,6 +148,8 @@ def test_expert_ffn_error_paths():
     assert call(layer(), x=0) == 1
     assert call(layer(), y=0) == 1
     assert call(layer(bits=5)) == 2
+    assert call(layer(codec=2)) == 2          # unknown codec
+    assert call(layer(codec=1, bits=2)) == 2  # log-scale layers run at 4 bits only
     assert call(layer(d=48)) == 3
     assert call(layer(E=0)) == 3
     assert call(layer(), T=-2) == 3

@@ -110,3 +110,50 @@ def test_fp16_experts_small(T):
 def test_fp16_experts_decode_config():
     """C1's layer with fp16 experts: the baseline row of the bit-width comparison."""
     _layer_parity(W.CONFIGS["c1"], 16)
+
+
+def _log_layer_parity(wl, residual=False, launch_mode=None):
+    """A layer of 4-bit log-scale codes (App. A: A' = P s 2^Q) through the FFN calls, against
+    the oracle's expert FFN on the oracle's log-dequantized weights."""
+    layer, x = W.make_layer(wl), W.make_tokens(wl)
+    ql = moqe.quantize_layer(dev(layer["w1"]), dev(layer["b1"]), dev(layer["w2"]), dev(layer["b2"]), 4,
+                             dev(layer["w_gate"]), codec=moqe.CODEC_LOG)
+    q1, s1 = O.quantize_log(layer["w1"], 4)
+    q2, s2 = O.quantize_log(layer["w2"], 4)
+    assert np.array_equal(ql.codes1.cpu().numpy(), O.pack(q1, 4)) and np.array_equal(ql.codes2.cpu().numpy(), O.pack(q2, 4))
+    xd = dev(x)
+    saved = moqe.moqe_set_launch_mode(launch_mode) if launch_mode is not None else None
+    try:
+        ws = moqe.alloc_workspace(moqe.moqe_layer_workspace_bytes(wl.T, wl.E, wl.d, wl.f), xd.device)
+        y, r = moqe.moqe_moe_layer(ql, xd, residual=xd if residual else None, workspace=ws)
+        torch.cuda.synchronize()
+        assert not moqe.workspace_error(ws)
+        r2 = moqe.moqe_route(xd, ql.w_gate)
+        y2 = moqe.moqe_expert_ffn(ql, xd, r2, residual=xd if residual else None)
+    finally:
+        if saved is not None:
+            moqe.moqe_set_launch_mode(saved)
+    idx, gate, offs, perm = route_to_numpy(r)
+    assert_route_equal((idx, gate, offs, perm), O.route(x, layer["w_gate"]), wl.T, wl.E)
+    ref = O.expert_ffn(x, idx, gate.astype(np.float64), O.dequantize_log(q1, s1, 4), layer["b1"],
+                       O.dequantize_log(q2, s2, 4), layer["b2"], residual=x if residual else None)
+    err = ffn_error(y.cpu().numpy(), ref)
+    assert err <= FFN_TOL, f"{wl.name} log4: max|err|/max|ref| = {err:.3e}"
+    assert np.array_equal(y.cpu().numpy().view(np.uint16), y2.cpu().numpy().view(np.uint16))
+
+
+@pytest.mark.parametrize("T", (1, 24, 37, 150))
+def test_log_scale_layer_small(T):
+    _log_layer_parity(W.small(T=T, seed=91 + T))
+
+
+def test_log_scale_layer_shapes_and_modes():
+    _log_layer_parity(W.small(E=4, d=512, f=2048, T=40, seed=95), residual=True)
+    _log_layer_parity(W.small(E=3, d=768, f=3072, T=21, seed=96))
+    _log_layer_parity(W.small(E=8, d=512, f=2048, T=24, seed=97), launch_mode=moqe.LAUNCH_FUSED)
+    # a batch that would take the tiled kernel with linear codes: log-scale codes stay on the decode kernel
+    _log_layer_parity(W.small(E=4, d=256, f=512, T=700, seed=98))
+
+
+def test_log_scale_layer_benchmark_shape():
+    _log_layer_parity(W.CONFIGS["c1"])
