@@ -87,14 +87,15 @@ __global__ __launch_bounds__(PF_THREADS, (PF_NT == 4 || BITS == 16) ? 2 : PF_WG_
   // A chunk here is what a wave fetches at a time for one column tile: one packed chunk (128
   // rows for int4, 256 for int2 / int3) or, where packed chunks are shorter (64 rows for int8,
   // 32 for unquantized fp16 weights, BITS = 16), the packed chunks of a staged block.
-  constexpr int SC = (BITS == 4 || BITS == 8 || BITS == 16) ? 4 : 8;  // steps of 32 rows per chunk
-  constexpr int PCH = BITS == 16 ? 4 : BITS == 8 ? 2 : 1;  // packed chunks per chunk
+  constexpr int FB = moqe_field_bits(BITS);   // stored bits per weight (4-bit log-scale codes: 4)
+  constexpr int SC = (FB == 4 || FB == 8 || FB == 16) ? 4 : 8;  // steps of 32 rows per chunk
+  constexpr int PCH = FB == 16 ? 4 : FB == 8 ? 2 : 1;  // packed chunks per chunk
   constexpr int SUB = SC / 4;                 // staged K blocks per chunk
-  constexpr int LO_BITS = BITS == 3 ? 2 : BITS;
+  constexpr int LO_BITS = FB == 3 ? 2 : FB;
   constexpr int LWC = (SC / PCH) * LO_BITS / 4;  // main-plane words per lane per packed chunk (4)
   constexpr int LW = LWC * PCH;               // ... per chunk
   constexpr int HW = BITS == 3 ? SC / 4 : 0;  // 1-bit-plane words per lane per chunk
-  constexpr int CHUNK_BYTES = 64 * SC * BITS;
+  constexpr int CHUNK_BYTES = 64 * SC * FB;
   constexpr int ROW_PIECES = PF_KB / 8;       // 16-byte pieces per staged row (256 bytes, no padding)
   constexpr int NBUF = 3;                     // staged blocks in LDS: one in use, two on their way
   constexpr int NLD = 4;                      // LDS-direct loads per wave and block (4 rows each)
@@ -146,7 +147,7 @@ __global__ __launch_bounds__(PF_THREADS, (PF_NT == 4 || BITS == 16) ? 2 : PF_WG_
   const int CT = N >> 4;
   const int Q = K / (32 * SC);   // packed chunks per column tile
   const int TB = Q * SUB;        // staged blocks per tile
-  const int64_t matrix_bytes = (int64_t)K * N * BITS / 8;
+  const int64_t matrix_bytes = (int64_t)K * N * FB / 8;
   const uint32_t lane_lo = (uint32_t)lane * LWC * 4, lane_hi = (64u * LWC + (uint32_t)lane * HW) * 4;
   UnpackConsts<BITS> uc;
   uc.init();
@@ -263,6 +264,8 @@ __global__ __launch_bounds__(PF_THREADS, (PF_NT == 4 || BITS == 16) ? 2 : PF_WG_
           w = unpack8_exact(b_lo[bbuf][ni][2 * s], b_lo[bbuf][ni][2 * s + 1], uc);
         } else if constexpr (BITS == 4) {
           w = unpack4_exact(b_lo[bbuf][ni][s], uc);
+        } else if constexpr (BITS == MOQE_LOG4) {
+          w = unpack4_log(b_lo[bbuf][ni][s], uc);
         } else if constexpr (BITS == 2) {
           const uint32_t d = b_lo[bbuf][ni][s >> 1];
           w = (s & 1) ? unpack2_exact<1>(d, uc) : unpack2_exact<0>(d, uc);
@@ -437,8 +440,9 @@ __global__ __launch_bounds__(PF_THREADS, (PF_NT == 4 || BITS == 16) ? 2 : PF_WG_
 }  // namespace
 
 bool moqe_prefill_supported(int bits, int64_t K, int64_t N) {
-  const int kc = (bits == 4 || bits == 8 || bits == 16) ? 128 : 256;
-  return (bits == 2 || bits == 3 || bits == 4 || bits == 8 || bits == 16) && K >= 256 && (K % kc) == 0 && N >= 16 && (N % 16) == 0;
+  const int fb = moqe_field_bits(bits);
+  const int kc = (fb == 4 || fb == 8 || fb == 16) ? 128 : 256;
+  return (fb == 2 || fb == 3 || fb == 4 || fb == 8 || fb == 16) && K >= 256 && (K % kc) == 0 && N >= 16 && (N % 16) == 0;
 }
 
 template <int BITS>
@@ -485,6 +489,7 @@ hipError_t moqe_launch_prefill(const PrefillArgs& a, int num_cus, hipStream_t st
     case 16: launch_bits<16>(a, pairs, num_cus, stream); break;
     case 8: launch_bits<8>(a, pairs, num_cus, stream); break;
     case 4: launch_bits<4>(a, pairs, num_cus, stream); break;
+    case MOQE_LOG4: launch_bits<MOQE_LOG4>(a, pairs, num_cus, stream); break;
     case 3: launch_bits<3>(a, pairs, num_cus, stream); break;
     case 2: launch_bits<2>(a, pairs, num_cus, stream); break;
     default: return hipErrorInvalidValue;

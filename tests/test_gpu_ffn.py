@@ -112,7 +112,7 @@ def test_fp16_experts_decode_config():
     _layer_parity(W.CONFIGS["c1"], 16)
 
 
-def _log_layer_parity(wl, residual=False, launch_mode=None):
+def _log_layer_parity(wl, residual=False, launch_mode=None, sample=None):
     """A layer of 4-bit log-scale codes (App. A: A' = P s 2^Q) through the FFN calls, against
     the oracle's expert FFN on the oracle's log-dequantized weights."""
     layer, x = W.make_layer(wl), W.make_tokens(wl)
@@ -135,11 +135,17 @@ def _log_layer_parity(wl, residual=False, launch_mode=None):
             moqe.moqe_set_launch_mode(saved)
     idx, gate, offs, perm = route_to_numpy(r)
     assert_route_equal((idx, gate, offs, perm), O.route(x, layer["w_gate"]), wl.T, wl.E)
+    assert np.array_equal(y.cpu().numpy().view(np.uint16), y2.cpu().numpy().view(np.uint16))
+    yh = y.cpu().numpy()
+    if sample is not None:  # a seeded sample of the rows plus every segment's first and last
+        rows = np.random.default_rng(wl.seed).choice(wl.T, size=sample, replace=False)
+        has = np.diff(offs) > 0
+        rows = np.concatenate([rows, perm[offs[:-1][has]], perm[offs[1:][has] - 1]])
+        x, idx, gate, yh = x[rows], idx[rows], gate[rows], yh[rows]
     ref = O.expert_ffn(x, idx, gate.astype(np.float64), O.dequantize_log(q1, s1, 4), layer["b1"],
                        O.dequantize_log(q2, s2, 4), layer["b2"], residual=x if residual else None)
-    err = ffn_error(y.cpu().numpy(), ref)
+    err = ffn_error(yh, ref)
     assert err <= FFN_TOL, f"{wl.name} log4: max|err|/max|ref| = {err:.3e}"
-    assert np.array_equal(y.cpu().numpy().view(np.uint16), y2.cpu().numpy().view(np.uint16))
 
 
 @pytest.mark.parametrize("T", (1, 24, 37, 150))
@@ -151,8 +157,11 @@ def test_log_scale_layer_shapes_and_modes():
     _log_layer_parity(W.small(E=4, d=512, f=2048, T=40, seed=95), residual=True)
     _log_layer_parity(W.small(E=3, d=768, f=3072, T=21, seed=96))
     _log_layer_parity(W.small(E=8, d=512, f=2048, T=24, seed=97), launch_mode=moqe.LAUNCH_FUSED)
-    # a batch that would take the tiled kernel with linear codes: log-scale codes stay on the decode kernel
+    # many tokens per expert: the tiled kernel (all three tile shapes over the two calls), then a
+    # Zipf load where the decode kernel takes the small segments beside it
     _log_layer_parity(W.small(E=4, d=256, f=512, T=700, seed=98))
+    _log_layer_parity(W.small(E=4, d=256, f=4096, T=8192, seed=99), sample=256)
+    _log_layer_parity(W.small(E=16, d=256, f=512, T=200, routing="zipf", n_empty=3, seed=85), residual=True)
 
 
 def test_log_scale_layer_benchmark_shape():
