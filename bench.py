@@ -53,6 +53,8 @@ def parse():
                              "n2_e128", "n2_dense"))
     ap.add_argument("--bits", type=int, default=None, choices=(2, 3, 4, 8, 16),
                     help="bit width of the headline line (default: the workload's own)")
+    ap.add_argument("--codec", default="linear", choices=("linear", "log"),
+                    help="log: 4-bit log-scale codes (App. A) instead of linear ones; needs --bits 4")
     ap.add_argument("--copies", type=int, default=None, help="independent layer copies cycled through "
                     "(default 8; 12 for the c4 stack: its 12 layers)")
     ap.add_argument("--other-bits", action="store_true", help="also time the other widths (fp16, 8, 4, 3, 2)")
@@ -79,8 +81,13 @@ def algorithmic_bytes(seg_offsets, bits, d, f, T, residual):
     return active, ffn1, ffn2
 
 
+LOG_CODEC = False  # set from --codec: the 4-bit codes are log-scale ones
+
+
 def wname(bits):
     """Weight format name of a bit width (16 = the unquantized baseline)."""
+    if LOG_CODEC and bits == 4:
+        return "log4"
     return "fp16" if bits == 16 else "int%d" % bits
 
 
@@ -111,6 +118,11 @@ def main():
     residual = wl.layers > 1               # the stack adds the layer's output to its input
     compute_bound = T >= 512               # the tiled MFMA kernel dominates, not the weight stream
     bits0 = args.bits if args.bits is not None else wl.bits[0]
+    global LOG_CODEC
+    LOG_CODEC = args.codec == "log"
+    if LOG_CODEC and bits0 != 4:
+        print("bench.py: --codec log needs --bits 4 (the expert FFN takes log-scale codes at 4 bits)", file=sys.stderr)
+        sys.exit(2)
     bit_list = [bits0] + ([b for b in (16, 8, 4, 3, 2) if b != bits0] if args.other_bits else [])
     copies = args.copies if args.copies is not None else (12 if wl.layers > 1 else 8)
     steps, warmup = args.steps, args.warmup
@@ -129,7 +141,8 @@ def main():
         w1, w2 = dev(host["w1"]), dev(host["w2"])
         b1, b2, wg = dev(host["b1"]), dev(host["b2"]), dev(host["w_gate"])
         for b in bit_list:
-            layers[b].append(moqe.quantize_layer(w1, b1, w2, b2, b, wg))
+            codec = moqe.CODEC_LOG if (LOG_CODEC and b == 4) else moqe.CODEC_LINEAR
+            layers[b].append(moqe.quantize_layer(w1, b1, w2, b2, b, wg, codec=codec))
         del w1, w2
         torch.cuda.synchronize()
         print(f"[bench] layer copy {i + 1}/{copies} ready ({time.time() - t0:.0f}s)", file=sys.stderr, flush=True)
@@ -210,6 +223,7 @@ def main():
         _, ev = time_steps(lambda i: g.replay(), reps, max(1, nwarm // copies))
         return ev / copies
 
+    kbits = lambda b: 104 if (LOG_CODEC and b == 4) else b  # the width the kernels are instantiated on
     results = {}
     for b in bit_list:
         qls = layers[b]
@@ -257,13 +271,13 @@ def main():
             res.update(bound="mfma", kernel_us=kern_us, kernel_work=flops, achieved=flops / (kern_us * 1e-6) / 1e12,
                        peak=MFMA_F16_PEAK_TFLOPS, unit="TFLOP/s",
                        kernel="moe_prefill_kernel<%d,*> (the launches of FFN1 and FFN2, each back to back, "
-                              "averaged)" % b)
+                              "averaged)" % kbits(b))
         else:
             kern_us = parts["ffn1_back_to_back_us"]
             res.update(bound="hbm", kernel_us=kern_us, kernel_work=ffn1_bytes,
                        achieved=ffn1_bytes / (kern_us * 1e-6) / 1e9, peak=HBM_PEAK_GBS, unit="GB/s",
                        kernel="moe_decode_kernel<%d,*,2> (FFN1; FFN2 is the same kernel on a matrix of the same "
-                              "size)" % b)
+                              "size)" % kbits(b))
         results[b] = res
         if b == 16 and not compute_bound:
             res["kernel"] = "moe_prefill_kernel<16,2> (FFN1; fp16 experts run on the tiled kernel at every batch size)"
@@ -288,6 +302,8 @@ def main():
             def __getitem__(self, e):
                 if bits0 == 16:
                     return O.unpack_fp16(self.codes[e], self.K, self.N).astype(np.float64)
+                if LOG_CODEC:
+                    return O.dequantize_log(O.unpack(self.codes[e], bits0, self.K, self.N), self.scales[e], bits0)
                 return O.dequantize(O.unpack(self.codes[e], bits0, self.K, self.N), self.scales[e])
 
         t = time.perf_counter()
@@ -308,7 +324,9 @@ def main():
         "dtype": "%s weights x f16 activations, f32 accumulate" % wname(bits0), "data": "synthetic",
         "config": {"workload": "%s: E=%d d_model=%d d_ff=%d T=%d top-1 (%s load), %s experts%s, seed %d, "
                                "%d layer copies cycled" % (wl.name, E, d, f, T, wl.routing,
-                                                           "unquantized fp16" if bits0 == 16 else "int%d per-channel RTN" % bits0,
+                                                           "unquantized fp16" if bits0 == 16 else
+                                                           "4-bit log-scale codes, per-channel absmax" if LOG_CODEC else
+                                                           "int%d per-channel RTN" % bits0,
                                                            ", fp16 residual add" if residual else "", wl.seed, copies),
                    "launch": "hip graph replay" if (r["graph_ms"] is not None and r["graph_ms"] <= r["eager_ms"]) else "eager",
                    "eager_ms_per_step": r["eager_ms"], "graph_ms_per_step": r["graph_ms"],
