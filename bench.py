@@ -54,7 +54,7 @@ def parse():
     ap.add_argument("--bits", type=int, default=None, choices=(2, 3, 4, 8, 16),
                     help="bit width of the headline line (default: the workload's own)")
     ap.add_argument("--codec", default="linear", choices=("linear", "log"),
-                    help="log: 4-bit log-scale codes (App. A) instead of linear ones; needs --bits 4")
+                    help="log: log-scale codes (App. A) instead of linear ones; needs --bits 2, 3 or 4")
     ap.add_argument("--copies", type=int, default=None, help="independent layer copies cycled through "
                     "(default 8; 12 for the c4 stack: its 12 layers)")
     ap.add_argument("--other-bits", action="store_true", help="also time the other widths (fp16, 8, 4, 3, 2)")
@@ -86,8 +86,8 @@ LOG_CODEC = False  # set from --codec: the 4-bit codes are log-scale ones
 
 def wname(bits):
     """Weight format name of a bit width (16 = the unquantized baseline)."""
-    if LOG_CODEC and bits == 4:
-        return "log4"
+    if LOG_CODEC and bits in (2, 3, 4):
+        return "log%d" % bits
     return "fp16" if bits == 16 else "int%d" % bits
 
 
@@ -120,8 +120,8 @@ def main():
     bits0 = args.bits if args.bits is not None else wl.bits[0]
     global LOG_CODEC
     LOG_CODEC = args.codec == "log"
-    if LOG_CODEC and bits0 != 4:
-        print("bench.py: --codec log needs --bits 4 (the expert FFN takes log-scale codes at 4 bits)", file=sys.stderr)
+    if LOG_CODEC and bits0 not in (2, 3, 4):
+        print("bench.py: --codec log needs --bits 2, 3 or 4", file=sys.stderr)
         sys.exit(2)
     bit_list = [bits0] + ([b for b in (16, 8, 4, 3, 2) if b != bits0] if args.other_bits else [])
     copies = args.copies if args.copies is not None else (12 if wl.layers > 1 else 8)
@@ -141,7 +141,7 @@ def main():
         w1, w2 = dev(host["w1"]), dev(host["w2"])
         b1, b2, wg = dev(host["b1"]), dev(host["b2"]), dev(host["w_gate"])
         for b in bit_list:
-            codec = moqe.CODEC_LOG if (LOG_CODEC and b == 4) else moqe.CODEC_LINEAR
+            codec = moqe.CODEC_LOG if (LOG_CODEC and b in (2, 3, 4)) else moqe.CODEC_LINEAR
             layers[b].append(moqe.quantize_layer(w1, b1, w2, b2, b, wg, codec=codec))
         del w1, w2
         torch.cuda.synchronize()
@@ -223,7 +223,7 @@ def main():
         _, ev = time_steps(lambda i: g.replay(), reps, max(1, nwarm // copies))
         return ev / copies
 
-    kbits = lambda b: 104 if (LOG_CODEC and b == 4) else b  # the width the kernels are instantiated on
+    kbits = lambda b: 100 + b if (LOG_CODEC and b in (2, 3, 4)) else b  # the width the kernels are instantiated on
     results = {}
     for b in bit_list:
         qls = layers[b]
@@ -325,7 +325,7 @@ def main():
         "config": {"workload": "%s: E=%d d_model=%d d_ff=%d T=%d top-1 (%s load), %s experts%s, seed %d, "
                                "%d layer copies cycled" % (wl.name, E, d, f, T, wl.routing,
                                                            "unquantized fp16" if bits0 == 16 else
-                                                           "4-bit log-scale codes, per-channel absmax" if LOG_CODEC else
+                                                           "%d-bit log-scale codes, per-channel absmax" % bits0 if LOG_CODEC else
                                                            "int%d per-channel RTN" % bits0,
                                                            ", fp16 residual add" if residual else "", wl.seed, copies),
                    "launch": "hip graph replay" if (r["graph_ms"] is not None and r["graph_ms"] <= r["eager_ms"]) else "eager",

@@ -169,11 +169,11 @@ enum { MOQE_CODEC_LINEAR = 0, MOQE_CODEC_LOG = 1 };
  * in the same packed layout as the linear codes (moqe_unpack returns u - 2^(bits-1)).  A zero
  * weight takes the smallest magnitude with a plus sign (the format has no zero); a channel of
  * zeros has s = 0.  bits must be 2, 3 or 4 (MOQE_ERR_BITS otherwise); other arguments, layouts
- * and errors as for moqe_quantize.  The expert FFN calls take a layer of such codes at 4 bits
+ * and errors as for moqe_quantize.  The expert FFN calls take a layer of such codes
  * (moqe_layer.codec = MOQE_CODEC_LOG; the weights unpack to +-2^Q by exponent insert in both
- * FFN kernels, the scale multiplies the finished sum as for linear codes).  Other widths stop
- * at the storage format.  A layer's codec field set to MOQE_CODEC_LOG with bits != 4, or to any other
- * value, is MOQE_ERR_BITS. */
+ * FFN kernels, the scale multiplies the finished sum as for linear codes).  A layer's codec
+ * field set to MOQE_CODEC_LOG with bits other than 2, 3 or 4, or to any other value, is
+ * MOQE_ERR_BITS. */
 moqe_status moqe_quantize_log(const float* w, int64_t E, int64_t K, int64_t N, int bits,
                               void* codes_out, moqe_f16* scales_out, void* stream);
 /* Dequantization of log-scale codes, A' = P s 2^Q, written as fp32 [E,K,N] (every value is
@@ -219,7 +219,7 @@ typedef struct {
   const void* codes2;
   const moqe_f16* scales2;
   const moqe_f16* bias2;
-  int codec; /* MOQE_CODEC_LINEAR (0), or MOQE_CODEC_LOG with bits = 4: codes from moqe_quantize_log */
+  int codec; /* MOQE_CODEC_LINEAR (0), or MOQE_CODEC_LOG (bits 2, 3 or 4): codes from moqe_quantize_log */
 } moqe_layer;
 
 /*

@@ -231,7 +231,7 @@ static moqe_status check_layer_ptrs(const moqe_layer* L) {
   if (!L) return MOQE_ERR_NULL;
   if (!L->codes1 || !L->scales1 || !L->bias1 || !L->codes2 || !L->scales2 || !L->bias2) return MOQE_ERR_NULL;
   if (!valid_bits(L->bits)) return MOQE_ERR_BITS;
-  if (L->codec != MOQE_CODEC_LINEAR && !(L->codec == MOQE_CODEC_LOG && L->bits == 4)) return MOQE_ERR_BITS;
+  if (L->codec != MOQE_CODEC_LINEAR && !(L->codec == MOQE_CODEC_LOG && L->bits >= 2 && L->bits <= 4)) return MOQE_ERR_BITS;
   int st = moqe_check_layer(L->bits, L->E, L->d, L->f);
   if (st != MOQE_OK) return (moqe_status)st;
   if (!aligned16(L->codes1) || !aligned16(L->scales1) || !aligned16(L->bias1) || !aligned16(L->codes2) ||
@@ -244,7 +244,7 @@ static moqe_status check_layer_ptrs(const moqe_layer* L) {
 static void base_args(DecodeArgs* a, const moqe_layer* L, int64_t T, const int32_t* expert_idx, const float* gate,
                       const int32_t* seg_offsets, const int32_t* perm) {
   memset(a, 0, sizeof(*a));
-  a->bits = L->codec == MOQE_CODEC_LOG ? MOQE_LOG4 : L->bits;  // what the kernels are instantiated on
+  a->bits = L->codec == MOQE_CODEC_LOG ? 100 + L->bits : L->bits;  // what the kernels are instantiated on (MOQE_LOG2..4)
   a->E = (int)L->E;
   a->T = (int)T;
   a->expert_idx = (int*)expert_idx;

@@ -28,10 +28,11 @@ struct PackGeom {
   int64_t matrix_bytes;
 };
 
-// What the kernels are instantiated on for 4-bit log-scale codes (App. A: sign bit + 3-bit
-// exponent): fields and layout are those of the linear 4-bit codes, only the unpack differs.
-constexpr int MOQE_LOG4 = 104;
-__host__ __device__ constexpr int moqe_field_bits(int bits) { return bits == MOQE_LOG4 ? 4 : bits; }
+// What the kernels are instantiated on for b-bit log-scale codes (App. A: sign bit + (b-1)-bit
+// exponent): fields and layout are those of the linear b-bit codes, only the unpack differs.
+constexpr int MOQE_LOG2 = 102, MOQE_LOG3 = 103, MOQE_LOG4 = 104;
+__host__ __device__ constexpr bool moqe_is_log(int bits) { return bits >= MOQE_LOG2 && bits <= MOQE_LOG4; }
+__host__ __device__ constexpr int moqe_field_bits(int bits) { return moqe_is_log(bits) ? bits - 100 : bits; }
 
 // (a slot owns at most 16 bytes of a chunk's main plane)
 __host__ __device__ inline int moqe_sc_max(int bits) { return bits == 16 ? 1 : bits == 8 ? 2 : bits == 4 ? 4 : 8; }

@@ -58,7 +58,7 @@ template <int BITS, int KSTEPS>
 struct UnitBuf {
   using S = Shape<BITS, KSTEPS>;
   uint32_t lo[S::NCH * S::LW];
-  uint32_t hi[BITS == 3 ? S::NCH * S::HW : 1];
+  uint32_t hi[S::FB == 3 ? S::NCH * S::HW : 1];
 };
 
 // What a wave needs to know about a unit besides its packed words (all wave-uniform
@@ -435,7 +435,7 @@ __global__ __launch_bounds__(WG_THREADS, min_waves(BITS, KSTEPS)) void moe_decod
   auto unit_rsrc = [&](const UnitMeta& m) -> rsrc_t { return make_rsrc(m.cp, m.active ? UNIT_BYTES : 0u); };
   auto issue_chunk = [&](Buf& b, rsrc_t r, int ch) {
     load_words<S::LW>(r, lane_lo + ch * S::CHUNK_WORDS * 4, &b.lo[ch * S::LW]);
-    if constexpr (BITS == 3) load_words<S::HW>(r, lane_hi + ch * S::CHUNK_WORDS * 4, &b.hi[ch * S::HW]);
+    if constexpr (S::FB == 3) load_words<S::HW>(r, lane_hi + ch * S::CHUNK_WORDS * 4, &b.hi[ch * S::HW]);
   };
   auto issue_unit = [&](Buf& b, const UnitMeta& m) {
     const rsrc_t r = unit_rsrc(m);
@@ -536,7 +536,7 @@ __global__ __launch_bounds__(WG_THREADS, min_waves(BITS, KSTEPS)) void moe_decod
       afrag = j < rows_valid ? &patch[j][grp] : &s_x[ZERO_ROW][grp];
       // bias + zero point carried by the unpacked values, summed against the rows
       // (log-scale codes unpack to their exact values: nothing to remove)
-      if constexpr (BITS != MOQE_LOG4) {
+      if constexpr (!moqe_is_log(BITS)) {
         float4_t c0 = {0, 0, 0, 0}, c1 = {0, 0, 0, 0};
 #pragma unroll
         for (int s = 0; s < KSTEPS; s += 2) {
@@ -564,7 +564,7 @@ __global__ __launch_bounds__(WG_THREADS, min_waves(BITS, KSTEPS)) void moe_decod
           {
             uint32_t x = 0;
             for (int q = 0; q < S::LW; ++q) x ^= b.lo[ch * S::LW + q];
-            if (BITS == 3) for (int q = 0; q < S::HW; ++q) x ^= b.hi[ch * S::HW + q];
+            if (S::FB == 3) for (int q = 0; q < S::HW; ++q) x ^= b.hi[ch * S::HW + q];
             acc0[0] += __builtin_bit_cast(float, x & 0x3fffffffu);
           }
           for (int s1 = 0; s1 < 0; ++s1) {
@@ -580,6 +580,13 @@ __global__ __launch_bounds__(WG_THREADS, min_waves(BITS, KSTEPS)) void moe_decod
               w = unpack4(b.lo[ch * S::LW + s1], uc);
             } else if constexpr (BITS == MOQE_LOG4) {
               w = unpack4_log(b.lo[ch * S::LW + s1], uc);
+            } else if constexpr (BITS == MOQE_LOG3) {
+              const uint32_t d = b.lo[ch * S::LW + (s1 >> 1)], hd = b.hi[ch * S::HW + (s1 >> 2)];
+              w = (s1 & 3) == 0 ? unpack3_log<0>(d, hd, uc) : (s1 & 3) == 1 ? unpack3_log<1>(d, hd, uc)
+                : (s1 & 3) == 2 ? unpack3_log<2>(d, hd, uc) : unpack3_log<3>(d, hd, uc);
+            } else if constexpr (BITS == MOQE_LOG2) {
+              const uint32_t d = b.lo[ch * S::LW + (s1 >> 1)];
+              w = (s1 & 1) ? unpack2_log<1>(d, uc) : unpack2_log<0>(d, uc);
             } else {
               const uint32_t d = b.lo[ch * S::LW + (s1 >> 1)];
               w = (s1 & 1) ? unpack2<1>(d, uc) : unpack2<0>(d, uc);
@@ -765,7 +772,7 @@ hipError_t launch_bits(const DecodeArgs& a, int num_cus, hipStream_t stream) {
     case 8: return launch_one<BITS, 8>(a, num_cus, stream);
     case 4: return launch_one<BITS, 4>(a, num_cus, stream);
     case 2:
-      if constexpr (BITS != 3) return launch_one<BITS, 2>(a, num_cus, stream);
+      if constexpr (moqe_field_bits(BITS) != 3) return launch_one<BITS, 2>(a, num_cus, stream);
       return hipErrorInvalidValue;
     default: return hipErrorInvalidValue;
   }
@@ -803,6 +810,8 @@ hipError_t moqe_launch_decode(const DecodeArgs& a, int num_cus, hipStream_t stre
     case 8: return launch_bits<8>(a, num_cus, stream);
     case 4: return launch_bits<4>(a, num_cus, stream);
     case MOQE_LOG4: return launch_bits<MOQE_LOG4>(a, num_cus, stream);
+    case MOQE_LOG3: return launch_bits<MOQE_LOG3>(a, num_cus, stream);
+    case MOQE_LOG2: return launch_bits<MOQE_LOG2>(a, num_cus, stream);
     case 3: return launch_bits<3>(a, num_cus, stream);
     case 2: return launch_bits<2>(a, num_cus, stream);
     default: return hipErrorInvalidValue;

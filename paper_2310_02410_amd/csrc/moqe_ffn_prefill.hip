@@ -94,7 +94,7 @@ __global__ __launch_bounds__(PF_THREADS, (PF_NT == 4 || BITS == 16) ? 2 : PF_WG_
   constexpr int LO_BITS = FB == 3 ? 2 : FB;
   constexpr int LWC = (SC / PCH) * LO_BITS / 4;  // main-plane words per lane per packed chunk (4)
   constexpr int LW = LWC * PCH;               // ... per chunk
-  constexpr int HW = BITS == 3 ? SC / 4 : 0;  // 1-bit-plane words per lane per chunk
+  constexpr int HW = FB == 3 ? SC / 4 : 0;    // 1-bit-plane words per lane per chunk
   constexpr int CHUNK_BYTES = 64 * SC * FB;
   constexpr int ROW_PIECES = PF_KB / 8;       // 16-byte pieces per staged row (256 bytes, no padding)
   constexpr int NBUF = 3;                     // staged blocks in LDS: one in use, two on their way
@@ -203,7 +203,7 @@ __global__ __launch_bounds__(PF_THREADS, (PF_NT == 4 || BITS == 16) ? 2 : PF_WG_
       for (int pc = 0; pc < PCH; ++pc)
         load_words<LWC, PF_B_NT>(brs[ni], (uint32_t)c * CHUNK_BYTES + pc * (CHUNK_BYTES / PCH) + lane_lo,
                                  &b_lo[buf][ni][LWC * pc]);
-      if constexpr (BITS == 3) load_words<HW, PF_B_NT>(brs[ni], (uint32_t)c * CHUNK_BYTES + lane_hi, b_hi[buf][ni]);
+      if constexpr (FB == 3) load_words<HW, PF_B_NT>(brs[ni], (uint32_t)c * CHUNK_BYTES + lane_hi, b_hi[buf][ni]);
     }
   };
 
@@ -266,6 +266,13 @@ __global__ __launch_bounds__(PF_THREADS, (PF_NT == 4 || BITS == 16) ? 2 : PF_WG_
           w = unpack4_exact(b_lo[bbuf][ni][s], uc);
         } else if constexpr (BITS == MOQE_LOG4) {
           w = unpack4_log(b_lo[bbuf][ni][s], uc);
+        } else if constexpr (BITS == MOQE_LOG2) {
+          const uint32_t d = b_lo[bbuf][ni][s >> 1];
+          w = (s & 1) ? unpack2_log<1>(d, uc) : unpack2_log<0>(d, uc);
+        } else if constexpr (BITS == MOQE_LOG3) {
+          const uint32_t d = b_lo[bbuf][ni][s >> 1], hd = b_hi[bbuf][ni][s >> 2];
+          w = (s & 3) == 0 ? unpack3_log<0>(d, hd, uc) : (s & 3) == 1 ? unpack3_log<1>(d, hd, uc)
+            : (s & 3) == 2 ? unpack3_log<2>(d, hd, uc) : unpack3_log<3>(d, hd, uc);
         } else if constexpr (BITS == 2) {
           const uint32_t d = b_lo[bbuf][ni][s >> 1];
           w = (s & 1) ? unpack2_exact<1>(d, uc) : unpack2_exact<0>(d, uc);
@@ -490,6 +497,8 @@ hipError_t moqe_launch_prefill(const PrefillArgs& a, int num_cus, hipStream_t st
     case 8: launch_bits<8>(a, pairs, num_cus, stream); break;
     case 4: launch_bits<4>(a, pairs, num_cus, stream); break;
     case MOQE_LOG4: launch_bits<MOQE_LOG4>(a, pairs, num_cus, stream); break;
+    case MOQE_LOG3: launch_bits<MOQE_LOG3>(a, pairs, num_cus, stream); break;
+    case MOQE_LOG2: launch_bits<MOQE_LOG2>(a, pairs, num_cus, stream); break;
     case 3: launch_bits<3>(a, pairs, num_cus, stream); break;
     case 2: launch_bits<2>(a, pairs, num_cus, stream); break;
     default: return hipErrorInvalidValue;

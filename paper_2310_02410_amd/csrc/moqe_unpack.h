@@ -40,6 +40,10 @@ struct UnpackConsts {
   uint32_t l_e0, l_e1, l_e2, l_e3, l_s0, l_s1, l_s2, l_s3, l_one;  // log-scale codes: exponent / sign masks
   __device__ inline void init() {
     if (BITS == 16) return;  // fp16 weights need no unpacking
+    if (BITS == MOQE_LOG2 || BITS == MOQE_LOG3) {
+      l_one = opaque_vgpr(BITS == MOQE_LOG2 ? 0x38003800u : 0x30003000u);
+      return;
+    }
     if (BITS == MOQE_LOG4) {
       l_e0 = opaque_sgpr(0x00070007u); l_s0 = opaque_sgpr(0x00080008u);
       l_e1 = opaque_sgpr(0x00700070u); l_s1 = opaque_sgpr(0x00800080u);
@@ -101,6 +105,41 @@ __device__ inline half8_t unpack4_log(uint32_t d, const C& c) {
   uint32_t r2 = (((d & c.l_e2) << 2) | c.l_one) | ((d & c.l_s2) << 4);
   uint32_t r3 = (((d >> 2) & c.l_e3) | c.l_one) | (d & c.l_s3);
   return frag_from_words(r0, r1, r2, r3);
+}
+
+// ---- 2-bit and 3-bit log-scale codes.  The exponent field sits where the linear codes keep
+// their 2-bit field (register i of a step's fragment: bit 2 i of each half in an even step, bit
+// 8 + 2 i in an odd one): one exponent bit for 2-bit codes, whose sign is the field's upper bit,
+// two for 3-bit codes, whose sign is the bit of the 1-bit plane (bit 4 ss + i of each half for
+// step ss of four).  Exponent bits go to bit 10 (and 11), the sign to bit 15, and l_one holds
+// the exponent offset: 2^Q = 2^(e - 1) has exponent field 14 + e, 2^(e - 3) has 12 + e.
+template <int POS, int NBITS>
+__device__ inline uint32_t log_field_to_exponent(uint32_t d) {
+  constexpr uint32_t m = ((1u << NBITS) - 1u) << POS;
+  constexpr uint32_t mask = m | (m << 16);
+  if constexpr (POS <= 10) return (d & mask) << (10 - POS);
+  else return (d & mask) >> (POS - 10);
+}
+template <int POS>
+__device__ inline uint32_t log_bit_to_sign(uint32_t d) {
+  constexpr uint32_t mask = (1u << POS) | (1u << (POS + 16));
+  return (d & mask) << (15 - POS);
+}
+template <int PARITY, class C>
+__device__ inline half8_t unpack2_log(uint32_t d, const C& c) {
+  constexpr int P = 8 * PARITY;
+  return frag_from_words(log_field_to_exponent<P + 0, 1>(d) | log_bit_to_sign<P + 1>(d) | c.l_one,
+                         log_field_to_exponent<P + 2, 1>(d) | log_bit_to_sign<P + 3>(d) | c.l_one,
+                         log_field_to_exponent<P + 4, 1>(d) | log_bit_to_sign<P + 5>(d) | c.l_one,
+                         log_field_to_exponent<P + 6, 1>(d) | log_bit_to_sign<P + 7>(d) | c.l_one);
+}
+template <int SS, class C>
+__device__ inline half8_t unpack3_log(uint32_t dl, uint32_t dh, const C& c) {
+  constexpr int P = 8 * (SS & 1), H = 4 * SS;
+  return frag_from_words(log_field_to_exponent<P + 0, 2>(dl) | log_bit_to_sign<H + 0>(dh) | c.l_one,
+                         log_field_to_exponent<P + 2, 2>(dl) | log_bit_to_sign<H + 1>(dh) | c.l_one,
+                         log_field_to_exponent<P + 4, 2>(dl) | log_bit_to_sign<H + 2>(dh) | c.l_one,
+                         log_field_to_exponent<P + 6, 2>(dl) | log_bit_to_sign<H + 3>(dh) | c.l_one);
 }
 
 // ---- int8: two words per step; word bit position of code i: 16 (i & 1) + 8 ((i >> 1) & 1), word
@@ -236,11 +275,11 @@ struct Shape {
   static constexpr int NCH = KSTEPS / SC;                     // chunks per wave slice
   static constexpr int LO_BITS = FB == 3 ? 2 : FB;
   static constexpr int LW = SC * LO_BITS / 4;                 // main-plane words per lane per chunk
-  static constexpr int HW = BITS == 3 ? SC / 4 : 0;           // 1-bit-plane words per lane per chunk
+  static constexpr int HW = FB == 3 ? SC / 4 : 0;             // 1-bit-plane words per lane per chunk
   static constexpr int CHUNK_WORDS = 16 * SC * FB;            // 64 * SC * FB / 4
   static_assert(KSTEPS % SC == 0, "slice must hold whole chunks");
   static_assert(LW >= 1, "lane owns at least a word");
-  static_assert(BITS != 3 || HW >= 1, "int3 needs 4 steps per chunk");
+  static_assert(FB != 3 || HW >= 1, "3-bit codes need 4 steps per chunk");
 };
 
 template <int N>

@@ -149,7 +149,7 @@ def test_expert_ffn_error_paths():
     assert call(layer(), y=0) == 1
     assert call(layer(bits=5)) == 2
     assert call(layer(codec=2)) == 2          # unknown codec
-    assert call(layer(codec=1, bits=2)) == 2  # log-scale layers run at 4 bits only
+    assert call(layer(codec=1, bits=8)) == 2  # log-scale codes have 2, 3 or 4 bits
     assert call(layer(d=48)) == 3
     assert call(layer(E=0)) == 3
     assert call(layer(), T=-2) == 3

@@ -112,15 +112,16 @@ def test_fp16_experts_decode_config():
     _layer_parity(W.CONFIGS["c1"], 16)
 
 
-def _log_layer_parity(wl, residual=False, launch_mode=None, sample=None):
-    """A layer of 4-bit log-scale codes (App. A: A' = P s 2^Q) through the FFN calls, against
-    the oracle's expert FFN on the oracle's log-dequantized weights."""
+def _log_layer_parity(wl, bits=4, residual=False, launch_mode=None, sample=None):
+    """A layer of log-scale codes (App. A: A' = P s 2^Q) through the FFN calls, against the
+    oracle's expert FFN on the oracle's log-dequantized weights."""
     layer, x = W.make_layer(wl), W.make_tokens(wl)
-    ql = moqe.quantize_layer(dev(layer["w1"]), dev(layer["b1"]), dev(layer["w2"]), dev(layer["b2"]), 4,
+    ql = moqe.quantize_layer(dev(layer["w1"]), dev(layer["b1"]), dev(layer["w2"]), dev(layer["b2"]), bits,
                              dev(layer["w_gate"]), codec=moqe.CODEC_LOG)
-    q1, s1 = O.quantize_log(layer["w1"], 4)
-    q2, s2 = O.quantize_log(layer["w2"], 4)
-    assert np.array_equal(ql.codes1.cpu().numpy(), O.pack(q1, 4)) and np.array_equal(ql.codes2.cpu().numpy(), O.pack(q2, 4))
+    q1, s1 = O.quantize_log(layer["w1"], bits)
+    q2, s2 = O.quantize_log(layer["w2"], bits)
+    assert np.array_equal(ql.codes1.cpu().numpy(), O.pack(q1, bits))
+    assert np.array_equal(ql.codes2.cpu().numpy(), O.pack(q2, bits))
     xd = dev(x)
     saved = moqe.moqe_set_launch_mode(launch_mode) if launch_mode is not None else None
     try:
@@ -142,27 +143,30 @@ def _log_layer_parity(wl, residual=False, launch_mode=None, sample=None):
         has = np.diff(offs) > 0
         rows = np.concatenate([rows, perm[offs[:-1][has]], perm[offs[1:][has] - 1]])
         x, idx, gate, yh = x[rows], idx[rows], gate[rows], yh[rows]
-    ref = O.expert_ffn(x, idx, gate.astype(np.float64), O.dequantize_log(q1, s1, 4), layer["b1"],
-                       O.dequantize_log(q2, s2, 4), layer["b2"], residual=x if residual else None)
+    ref = O.expert_ffn(x, idx, gate.astype(np.float64), O.dequantize_log(q1, s1, bits), layer["b1"],
+                       O.dequantize_log(q2, s2, bits), layer["b2"], residual=x if residual else None)
     err = ffn_error(yh, ref)
-    assert err <= FFN_TOL, f"{wl.name} log4: max|err|/max|ref| = {err:.3e}"
+    assert err <= FFN_TOL, f"{wl.name} log{bits}: max|err|/max|ref| = {err:.3e}"
 
 
+@pytest.mark.parametrize("bits", (4, 3, 2))
 @pytest.mark.parametrize("T", (1, 24, 37, 150))
-def test_log_scale_layer_small(T):
-    _log_layer_parity(W.small(T=T, seed=91 + T))
+def test_log_scale_layer_small(bits, T):
+    _log_layer_parity(W.small(T=T, seed=91 + T), bits)
 
 
-def test_log_scale_layer_shapes_and_modes():
-    _log_layer_parity(W.small(E=4, d=512, f=2048, T=40, seed=95), residual=True)
-    _log_layer_parity(W.small(E=3, d=768, f=3072, T=21, seed=96))
-    _log_layer_parity(W.small(E=8, d=512, f=2048, T=24, seed=97), launch_mode=moqe.LAUNCH_FUSED)
+@pytest.mark.parametrize("bits", (4, 3, 2))
+def test_log_scale_layer_shapes_and_modes(bits):
+    _log_layer_parity(W.small(E=4, d=512, f=2048, T=40, seed=95), bits, residual=True)
+    _log_layer_parity(W.small(E=3, d=768, f=3072, T=21, seed=96), bits)
+    _log_layer_parity(W.small(E=8, d=512, f=2048, T=24, seed=97), bits, launch_mode=moqe.LAUNCH_FUSED)
     # many tokens per expert: the tiled kernel (all three tile shapes over the two calls), then a
     # Zipf load where the decode kernel takes the small segments beside it
-    _log_layer_parity(W.small(E=4, d=256, f=512, T=700, seed=98))
-    _log_layer_parity(W.small(E=4, d=256, f=4096, T=8192, seed=99), sample=256)
-    _log_layer_parity(W.small(E=16, d=256, f=512, T=200, routing="zipf", n_empty=3, seed=85), residual=True)
+    _log_layer_parity(W.small(E=4, d=256, f=512, T=700, seed=98), bits)
+    _log_layer_parity(W.small(E=4, d=256, f=4096, T=8192, seed=99), bits, sample=256)
+    _log_layer_parity(W.small(E=16, d=256, f=512, T=200, routing="zipf", n_empty=3, seed=85), bits, residual=True)
 
 
-def test_log_scale_layer_benchmark_shape():
-    _log_layer_parity(W.CONFIGS["c1"])
+@pytest.mark.parametrize("bits", (4, 3, 2))
+def test_log_scale_layer_benchmark_shape(bits):
+    _log_layer_parity(W.CONFIGS["c1"], bits)
