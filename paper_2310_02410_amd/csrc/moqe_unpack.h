@@ -11,6 +11,8 @@
 
 #include "moqe_dev.h"
 
+typedef short short2_t __attribute__((ext_vector_type(2)));
+
 __device__ inline half8_t frag_from_words(uint32_t r0, uint32_t r1, uint32_t r2, uint32_t r3) {
   uint4_t v = {r0, r1, r2, r3};
   return __builtin_bit_cast(half8_t, v);
@@ -37,18 +39,16 @@ struct UnpackConsts {
   uint32_t m_0030, m_00c0, m_0300;          // 2-bit field masks at bits 4, 6, 8
   uint32_t m_0040, m_0080, m_0100, m_0200;  // single-bit masks at bits 6..9 (int3 high plane)
   uint32_t x1024, x64, x32, x16, x8, x4;    // exponent patterns
-  uint32_t l_e0, l_e1, l_e2, l_e3, l_s0, l_s1, l_s2, l_s3, l_one;  // log-scale codes: exponent / sign masks
+  uint32_t l_e3, l_one;                     // log-scale codes: kept bits, exponent offset
   __device__ inline void init() {
     if (BITS == 16) return;  // fp16 weights need no unpacking
     if (BITS == MOQE_LOG2 || BITS == MOQE_LOG3) {
+      l_e3 = opaque_sgpr(0x84008400u);  // (2-bit codes) sign and the exponent bit of an fp16 word
       l_one = opaque_vgpr(BITS == MOQE_LOG2 ? 0x38003800u : 0x30003000u);
       return;
     }
     if (BITS == MOQE_LOG4) {
-      l_e0 = opaque_sgpr(0x00070007u); l_s0 = opaque_sgpr(0x00080008u);
-      l_e1 = opaque_sgpr(0x00700070u); l_s1 = opaque_sgpr(0x00800080u);
-      l_e2 = opaque_sgpr(0x07000700u); l_s2 = opaque_sgpr(0x08000800u);
-      l_e3 = opaque_sgpr(0x1C001C00u); l_s3 = opaque_sgpr(0x80008000u);
+      l_e3 = opaque_sgpr(0x9C009C00u);  // sign and the three exponent bits of an fp16 word
       l_one = opaque_vgpr(0x20002000u);
       return;
     }
@@ -95,16 +95,22 @@ __device__ inline half8_t unpack4(uint32_t d, const C& c) {
 
 // ---- 4-bit log-scale codes (App. A: A' = P s 2^Q): same nibble positions as int4; a nibble
 // holds the exponent e = Q + 7 in its low three bits and the sign in its top bit.  The fp16
-// number +-2^Q has exponent field e + 8 and no mantissa: the three bits go to bits 10..12,
-// 0x2000 adds the 8, the sign bit goes to bit 15.  No multiply, and nothing to correct after
-// the K-sum (the value is exact; the format has no zero point).
+// number +-2^Q has exponent field e + 8 and no mantissa.  The nibble is shifted to the top of
+// its 16-bit half; an arithmetic shift right by two (per half) then leaves the sign in bit 15
+// and the exponent in bits 10..12 (bits 13 and 14 hold copies of the sign, masked away), and
+// 0x2000 adds the 8.  No multiply, and nothing to correct after the K-sum (the value is exact;
+// the format has no zero point).  A 32-bit shift may be used to move the nibbles up: what it
+// carries from the low half into the high one lands below bit 26 and is masked away.
+template <class C>
+__device__ inline uint32_t log4_top_nibble(uint32_t v, const C& c) {
+  short2_t h = __builtin_bit_cast(short2_t, v);
+  h = h >> 2;
+  return (__builtin_bit_cast(uint32_t, h) & c.l_e3) | c.l_one;
+}
 template <class C>
 __device__ inline half8_t unpack4_log(uint32_t d, const C& c) {
-  uint32_t r0 = (((d & c.l_e0) << 10) | c.l_one) | ((d & c.l_s0) << 12);
-  uint32_t r1 = (((d & c.l_e1) << 6) | c.l_one) | ((d & c.l_s1) << 8);
-  uint32_t r2 = (((d & c.l_e2) << 2) | c.l_one) | ((d & c.l_s2) << 4);
-  uint32_t r3 = (((d >> 2) & c.l_e3) | c.l_one) | (d & c.l_s3);
-  return frag_from_words(r0, r1, r2, r3);
+  return frag_from_words(log4_top_nibble(d << 12, c), log4_top_nibble(d << 8, c), log4_top_nibble(d << 4, c),
+                         log4_top_nibble(d, c));
 }
 
 // ---- 2-bit and 3-bit log-scale codes.  The exponent field sits where the linear codes keep
@@ -125,13 +131,20 @@ __device__ inline uint32_t log_bit_to_sign(uint32_t d) {
   constexpr uint32_t mask = (1u << POS) | (1u << (POS + 16));
   return (d & mask) << (15 - POS);
 }
+// (2-bit codes: the field [sign, exponent bit] is shifted to the top of its half; an arithmetic
+// shift right by four then leaves the sign in bit 15 and the exponent bit in bit 10, with
+// copies of the sign in between that are masked away - as for the 4-bit codes)
+template <int POS, class C>
+__device__ inline uint32_t log2_field(uint32_t d, const C& c) {
+  short2_t h = __builtin_bit_cast(short2_t, POS == 14 ? d : d << (14 - POS));
+  h = h >> 4;
+  return (__builtin_bit_cast(uint32_t, h) & c.l_e3) | c.l_one;
+}
 template <int PARITY, class C>
 __device__ inline half8_t unpack2_log(uint32_t d, const C& c) {
   constexpr int P = 8 * PARITY;
-  return frag_from_words(log_field_to_exponent<P + 0, 1>(d) | log_bit_to_sign<P + 1>(d) | c.l_one,
-                         log_field_to_exponent<P + 2, 1>(d) | log_bit_to_sign<P + 3>(d) | c.l_one,
-                         log_field_to_exponent<P + 4, 1>(d) | log_bit_to_sign<P + 5>(d) | c.l_one,
-                         log_field_to_exponent<P + 6, 1>(d) | log_bit_to_sign<P + 7>(d) | c.l_one);
+  return frag_from_words(log2_field<P + 0>(d, c), log2_field<P + 2>(d, c), log2_field<P + 4>(d, c),
+                         log2_field<P + 6>(d, c));
 }
 template <int SS, class C>
 __device__ inline half8_t unpack3_log(uint32_t dl, uint32_t dh, const C& c) {
