@@ -36,7 +36,8 @@
  *   g = (k % 32) / 8, i = k % 8; slot l = 16 g + j; SC = min(SCmax, K/32);
  *   chunk p = s / SC, s' = s % SC, m = 8 s' + i.  Chunks are stored column
  *   tile major: chunk (c, p) starts at byte (c * K/(32 SC) + p) * 64 SC bits.
- *   Stored field value u = q + 2^(bits-1) (offset binary).
+ *   Stored field value u = q + 2^(bits-1) (offset binary); log-scale codes
+ *   (moqe_quantize_log) store u = sign * 2^(bits-1) + exponent code in the same fields.
  *   bits 2,4,8,16: the chunk is 64 slots of SC*bits bytes; inside a slot, 32/bits
  *     codes fill a little-endian 32-bit word: word = m / (32/bits),
  *     t = m % (32/bits), bit position = 16 (t & 1) + bits (t >> 1).
@@ -62,7 +63,7 @@ typedef uint16_t moqe_f16;
 typedef enum {
   MOQE_OK = 0,
   MOQE_ERR_NULL = 1,      /* a required pointer is NULL */
-  MOQE_ERR_BITS = 2,      /* bits not in {2,3,4} */
+  MOQE_ERR_BITS = 2,      /* bits not in {2,3,4,8,16}, or not a width the codec has */
   MOQE_ERR_SHAPE = 3,     /* a dimension is negative, zero where it may not be, or unsupported */
   MOQE_ERR_ALIGN = 4,     /* a device pointer is not 16-byte aligned */
   MOQE_ERR_WORKSPACE = 5, /* workspace_bytes is smaller than the matching *_workspace_bytes() */
