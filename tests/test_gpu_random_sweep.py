@@ -1,0 +1,79 @@
+"""A seeded sweep of whole layer steps over random combinations of what the other GPU tests
+vary one at a time: layer shape, token count, load shape, weight width and codec, residual,
+launch mode and path-choice thresholds.  Every case: routing tables bit-exact against the
+oracle, the FFN output within the bound, and a second call bit-identical to the first."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import moqe_oracle as O
+from paper_2310_02410_amd import moqe, workloads as W
+from tests.helpers import FFN_TOL, assert_route_equal, dev, ffn_error, route_to_numpy
+
+pytestmark = pytest.mark.gpu
+
+DIMS = (64, 128, 256, 384, 512, 768, 1024, 1536, 2048)
+POLICIES = ((5, 65, 16), (1, 1, moqe.PREFILL_NEVER), (5, 1, moqe.PREFILL_NEVER), (1 << 20, 1, moqe.PREFILL_NEVER),
+            (3, 20, 4))
+
+
+def _cases(seed, n):
+    rng = np.random.default_rng(seed)
+    L = moqe.lib()
+    out = []
+    while len(out) < n:
+        bits = int(rng.choice([2, 3, 4, 8, 16]))
+        codec = int(rng.random() < 0.35) if bits in (2, 3, 4) else 0
+        E = int(rng.choice([1, 2, 3, 5, 8, 16, 32, 40, 64]))
+        d, f = int(rng.choice(DIMS)), int(rng.choice(DIMS))
+        T = int(rng.choice([1, 2, 3, 7, 24, 33, 64, 65, 100, 257, 700, 1500]))
+        zipf = bool(E >= 8 and rng.random() < 0.3)
+        residual = bool(rng.random() < 0.4)
+        mode = int(rng.choice([moqe.LAUNCH_AUTO, moqe.LAUNCH_SEPARATE, moqe.LAUNCH_FUSED]))
+        policy = POLICIES[int(rng.integers(len(POLICIES)))]
+        wseed = int(rng.integers(1 << 20))
+        if L.moqe_check_layer(bits, E, d, f) != 0 or E * d * f > 1e8:
+            continue
+        out.append((bits, codec, E, d, f, T, zipf, residual, mode, policy, wseed))
+    return out
+
+
+def _weights(layer, bits, codec):
+    if bits == 16:
+        return O.quantize_fp16(layer["w1"]), O.quantize_fp16(layer["w2"])
+    if codec:
+        (q1, s1), (q2, s2) = O.quantize_log(layer["w1"], bits), O.quantize_log(layer["w2"], bits)
+        return O.dequantize_log(q1, s1, bits), O.dequantize_log(q2, s2, bits)
+    (q1, s1), (q2, s2) = O.quantize(layer["w1"], bits), O.quantize(layer["w2"], bits)
+    return O.dequantize(q1, s1), O.dequantize(q2, s2)
+
+
+@pytest.mark.parametrize("chunk", range(4))
+def test_random_layer_steps(chunk):
+    for case in _cases(1000 + chunk, 12):
+        bits, codec, E, d, f, T, zipf, residual, mode, policy, wseed = case
+        wl = W.small(E=E, d=d, f=f, T=T, seed=wseed, routing="zipf" if zipf else "uniform", n_empty=2 if zipf else 0)
+        layer, x = W.make_layer(wl), W.make_tokens(wl)
+        ql = moqe.quantize_layer(dev(layer["w1"]), dev(layer["b1"]), dev(layer["w2"]), dev(layer["b2"]), bits,
+                                 dev(layer["w_gate"]), codec=codec)
+        xd = dev(x)
+        saved = moqe.moqe_set_launch_mode(mode)
+        moqe.moqe_set_prefill_policy(*policy)
+        try:
+            ws = moqe.alloc_workspace(moqe.moqe_layer_workspace_bytes(T, E, d, f), xd.device)
+            y, r = moqe.moqe_moe_layer(ql, xd, residual=xd if residual else None, workspace=ws)
+            y2, _ = moqe.moqe_moe_layer(ql, xd, residual=xd if residual else None, workspace=ws)
+            torch.cuda.synchronize()
+            assert not moqe.workspace_error(ws), case
+        finally:
+            moqe.moqe_set_launch_mode(saved)
+            moqe.moqe_set_prefill_policy()
+        got = route_to_numpy(r)
+        assert_route_equal(got, O.route(x, layer["w_gate"]), T, E)
+        w1, w2 = _weights(layer, bits, codec)
+        ref = O.expert_ffn(x, got[0], got[1].astype(np.float64), w1, layer["b1"], w2, layer["b2"],
+                           residual=x if residual else None)
+        err = ffn_error(y.cpu().numpy(), ref)
+        assert err <= FFN_TOL, (case, err)
+        assert np.array_equal(y.cpu().numpy().view(np.uint16), y2.cpu().numpy().view(np.uint16)), case
