@@ -77,3 +77,28 @@ def test_random_layer_steps(chunk):
         err = ffn_error(y.cpu().numpy(), ref)
         assert err <= FFN_TOL, (case, err)
         assert np.array_equal(y.cpu().numpy().view(np.uint16), y2.cpu().numpy().view(np.uint16)), case
+
+
+def test_random_router_shapes():
+    """moqe_route and moqe_route_logits over 40 seeded random (E, d, T), expert counts that no
+    kernel is specialised for and token counts on both sides of every kernel's limit among them;
+    the given logits are small integers, so exact ties are everywhere."""
+    rng = np.random.default_rng(2000)
+    done = 0
+    while done < 40:
+        E = int(rng.choice([1, 2, 3, 4, 7, 8, 13, 16, 24, 32, 33, 64, 100, 128, 129, 200, 256, 300, 511, 1024]))
+        d = int(rng.choice([8, 16, 24, 32, 64, 96, 128, 256, 264, 512, 768, 1024, 2048]))
+        T = int(rng.choice([1, 2, 15, 16, 17, 24, 32, 33, 63, 64, 65, 128, 255, 256, 257, 1000, 1536, 4096, 5000, 20000]))
+        zipf = bool(E >= 8 and rng.random() < 0.3)
+        wseed = int(rng.integers(1 << 20))
+        if T * d > 2e7 or E * d > 2e5:
+            continue
+        done += 1
+        wl = W.small(E=E, d=d, f=32, T=T, seed=wseed, routing="zipf" if zipf else "uniform",
+                     n_empty=min(2, E - 1) if zipf else 0)
+        layer, x = W.make_layer(wl), W.make_tokens(wl)
+        r = moqe.moqe_route(dev(x), dev(layer["w_gate"]))
+        assert_route_equal(route_to_numpy(r), O.route(x, layer["w_gate"]), T, E)
+        logits = rng.integers(-3, 4, size=(T, E)).astype(np.float32)
+        r2 = moqe.moqe_route_logits(dev(logits))
+        assert_route_equal(route_to_numpy(r2), O.route_from_logits(logits), T, E)
