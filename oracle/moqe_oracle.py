@@ -402,13 +402,18 @@ def route_from_logits(logits):
     no capacity limit or token dropping, no jitter, no gating dropout.  Dispatch
     bookkeeping: count per expert, exclusive prefix sum (seg_offsets[E] = T),
     and the stable permutation (tokens of one expert stay in ascending order).
+    Non-finite logits are outside the method's domain; the definition is kept total all the
+    same: a NaN counts as the row maximum (first NaN wins), a row of -inf takes expert 0, so
+    the index is always in [0, E) and every token lands in exactly one segment (the gate of
+    such a row is NaN).
     Returns (expert_idx int32 [T], gate f64 [T], seg_offsets int32 [E+1], perm int32 [T]).
     """
     l = np.asarray(logits, dtype=np.float64)
     T, E = l.shape
     expert_idx = np.argmax(l, axis=1).astype(np.int32) if T else np.zeros(0, np.int32)
     top = l[np.arange(T), expert_idx] if T else np.zeros(0)
-    gate = 1.0 / np.sum(np.exp(l - top[:, None]), axis=1) if T else np.zeros(0)
+    with np.errstate(invalid="ignore"):  # (-inf) - (-inf) and NaN rows give a NaN gate, by definition above
+        gate = 1.0 / np.sum(np.exp(l - top[:, None]), axis=1) if T else np.zeros(0)
     counts = np.bincount(expert_idx, minlength=E)
     seg_offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
     perm = np.argsort(expert_idx, kind="stable").astype(np.int32)

@@ -5,6 +5,8 @@ from __future__ import annotations
 import os
 import shutil
 import subprocess
+import tempfile
+from concurrent.futures import ThreadPoolExecutor
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
@@ -19,23 +21,40 @@ def hipcc() -> str:
     return exe
 
 
-def build_library(verbose: bool = False, extra=()) -> str:
-    """Compile every HIP source into paper_2310_02410_amd/libmoqe.so (always recompiles)."""
-    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           # keep the four words of an unpacked MFMA fragment as scalar ops: the SLP vectorizer
-           # would turn (a & mask) | magic into vector ops that no longer select v_and_or_b32
-           "-fno-slp-vectorize",
-           "-Wno-unused-command-line-argument",
-           "-I", os.path.join(os.path.dirname(PKG), "include"), *extra,
-           *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB + ".tmp"]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
-    os.replace(LIB + ".tmp", LIB)
-    return LIB
+def build_library(verbose: bool = False, extra=(), out: str = LIB) -> str:
+    """Compile every HIP source (in parallel, one object each) and link them into
+    paper_2310_02410_amd/libmoqe.so; always recompiles."""
+    flags = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+             # keep the four words of an unpacked MFMA fragment as scalar ops: the SLP vectorizer
+             # would turn (a & mask) | magic into vector ops that no longer select v_and_or_b32
+             "-fno-slp-vectorize",
+             "-Wno-unused-command-line-argument",
+             "-I", os.path.join(os.path.dirname(PKG), "include"), *extra]
+    objdir = tempfile.mkdtemp(prefix="moqe_build_")
+    try:
+        def compile_one(src):
+            obj = os.path.join(objdir, src + ".o")
+            cmd = [hipcc(), *flags, "-c", os.path.join(CSRC, src), "-o", obj]
+            if verbose:
+                print(" ".join(cmd), flush=True)
+            res = subprocess.run(cmd, capture_output=True, text=True)
+            if res.returncode != 0:
+                raise RuntimeError(f"hipcc failed on {src}:\n" + res.stdout + res.stderr)
+            return obj
+
+        with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 1)) as pool:
+            objs = list(pool.map(compile_one, SOURCES))
+        cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", out + ".tmp"]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("link failed:\n" + res.stdout + res.stderr)
+        os.replace(out + ".tmp", out)
+    finally:
+        shutil.rmtree(objdir, ignore_errors=True)
+    return out
 
 
 if __name__ == "__main__":

@@ -222,16 +222,19 @@ __global__ __launch_bounds__(WG_THREADS, min_waves(BITS, KSTEPS)) void moe_decod
       if (wave == 0) {
         // wavefront-level argmax (lowest index on ties) and softmax probability
         const float* row = s_route[WG_WAVES];
+        // (a NaN ranks above every number and ties with another NaN; an all -inf row keeps index 0)
         float best = -INFINITY;
-        int bidx = 0x7fffffff;
+        int bidx = 0;
         for (int e = lane; e < E; e += 64) {
           const float v = row[e];
-          if (v > best) { best = v; bidx = e; }
+          if ((v > best) || (v != v && best == best)) { best = v; bidx = e; }
         }
         for (int off = 32; off >= 1; off >>= 1) {
           const float ov = __shfl_xor(best, off, 64);
           const int oi = __shfl_xor(bidx, off, 64);
-          const bool take = (ov > best) || (ov == best && oi < bidx);
+          const bool above = (ov > best) || (ov != ov && best == best);
+          const bool same = (ov == best) || (ov != ov && best != best);
+          const bool take = above || (same && oi < bidx);
           best = take ? ov : best;
           bidx = take ? oi : bidx;
         }

@@ -16,15 +16,22 @@ constexpr int SCORE_THREADS = 256;
 constexpr int SEG_THREADS = 1024;
 constexpr int SEG_LDS_INTS = 9216;
 
+// Order of the top-1 comparison: a NaN ranks above every number and ties with another NaN, as
+// in the plain definition "first index of the row maximum" once a NaN is met (non-finite logits
+// are outside the method's domain; what matters is that the index stays in [0, E) and is unique).
+__device__ inline bool logit_above(float a, float b) { return (a > b) || (a != a && b == b); }
+__device__ inline bool logit_same(float a, float b) { return (a == b) || (a != a && b != b); }
+
 // Wave-level top-1 over one row of logits held in LDS or global memory.
 // Returns through lane 0 semantics: every lane gets the same (idx, gate).
+// A row without any value above -inf (all -inf) keeps index 0.
 __device__ inline void wave_pick(const float* row, int E, int* idx_out, float* gate_out) {
   const int lane = lane_id();
   float best = -INFINITY;
-  int bidx = 0x7fffffff;
+  int bidx = 0;
   for (int e = lane; e < E; e += 64) {
     float v = row[e];
-    if (v > best) {  // ascending e: strict > keeps the lowest index
+    if (logit_above(v, best)) {  // ascending e: strictly above keeps the lowest index
       best = v;
       bidx = e;
     }
@@ -32,7 +39,7 @@ __device__ inline void wave_pick(const float* row, int E, int* idx_out, float* g
   for (int off = 32; off >= 1; off >>= 1) {
     float ov = __shfl_xor(best, off, 64);
     int oi = __shfl_xor(bidx, off, 64);
-    bool take = (ov > best) || (ov == best && oi < bidx);
+    bool take = logit_above(ov, best) || (logit_same(ov, best) && oi < bidx);
     best = take ? ov : best;
     bidx = take ? oi : bidx;
   }
@@ -234,7 +241,7 @@ __global__ __launch_bounds__(SEG_THREADS) void route_segments_kernel(const int* 
 #pragma unroll
   for (int i = 0; i < KEEP; ++i) {
     const int t = (wave + i * nwaves) * 64 + lane;
-    keep_key[i] = t < T ? expert_idx[t] : E;  // asked for before the table is cleared
+    keep_key[i] = t < T ? min(max(expert_idx[t], 0), E - 1) : E;  // asked for before the table is cleared
   }
   for (int i = tid; i < CP * E; i += nthreads) cnt[i] = 0;
   __syncthreads();
@@ -251,7 +258,8 @@ __global__ __launch_bounds__(SEG_THREADS) void route_segments_kernel(const int* 
   for (int c = wave + KEEP * nwaves; c < nchunks; c += nwaves) {
     int t = c * 64 + lane;
     bool valid = t < T;
-    int key = valid ? expert_idx[t] : E;
+    int key = valid ? min(max(expert_idx[t], 0), E - 1) : E;  // (an index outside [0, E) cannot come from the
+                                                                // scoring kernels; a caller's own must not write wild)
     uint64_t m = match_any(key, nb);
     bool leader = (__ffsll((long long)m) - 1) == lane;
     if (valid && leader) cnt[key * CP + c] = __popcll(m);
@@ -310,7 +318,7 @@ __global__ __launch_bounds__(SEG_THREADS) void route_segments_kernel(const int* 
   for (int c = wave + KEEP * nwaves; c < nchunks; c += nwaves) {
     int t = c * 64 + lane;
     bool valid = t < T;
-    int key = valid ? expert_idx[t] : E;
+    int key = valid ? min(max(expert_idx[t], 0), E - 1) : E;
     uint64_t m = match_any(key, nb);
     if (valid) {
       int rank = __popcll(m & ((1ull << lane) - 1ull));

@@ -91,6 +91,47 @@ def test_logits_with_exact_ties_and_forced_loads():
     assert np.all(got[0][40:80] == 7)
 
 
+@pytest.mark.parametrize("T,E", [(24, 32), (200, 32), (24, 8), (5000, 100)])
+def test_non_finite_logits_stay_in_the_dispatch(T, E):
+    """Rows of -inf, rows of NaN, NaN or +inf among numbers: outside the method's domain, but no
+    token may leave the dispatch (an index beyond E would send a kernel's row access astray).
+    The oracle pins the convention: a NaN counts as the maximum, a row of -inf takes expert 0."""
+    rng = np.random.default_rng(T + E)
+    l = rng.standard_normal((T, E)).astype(np.float32)
+    l[1] = -np.inf
+    l[2] = np.nan
+    l[3, E // 2] = np.nan
+    l[4, [1, E - 1]] = np.inf
+    l[T - 1] = -np.inf
+    l[T - 2, E - 1] = np.nan
+    got = route_to_numpy(moqe.moqe_route_logits(dev(l)))
+    torch.cuda.synchronize()
+    ri, rg, ro, rp = O.route_from_logits(l)
+    assert np.array_equal(got[0], ri) and np.array_equal(got[2], ro) and np.array_equal(got[3], rp)
+    assert got[0].min() >= 0 and got[0].max() < E
+    assert np.allclose(got[1], rg, rtol=2e-6, atol=0, equal_nan=True)
+
+
+def test_non_finite_activations_through_the_router():
+    """A NaN or inf in x makes a whole row of logits non-finite on every scoring kernel: the
+    index stays in range and the tables stay a partition of the tokens."""
+    for T, d, E in ((24, 1024, 32), (200, 1024, 32), (24, 96, 24), (3000, 64, 10)):
+        wl = W.small("nf", E=E, d=d, f=32, T=T, seed=T + d)
+        x, wg = W.make_tokens(wl), W.make_layer(wl)["w_gate"]
+        x[1, 5] = np.nan
+        x[T - 1, 0] = np.inf
+        x[T - 1, 1] = -np.inf
+        idx, gate, offs, perm = route_to_numpy(moqe.moqe_route(dev(x), dev(wg)))
+        torch.cuda.synchronize()
+        assert idx.min() >= 0 and idx.max() < E and idx[1] == 0
+        assert np.array_equal(np.diff(offs), np.bincount(idx, minlength=E)) and offs[-1] == T
+        assert sorted(perm.tolist()) == list(range(T)) and np.array_equal(perm, np.argsort(idx, kind="stable"))
+        keep = np.ones(T, bool)
+        keep[[1, T - 1]] = False
+        ri, rg, _, _ = O.route(x[keep], wg)
+        assert np.array_equal(idx[keep], ri)
+
+
 def test_deterministic():
     wl = W.small("r", E=32, d=1024, f=32, T=1536, routing="zipf", n_empty=4)
     layer, x = W.make_layer(wl), W.make_tokens(wl)

@@ -77,3 +77,24 @@ def test_empty_batch():
 def test_margin_helper():
     l = np.array([[0.0, 3.0, 1.0], [2.0, 2.0, -1.0]])
     assert O.top2_margin(l).tolist() == [2.0, 0.0]
+
+
+def test_non_finite_rows_stay_in_range():
+    """Outside the method's domain, pinned so that no token can fall out of the dispatch: a NaN
+    counts as the row maximum (the first one wins), a row of -inf takes expert 0."""
+    inf = np.inf
+    l = np.array([[0.5, np.nan, 2.0, np.nan],      # first NaN
+                  [-inf, -inf, -inf, -inf],        # nothing above -inf
+                  [np.nan, np.nan, np.nan, np.nan],
+                  [-inf, 1.0, inf, inf],           # +inf is an ordinary maximum, lowest index
+                  [3.0, 1.0, 3.0, -2.0]])          # finite row, exact tie
+    idx, gate, offs, perm = O.route_from_logits(l)
+    assert idx.tolist() == [1, 0, 0, 2, 0]
+    assert offs.tolist() == [0, 3, 4, 5, 5] and perm.tolist() == [1, 2, 4, 0, 3]
+    assert np.isnan(gate[:4]).all() and np.isclose(gate[4], 1.0 / (2.0 + np.exp(-2.0) + np.exp(-5.0)))
+    # by hand, independent of argmax: scan each row for the first entry no other entry ranks above
+    def first_max(row):
+        rank = lambda v: (2, 0.0) if np.isnan(v) else (1, v)
+        best = max(rank(v) for v in row)
+        return next(i for i, v in enumerate(row) if rank(v) == best)
+    assert [first_max(r) for r in l] == idx.tolist()
