@@ -252,6 +252,25 @@ moqe_status moqe_moe_layer(const moqe_layer* layer /* host */, const moqe_f16* w
                            void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * moqe_moe_layer for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the same step with the same outputs,
+ * its scratch taken from an array inside the library instead of a workspace argument.  The
+ * array holds MOQE_STATIC_SCRATCH_BYTES on every GPU the library runs on, from the first call
+ * on that GPU until the process ends; a step whose moqe_layer_workspace_bytes(T, E, d, f)
+ * exceeds that is refused with MOQE_ERR_WORKSPACE before anything is launched (d_ff 4096:
+ * up to 255 tokens).  The call allocates and frees nothing; its first call on a device looks
+ * up the array's address (make that call outside a graph capture).  The array starts zeroed and
+ * carries state from call to call exactly as a caller's workspace does; every call on a GPU
+ * shares that GPU's array, so calls that may overlap on one GPU (two streams, two threads)
+ * race: issue them one after the other, or use moqe_moe_layer with a buffer per stream.
+ * Other arguments and errors as for moqe_moe_layer.
+ */
+#define MOQE_STATIC_SCRATCH_BYTES (4u << 20)
+moqe_status moqe_moe_layer_static(const moqe_layer* layer /* host */, const moqe_f16* w_gate, const moqe_f16* x,
+                                  int64_t T, int32_t* expert_idx, float* gate, int32_t* seg_offsets,
+                                  int32_t* perm, const moqe_f16* residual, moqe_f16* y, void* stream);
+
+/*
  * The two contractions of moqe_expert_ffn as separate calls, for callers that
  * time them or put other work between them.  h is fp16 [T,f] with rows in
  * sorted-token order (row i belongs to token perm[i]); moqe_expert_ffn keeps it

@@ -3,6 +3,7 @@
 // exercised without a GPU.
 #include <limits.h>
 #include <atomic>
+#include <mutex>
 #include <stdio.h>
 #include <string.h>
 
@@ -465,6 +466,62 @@ moqe_status moqe_moe_layer(const moqe_layer* L, const moqe_f16* w_gate, const mo
   if (!L || !w_gate || !x || !expert_idx || !gate || !seg_offsets || !perm || !y || !workspace) return MOQE_ERR_NULL;
   return run_layer(L, w_gate, x, T, expert_idx, gate, seg_offsets, perm, residual, y, workspace, workspace_bytes,
                    stream);
+}
+
+// ---------------------------------------------------------------------------
+// the layer step on the library's own scratch (callers that cannot allocate)
+// ---------------------------------------------------------------------------
+}  // extern "C"
+
+// What moqe_moe_layer takes as `workspace`, held by the library: one copy per GPU the library
+// runs on, zero when the code object is loaded (the state the single-launch mode wants to find)
+// and kept from call to call like a caller's buffer.  In host code this name is only a handle
+// for hipGetSymbolAddress; kernels get the address that call returns.
+static __device__ __align__(256) unsigned char moqe_static_scratch[MOQE_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+void* g_scratch_ptr[MAX_DEVICES];  // device address of moqe_static_scratch on each device, once known
+std::mutex g_scratch_mutex;
+
+// Address of the current device's copy of the scratch array (looked up once per device).
+moqe_status static_scratch(void** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e);
+  if (dev < 0 || dev >= MAX_DEVICES) return hip_fail(hipErrorInvalidDevice);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(moqe_static_scratch));
+    if (e != hipSuccess) return hip_fail(e);
+    if (!p) return hip_fail(hipErrorInvalidSymbol);
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return MOQE_OK;
+}
+}  // namespace
+
+extern "C" {
+
+moqe_status moqe_moe_layer_static(const moqe_layer* L, const moqe_f16* w_gate, const moqe_f16* x, int64_t T,
+                                  int32_t* expert_idx, float* gate, int32_t* seg_offsets, int32_t* perm,
+                                  const moqe_f16* residual, moqe_f16* y, void* stream) {
+  if (!L || !w_gate || !x || !expert_idx || !gate || !seg_offsets || !perm || !y) return MOQE_ERR_NULL;
+  moqe_status st = check_layer_ptrs(L);
+  if (st != MOQE_OK) return st;
+  if (T < 0 || T > MAX_TOKENS) return MOQE_ERR_SHAPE;
+  if (!aligned16(x) || !aligned16(expert_idx) || !aligned16(gate) || !aligned16(seg_offsets) || !aligned16(perm) ||
+      !aligned16(y) || (residual && !aligned16(residual)) || !aligned16(w_gate))
+    return MOQE_ERR_ALIGN;
+  // the scratch a caller of moqe_moe_layer would bring for these sizes must fit the array
+  const size_t need = moqe_layer_workspace_bytes(T, L->E, L->d, L->f);
+  if (need > (size_t)MOQE_STATIC_SCRATCH_BYTES) return MOQE_ERR_WORKSPACE;
+  void* scratch = nullptr;
+  st = static_scratch(&scratch);
+  if (st != MOQE_OK) return st;
+  return run_layer(L, w_gate, x, T, expert_idx, gate, seg_offsets, perm, residual, y, scratch, need, stream);
 }
 
 }  // extern "C"

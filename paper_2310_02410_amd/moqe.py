@@ -27,6 +27,7 @@ EXPORTS = (
     "moqe_route_logits", "moqe_expert_ffn", "moqe_expert_ffn1", "moqe_expert_ffn2",
     "moqe_layer_workspace_bytes", "moqe_moe_layer", "moqe_set_launch_mode",
     "moqe_set_prefill_policy", "moqe_quantize_tensor_scale", "moqe_quantize_log", "moqe_dequantize_log",
+    "moqe_moe_layer_static",
 )
 
 LAUNCH_AUTO, LAUNCH_SEPARATE, LAUNCH_FUSED = 0, 1, 2
@@ -87,6 +88,8 @@ def lib() -> ctypes.CDLL:
     L.moqe_layer_workspace_bytes.argtypes = [i64, i64, i64, i64]
     L.moqe_moe_layer.restype = ci
     L.moqe_moe_layer.argtypes = [ctypes.POINTER(CLayer), vp, vp, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.moqe_moe_layer_static.restype = ci
+    L.moqe_moe_layer_static.argtypes = [ctypes.POINTER(CLayer), vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
     L.moqe_quantize.restype = ci
     L.moqe_quantize.argtypes = [vp, i64, i64, i64, ci, vp, vp, vp]
     L.moqe_quantize_tensor_scale.restype = ci
@@ -367,6 +370,24 @@ def moqe_moe_layer(layer: QuantLayer, x: torch.Tensor, residual: torch.Tensor = 
                                 _ptr(route.gate), route.seg_offsets.data_ptr(), _ptr(route.perm), _ptr(residual),
                                 out.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream(stream)),
            "moqe_moe_layer")
+    return out, route
+
+
+STATIC_SCRATCH_BYTES = 4 << 20  # MOQE_STATIC_SCRATCH_BYTES of include/moqe.h
+
+
+def moqe_moe_layer_static(layer: QuantLayer, x: torch.Tensor, out: torch.Tensor, route: Route,
+                          residual: torch.Tensor = None, stream=None):
+    """moqe_moe_layer on the library's own scratch: the call itself allocates nothing, so the
+    caller brings every output (out fp16 [T,d], route)."""
+    _dev(x, torch.float16, "x")
+    if layer.w_gate is None:
+        raise ValueError("layer has no router weights")
+    cl = layer.c_struct()
+    _check(lib().moqe_moe_layer_static(ctypes.byref(cl), layer.w_gate.data_ptr(), x.data_ptr(), x.shape[0],
+                                       _ptr(route.expert_idx), _ptr(route.gate), route.seg_offsets.data_ptr(),
+                                       _ptr(route.perm), _ptr(residual), out.data_ptr(), _stream(stream)),
+           "moqe_moe_layer_static")
     return out, route
 
 

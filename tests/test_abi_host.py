@@ -169,6 +169,22 @@ def test_expert_ffn_error_paths():
     assert fused(layer(f=100)) == 3
     assert fused(layer(), wg=P + 2) == 4
     assert fused(layer(), wsb=moqe.moqe_ffn_workspace_bytes(8, 4, 64, 256)) == 5   # route scratch missing
+    # the same step on the library's own scratch: same checks, and sizes beyond the array refused
+    def static(lay, wg=P, x=P, T=8, idx=P, gate=P, seg=P, perm=P, res=None, y=P):
+        return L.moqe_moe_layer_static(ctypes.byref(lay) if lay is not None else None, wg, x, T, idx, gate, seg, perm,
+                                       res, y, None)
+
+    assert static(None) == 1
+    assert static(layer(), perm=0) == 1
+    assert static(layer(bits=7)) == 2
+    assert static(layer(d=48)) == 3
+    assert static(layer(), T=-1) == 3
+    assert static(layer(), y=P + 2) == 4
+    big = layer(E=32, d=1024, f=4096)
+    assert moqe.moqe_layer_workspace_bytes(255, 32, 1024, 4096) <= moqe.STATIC_SCRATCH_BYTES
+    assert moqe.moqe_layer_workspace_bytes(300, 32, 1024, 4096) > moqe.STATIC_SCRATCH_BYTES
+    assert static(big, T=300) == 5
+    assert static(big, T=4096) == 5
     assert L.moqe_expert_ffn1(ctypes.byref(layer()), P, 8, P, P, 0, None) == 1
     assert L.moqe_expert_ffn2(ctypes.byref(layer()), P, 8, P, P, P, None, P + 4, None) == 4
 

@@ -1,0 +1,74 @@
+"""The layer step on the library's own scratch (moqe_moe_layer_static, for callers that cannot
+allocate): same outputs as moqe_moe_layer on a caller's workspace, on two calls in a row, the
+second with a smaller batch, and the FFN output within the oracle's bound."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import moqe_oracle as O
+from paper_2310_02410_amd import moqe, workloads as W
+from tests.helpers import FFN_TOL, dev, ffn_error, gpu_quantize_layer, oracle_layer_output, route_to_numpy
+
+pytestmark = pytest.mark.gpu
+
+
+def _both(ql, x, residual):
+    """(static entry point, existing entry point) on the same inputs: outputs as numpy."""
+    T = x.shape[0]
+    res = x if residual else None
+    y_s, r_s = torch.empty_like(x), moqe.alloc_route(T, ql.E, x.device)[0]
+    moqe.moqe_moe_layer_static(ql, x, y_s, r_s, residual=res)
+    y_e, r_e = moqe.moqe_moe_layer(ql, x, residual=res)
+    torch.cuda.synchronize()
+    return (y_s.cpu().numpy(), route_to_numpy(r_s)), (y_e.cpu().numpy(), route_to_numpy(r_e))
+
+
+@pytest.mark.parametrize("bits,residual", [(4, False), (2, True), (3, False)])
+def test_two_calls_in_a_row_second_one_smaller(bits, residual):
+    wl = W.small("static", E=8, d=256, f=512, T=150, seed=31 + bits)
+    layer, x_all = W.make_layer(wl), W.make_tokens(wl)
+    ql = gpu_quantize_layer(layer, bits)
+    oq = O.quantize_layer(layer, bits)
+    for T in (150, 24):   # the second call leaves most of what the first wrote in the scratch untouched
+        x = x_all[:T]
+        (ys, rs), (ye, re) = _both(ql, dev(x), residual)
+        for a, b in zip(rs[:1] + rs[2:], re[:1] + re[2:]):
+            assert np.array_equal(a, b)                       # indices, offsets, permutation: bit-exact
+        assert np.array_equal(rs[1], re[1])                   # same kernels, same order of sums
+        ref_idx, ref_gate, ref_offs, ref_perm = O.route(x, layer["w_gate"])
+        assert np.array_equal(rs[0], ref_idx) and np.array_equal(rs[2], ref_offs) and np.array_equal(rs[3], ref_perm)
+        ref = oracle_layer_output(x, layer, bits, ref_idx, ref_gate, residual=residual, qlayer=oq)
+        assert ffn_error(ys, ref) <= FFN_TOL and ffn_error(ye, ref) <= FFN_TOL
+        assert ffn_error(ys, ye.astype(np.float64)) <= FFN_TOL
+        assert np.array_equal(ys, ye)
+
+
+def test_decode_step_at_full_size_then_smaller():
+    """The benchmarked shape (E=32, d_model 1024, d_ff 4096, 24 tokens, int4), then 5 tokens."""
+    wl = W.CONFIGS["c1"]
+    layer, x_all = W.make_layer(wl), W.make_tokens(wl)
+    ql = gpu_quantize_layer(layer, 4)
+    oq = O.quantize_layer(layer, 4)
+    for T in (24, 5):
+        x = x_all[:T]
+        (ys, rs), (ye, re) = _both(ql, dev(x), False)
+        for a, b in zip(rs, re):
+            assert np.array_equal(a, b)
+        idx, gate, _, _ = O.route(x, layer["w_gate"])
+        assert np.array_equal(rs[0], idx)
+        ref = oracle_layer_output(x, layer, 4, idx, gate, qlayer=oq)
+        assert ffn_error(ys, ref) <= FFN_TOL
+        assert np.array_equal(ys, ye)
+
+
+def test_sizes_beyond_the_array_are_refused():
+    wl = W.small("static_big", E=8, d=256, f=4096, T=300, seed=5)
+    layer = W.make_layer(wl)
+    ql = gpu_quantize_layer(layer, 4)
+    x = dev(W.make_tokens(wl))
+    assert moqe.moqe_layer_workspace_bytes(300, 8, 256, 4096) > moqe.STATIC_SCRATCH_BYTES
+    y, r = torch.empty_like(x), moqe.alloc_route(300, 8, x.device)[0]
+    with pytest.raises(moqe.MoqeError) as err:
+        moqe.moqe_moe_layer_static(ql, x, y, r)
+    assert err.value.status == 5
