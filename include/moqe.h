@@ -88,6 +88,14 @@ int moqe_version(void);
 enum { MOQE_LAUNCH_AUTO = 0, MOQE_LAUNCH_SEPARATE = 1, MOQE_LAUNCH_FUSED = 2 };
 int moqe_set_launch_mode(int mode);
 
+/* Which dequantize-in-register kernel serves decode-sized batches (a process-wide setting, for
+ * tests and comparisons; results are identical): AUTO takes the kernel specialised for batches
+ * of at most 64 tokens (at most 128 experts, 2- to 4-bit codes) where it applies and the
+ * general one elsewhere; GENERAL always takes the general one.  Launch mode FUSED uses the
+ * general kernel.  Returns the previous setting, or -1 (nothing changed) for an unknown one. */
+enum { MOQE_DECODE_AUTO = 0, MOQE_DECODE_GENERAL = 1 };
+int moqe_set_decode_kernel(int which);
+
 /* Path choice inside the expert FFN (process-wide, for tuning and tests; results are within
  * the same tolerance either way): in a batch of at least min_batch_tokens tokens, expert
  * segments with at least min_segment_tokens tokens are computed by the tiled MFMA kernel (token

@@ -51,6 +51,8 @@ std::atomic<int> g_launch_mode{MOQE_LAUNCH_AUTO};
 std::atomic<int> g_prefill_min{MOQE_PREFILL_MIN_SEGMENT_DEFAULT};
 std::atomic<int> g_prefill_batch{MOQE_PREFILL_MIN_BATCH_DEFAULT};
 std::atomic<int> g_prefill_all{MOQE_PREFILL_ALL_TILED_DEFAULT};
+// Decode-sized batches take the lean decode kernel where it applies (moqe_set_decode_kernel).
+std::atomic<int> g_small_decode{1};
 
 }  // namespace
 
@@ -79,6 +81,11 @@ int moqe_set_prefill_policy(int min_segment_tokens, int min_batch_tokens, int al
   g_prefill_batch.store(min_batch_tokens);
   g_prefill_all.store(all_tiled_tokens_per_expert);
   return 0;
+}
+
+int moqe_set_decode_kernel(int which) {
+  if (which != MOQE_DECODE_AUTO && which != MOQE_DECODE_GENERAL) return -1;
+  return g_small_decode.exchange(which == MOQE_DECODE_AUTO) ? MOQE_DECODE_AUTO : MOQE_DECODE_GENERAL;
 }
 
 int moqe_set_launch_mode(int mode) {
@@ -308,7 +315,33 @@ static hipError_t launch_contraction(DecodeArgs& a, int phase, int ksteps, hipSt
   a.max_tokens = split ? pmin : INT_MAX;
   // (with a threshold of one token every segment is the tiled kernel's: no decode launch)
   if (!split || pmin > 1) {
-    hipError_t e = moqe_launch_decode(a, num_cus(), stream);
+    hipError_t e;
+    if (g_small_decode.load() && moqe_decode_small_supported(a.bits, a.T, a.E, p.K, p.N, num_cus())) {
+      // decode-sized batch: the lean kernel (one pair per workgroup)
+      SmallDecodeArgs s;
+      memset(&s, 0, sizeof(s));
+      s.bits = a.bits;
+      s.ksteps = ksteps;
+      s.ksplit = p.ksplit;
+      s.mode = p.mode;
+      s.E = a.E;
+      s.T = a.T;
+      s.N = p.N;
+      s.min_tokens = a.min_tokens;
+      s.max_tokens = a.max_tokens;
+      s.codes = p.codes;
+      s.scales = p.scales;
+      s.bias = p.bias;
+      s.a = p.a;
+      s.out = p.out;
+      s.residual = p.residual;
+      s.gate = a.gate;
+      s.seg_offsets = a.seg_offsets;
+      s.perm = a.perm;
+      e = moqe_launch_decode_small(s, num_cus(), stream);
+    } else {
+      e = moqe_launch_decode(a, num_cus(), stream);
+    }
     if (e != hipSuccess || !split) return e;
   }
   PrefillArgs q;

@@ -1,0 +1,422 @@
+// One expert contraction of a decode-sized batch (at most 64 tokens, at most 128 experts) as a
+// fused dequantize-in-register grouped GEMM, bound by the packed weight bytes it reads:
+//
+//   out[rows of expert e, n] = epilogue( sum_k a[row, k] * (Q_e[k, n] * s_e[n]) + b_e[n] )
+// (paper Sec. 2.1 two-layer FFN, App. A dequantization A' = Q s; the per-channel scale
+// multiplies the finished K-sum because it does not depend on k).
+//
+// A step of this size moves a few tens of MB and lasts microseconds, so the kernel is built
+// around the latencies in front of and behind the weight stream rather than around throughput:
+//   * every wave reads the routing tables itself, with three loads into registers (one round
+//     trip, no LDS staging, no workgroup barrier), and finds its work with ballots;
+//   * a workgroup serves ONE pair (expert, tile of up to 4 of its tokens): the persistent grid
+//     is split into as many equal groups as there are pairs and a group's workgroups share the
+//     pair's column tiles.  A wave therefore parks its token rows in LDS once, computes the
+//     K-sum of the code offsets once, and after that only streams weights;
+//   * all requests of a wave's first two units are issued at once (token rows first, then 16 KiB
+//     of packed codes) and the code from there to the last store is free of branches that hold
+//     memory operations: loads and stores take an empty buffer descriptor or an out-of-range
+//     offset where a unit, a row or a lane has nothing to do.  Loads return in order under one
+//     counter, and only in such code does the compiler wait for exactly the chunk it is about
+//     to unpack while the younger ones stay in flight - the unpack and the MFMAs of a chunk then
+//     run under the latency of the next one.
+//
+// Work decomposition: unit = (pair, column tile of 16 channels); `R` waves of a workgroup share a
+// unit along K (each owns 32*KS rows, partial sums meet in LDS), 4/R teams per workgroup.  Codes go
+// straight from registers into v_mfma_f32_16x16x32_f16 as the B operand (see moqe_unpack.h), the
+// token rows are the A operand (rows 4..15 of a fragment read a row of zeros).
+#include "moqe_dev.h"
+#include "moqe_kernels.h"
+#include "moqe_unpack.h"
+
+namespace {
+
+constexpr int WG_THREADS = 256;
+constexpr int WG_WAVES = 4;
+constexpr int TILE_ROWS = 4;
+#ifndef MOQE_SMALL_WG_PER_CU
+#define MOQE_SMALL_WG_PER_CU 3
+#endif
+constexpr int MIN_WAVES = MOQE_SMALL_WG_PER_CU;  // workgroups per CU the register and LDS budgets are sized for
+constexpr uint32_t NOWHERE = 0x80000000u;  // a buffer offset beyond every descriptor: loads give 0, stores vanish
+
+// Inclusive prefix sum over the 64 lanes.
+__device__ inline int wave_inclusive_scan(int v) {
+  const int lane = lane_id();
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int o = __shfl_up(v, off, 64);
+    if (lane >= off) v += o;
+  }
+  return v;
+}
+
+__device__ inline int read_lane(int v, int l) { return __builtin_amdgcn_readlane(v, l); }
+__device__ inline float read_lane(float v, int l) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
+}
+
+// Packed words of one unit (16 channels x this wave's K-slice) as one lane holds them.
+template <int BITS, int KS>
+struct UnitWords {
+  using S = Shape<BITS, KS>;
+  uint32_t lo[S::NCH * S::LW];
+  uint32_t hi[S::FB == 3 ? S::NCH * S::HW : 1];
+};
+
+// What a wave knows about a unit besides its packed words.
+struct Unit {
+  bool active;       // (wave-uniform) an inactive unit loads nothing and stores nothing
+  int col;           // column tile
+  rsrc_t codes;      // this wave's K-slice of the unit's packed words (empty when inactive)
+  uint16_t sc, bi;   // fp16 scale and bias of the lane's channel
+  uint16_t res[TILE_ROWS];  // MODE 1: residual of the lane's channel for the pair's tokens (0 without one)
+};
+
+// MODE 0: rows of `a` by token (through perm), out = relu(.) by sorted position (FFN1 -> h)
+// MODE 1: rows of `a` by sorted position, out = gate * (.) (+ residual) by token (FFN2 -> y)
+template <int BITS, int KS, int MODE>
+__global__ __launch_bounds__(WG_THREADS, MIN_WAVES) void moe_decode_small_kernel(SmallDecodeArgs A) {
+  using S = Shape<BITS, KS>;
+  using Words = UnitWords<BITS, KS>;
+  constexpr int PIECES = KS * 4;             // 16-byte pieces of a row slice
+  constexpr int NPL = (PIECES + 63) / 64;    // pieces per lane and row
+  constexpr int ROW_PIECES = NPL * 64 + 4;   // parked row: whole wave-loads, padded by 64 bytes against bank conflicts
+  constexpr int ZERO_ROW = WG_WAVES * TILE_ROWS;
+  constexpr uint32_t UNIT_BYTES = S::NCH * S::CHUNK_WORDS * 4;
+
+  __shared__ uint4_t s_x[WG_WAVES * TILE_ROWS + 1][ROW_PIECES];
+  __shared__ float4_t s_red[2][WG_WAVES][16];
+
+  UnpackConsts<BITS> uc;
+  uc.init();
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = uniform_i32(tid >> 6);
+  const int grp = lane >> 4;  // MFMA row group (k sub-block for A/B, token quad for D)
+  const int j = lane & 15;    // token row for A, channel for B and D
+  const int E = A.E, T = A.T, N = A.N, R = A.ksplit;
+  const int K = 32 * KS * R;
+  const int G = (int)gridDim.x, bid = (int)blockIdx.x;
+
+  // ---- one round trip: the routing tables into registers (lane e: expert e and e + 64; lane t: token t) ----
+  const rsrc_t seg_rs = make_rsrc(A.seg_offsets, (uint32_t)(E + 1) * 4u);
+  const rsrc_t tok_rs = make_rsrc(A.perm, (uint32_t)T * 4u);
+  const uint32_t l4 = (uint32_t)lane * 4u;
+  int s0 = (int)__builtin_amdgcn_raw_buffer_load_b32(seg_rs, l4, 0, 0);
+  int s1 = (int)__builtin_amdgcn_raw_buffer_load_b32(seg_rs, l4 + 4u, 0, 0);
+  int s2 = (int)__builtin_amdgcn_raw_buffer_load_b32(seg_rs, l4 + 256u, 0, 0);
+  int s3 = (int)__builtin_amdgcn_raw_buffer_load_b32(seg_rs, l4 + 260u, 0, 0);
+  int pm = (int)__builtin_amdgcn_raw_buffer_load_b32(tok_rs, l4, 0, 0);
+  float gt = 0.0f;
+  if constexpr (MODE == 1)
+    gt = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(make_rsrc(A.gate, (uint32_t)T * 4u), l4, 0, 0));
+  // the zero row, while the tables travel (every wave writes the same zeros and reads only after
+  // its own writes)
+  {
+#pragma unroll
+    for (int i = 0; i < NPL; ++i) s_x[ZERO_ROW][64 * i + lane] = uint4_t{0, 0, 0, 0};
+  }
+  // (tables a caller made up are clamped into range: a wild row or token index must not become
+  // a wild address)
+  s0 = min(max(s0, 0), T);
+  s2 = min(max(s2, 0), T);
+  const int n0 = lane < E ? min(max(s1 - s0, 0), T - s0) : 0;
+  const int n1 = lane + 64 < E ? min(max(s3 - s2, 0), T - s2) : 0;
+  pm = min(max(pm, 0), T - 1);
+
+  // ---- token tiles per expert, their prefix, the pair this workgroup serves ----
+  const int t0 = (n0 >= A.min_tokens && n0 < A.max_tokens) ? (n0 + TILE_ROWS - 1) / TILE_ROWS : 0;
+  const int t1 = (n1 >= A.min_tokens && n1 < A.max_tokens) ? (n1 + TILE_ROWS - 1) / TILE_ROWS : 0;
+  const int incl0 = wave_inclusive_scan(t0);
+  const int tot0 = read_lane(incl0, 63);
+  int incl1 = tot0, P = tot0;
+  if (E > 64) {  // (uniform)
+    incl1 = tot0 + wave_inclusive_scan(t1);
+    P = read_lane(incl1, 63);
+  }
+  if (P <= 0) return;
+  const int wpp = max(1, G / P);  // workgroups per pair
+  const int pair = bid / wpp, slot = bid - pair * wpp;
+  if (pair >= P) return;
+  // (lanes past the last expert hold the total, which no pair index reaches)
+  int e = __popcll(__ballot(incl0 <= pair));
+  if (E > 64) e += __popcll(__ballot(incl1 <= pair));
+  e = uniform_i32(min(e, E - 1));
+  const bool upper = e >= 64;
+  const int el = e & 63;
+  const int first = read_lane(upper ? incl1 - t1 : incl0 - t0, el);
+  const int seg0 = read_lane(upper ? s2 : s0, el);
+  const int n_e = read_lane(upper ? n1 : n0, el);
+  const int m = pair - first;
+  const int row0 = seg0 + TILE_ROWS * m;  // sorted position of the pair's first token
+  const int rows_valid = min(TILE_ROWS, n_e - TILE_ROWS * m);
+  int tk[TILE_ROWS];  // the pair's tokens
+#pragma unroll
+  for (int r = 0; r < TILE_ROWS; ++r) tk[r] = read_lane(pm, (row0 + r) & 63);
+
+  // ---- this workgroup's column tiles, this wave's place in it ----
+  const int CT = N >> 4;
+  const int cbase = CT / wpp, crem = CT - cbase * wpp;
+  const int c_begin = slot * cbase + min(slot, crem);
+  const int c_end = c_begin + cbase + (slot < crem ? 1 : 0);
+  const int teams = WG_WAVES / R, team = wave / R, ks = wave - team * R;
+  const int nl = (c_end - c_begin + teams - 1) / teams;  // units per team, the same for every wave
+  if (nl <= 0) return;
+
+  const int Q = K / (32 * S::SC);  // chunks per column tile
+  const int64_t matrix_words = (int64_t)K * N * S::FB / 32;
+  const uint32_t* const codes_e = A.codes + (int64_t)e * matrix_words + (int64_t)ks * S::NCH * S::CHUNK_WORDS;
+  const rsrc_t scale_rs = make_rsrc((const uint16_t*)A.scales + (int64_t)e * N, (uint32_t)N * 2u);
+  const rsrc_t bias_rs = make_rsrc((const uint16_t*)A.bias + (int64_t)e * N, (uint32_t)N * 2u);
+  const rsrc_t res_rs = make_rsrc(A.residual, (MODE == 1 && A.residual) ? (uint32_t)T * (uint32_t)N * 2u : 0u);
+  const rsrc_t out_rs = make_rsrc(A.out, (uint32_t)T * (uint32_t)N * 2u);
+
+  auto make_unit = [&](int it) -> Unit {
+    Unit u;
+    u.col = c_begin + team + it * teams;
+    u.active = it < nl && u.col < c_end;
+    u.codes = make_rsrc(codes_e + (int64_t)u.col * Q * S::CHUNK_WORDS, u.active ? UNIT_BYTES : 0u);
+    const uint32_t unit_nowhere = u.active ? 0u : NOWHERE;
+    const uint32_t ch = ((uint32_t)(16 * u.col + j) * 2u) | unit_nowhere;
+    u.sc = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(scale_rs, ch, 0, 0);
+    u.bi = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(bias_rs, ch, 0, 0);
+#pragma unroll
+    for (int r = 0; r < TILE_ROWS; ++r) {
+      u.res[r] = 0;
+      if constexpr (MODE == 1) {
+        const uint32_t at = (((uint32_t)tk[r] * (uint32_t)N + (uint32_t)(16 * u.col + j)) * 2u) | unit_nowhere |
+                            (r < rows_valid ? 0u : NOWHERE);
+        u.res[r] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(res_rs, at, 0, 0);
+      }
+    }
+    return u;
+  };
+  const uint32_t lane_lo = (uint32_t)lane * S::LW * 4, lane_hi = (64u * S::LW + (uint32_t)lane * S::HW) * 4;
+  auto issue_chunk = [&](Words& b, rsrc_t r, int ch) {
+    load_words<S::LW>(r, lane_lo + ch * S::CHUNK_WORDS * 4, &b.lo[ch * S::LW]);
+    if constexpr (S::FB == 3) load_words<S::HW>(r, lane_hi + ch * S::CHUNK_WORDS * 4, &b.hi[ch * S::HW]);
+  };
+
+  // ---- all first requests at once: token rows, then the first two units ----
+  // rows: this wave's K-slice of the pair's rows, 16 bytes per lane; rows the pair does not have
+  // and pieces past the slice read as zeros
+  const rsrc_t a_rs = make_rsrc(A.a, (uint32_t)T * (uint32_t)K * 2u);
+  uint4_t rows[TILE_ROWS][NPL];
+#pragma unroll
+  for (int r = 0; r < TILE_ROWS; ++r) {
+    const uint32_t arow = MODE == 0 ? (uint32_t)tk[r] : (uint32_t)(row0 + r);
+    const uint32_t rbase = (arow * (uint32_t)K + (uint32_t)ks * (KS * 32)) * 2u;
+#pragma unroll
+    for (int i = 0; i < NPL; ++i) {
+      const int q = 64 * i + lane;
+      const uint32_t off = (r < rows_valid && q < PIECES) ? rbase + (uint32_t)q * 16u : NOWHERE;
+      rows[r][i] = __builtin_amdgcn_raw_buffer_load_b128(a_rs, off, 0, 0);
+    }
+  }
+  Unit uA = make_unit(0), uB = make_unit(1);
+  Words wA, wB;
+#pragma unroll
+  for (int ch = 0; ch < S::NCH; ++ch) issue_chunk(wA, uA.codes, ch);
+#pragma unroll
+  for (int ch = 0; ch < S::NCH; ++ch) issue_chunk(wB, uB.codes, ch);
+
+  // park the rows: lane (grp, j) later reads row j, k = 32 s + 8 grp .. +7 of this wave's slice
+  uint4_t(*patch)[ROW_PIECES] = &s_x[wave * TILE_ROWS];
+#pragma unroll
+  for (int r = 0; r < TILE_ROWS; ++r)
+#pragma unroll
+    for (int i = 0; i < NPL; ++i) patch[r][64 * i + lane] = rows[r][i];
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  const uint4_t* const afrag = j < TILE_ROWS ? &patch[j][grp] : &s_x[ZERO_ROW][grp];
+
+  // offsets the unpacked values carry (exponent bias + zero point), summed against the rows once
+  // for the pair (log-scale codes unpack to their exact values: nothing to remove)
+  float4_t corr = {0, 0, 0, 0};
+  if constexpr (!moqe_is_log(BITS)) {
+    float4_t c0 = {0, 0, 0, 0}, c1 = {0, 0, 0, 0};
+#pragma unroll
+    for (int s = 0; s < KS; s += 2) {
+      c0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, afrag[4 * s]), bias_frag<BITS>(0), c0, 0, 0, 0);
+      c1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, afrag[4 * s + 4]), bias_frag<BITS>(1), c1, 0,
+                                                  0, 0);
+    }
+    corr = c0 + c1;
+  }
+
+  // gate of the pair's tokens (MODE 1)
+  float g[TILE_ROWS];
+#pragma unroll
+  for (int r = 0; r < TILE_ROWS; ++r) g[r] = MODE == 1 ? read_lane(gt, tk[r] & 63) : 1.0f;
+
+  // Consumes the unit in `b` chunk by chunk; as soon as a chunk's words are unpacked the same
+  // registers are refilled with the matching chunk of unit `nx` (two units ahead).
+  auto compute_unit = [&](Words& b, const Unit& u, const Unit& nx) -> float4_t {
+    float4_t acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
+#pragma unroll
+    for (int ch = 0; ch < S::NCH; ++ch) {
+      // A wave without this unit skips the arithmetic and nothing else: the reloads below are
+      // issued on every path, so that all paths have the same history of memory operations.
+      // (The flag is made opaque per chunk: were the chunks' tests merged into one, the
+      // compiler would lay the unit out as two separate sequences of loads again.)
+      int act = uniform_i32((int)u.active);
+      asm volatile("" : "+s"(act));
+      if (act) {
+#pragma unroll
+        for (int s1 = 0; s1 < S::SC; ++s1) {
+          const int s = ch * S::SC + s1;
+          half8_t w;
+          if constexpr (BITS == 4) {
+            w = unpack4(b.lo[ch * S::LW + s1], uc);
+          } else if constexpr (BITS == MOQE_LOG4) {
+            w = unpack4_log(b.lo[ch * S::LW + s1], uc);
+          } else if constexpr (BITS == MOQE_LOG3) {
+            const uint32_t d = b.lo[ch * S::LW + (s1 >> 1)], hd = b.hi[ch * S::HW + (s1 >> 2)];
+            w = (s1 & 3) == 0 ? unpack3_log<0>(d, hd, uc) : (s1 & 3) == 1 ? unpack3_log<1>(d, hd, uc)
+              : (s1 & 3) == 2 ? unpack3_log<2>(d, hd, uc) : unpack3_log<3>(d, hd, uc);
+          } else if constexpr (BITS == MOQE_LOG2) {
+            const uint32_t d = b.lo[ch * S::LW + (s1 >> 1)];
+            w = (s1 & 1) ? unpack2_log<1>(d, uc) : unpack2_log<0>(d, uc);
+          } else {
+            const uint32_t d = b.lo[ch * S::LW + (s1 >> 1)];
+            w = (s1 & 1) ? unpack2<1>(d, uc) : unpack2<0>(d, uc);
+          }
+          const half8_t a = __builtin_bit_cast(half8_t, afrag[4 * s]);
+          acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, w, acc0, 0, 0, 0);
+          if constexpr (BITS == 3) {  // the 1-bit plane as a second MFMA
+            const uint32_t hd = b.hi[ch * S::HW + (s1 >> 2)];
+            const half8_t wh = (s1 & 3) == 0 ? unpack1x4<0>(hd, uc) : (s1 & 3) == 1 ? unpack1x4<1>(hd, uc)
+                             : (s1 & 3) == 2 ? unpack1x4<2>(hd, uc) : unpack1x4<3>(hd, uc);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, wh, acc1, 0, 0, 0);
+          }
+        }
+      }
+      issue_chunk(b, nx.codes, ch);  // the chunk's words are consumed: refill two units ahead
+    }
+    return acc0 + acc1 - corr;
+  };
+
+  // where the pair's output rows start (bytes), and the top bit for rows the pair does not have
+  // and for lanes that hold no result
+  uint32_t out_row[TILE_ROWS], out_row_nowhere[TILE_ROWS];
+#pragma unroll
+  for (int r = 0; r < TILE_ROWS; ++r) {
+    out_row[r] = (uint32_t)(MODE == 0 ? row0 + r : tk[r]) * (uint32_t)N * 2u;
+    out_row_nowhere[r] = r < rows_valid ? 0u : NOWHERE;
+  }
+  const uint32_t lane_nowhere = (ks == 0 && lane < 16) ? 0u : NOWHERE;
+
+  int par = 0;
+  auto finish_unit = [&](const Unit& u, float4_t part) {
+    // the pair's rows are rows 0..3 of the MFMA tile: lanes 0..15 hold them, one channel each
+    if (R > 1) {  // (uniform; every wave of the workgroup runs the same number of units)
+      if (lane < 16) s_red[par][wave][lane] = part;
+      __syncthreads();
+      if (ks == 0 && lane < 16) {
+        for (int q = 1; q < R; ++q) part = part + s_red[par][wave + q][lane];
+      }
+      par ^= 1;
+    }
+    const float sc = (float)half_from_bits(u.sc);
+    const float bi = (float)half_from_bits(u.bi);
+    // one 2-byte store per row from lanes 0..15 of the team's first wave; everything else is
+    // sent NOWHERE by or-ing the top bit into the offset (the sums stay below 2^31)
+    const uint32_t unit_off = ((uint32_t)(16 * u.col + j) * 2u) | (u.active ? lane_nowhere : NOWHERE);
+#pragma unroll
+    for (int r = 0; r < TILE_ROWS; ++r) {
+      float o = fmaf(part[r], sc, bi);
+      if constexpr (MODE == 0) {
+        o = fmaxf(o, 0.0f);  // ReLU
+      } else {
+        o = fmaf(g[r], o, (float)half_from_bits(u.res[r]));
+      }
+      const uint16_t hb = half_to_bits((half_t)o);
+      __builtin_amdgcn_raw_buffer_store_b16(hb, out_rs, (out_row[r] + unit_off) | out_row_nowhere[r], 0, 0);
+    }
+  };
+
+  for (int it = 0; it < nl; it += 2) {
+    {
+      const Unit nA = make_unit(it + 2);
+      const float4_t part = compute_unit(wA, uA, nA);
+      finish_unit(uA, part);
+      uA = nA;
+    }
+    {
+      const Unit nB = make_unit(it + 3);
+      const float4_t part = compute_unit(wB, uB, nB);
+      finish_unit(uB, part);
+      uB = nB;
+    }
+  }
+}
+
+// Workgroups per CU of one instantiation on the current device (asked once per device).
+template <int BITS, int KS, int MODE>
+int resident_per_cu() {
+  static int cache[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 1;
+  if (cache[dev] == 0) {
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, moe_decode_small_kernel<BITS, KS, MODE>, WG_THREADS, 0) != hipSuccess ||
+        n < 1)
+      n = 1;
+    cache[dev] = n > MIN_WAVES ? MIN_WAVES : n;
+  }
+  return cache[dev];
+}
+
+template <int BITS, int KS>
+hipError_t launch_mode(const SmallDecodeArgs& a, int num_cus, hipStream_t stream) {
+  if (a.mode == 0) {
+    hipLaunchKernelGGL((moe_decode_small_kernel<BITS, KS, 0>), dim3(resident_per_cu<BITS, KS, 0>() * num_cus),
+                       dim3(WG_THREADS), 0, stream, a);
+  } else {
+    hipLaunchKernelGGL((moe_decode_small_kernel<BITS, KS, 1>), dim3(resident_per_cu<BITS, KS, 1>() * num_cus),
+                       dim3(WG_THREADS), 0, stream, a);
+  }
+  return hipGetLastError();
+}
+
+template <int BITS>
+hipError_t launch_bits(const SmallDecodeArgs& a, int num_cus, hipStream_t stream) {
+  switch (a.ksteps) {
+    case 32: return launch_mode<BITS, 32>(a, num_cus, stream);
+    case 24: return launch_mode<BITS, 24>(a, num_cus, stream);
+    case 16: return launch_mode<BITS, 16>(a, num_cus, stream);
+    case 8: return launch_mode<BITS, 8>(a, num_cus, stream);
+    case 4: return launch_mode<BITS, 4>(a, num_cus, stream);
+    case 2:
+      if constexpr (moqe_field_bits(BITS) != 3) return launch_mode<BITS, 2>(a, num_cus, stream);
+      return hipErrorInvalidValue;
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace
+
+bool moqe_decode_small_supported(int bits, int64_t T, int64_t E, int64_t K, int64_t N, int grid_min) {
+  const int fb = moqe_field_bits(bits);
+  if (fb != 2 && fb != 3 && fb != 4) return false;
+  // (every pair needs a workgroup of its own, and there are at most T pairs)
+  if (T < 1 || T > 64 || T > grid_min || E < 1 || E > 128) return false;
+  // rows and outputs are addressed with 32-bit byte offsets inside their buffers
+  if (T * K * 2 >= (1ll << 31) || T * N * 2 >= (1ll << 31)) return false;
+  int ks = 0, r = 0;
+  return moqe_pick_ksplit(bits > 100 ? fb : bits, K, &ks, &r);
+}
+
+hipError_t moqe_launch_decode_small(const SmallDecodeArgs& a, int num_cus, hipStream_t stream) {
+  switch (a.bits) {
+    case 4: return launch_bits<4>(a, num_cus, stream);
+    case 3: return launch_bits<3>(a, num_cus, stream);
+    case 2: return launch_bits<2>(a, num_cus, stream);
+    case MOQE_LOG4: return launch_bits<MOQE_LOG4>(a, num_cus, stream);
+    case MOQE_LOG3: return launch_bits<MOQE_LOG3>(a, num_cus, stream);
+    case MOQE_LOG2: return launch_bits<MOQE_LOG2>(a, num_cus, stream);
+    default: return hipErrorInvalidValue;
+  }
+}

@@ -89,7 +89,29 @@ struct PrefillArgs {
 bool moqe_prefill_supported(int bits, int64_t K, int64_t N);
 hipError_t moqe_launch_prefill(const PrefillArgs& a, int num_cus, hipStream_t stream);
 
-// Dequantize-in-register path for few tokens per expert (tiles of 4 tokens).
+// One contraction of a decode-sized batch (T <= 64, E <= 128, 2- to 4-bit codes): the lean
+// dequantize-in-register kernel, one pair (expert, 4 tokens) per workgroup.
+struct SmallDecodeArgs {
+  int bits, ksteps, ksplit;  // K = 32 * ksteps * ksplit
+  int mode;                  // as in PhaseArgs
+  int E, T, N;
+  int min_tokens, max_tokens;  // expert segments with min_tokens <= n < max_tokens are handled
+  const uint32_t* codes;
+  const uint16_t* scales;
+  const uint16_t* bias;
+  const uint16_t* a;
+  uint16_t* out;
+  const uint16_t* residual;  // mode 1, may be NULL
+  const float* gate;         // mode 1
+  const int* seg_offsets;
+  const int* perm;
+};
+// (bits as the kernels are instantiated: 2, 3, 4 or MOQE_LOG2..4; grid_min = workgroups the
+// launch will have at least: one per CU)
+bool moqe_decode_small_supported(int bits, int64_t T, int64_t E, int64_t K, int64_t N, int grid_min);
+hipError_t moqe_launch_decode_small(const SmallDecodeArgs& a, int num_cus, hipStream_t stream);
+
+// Dequantize-in-register path for few tokens per expert (tiles of 4 tokens), any batch size.
 hipError_t moqe_launch_decode(const DecodeArgs& a, int num_cus, hipStream_t stream);
 // Picks (ksteps, ksplit) for a contraction length K; false if unsupported.
 bool moqe_pick_ksplit(int bits, int64_t K, int* ksteps, int* ksplit);

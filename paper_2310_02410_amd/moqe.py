@@ -27,7 +27,7 @@ EXPORTS = (
     "moqe_route_logits", "moqe_expert_ffn", "moqe_expert_ffn1", "moqe_expert_ffn2",
     "moqe_layer_workspace_bytes", "moqe_moe_layer", "moqe_set_launch_mode",
     "moqe_set_prefill_policy", "moqe_quantize_tensor_scale", "moqe_quantize_log", "moqe_dequantize_log",
-    "moqe_moe_layer_static",
+    "moqe_moe_layer_static", "moqe_set_decode_kernel",
 )
 
 LAUNCH_AUTO, LAUNCH_SEPARATE, LAUNCH_FUSED = 0, 1, 2
@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
     L.moqe_version.restype = ci
     L.moqe_set_launch_mode.restype = ci
     L.moqe_set_launch_mode.argtypes = [ci]
+    L.moqe_set_decode_kernel.restype = ci
+    L.moqe_set_decode_kernel.argtypes = [ci]
     L.moqe_set_prefill_policy.restype = ci
     L.moqe_set_prefill_policy.argtypes = [ci, ci, ci]
     L.moqe_packed_bytes.restype = sz
@@ -159,6 +161,18 @@ def moqe_set_launch_mode(mode: int) -> int:
     old = lib().moqe_set_launch_mode(mode)
     if old < 0:
         raise ValueError(f"unknown launch mode {mode}")
+    return old
+
+
+DECODE_AUTO, DECODE_GENERAL = 0, 1
+
+
+def moqe_set_decode_kernel(which: int) -> int:
+    """Process-wide: DECODE_AUTO (the kernel specialised for batches of at most 64 tokens where it
+    applies) or DECODE_GENERAL (always the general decode kernel); returns the old setting."""
+    old = lib().moqe_set_decode_kernel(which)
+    if old < 0:
+        raise ValueError(f"unknown decode kernel choice {which}")
     return old
 
 
