@@ -11,20 +11,31 @@
 //     trip, no LDS staging, no workgroup barrier), and finds its work with ballots;
 //   * a workgroup serves ONE pair (expert, tile of up to 4 of its tokens): the persistent grid
 //     is split into as many equal groups as there are pairs and a group's workgroups share the
-//     pair's column tiles.  A wave therefore parks its token rows in LDS once, computes the
-//     K-sum of the code offsets once, and after that only streams weights;
-//   * all requests of a wave's first two units are issued at once (token rows first, then 16 KiB
-//     of packed codes) and the code from there to the last store is free of branches that hold
-//     memory operations: loads and stores take an empty buffer descriptor or an out-of-range
-//     offset where a unit, a row or a lane has nothing to do.  Loads return in order under one
-//     counter, and only in such code does the compiler wait for exactly the chunk it is about
-//     to unpack while the younger ones stay in flight - the unpack and the MFMAs of a chunk then
-//     run under the latency of the next one.
+//     pair's column tiles, so a wave needs one set of token rows for all its units;
+//   * the token rows ride along with the weights: a CU's (and the memory fabric's) requests are
+//     served in order, so rows asked for on their own arrive behind whatever weights other waves
+//     asked for a moment earlier - measured: microseconds late, with all arithmetic left for the
+//     end.  Instead a wave's first unit asks for the rows in blocks of 128 columns, each block
+//     directly in front of the weight chunk that meets it (one 16-byte load per lane brings the
+//     block of all four rows), parks a block in LDS when its chunk is due, and folds the K-sum of
+//     the code offsets into the same steps; later units find the rows in LDS;
+//   * a wave keeps a window of four chunks (4 KiB of packed codes) in flight and refills a slot
+//     as soon as its chunk is unpacked.  A wave issues in order: while it is still queueing
+//     requests it cannot start on data that has already arrived, and a CU takes only so many
+//     requests at a time, so asking for a unit or two up front (measured) held every wave in the
+//     request queue for microseconds and left the arithmetic for the end;
+//   * from the first request to the last store the code is free of branches that hold memory
+//     operations: loads and stores take an empty buffer descriptor or an out-of-range offset
+//     where a unit, a row or a lane has nothing to do.  Loads return in order under one counter,
+//     and only in such code does the compiler wait for exactly the chunk it is about to unpack
+//     while the younger ones stay in flight.
 //
 // Work decomposition: unit = (pair, column tile of 16 channels); `R` waves of a workgroup share a
 // unit along K (each owns 32*KS rows, partial sums meet in LDS), 4/R teams per workgroup.  Codes go
 // straight from registers into v_mfma_f32_16x16x32_f16 as the B operand (see moqe_unpack.h), the
 // token rows are the A operand (rows 4..15 of a fragment read a row of zeros).
+#include <type_traits>
+
 #include "moqe_dev.h"
 #include "moqe_kernels.h"
 #include "moqe_unpack.h"
@@ -38,6 +49,20 @@ constexpr int TILE_ROWS = 4;
 #define MOQE_SMALL_WG_PER_CU 3
 #endif
 constexpr int MIN_WAVES = MOQE_SMALL_WG_PER_CU;  // workgroups per CU the register and LDS budgets are sized for
+#ifndef MOQE_SMALL_WINDOW
+#define MOQE_SMALL_WINDOW 4
+#endif
+// Chunks (1 KiB of packed codes, 1.5 KiB for 3-bit codes) a wave has in flight at most.  A wave
+// issues in order: while it is still queueing requests it cannot start on data that is already
+// there, so asking for everything up front leaves the arithmetic for the end; a window that
+// just covers the latency keeps request and arithmetic going side by side.
+constexpr int MAX_WINDOW = MOQE_SMALL_WINDOW;
+// (the window divides the chunks of a unit, so that a chunk's slot is known at compile time)
+constexpr int window_chunks(int nch) {
+  int w = nch < MAX_WINDOW ? nch : MAX_WINDOW;
+  while (nch % w) --w;
+  return w;
+}
 constexpr uint32_t NOWHERE = 0x80000000u;  // a buffer offset beyond every descriptor: loads give 0, stores vanish
 
 // Inclusive prefix sum over the 64 lanes.
@@ -56,12 +81,12 @@ __device__ inline float read_lane(float v, int l) {
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
 }
 
-// Packed words of one unit (16 channels x this wave's K-slice) as one lane holds them.
-template <int BITS, int KS>
-struct UnitWords {
+// Packed words of the chunks in flight (WIN slots) as one lane holds them.
+template <int BITS, int KS, int WIN>
+struct WindowWords {
   using S = Shape<BITS, KS>;
-  uint32_t lo[S::NCH * S::LW];
-  uint32_t hi[S::FB == 3 ? S::NCH * S::HW : 1];
+  uint32_t lo[WIN * S::LW];
+  uint32_t hi[S::FB == 3 ? WIN * S::HW : 1];
 };
 
 // What a wave knows about a unit besides its packed words.
@@ -78,11 +103,16 @@ struct Unit {
 template <int BITS, int KS, int MODE>
 __global__ __launch_bounds__(WG_THREADS, MIN_WAVES) void moe_decode_small_kernel(SmallDecodeArgs A) {
   using S = Shape<BITS, KS>;
-  using Words = UnitWords<BITS, KS>;
-  constexpr int PIECES = KS * 4;             // 16-byte pieces of a row slice
-  constexpr int NPL = (PIECES + 63) / 64;    // pieces per lane and row
-  constexpr int ROW_PIECES = NPL * 64 + 4;   // parked row: whole wave-loads, padded by 64 bytes against bank conflicts
+  constexpr int WIN = window_chunks(S::NCH);  // chunks in flight
+  using Words = WindowWords<BITS, KS, WIN>;
+  constexpr int PIECES = KS * 4;          // 16-byte pieces of a row slice (8 columns each)
+  constexpr int ROW_PIECES = PIECES + 4;  // parked row, padded by 64 bytes against bank conflicts
   constexpr int ZERO_ROW = WG_WAVES * TILE_ROWS;
+  // token rows travel in blocks of (up to) 4 steps = 128 columns of all four rows: 16 lanes per row
+  constexpr int BLK_PER_CHUNK = S::SC >= 4 ? S::SC / 4 : 1;
+  constexpr int BLK_STEPS = S::SC / BLK_PER_CHUNK;
+  constexpr int BLK_PIECES = BLK_STEPS * 4;  // pieces of one row in a block
+  constexpr int NBLK = S::NCH * BLK_PER_CHUNK;
   constexpr uint32_t UNIT_BYTES = S::NCH * S::CHUNK_WORDS * 4;
 
   __shared__ uint4_t s_x[WG_WAVES * TILE_ROWS + 1][ROW_PIECES];
@@ -115,7 +145,8 @@ __global__ __launch_bounds__(WG_THREADS, MIN_WAVES) void moe_decode_small_kernel
   // its own writes)
   {
 #pragma unroll
-    for (int i = 0; i < NPL; ++i) s_x[ZERO_ROW][64 * i + lane] = uint4_t{0, 0, 0, 0};
+    for (int i = 0; i < (PIECES + 63) / 64; ++i)
+      if (64 * i + lane < PIECES) s_x[ZERO_ROW][64 * i + lane] = uint4_t{0, 0, 0, 0};
   }
   // (tables a caller made up are clamped into range: a wild row or token index must not become
   // a wild address)
@@ -193,68 +224,65 @@ __global__ __launch_bounds__(WG_THREADS, MIN_WAVES) void moe_decode_small_kernel
     return u;
   };
   const uint32_t lane_lo = (uint32_t)lane * S::LW * 4, lane_hi = (64u * S::LW + (uint32_t)lane * S::HW) * 4;
+  // chunk ch of a unit into window slot ch % WIN
   auto issue_chunk = [&](Words& b, rsrc_t r, int ch) {
-    load_words<S::LW>(r, lane_lo + ch * S::CHUNK_WORDS * 4, &b.lo[ch * S::LW]);
-    if constexpr (S::FB == 3) load_words<S::HW>(r, lane_hi + ch * S::CHUNK_WORDS * 4, &b.hi[ch * S::HW]);
+    const int slot = ch % WIN;
+    load_words<S::LW>(r, lane_lo + ch * S::CHUNK_WORDS * 4, &b.lo[slot * S::LW]);
+    if constexpr (S::FB == 3) load_words<S::HW>(r, lane_hi + ch * S::CHUNK_WORDS * 4, &b.hi[slot * S::HW]);
   };
 
-  // ---- all first requests at once: token rows, then the first two units ----
-  // rows: this wave's K-slice of the pair's rows, 16 bytes per lane; rows the pair does not have
-  // and pieces past the slice read as zeros
+  // ---- the first requests: the first WIN chunks of the first unit, the token rows woven in ----
+  // row block b: lane (r, p) = (lane / 16, lane % 16) asks for piece p of the block of row r; rows
+  // the pair does not have and pieces past the block read as zeros
   const rsrc_t a_rs = make_rsrc(A.a, (uint32_t)T * (uint32_t)K * 2u);
-  uint4_t rows[TILE_ROWS][NPL];
-#pragma unroll
-  for (int r = 0; r < TILE_ROWS; ++r) {
-    const uint32_t arow = MODE == 0 ? (uint32_t)tk[r] : (uint32_t)(row0 + r);
-    const uint32_t rbase = (arow * (uint32_t)K + (uint32_t)ks * (KS * 32)) * 2u;
-#pragma unroll
-    for (int i = 0; i < NPL; ++i) {
-      const int q = 64 * i + lane;
-      const uint32_t off = (r < rows_valid && q < PIECES) ? rbase + (uint32_t)q * 16u : NOWHERE;
-      rows[r][i] = __builtin_amdgcn_raw_buffer_load_b128(a_rs, off, 0, 0);
-    }
+  const int rr = lane >> 4, rp = lane & 15;
+  uint32_t row_off;  // byte offset of this lane's piece of block 0
+  {
+    const int tok = rr == 0 ? tk[0] : rr == 1 ? tk[1] : rr == 2 ? tk[2] : tk[3];
+    const uint32_t arow = MODE == 0 ? (uint32_t)tok : (uint32_t)(row0 + rr);
+    row_off = (rr < rows_valid && rp < BLK_PIECES) ? (arow * (uint32_t)K + (uint32_t)ks * (KS * 32) + (uint32_t)rp * 8u) * 2u
+                                                   : NOWHERE;
   }
-  Unit uA = make_unit(0), uB = make_unit(1);
-  Words wA, wB;
+  uint4_t rows[WIN * BLK_PER_CHUNK];  // row blocks in flight, slot as for the chunks
+  auto issue_rows = [&](int ch) {
 #pragma unroll
-  for (int ch = 0; ch < S::NCH; ++ch) issue_chunk(wA, uA.codes, ch);
+    for (int bi = 0; bi < BLK_PER_CHUNK; ++bi) {
+      const int b = ch * BLK_PER_CHUNK + bi;
+      rows[(ch % WIN) * BLK_PER_CHUNK + bi] = __builtin_amdgcn_raw_buffer_load_b128(a_rs, row_off + (uint32_t)(b * BLK_STEPS * 64), 0, 0);
+    }
+  };
+  // (the scheduling fences keep the requests in this order: the scale and bias, which the first
+  // store waits for, in front of everything, each row block in front of its chunk)
+  Unit uA = make_unit(0);
+  __builtin_amdgcn_sched_barrier(0);
+  Words wA;
 #pragma unroll
-  for (int ch = 0; ch < S::NCH; ++ch) issue_chunk(wB, uB.codes, ch);
+  for (int ch = 0; ch < WIN; ++ch) {
+    issue_rows(ch);
+    issue_chunk(wA, uA.codes, ch);
+    __builtin_amdgcn_sched_barrier(0);
+  }
 
-  // park the rows: lane (grp, j) later reads row j, k = 32 s + 8 grp .. +7 of this wave's slice
+  // where the rows are parked: lane (grp, j) reads row j, k = 32 s + 8 grp .. +7 of this wave's slice
   uint4_t(*patch)[ROW_PIECES] = &s_x[wave * TILE_ROWS];
-#pragma unroll
-  for (int r = 0; r < TILE_ROWS; ++r)
-#pragma unroll
-    for (int i = 0; i < NPL; ++i) patch[r][64 * i + lane] = rows[r][i];
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   const uint4_t* const afrag = j < TILE_ROWS ? &patch[j][grp] : &s_x[ZERO_ROW][grp];
-
-  // offsets the unpacked values carry (exponent bias + zero point), summed against the rows once
-  // for the pair (log-scale codes unpack to their exact values: nothing to remove)
+  // offsets the unpacked values carry (exponent bias + zero point), summed against the rows by
+  // the first unit (log-scale codes unpack to their exact values: nothing to remove)
   float4_t corr = {0, 0, 0, 0};
-  if constexpr (!moqe_is_log(BITS)) {
-    float4_t c0 = {0, 0, 0, 0}, c1 = {0, 0, 0, 0};
-#pragma unroll
-    for (int s = 0; s < KS; s += 2) {
-      c0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, afrag[4 * s]), bias_frag<BITS>(0), c0, 0, 0, 0);
-      c1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, afrag[4 * s + 4]), bias_frag<BITS>(1), c1, 0,
-                                                  0, 0);
-    }
-    corr = c0 + c1;
-  }
 
   // gate of the pair's tokens (MODE 1)
   float g[TILE_ROWS];
 #pragma unroll
   for (int r = 0; r < TILE_ROWS; ++r) g[r] = MODE == 1 ? read_lane(gt, tk[r] & 63) : 1.0f;
 
-  // Consumes the unit in `b` chunk by chunk; as soon as a chunk's words are unpacked the same
-  // registers are refilled with the matching chunk of unit `nx` (two units ahead).
-  auto compute_unit = [&](Words& b, const Unit& u, const Unit& nx) -> float4_t {
+  // Consumes unit `u` chunk by chunk; as soon as a chunk's words are unpacked its slot is
+  // refilled with the chunk WIN further on, of this unit or of the next one, `nx`.  The wave's
+  // first unit (FIRST) also parks the row blocks as they arrive, asks for the later ones in
+  // front of their chunks, and accumulates `corr`.
+  auto compute_unit = [&](auto first_tag, Words& b, const Unit& u, const Unit& nx) -> float4_t {
+    constexpr bool FIRST = decltype(first_tag)::value;
     float4_t acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
+    float4_t c0 = {0, 0, 0, 0}, c1 = {0, 0, 0, 0};
 #pragma unroll
     for (int ch = 0; ch < S::NCH; ++ch) {
       // A wave without this unit skips the arithmetic and nothing else: the reloads below are
@@ -263,38 +291,59 @@ __global__ __launch_bounds__(WG_THREADS, MIN_WAVES) void moe_decode_small_kernel
       // compiler would lay the unit out as two separate sequences of loads again.)
       int act = uniform_i32((int)u.active);
       asm volatile("" : "+s"(act));
+      if constexpr (FIRST) {
+#pragma unroll
+        for (int bi = 0; bi < BLK_PER_CHUNK; ++bi) {
+          const int blk = ch * BLK_PER_CHUNK + bi;
+          if (rp < BLK_PIECES) patch[rr][blk * BLK_PIECES + rp] = rows[(ch % WIN) * BLK_PER_CHUNK + bi];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      }
       if (act) {
 #pragma unroll
         for (int s1 = 0; s1 < S::SC; ++s1) {
           const int s = ch * S::SC + s1;
           half8_t w;
           if constexpr (BITS == 4) {
-            w = unpack4(b.lo[ch * S::LW + s1], uc);
+            w = unpack4(b.lo[(ch % WIN) * S::LW + s1], uc);
           } else if constexpr (BITS == MOQE_LOG4) {
-            w = unpack4_log(b.lo[ch * S::LW + s1], uc);
+            w = unpack4_log(b.lo[(ch % WIN) * S::LW + s1], uc);
           } else if constexpr (BITS == MOQE_LOG3) {
-            const uint32_t d = b.lo[ch * S::LW + (s1 >> 1)], hd = b.hi[ch * S::HW + (s1 >> 2)];
+            const uint32_t d = b.lo[(ch % WIN) * S::LW + (s1 >> 1)], hd = b.hi[(ch % WIN) * S::HW + (s1 >> 2)];
             w = (s1 & 3) == 0 ? unpack3_log<0>(d, hd, uc) : (s1 & 3) == 1 ? unpack3_log<1>(d, hd, uc)
               : (s1 & 3) == 2 ? unpack3_log<2>(d, hd, uc) : unpack3_log<3>(d, hd, uc);
           } else if constexpr (BITS == MOQE_LOG2) {
-            const uint32_t d = b.lo[ch * S::LW + (s1 >> 1)];
+            const uint32_t d = b.lo[(ch % WIN) * S::LW + (s1 >> 1)];
             w = (s1 & 1) ? unpack2_log<1>(d, uc) : unpack2_log<0>(d, uc);
           } else {
-            const uint32_t d = b.lo[ch * S::LW + (s1 >> 1)];
+            const uint32_t d = b.lo[(ch % WIN) * S::LW + (s1 >> 1)];
             w = (s1 & 1) ? unpack2<1>(d, uc) : unpack2<0>(d, uc);
           }
           const half8_t a = __builtin_bit_cast(half8_t, afrag[4 * s]);
           acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, w, acc0, 0, 0, 0);
+          if constexpr (FIRST && !moqe_is_log(BITS)) {
+            if (s & 1) c1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bias_frag<BITS>(1), c1, 0, 0, 0);
+            else c0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bias_frag<BITS>(0), c0, 0, 0, 0);
+          }
           if constexpr (BITS == 3) {  // the 1-bit plane as a second MFMA
-            const uint32_t hd = b.hi[ch * S::HW + (s1 >> 2)];
+            const uint32_t hd = b.hi[(ch % WIN) * S::HW + (s1 >> 2)];
             const half8_t wh = (s1 & 3) == 0 ? unpack1x4<0>(hd, uc) : (s1 & 3) == 1 ? unpack1x4<1>(hd, uc)
                              : (s1 & 3) == 2 ? unpack1x4<2>(hd, uc) : unpack1x4<3>(hd, uc);
             acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, wh, acc1, 0, 0, 0);
           }
         }
       }
-      issue_chunk(b, nx.codes, ch);  // the chunk's words are consumed: refill two units ahead
+      // the chunk's words are consumed: refill its slot WIN chunks ahead
+      if (ch + WIN < S::NCH) {
+        if constexpr (FIRST) issue_rows(ch + WIN);
+        issue_chunk(b, u.codes, ch + WIN);
+      } else {
+        issue_chunk(b, nx.codes, ch + WIN - S::NCH);
+      }
     }
+    if constexpr (FIRST) corr = c0 + c1;
     return acc0 + acc1 - corr;
   };
 
@@ -337,19 +386,17 @@ __global__ __launch_bounds__(WG_THREADS, MIN_WAVES) void moe_decode_small_kernel
     }
   };
 
-  for (int it = 0; it < nl; it += 2) {
-    {
-      const Unit nA = make_unit(it + 2);
-      const float4_t part = compute_unit(wA, uA, nA);
-      finish_unit(uA, part);
-      uA = nA;
-    }
-    {
-      const Unit nB = make_unit(it + 3);
-      const float4_t part = compute_unit(wB, uB, nB);
-      finish_unit(uB, part);
-      uB = nB;
-    }
+  {
+    const Unit nA = make_unit(1);
+    const float4_t part = compute_unit(std::true_type{}, wA, uA, nA);
+    finish_unit(uA, part);
+    uA = nA;
+  }
+  for (int it = 1; it < nl; ++it) {
+    const Unit nA = make_unit(it + 1);
+    const float4_t part = compute_unit(std::false_type{}, wA, uA, nA);
+    finish_unit(uA, part);
+    uA = nA;
   }
 }
 
@@ -371,6 +418,9 @@ int resident_per_cu() {
 
 template <int BITS, int KS>
 hipError_t launch_mode(const SmallDecodeArgs& a, int num_cus, hipStream_t stream) {
+  // A persistent grid split evenly over the pairs.  (A grid sized for the largest possible number
+  // of pairs with one unit per wave, handed out by the hardware as slots become free, measured
+  // 1.5 us slower: every late workgroup pays the table round trip again.)
   if (a.mode == 0) {
     hipLaunchKernelGGL((moe_decode_small_kernel<BITS, KS, 0>), dim3(resident_per_cu<BITS, KS, 0>() * num_cus),
                        dim3(WG_THREADS), 0, stream, a);
