@@ -14,8 +14,10 @@ one: the weights really come from HBM.
 
 Prints ONE JSON line: tokens/s (metric), ms per step, the roofline of the dominant
 kernel (algorithmic bytes or flops per launch / measured kernel time, against the
-8 TB/s HBM peak or the 2.5 PFLOP/s fp16 MFMA peak) and the CPU oracle timed on the
-host's cores on a bounded sample of the same workload.
+8 TB/s HBM peak or the 2.5 PFLOP/s fp16 MFMA peak; for the HBM-bound workloads also
+against a plain streaming read of the same number of bytes measured in the same run)
+and the CPU oracle timed on the host's cores on a bounded sample of the same workload.
+The decode workloads (c1, c2) time int4, int3 and int2 experts (`by_bits`).
 """
 
 from __future__ import annotations
@@ -36,11 +38,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 MFMA_F16_PEAK_TFLOPS = 2500.0
 
-# HBM traffic per launch of the dominant kernel (FFN1 of c1) measured with rocprofv3 --pmc
-# (FETCH_SIZE and WRITE_SIZE runs of this script, scaled by a 256 MiB device copy in the
-# same run: FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); from profiles/decode_c1_int4_hbm_traffic.txt.
-# Not measured for the other workloads and bit widths.
-MEASURED_TRAFFIC_BYTES = {("c1", 4): 35390084}
+# HBM traffic per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
+# WRITE_SIZE runs of this script, each scaled by what the same counter reads for a 256 MiB
+# device copy in the same run); from the profiles/*_hbm_traffic.txt summaries.  None where no
+# counter run was made.
+MEASURED_TRAFFIC_BYTES = {}
 
 
 def parse():
@@ -57,9 +59,11 @@ def parse():
                     help="log: log-scale codes (App. A) instead of linear ones; needs --bits 2, 3 or 4")
     ap.add_argument("--copies", type=int, default=None, help="independent layer copies cycled through "
                     "(default 8; 12 for the c4 stack: its 12 layers)")
-    ap.add_argument("--other-bits", action="store_true", help="also time the other widths (fp16, 8, 4, 3, 2)")
+    ap.add_argument("--other-bits", action="store_true", help="also time the remaining widths (fp16, int8, and 4 / 3 / "
+                    "2 bits where the workload does not time them anyway)")
+    ap.add_argument("--only-bits", action="store_true", help="time the headline width alone")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-steps", type=int, default=None, help="oracle steps timed (default 8; 1 from 512 tokens on)")
+    ap.add_argument("--cpu-steps", type=int, default=None, help="oracle steps timed, the median is reported (default 5; 1 from 512 tokens on)")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches only")
     ap.add_argument("--parts", action="store_true", help="also time each kernel of the step on its own")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
@@ -117,18 +121,22 @@ def main():
     E, d, f, T = wl.E, wl.d, wl.f, wl.T
     residual = wl.layers > 1               # the stack adds the layer's output to its input
     compute_bound = T >= 512               # the tiled MFMA kernel dominates, not the weight stream
-    bits0 = args.bits if args.bits is not None else wl.bits[0]
     global LOG_CODEC
     LOG_CODEC = args.codec == "log"
+    bits0 = args.bits if args.bits is not None else wl.bits[0]
     if LOG_CODEC and bits0 not in (2, 3, 4):
         print("bench.py: --codec log needs --bits 2, 3 or 4", file=sys.stderr)
         sys.exit(2)
-    bit_list = [bits0] + ([b for b in (16, 8, 4, 3, 2) if b != bits0] if args.other_bits else [])
+    # the metric is quoted at int4 / int3 / int2: the decode workloads time all three
+    decode_set = [4, 3, 2] if (wl.name in ("c1", "c2") and not LOG_CODEC and not args.only_bits) else []
+    bit_list = [bits0] + [b for b in decode_set if b != bits0]
+    if args.other_bits:
+        bit_list += [b for b in (16, 8, 4, 3, 2) if b not in bit_list]
     copies = args.copies if args.copies is not None else (12 if wl.layers > 1 else 8)
     steps, warmup = args.steps, args.warmup
     if compute_bound and steps == 400 and warmup == 40:
         steps, warmup = 100, 10            # defaults sized to keep the timed work near a minute at most
-    cpu_steps = args.cpu_steps if args.cpu_steps is not None else (1 if compute_bound else 8)
+    cpu_steps = args.cpu_steps if args.cpu_steps is not None else (1 if compute_bound else 5)
 
     # ---- layer copies: generated on the host (seeded), quantized on the device ----
     t0 = time.time()
@@ -211,7 +219,9 @@ def main():
 
     def time_graph(run, nsteps, nwarm):
         """The same calls captured once per layer copy into ONE graph (a pass over all copies),
-        replayed: launch cost leaves the picture.  Returns event ms per call."""
+        replayed: launch cost leaves the picture.  At least 10 replays, each timed by its own
+        pair of events.  Returns (ms per step over all replays together, median and min over the
+        replays of a replay's ms per step)."""
         side = torch.cuda.Stream()
         with torch.cuda.stream(side):
             g = torch.cuda.CUDAGraph()
@@ -219,9 +229,38 @@ def main():
                 for k in range(copies):
                     run(k, torch.cuda.current_stream().cuda_stream)
         torch.cuda.synchronize()
-        reps = max(1, nsteps // copies)
-        _, ev = time_steps(lambda i: g.replay(), reps, max(1, nwarm // copies))
-        return ev / copies
+        reps = max(10, nsteps // copies)
+        for _ in range(max(2, nwarm // copies)):
+            g.replay()
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        ev[0].record()
+        for i in range(reps):
+            g.replay()
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        each = np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(reps)]) / copies
+        return ev[0].elapsed_time(ev[reps]) / reps / copies, float(np.median(each)), float(each.min())
+
+    # ---- the ceiling: a plain streaming read of as many bytes as the dominant kernel's launch
+    # must read, on memory that is not cache resident (an arena twice the last-level cache,
+    # walked launch by launch), in the decode kernels' launch shape ----
+    arena = torch.empty(768 << 20, dtype=torch.uint8, device="cuda").fill_(1) if not compute_bound else None
+    sink = torch.zeros(64, dtype=torch.uint8, device="cuda")
+
+    def time_stream_read(nbytes, nlaunch=200):
+        nbytes = max(1024, int(nbytes) // 1024 * 1024)
+        stride = (nbytes + (2 << 20) - 1) // (2 << 20) * (2 << 20)
+        slots = arena.numel() // stride
+        stream = torch.cuda.current_stream().cuda_stream
+        base, sp = arena.data_ptr(), sink.data_ptr()
+
+        def go(i):
+            st = L.moqe_stream_read(base + (i % slots) * stride, nbytes, sp, stream)
+            if st:
+                raise RuntimeError(f"moqe_stream_read failed with status {st}")
+        _, ev = time_steps(go, nlaunch, 20)
+        return ev * 1e3  # us per launch, back to back
 
     kbits = lambda b: 100 + b if (LOG_CODEC and b in (2, 3, 4)) else b  # the width the kernels are instantiated on
     results = {}
@@ -239,7 +278,7 @@ def main():
             raise RuntimeError("a phase wait timed out: results invalid")
         # ---- the timed region: K whole steps ----
         eager_ms, eager_ev_ms = time_steps(lambda i: step(i, stream), steps, warmup)
-        graph_ms = None if args.no_graph else time_graph(step, steps, warmup)
+        graph_ms, graph_med_ms, graph_min_ms = (None, None, None) if args.no_graph else time_graph(step, steps, warmup)
         # ---- the step's kernels on their own: the same launches through the per-step entry
         # points, K of them back to back between two HIP events on the launch stream.  The
         # dominant kernel is the expert contraction (FFN1 and FFN2 run the same kernel on
@@ -248,11 +287,7 @@ def main():
         # committed profile summaries list both populations.
         parts = {}
         for name, fn in (("router", router), ("ffn1", ffn1), ("ffn2", ffn2)):
-            if name == "router" and not args.parts:
-                continue
-            if name == "ffn2" and not (args.parts or compute_bound):
-                continue
-            _, ev = time_steps(lambda i: fn(i, stream), steps, warmup)
+            _, ev = time_steps(lambda i: fn(i, stream), max(steps, 100), warmup)
             parts[name + "_back_to_back_us"] = ev * 1e3
         if moqe.workspace_error(ws):
             raise RuntimeError("a phase wait timed out: results invalid")
@@ -260,7 +295,12 @@ def main():
         layer_bytes = float(np.mean([a[1] + a[2] for a in ab])) + 2 * d * E
         ffn1_bytes = float(np.mean([a[1] for a in ab]))
         best_ms = min(eager_ms, graph_ms) if graph_ms is not None else eager_ms
-        res = dict(ms_per_step=best_ms, eager_ms=eager_ms, graph_ms=graph_ms, tokens_per_s=T / (best_ms * 1e-3),
+        # what a step takes beyond its three kernels launched back to back on their own: inside a
+        # step each kernel starts on an idle chip behind a different predecessor (the profile
+        # summaries under profiles/ list the in-step durations kernel by kernel)
+        parts["step_minus_parts_us"] = best_ms * 1e3 - sum(v for k, v in parts.items() if k.endswith("_back_to_back_us"))
+        res = dict(ms_per_step=best_ms, eager_ms=eager_ms, graph_ms=graph_ms, graph_median_ms=graph_med_ms,
+                   graph_min_ms=graph_min_ms, tokens_per_s=T / (best_ms * 1e-3),
                    active_experts=float(np.mean([a[0] for a in ab])), layer_bytes=layer_bytes, parts=parts,
                    step_gbs=layer_bytes / (best_ms * 1e-3) / 1e9, step_tflops=4.0 * T * d * f / (best_ms * 1e-3) / 1e12)
         if compute_bound:
@@ -274,10 +314,14 @@ def main():
                               "averaged)" % kbits(b))
         else:
             kern_us = parts["ffn1_back_to_back_us"]
-            res.update(bound="hbm", kernel_us=kern_us, kernel_work=ffn1_bytes,
+            read_us = time_stream_read(ffn1_bytes)
+            res.update(bound="hbm", kernel_us=kern_us, kernel_work=ffn1_bytes, ceiling_us=read_us,
+                       ceiling_gbs=ffn1_bytes / (read_us * 1e-6) / 1e9,
                        achieved=ffn1_bytes / (kern_us * 1e-6) / 1e9, peak=HBM_PEAK_GBS, unit="GB/s",
-                       kernel="moe_decode_kernel<%d,*,2> (FFN1; FFN2 is the same kernel on a matrix of the same "
-                              "size)" % kbits(b))
+                       kernel=("moe_decode_small_kernel<%d,*,0> (FFN1; FFN2 is the same kernel, mode 1, on a matrix of "
+                               "the same size)" if b in (2, 3, 4) and T <= 64 and E <= 128 else
+                               "moe_decode_kernel<%d,*,2> (FFN1; FFN2 is the same kernel on a matrix of the same "
+                               "size)") % kbits(b))
         results[b] = res
         if b == 16 and not compute_bound:
             res["kernel"] = "moe_prefill_kernel<16,2> (FFN1; fp16 experts run on the tiled kernel at every batch size)"
@@ -306,15 +350,17 @@ def main():
                     return O.dequantize_log(O.unpack(self.codes[e], bits0, self.K, self.N), self.scales[e], bits0)
                 return O.dequantize(O.unpack(self.codes[e], bits0, self.K, self.N), self.scales[e])
 
-        t = time.perf_counter()
+        times = []
         for _ in range(cpu_steps):
+            t = time.perf_counter()
             idx, gate, offs, perm = O.route(x_host, layer0_host["w_gate"])
             O.expert_ffn(x_host, idx, gate, Lazy(c1, s1, d, f), layer0_host["b1"], Lazy(c2, s2, f, d),
                          layer0_host["b2"], residual=x_host if residual else None)
-        dt = time.perf_counter() - t
-        cpu = dict(value=T * cpu_steps / dt, unit="tokens/s", cores=cores, kind="oracle",
-                   sample=f"{cpu_steps} step(s) of route + expert FFN on layer copy 0 (T={T}, {wname(bits0)}, fp64, "
-                          f"codes unpacked per call), {dt:.1f} s")
+            times.append(time.perf_counter() - t)
+        med = float(np.median(times))
+        cpu = dict(value=T / med, unit="tokens/s", cores=cores, kind="oracle",
+                   sample=f"median of {cpu_steps} step(s) of route + expert FFN on layer copy 0 (T={T}, {wname(bits0)}, fp64, "
+                          f"codes unpacked per call), {sum(times):.1f} s in all, fastest step {min(times):.2f} s")
 
     r = results[bits0]
     out = {
@@ -330,19 +376,31 @@ def main():
                                                            ", fp16 residual add" if residual else "", wl.seed, copies),
                    "launch": "hip graph replay" if (r["graph_ms"] is not None and r["graph_ms"] <= r["eager_ms"]) else "eager",
                    "eager_ms_per_step": r["eager_ms"], "graph_ms_per_step": r["graph_ms"],
+                   "graph_replay_ms_per_step_median": r["graph_median_ms"], "graph_replay_ms_per_step_min": r["graph_min_ms"],
                    "active_experts": r["active_experts"], "layer_algorithmic_bytes": r["layer_bytes"],
                    "step_gb_per_s": r["step_gbs"], "step_tflop_per_s": r["step_tflops"], "kernels_us": r["parts"]},
         "roofline": {"bound": r["bound"], "achieved": r["achieved"], "peak": r["peak"], "unit": r["unit"],
                      "frac": r["achieved"] / r["peak"], "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, bits0)),
                      "kernel": r["kernel"], "avg_kernel_us": r["kernel_us"],
+                     **({"ceiling_gb_per_s": r["ceiling_gbs"], "frac_of_ceiling": r["achieved"] / r["ceiling_gbs"],
+                         "ceiling": "plain streaming read of the same number of bytes (moqe_stream_read, back to back "
+                                    "on memory that is not cache resident): %.2f us per launch" % r["ceiling_us"]}
+                        if r["bound"] == "hbm" else {}),
                      ("algorithmic_flops_per_launch" if r["bound"] == "mfma" else "algorithmic_bytes_per_launch"):
                          r["kernel_work"]},
         "cpu_baseline": cpu,
     }
     if len(results) > 1:
         out["by_bits"] = {str(b): {"tokens_per_s": v["tokens_per_s"], "ms_per_step": v["ms_per_step"],
+                                   "graph_replay_ms_per_step_median": v["graph_median_ms"],
+                                   "graph_replay_ms_per_step_min": v["graph_min_ms"],
                                    "kernel_achieved": v["achieved"], "unit": v["unit"],
-                                   "frac_of_peak": v["achieved"] / v["peak"], "avg_kernel_us": v["kernel_us"]}
+                                   "frac_of_peak": v["achieved"] / v["peak"], "avg_kernel_us": v["kernel_us"],
+                                   **({"ceiling_gb_per_s": v["ceiling_gbs"], "frac_of_ceiling": v["achieved"] / v["ceiling_gbs"]}
+                                      if v["bound"] == "hbm" else {}),
+                                   "algorithmic_bytes_per_launch" if v["bound"] == "hbm" else "algorithmic_flops_per_launch":
+                                       v["kernel_work"],
+                                   "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, b)), "kernels_us": v["parts"]}
                           for b, v in results.items()}
     print(json.dumps(out))
 

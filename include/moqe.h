@@ -9,10 +9,16 @@
  *
  * Conventions shared by every call
  *   - Every pointer is a DEVICE pointer unless its comment says "host".
- *   - The caller owns every buffer.  The library allocates nothing, keeps no
- *     state between calls, never synchronises and never frees: each call
- *     validates its arguments on the host, enqueues kernels on `stream`
- *     (a hipStream_t passed as void*, NULL = the null stream) and returns.
+ *   - The caller owns every buffer.  The library allocates nothing, never frees and
+ *     (moqe_workspace_status apart) never synchronises: each call validates its
+ *     arguments on the host, enqueues kernels on `stream` (a hipStream_t passed as
+ *     void*, NULL = the null stream) and returns.
+ *   - State the library keeps between calls: three process-wide tuning settings
+ *     (moqe_set_launch_mode, moqe_set_decode_kernel, moqe_set_prefill_policy; plain
+ *     atomics, results do not depend on them), per-device cached device properties,
+ *     and the array behind moqe_moe_layer_static.  Everything else that survives a
+ *     call lives in the caller's FFN / layer workspace (see the *_workspace_bytes
+ *     functions below).
  *   - Device buffers must be 16-byte aligned (MOQE_ERR_ALIGN otherwise).
  *   - Argument errors are reported before anything is launched, so a failed
  *     call leaves all outputs untouched.  A failed launch returns
@@ -67,7 +73,8 @@ typedef enum {
   MOQE_ERR_SHAPE = 3,     /* a dimension is negative, zero where it may not be, or unsupported */
   MOQE_ERR_ALIGN = 4,     /* a device pointer is not 16-byte aligned */
   MOQE_ERR_WORKSPACE = 5, /* workspace_bytes is smaller than the matching *_workspace_bytes() */
-  MOQE_ERR_HIP = 6        /* the HIP runtime refused a launch */
+  MOQE_ERR_HIP = 6,       /* the HIP runtime refused a launch */
+  MOQE_ERR_TIMEOUT = 7    /* moqe_workspace_status: a wait inside a single-launch step timed out */
 } moqe_status;
 
 /* Human-readable name of a status; static storage, never NULL. */
@@ -133,11 +140,28 @@ int moqe_check_layer(int bits, int64_t E, int64_t d, int64_t f);
  * after that any mix of calls and batch sizes may use it, one call at a time (calls that
  * may run concurrently need scratch buffers of their own).  The 32-bit word at byte 640
  * is an error flag: it becomes 1 and stays 1 if a wait inside a launch ever timed out
- * (buffer not zeroed, or the device shared so that the grid was not resident); outputs
- * are then invalid and the buffer has to be zeroed again. */
+ * (buffer not zeroed, or the device shared so that the grid was not resident).  The calls
+ * themselves cannot report that - they return before the kernels run - so every wait is
+ * bounded, the grid always drains, the outputs of that and of every later FUSED call on
+ * the buffer are invalid, and moqe_workspace_status tells: zero the buffer again after it
+ * returned MOQE_ERR_TIMEOUT.  Only launch mode FUSED has such waits. */
 size_t moqe_route_workspace_bytes(int64_t T, int64_t E);
 size_t moqe_ffn_workspace_bytes(int64_t T, int64_t E, int64_t d, int64_t f);
 size_t moqe_layer_workspace_bytes(int64_t T, int64_t E, int64_t d, int64_t f); /* for moqe_moe_layer */
+/* Waits for the work queued on `stream`, then reads the workspace's error flag (a 4-byte
+ * copy to the host): MOQE_OK, or MOQE_ERR_TIMEOUT if a wait of a FUSED launch that used this
+ * FFN / layer workspace has timed out since the buffer was last zeroed.  The one call of
+ * the library that synchronises; meant for after a batch of steps, not for the hot loop.
+ * workspace NULL: MOQE_ERR_NULL; smaller than 1024 bytes: MOQE_ERR_WORKSPACE. */
+moqe_status moqe_workspace_status(const void* workspace, size_t workspace_bytes, void* stream);
+
+/* Measurement aid: a launch that only reads `bytes` bytes (a multiple of 1024) from src with
+ * 16-byte streaming loads, in the launch shape of the decode kernels, and writes at most four
+ * bytes to sink.  Its duration on buffers that are not cache resident is the ceiling this
+ * machine sets for a kernel that must read that many bytes; bench.py reports the expert
+ * kernels' rate against it.  MOQE_ERR_SHAPE if bytes is 0, not a multiple of 1024, or 2 GiB
+ * and more. */
+moqe_status moqe_stream_read(const void* src, size_t bytes, void* sink, void* stream);
 
 /*
  * Offline round-to-nearest quantization and bit packing of a stack of E

@@ -35,9 +35,6 @@ int num_cus() {
   return cache[dev];
 }
 
-#ifdef MOQE_PHASE_TRACE
-long long* g_trace = nullptr;  // debug builds only: set through moqe_debug_set_trace
-#endif
 
 constexpr int64_t MAX_TOKENS = 1 << 22;
 constexpr int64_t MAX_EXPERTS = 1024;
@@ -67,6 +64,7 @@ const char* moqe_status_string(int status) {
     case MOQE_ERR_ALIGN: return "MOQE_ERR_ALIGN: device pointer not 16-byte aligned";
     case MOQE_ERR_WORKSPACE: return "MOQE_ERR_WORKSPACE: workspace too small";
     case MOQE_ERR_HIP: return "MOQE_ERR_HIP: HIP runtime error";
+    case MOQE_ERR_TIMEOUT: return "MOQE_ERR_TIMEOUT: a wait inside a single-launch step timed out";
     default: return "unknown status";
   }
 }
@@ -93,9 +91,6 @@ int moqe_set_launch_mode(int mode) {
   return g_launch_mode.exchange(mode);
 }
 
-#ifdef MOQE_PHASE_TRACE
-void moqe_debug_set_trace(long long* p) { g_trace = p; }
-#endif
 
 // 2, 3, 4, 8: quantized codes; 16: unquantized fp16 weights (the paper's baseline row)
 static bool valid_bits(int bits) { return bits == 2 || bits == 3 || bits == 4 || bits == 8 || bits == 16; }
@@ -144,6 +139,24 @@ size_t moqe_ffn_workspace_bytes(int64_t T, int64_t E, int64_t d, int64_t f) {
 
 size_t moqe_layer_workspace_bytes(int64_t T, int64_t E, int64_t d, int64_t f) {
   return moqe_ffn_workspace_bytes(T, E, d, f) + moqe_route_workspace_bytes(T, E);
+}
+
+moqe_status moqe_workspace_status(const void* workspace, size_t workspace_bytes, void* stream) {
+  if (!workspace) return MOQE_ERR_NULL;
+  if (workspace_bytes < 1024) return MOQE_ERR_WORKSPACE;
+  unsigned flag = 0;
+  hipError_t e = hipMemcpyAsync(&flag, (const char*)workspace + 640, sizeof(flag), hipMemcpyDeviceToHost, (hipStream_t)stream);
+  if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e);
+  return flag ? MOQE_ERR_TIMEOUT : MOQE_OK;
+}
+
+moqe_status moqe_stream_read(const void* src, size_t bytes, void* sink, void* stream) {
+  if (!src || !sink) return MOQE_ERR_NULL;
+  if (bytes == 0 || (bytes % 1024) != 0 || bytes >= ((size_t)1 << 31)) return MOQE_ERR_SHAPE;
+  if (!aligned16(src) || !aligned16(sink)) return MOQE_ERR_ALIGN;
+  hipError_t e = moqe_launch_stream_read(src, bytes, (uint32_t*)sink, num_cus(), (hipStream_t)stream);
+  return e == hipSuccess ? MOQE_OK : hip_fail(e);
 }
 
 static moqe_status quantize_common(const float* w, int64_t E, int64_t K, int64_t N, int bits, void* codes_out,
@@ -261,9 +274,6 @@ static void base_args(DecodeArgs* a, const moqe_layer* L, int64_t T, const int32
   a->perm = (int*)perm;
   a->min_tokens = 1;
   a->max_tokens = INT_MAX;
-#ifdef MOQE_PHASE_TRACE
-  a->trace = g_trace;
-#endif
 }
 
 static void set_ffn1(DecodeArgs* a, const moqe_layer* L, const moqe_f16* x, moqe_f16* h, int* ksteps) {
@@ -362,9 +372,6 @@ static hipError_t launch_contraction(DecodeArgs& a, int phase, int ksteps, hipSt
   q.seg_offsets = a.seg_offsets;
   q.perm = a.perm;
   q.gate = a.gate;
-#ifdef MOQE_PHASE_TRACE
-  q.trace = g_trace;
-#endif
   return moqe_launch_prefill(q, num_cus(), stream);
 }
 

@@ -27,18 +27,7 @@
 #include "moqe_kernels.h"
 #include "moqe_unpack.h"
 
-#ifdef MOQE_PHASE_TRACE
-#define STAMP(i)                                                                       \
-  do {                                                                                 \
-    if (A.trace && (threadIdx.x == 0)) A.trace[blockIdx.x * 16 + (i)] = wall_clock64(); \
-  } while (0)
-#else
-#define STAMP(i)
-#endif
-
-#ifndef MOQE_MIN_WAVES
 #define MOQE_MIN_WAVES 3  // waves per SIMD the register and LDS budgets are sized for
-#endif
 
 namespace {
 
@@ -138,8 +127,6 @@ __global__ __launch_bounds__(WG_THREADS, min_waves(BITS, KSTEPS)) void moe_decod
   __shared__ float4_t s_out[WG_WAVES][STASH_UNITS][16];
   __shared__ int s_ometa[WG_WAVES][STASH_UNITS][4];
   __shared__ int s_share[2][4];  // per contraction: this workgroup's first unit, end, iterations
-
-  STAMP(0);
   UnpackConsts<BITS> uc;
   uc.init();
   const int tid = threadIdx.x;
@@ -269,7 +256,6 @@ __global__ __launch_bounds__(WG_THREADS, min_waves(BITS, KSTEPS)) void moe_decod
         }
         __builtin_amdgcn_s_sleep(8);
       }
-      STAMP(1);
       const int key = valid ? min((int)(unsigned)w0, E - 1) : E;
       const float g = valid ? __builtin_bit_cast(float, (unsigned)w1) : 0.0f;
       int nb = 0;
@@ -370,7 +356,6 @@ __global__ __launch_bounds__(WG_THREADS, min_waves(BITS, KSTEPS)) void moe_decod
     P = s_incl[E - 1];
   }
   P = uniform_i32(P);
-  STAMP(2);
 
   // pair index -> expert (wave-uniform)
   auto expert_of = [&](int p) -> int {
@@ -449,7 +434,6 @@ __global__ __launch_bounds__(WG_THREADS, min_waves(BITS, KSTEPS)) void moe_decod
 
   // =========================== the contractions ===========================
   for (int phase = 0; phase < 2; ++phase) {
-    const int stamp_base = 3 + 4 * phase;
     if (!(phase_mask & (2 << phase))) continue;
     const PhaseArgs& ph = A.ph[phase];
     const int K = ph.K, N = ph.N, mode = ph.mode, ksplit = ph.ksplit;
@@ -563,18 +547,8 @@ __global__ __launch_bounds__(WG_THREADS, min_waves(BITS, KSTEPS)) void moe_decod
 
 #pragma unroll
         for (int ch = 0; ch < S::NCH; ++ch) {
-#ifdef MOQE_DBG_NOCOMPUTE
-          {
-            uint32_t x = 0;
-            for (int q = 0; q < S::LW; ++q) x ^= b.lo[ch * S::LW + q];
-            if (S::FB == 3) for (int q = 0; q < S::HW; ++q) x ^= b.hi[ch * S::HW + q];
-            acc0[0] += __builtin_bit_cast(float, x & 0x3fffffffu);
-          }
-          for (int s1 = 0; s1 < 0; ++s1) {
-#else
 #pragma unroll
           for (int s1 = 0; s1 < S::SC; ++s1) {
-#endif
             const int s = ch * S::SC + s1;
             half8_t w;
             if constexpr (BITS == 8) {
@@ -693,7 +667,6 @@ __global__ __launch_bounds__(WG_THREADS, min_waves(BITS, KSTEPS)) void moe_decod
       issue_unit(bufA, m0);
       issue_unit(bufB, m1);
     }
-    STAMP(stamp_base);
     for (int it = 0; it < nl; it += 2) {
       {
         const UnitMeta n0 = make_meta(phase, it + 2);
@@ -710,7 +683,6 @@ __global__ __launch_bounds__(WG_THREADS, min_waves(BITS, KSTEPS)) void moe_decod
       if (n_stash + 2 > STASH_UNITS) flush_outputs();
     }
     flush_outputs();
-    STAMP(stamp_base + 1);
   }
 
   // ---- end of launch (multi-phase launches) ----
@@ -739,7 +711,6 @@ __global__ __launch_bounds__(WG_THREADS, min_waves(BITS, KSTEPS)) void moe_decod
       }
     }
   }
-  STAMP(15);
 }
 
 template <int BITS, int KSTEPS, int PM>
@@ -747,14 +718,17 @@ hipError_t launch_mask(const DecodeArgs& a, int num_cus, hipStream_t stream) {
   // Persistent grid: every workgroup must be resident at once (phases meet at grid-wide
   // counters), so the grid is what the occupancy query says fits, at most MOQE_MIN_WAVES
   // workgroups (of four waves: one wave per SIMD each) per CU.
-  static int per_cu = 0;
-  if (per_cu == 0) {
+  static int per_cu_of[64];  // asked once per device
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  if (per_cu_of[dev] == 0) {
     int n = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, moe_decode_kernel<BITS, KSTEPS, PM>, WG_THREADS, 0) != hipSuccess ||
         n < 1)
       n = 1;
-    per_cu = n > min_waves(BITS, KSTEPS) ? min_waves(BITS, KSTEPS) : n;
+    per_cu_of[dev] = n > min_waves(BITS, KSTEPS) ? min_waves(BITS, KSTEPS) : n;
   }
+  const int per_cu = per_cu_of[dev];
   hipLaunchKernelGGL((moe_decode_kernel<BITS, KSTEPS, PM>), dim3(per_cu * num_cus), dim3(WG_THREADS), 0, stream, a);
   return hipGetLastError();
 }

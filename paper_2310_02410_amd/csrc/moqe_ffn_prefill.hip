@@ -42,18 +42,6 @@
 
 #include <type_traits>
 
-#ifdef MOQE_PHASE_TRACE
-#define PF_T0() long long pf_t = clock64()
-#define PF_ACC(i)                \
-  do {                           \
-    const long long n = clock64(); \
-    pf_sum[i] += n - pf_t;       \
-    pf_t = n;                    \
-  } while (0)
-#else
-#define PF_T0()
-#define PF_ACC(i)
-#endif
 
 namespace {
 
@@ -298,10 +286,6 @@ __global__ __launch_bounds__(PF_THREADS, (PF_NT == 4 || BITS == 16) ? 2 : PF_WG_
   using I1 = std::integral_constant<int, 1>;
   constexpr int WAIT_ALL = 0x0F70;                 // s_waitcnt vmcnt(0)
   constexpr int WAIT_BUT_NLD = 0x0F70 | NLD;       // s_waitcnt vmcnt(NLD)
-#ifdef MOQE_PHASE_TRACE
-  long long pf_sum[8] = {0, 0, 0, 0, 0, 0, 0, 0};  // setup, issue, compute, wait, barrier, epilogue
-#endif
-  PF_T0();
   PfTile cur = find(t_first);
   rsrc_t cur_brs[PF_NT], nxt_brs[PF_NT];
   make_brs(cur, cur_brs);
@@ -338,7 +322,6 @@ __global__ __launch_bounds__(PF_THREADS, (PF_NT == 4 || BITS == 16) ? 2 : PF_WG_
       sc2[ni] = *(const uint2_t*)(A.scales + (int64_t)cur.e * N + c0);
       bi2[ni] = *(const uint2_t*)(A.bias + (int64_t)cur.e * N + c0);
     }
-    PF_ACC(0);
 #pragma unroll
     for (int mi = 0; mi < PF_MT; ++mi)
 #pragma unroll
@@ -361,14 +344,10 @@ __global__ __launch_bounds__(PF_THREADS, (PF_NT == 4 || BITS == 16) ? 2 : PF_WG_
         if (ahead < TB) load_a(cur_off, ahead, (gb + 2) % NBUF);
         else if (nxt.valid) load_a(row_offsets(nxt_rows), ahead - TB, (gb + 2) % NBUF);
         else issued = false;
-        PF_ACC(1);
         compute(gb % NBUF, BUF, SUBI);
-        PF_ACC(2);
         if (issued) __builtin_amdgcn_s_waitcnt(WAIT_BUT_NLD);
         else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
-        PF_ACC(3);
         __syncthreads();
-        PF_ACC(4);
         ++gb;
       };
       do_block(I0{});
@@ -430,18 +409,11 @@ __global__ __launch_bounds__(PF_THREADS, (PF_NT == 4 || BITS == 16) ? 2 : PF_WG_
         *(uint2_t*)(A.out + out_row[mi] + c0) = pk;
       }
     }
-    PF_ACC(5);
     cur = nxt;
 #pragma unroll
     for (int ni = 0; ni < PF_NT; ++ni) cur_brs[ni] = nxt_brs[ni];
     cur_off = row_offsets(nxt_rows);
   }
-#ifdef MOQE_PHASE_TRACE
-  if (A.trace && lane == 0) {
-    for (int i = 0; i < 6; ++i) A.trace[((int64_t)bid * 4 + wave) * 8 + i] = pf_sum[i];
-    A.trace[((int64_t)bid * 4 + wave) * 8 + 6] = gb;
-  }
-#endif
 }
 
 }  // namespace

@@ -17,6 +17,9 @@ hipError_t moqe_launch_dequantize_log(const void* codes, const uint16_t* scales,
                                       float* w_out, hipStream_t stream);
 hipError_t moqe_launch_unpack(const void* codes, int64_t E, const PackGeom& g, int8_t* q_out, hipStream_t stream);
 
+// Plain read of `bytes` (a multiple of 1024) from src; sink receives at most one word.
+hipError_t moqe_launch_stream_read(const void* src, size_t bytes, uint32_t* sink, int num_cus, hipStream_t stream);
+
 size_t moqe_route_ws_bytes(int64_t T, int64_t E);
 // logits != NULL: start from given logits (x, wg, d unused).
 hipError_t moqe_launch_route(const uint16_t* x, const uint16_t* wg, const float* logits, int T, int d, int E,
@@ -63,8 +66,6 @@ struct DecodeArgs {
   uint16_t* h_base;
   size_t h_stride;
   unsigned h_bytes;  // bytes of h this launch writes (T * f * 2)
-  // debug builds (-DMOQE_PHASE_TRACE): 16 wall-clock stamps per workgroup, else unused
-  long long* trace;
 };
 
 // One contraction over the expert segments with at least min_tokens tokens: tiled MFMA
@@ -84,7 +85,6 @@ struct PrefillArgs {
   const int* seg_offsets;
   const int* perm;
   const float* gate;
-  long long* trace;  // debug builds (-DMOQE_PHASE_TRACE): cycle sums per wave, else unused
 };
 bool moqe_prefill_supported(int bits, int64_t K, int64_t N);
 hipError_t moqe_launch_prefill(const PrefillArgs& a, int num_cus, hipStream_t stream);

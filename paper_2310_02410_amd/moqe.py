@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libmoqe.so")
 
 MOQE_OK = 0
 STATUS_NAMES = ("MOQE_OK", "MOQE_ERR_NULL", "MOQE_ERR_BITS", "MOQE_ERR_SHAPE", "MOQE_ERR_ALIGN",
-                "MOQE_ERR_WORKSPACE", "MOQE_ERR_HIP")
+                "MOQE_ERR_WORKSPACE", "MOQE_ERR_HIP", "MOQE_ERR_TIMEOUT")
 
 EXPORTS = (
     "moqe_status_string", "moqe_last_hip_error", "moqe_version", "moqe_packed_bytes",
@@ -27,7 +27,8 @@ EXPORTS = (
     "moqe_route_logits", "moqe_expert_ffn", "moqe_expert_ffn1", "moqe_expert_ffn2",
     "moqe_layer_workspace_bytes", "moqe_moe_layer", "moqe_set_launch_mode",
     "moqe_set_prefill_policy", "moqe_quantize_tensor_scale", "moqe_quantize_log", "moqe_dequantize_log",
-    "moqe_moe_layer_static", "moqe_set_decode_kernel",
+    "moqe_moe_layer_static", "moqe_set_decode_kernel", "moqe_workspace_status",
+    "moqe_stream_read",
 )
 
 LAUNCH_AUTO, LAUNCH_SEPARATE, LAUNCH_FUSED = 0, 1, 2
@@ -72,6 +73,10 @@ def lib() -> ctypes.CDLL:
     L.moqe_version.restype = ci
     L.moqe_set_launch_mode.restype = ci
     L.moqe_set_launch_mode.argtypes = [ci]
+    L.moqe_stream_read.restype = ci
+    L.moqe_stream_read.argtypes = [vp, sz, vp, vp]
+    L.moqe_workspace_status.restype = ci
+    L.moqe_workspace_status.argtypes = [vp, sz, vp]
     L.moqe_set_decode_kernel.restype = ci
     L.moqe_set_decode_kernel.argtypes = [ci]
     L.moqe_set_prefill_policy.restype = ci
@@ -405,6 +410,10 @@ def moqe_moe_layer_static(layer: QuantLayer, x: torch.Tensor, out: torch.Tensor,
     return out, route
 
 
-def workspace_error(workspace: torch.Tensor) -> bool:
-    """True if a phase wait of a call using this FFN / layer scratch ever timed out."""
-    return bool(workspace[640:644].view(torch.int32).item() != 0)
+def workspace_error(workspace: torch.Tensor, stream=None) -> bool:
+    """True if a wait of a single-launch (FUSED) step using this FFN / layer scratch has timed out
+    (moqe_workspace_status; synchronises the stream)."""
+    st = lib().moqe_workspace_status(workspace.data_ptr(), workspace.numel(), _stream(stream))
+    if st not in (0, 7):
+        raise MoqeError(st, "moqe_workspace_status")
+    return st == 7

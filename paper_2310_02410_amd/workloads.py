@@ -110,11 +110,12 @@ def _calibrate_bias(p_target: np.ndarray, sigma_logit: float, seed: int) -> np.n
     return beta
 
 
-def make_layer(wl: Workload, layer: int = 0, zipf_gate: bool = False) -> dict:
+def make_layer(wl: Workload, layer: int = 0, zipf_gate: bool = False, lattice: bool = True) -> dict:
     """One MoE layer: fp32 'w1' [E,d,f], 'w2' [E,f,d]; fp16 'b1' [E,f], 'b2' [E,d];
     fp16 'w_gate' [d,E].  With zipf_gate a uniform-routing workload also gets
     'w_gate_zipf': the same router with the Zipf bias row (4 experts empty), so that one
-    set of expert weights serves both load shapes."""
+    set of expert weights serves both load shapes.  lattice=False: W_g ~ N(0, 0.02) cast
+    straight to fp16 (same draws, no rounding to the 2^-9 lattice)."""
     rng = np.random.default_rng([wl.seed, 1000 + layer])
     E, d, f = wl.E, wl.d, wl.f
     w1 = np.empty((E, d, f), dtype=np.float32)
@@ -137,7 +138,9 @@ def make_layer(wl: Workload, layer: int = 0, zipf_gate: bool = False) -> dict:
         w2[e] = matrix(f, d)
         b2[e] = (rng.standard_normal(d) * SIGMA_B).astype(np.float16)
 
-    wg = np.clip(np.rint(rng.standard_normal((d, E)) * SIGMA_W * 512.0), -96, 96) / 512.0
+    wg = rng.standard_normal((d, E)) * SIGMA_W
+    if lattice:
+        wg = np.clip(np.rint(wg * 512.0), -96, 96) / 512.0
     out = dict(w1=w1, b1=b1, w2=w2, b2=b2)
     if wl.routing == "zipf":
         p = zipf_probs(E, wl.zipf_s, wl.n_empty, rng)
@@ -153,11 +156,14 @@ def make_layer(wl: Workload, layer: int = 0, zipf_gate: bool = False) -> dict:
     return out
 
 
-def make_tokens(wl: Workload) -> np.ndarray:
+def make_tokens(wl: Workload, lattice: bool = True) -> np.ndarray:
     """fp16 activations [T,d] ~ N(0,1) on the 2^-4 lattice; under zipf routing
-    feature 0 is the constant 1 that the router's bias row multiplies."""
+    feature 0 is the constant 1 that the router's bias row multiplies.
+    lattice=False: the same draws cast straight to fp16."""
     rng = np.random.default_rng([wl.seed, 7])
-    x = np.clip(np.rint(rng.standard_normal((wl.T, wl.d)) * 16.0), -112, 112) / 16.0
+    x = rng.standard_normal((wl.T, wl.d))
+    if lattice:
+        x = np.clip(np.rint(x * 16.0), -112, 112) / 16.0
     if wl.routing == "zipf":
         x[:, 0] = 1.0
     return x.astype(np.float16)

@@ -41,8 +41,14 @@ def test_version_and_strings():
     old = L.moqe_set_launch_mode(moqe.LAUNCH_SEPARATE)
     assert L.moqe_set_launch_mode(old) == moqe.LAUNCH_SEPARATE
     assert L.moqe_status_string(0) == b"MOQE_OK"
-    for s in range(1, 7):
+    for s in range(1, 8):
         assert L.moqe_status_string(s).decode().startswith(moqe.STATUS_NAMES[s])
+    assert L.moqe_set_decode_kernel(5) == -1
+    old = L.moqe_set_decode_kernel(moqe.DECODE_GENERAL)
+    assert L.moqe_set_decode_kernel(old) == moqe.DECODE_GENERAL
+    assert L.moqe_workspace_status(None, 4096, None) == 1 and L.moqe_workspace_status(P, 512, None) == 5
+    assert L.moqe_stream_read(None, 1024, P, None) == 1 and L.moqe_stream_read(P, 1000, P, None) == 3
+    assert L.moqe_stream_read(P, 0, P, None) == 3 and L.moqe_stream_read(P + 8, 1024, P, None) == 4
     assert L.moqe_status_string(99) == b"unknown status"
 
 

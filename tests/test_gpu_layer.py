@@ -178,3 +178,15 @@ def test_one_workspace_serves_changing_batch_sizes(launch_mode, mode):
         assert_route_equal(got, O.route(x, layer["w_gate"]), T, E)
         ref = oracle_layer_output(x, layer, 2, got[0], got[1].astype(np.float64), qlayer=oq)
         assert ffn_error(y.cpu().numpy(), ref) <= FFN_TOL, f"T={T}"
+
+
+def test_workspace_status_reports_the_error_flag():
+    """moqe_workspace_status reads the flag a timed-out wait would leave (set here from the host:
+    no kernel is made to wait) and clears with the buffer."""
+    ws = moqe.alloc_workspace(moqe.moqe_layer_workspace_bytes(24, 8, 128, 256), "cuda")
+    assert not moqe.workspace_error(ws)
+    ws[640:644] = torch.tensor([1, 0, 0, 0], dtype=torch.uint8, device="cuda")
+    assert moqe.workspace_error(ws)
+    assert moqe.lib().moqe_workspace_status(ws.data_ptr(), ws.numel(), None) == 7
+    ws.zero_()
+    assert not moqe.workspace_error(ws)
