@@ -88,3 +88,71 @@ __device__ inline uint32_t opaque_vgpr(uint32_t c) {
   asm volatile("" : "+v"(c));
   return c;
 }
+
+// ---------------------------------------------------------------------------
+// Wave-level top-1 and sum (the router's argmax and softmax denominator; App. B top-1 gating)
+// ---------------------------------------------------------------------------
+// Order of the top-1 comparison: a NaN ranks above every number and ties with another NaN, as
+// in the plain definition "first index of the row maximum" once a NaN is met (non-finite logits
+// are outside the method's domain; what matters is that the index stays in [0, E) and is unique).
+__device__ inline bool logit_above(float a, float b) { return (a > b) || (a != a && b == b); }
+__device__ inline bool logit_same(float a, float b) { return (a == b) || (a != a && b != b); }
+
+// Cross-lane moves inside a row of 16 lanes, as DPP operands of ordinary vector instructions (no
+// trip through the LDS crossbar, which is what a general shuffle costs): lane ^ 1, lane ^ 2, then
+// the mirror images within 8 and within 16 lanes.  After the four steps of a symmetric reduction
+// every lane of a row holds the row's result; the four rows meet through readlane.
+template <int CTRL>
+__device__ inline float dpp_f32(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
+}
+template <int CTRL>
+__device__ inline int dpp_i32(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, false);
+}
+constexpr int DPP_XOR1 = 0xB1, DPP_XOR2 = 0x4E, DPP_HALF_MIRROR = 0x141, DPP_MIRROR = 0x140;
+
+__device__ inline float readlane_f32(float v, int l) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
+}
+
+// All lanes' (value, index) pairs -> the pair every lane agrees on: the largest value, the lowest
+// index among equals (a symmetric rule, so both lanes of a DPP pair end up with the same winner).
+__device__ inline void wave_top1(float best, int bidx, float* best_out, int* idx_out) {
+#define MOQE_PICK_STEP(CTRL)                                                        \
+  {                                                                                 \
+    const float ov = dpp_f32<CTRL>(best);                                           \
+    const int oi = dpp_i32<CTRL>(bidx);                                             \
+    const bool take = logit_above(ov, best) || (logit_same(ov, best) && oi < bidx); \
+    best = take ? ov : best;                                                        \
+    bidx = take ? oi : bidx;                                                        \
+  }
+  MOQE_PICK_STEP(DPP_XOR1)
+  MOQE_PICK_STEP(DPP_XOR2)
+  MOQE_PICK_STEP(DPP_HALF_MIRROR)
+  MOQE_PICK_STEP(DPP_MIRROR)
+#undef MOQE_PICK_STEP
+  float wbest = readlane_f32(best, 0);
+  int widx = __builtin_amdgcn_readlane(bidx, 0);
+#pragma unroll
+  for (int r = 1; r < 4; ++r) {
+    const float ov = readlane_f32(best, 16 * r);
+    const int oi = __builtin_amdgcn_readlane(bidx, 16 * r);
+    const bool take = logit_above(ov, wbest) || (logit_same(ov, wbest) && oi < widx);
+    wbest = take ? ov : wbest;
+    widx = take ? oi : widx;
+  }
+  *best_out = wbest;
+  *idx_out = widx;
+}
+
+// Sum over the 64 lanes in a fixed order (the same in every kernel that computes a gate, so that
+// the gate does not depend on which kernel routed).
+__device__ inline float wave_sum(float sum) {
+  sum += dpp_f32<DPP_XOR1>(sum);
+  sum += dpp_f32<DPP_XOR2>(sum);
+  sum += dpp_f32<DPP_HALF_MIRROR>(sum);
+  sum += dpp_f32<DPP_MIRROR>(sum);
+  return (readlane_f32(sum, 0) + readlane_f32(sum, 16)) + (readlane_f32(sum, 32) + readlane_f32(sum, 48));
+}
+

@@ -209,25 +209,19 @@ __global__ __launch_bounds__(WG_THREADS, min_waves(BITS, KSTEPS)) void moe_decod
       if (wave == 0) {
         // wavefront-level argmax (lowest index on ties) and softmax probability
         const float* row = s_route[WG_WAVES];
-        // (a NaN ranks above every number and ties with another NaN; an all -inf row keeps index 0)
-        float best = -INFINITY;
-        int bidx = 0;
+        // (the same comparisons and the same order of additions as the router kernels)
+        float lbest = -INFINITY;
+        int lidx = 0;
         for (int e = lane; e < E; e += 64) {
           const float v = row[e];
-          if ((v > best) || (v != v && best == best)) { best = v; bidx = e; }
+          if (logit_above(v, lbest)) { lbest = v; lidx = e; }
         }
-        for (int off = 32; off >= 1; off >>= 1) {
-          const float ov = __shfl_xor(best, off, 64);
-          const int oi = __shfl_xor(bidx, off, 64);
-          const bool above = (ov > best) || (ov != ov && best == best);
-          const bool same = (ov == best) || (ov != ov && best != best);
-          const bool take = above || (same && oi < bidx);
-          best = take ? ov : best;
-          bidx = take ? oi : bidx;
-        }
+        float best;
+        int bidx;
+        wave_top1(lbest, lidx, &best, &bidx);
         float sum = 0.0f;
         for (int e = lane; e < E; e += 64) sum += expf(row[e] - best);
-        for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, 64);
+        sum = wave_sum(sum);
         if (lane == 0) {
           const float g = 1.0f / sum;
           A.expert_idx[bid] = bidx;

@@ -16,15 +16,8 @@ constexpr int SCORE_THREADS = 256;
 constexpr int SEG_THREADS = 1024;
 constexpr int SEG_LDS_INTS = 9216;
 
-// Order of the top-1 comparison: a NaN ranks above every number and ties with another NaN, as
-// in the plain definition "first index of the row maximum" once a NaN is met (non-finite logits
-// are outside the method's domain; what matters is that the index stays in [0, E) and is unique).
-__device__ inline bool logit_above(float a, float b) { return (a > b) || (a != a && b == b); }
-__device__ inline bool logit_same(float a, float b) { return (a == b) || (a != a && b != b); }
-
 // Wave-level top-1 over one row of logits held in LDS or global memory.
-// Returns through lane 0 semantics: every lane gets the same (idx, gate).
-// A row without any value above -inf (all -inf) keeps index 0.
+// Every lane gets the same (idx, gate).  A row without any value above -inf keeps index 0.
 __device__ inline void wave_pick(const float* row, int E, int* idx_out, float* gate_out) {
   const int lane = lane_id();
   float best = -INFINITY;
@@ -36,18 +29,14 @@ __device__ inline void wave_pick(const float* row, int E, int* idx_out, float* g
       bidx = e;
     }
   }
-  for (int off = 32; off >= 1; off >>= 1) {
-    float ov = __shfl_xor(best, off, 64);
-    int oi = __shfl_xor(bidx, off, 64);
-    bool take = logit_above(ov, best) || (logit_same(ov, best) && oi < bidx);
-    best = take ? ov : best;
-    bidx = take ? oi : bidx;
-  }
+  float wbest;
+  int widx;
+  wave_top1(best, bidx, &wbest, &widx);
   float sum = 0.0f;
-  for (int e = lane; e < E; e += 64) sum += expf(row[e] - best);
-  for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, 64);
-  *idx_out = bidx;
-  *gate_out = 1.0f / sum;
+  for (int e = lane; e < E; e += 64) sum += expf(row[e] - wbest);
+  const float total = wave_sum(sum);
+  *idx_out = widx;
+  *gate_out = 1.0f / total;
 }
 
 // Block = 256 threads, TB tokens.  Thread (e_l, kp): partial logit of expert
@@ -355,7 +344,8 @@ __global__ __launch_bounds__(SMALL_THREADS) void route_small_kernel(const half_t
   x += (int64_t)t_base * d;
   expert_idx += t_base;
   gate += t_base;
-  __shared__ float4_t s_part[SMALL_WAVES][NT][64];  // one token tile's partial sums at a time
+  constexpr int PART_TILES = NT < 4 ? 4 : NT;  // 16 x 16 result tiles the partial-sum buffer holds per wave
+  __shared__ float4_t s_part[SMALL_WAVES][PART_TILES][64];
   __shared__ float s_logit[MT * 16 * E];
   __shared__ int s_idx[64];
   __shared__ int s_seg[E + 1];
@@ -390,18 +380,27 @@ __global__ __launch_bounds__(SMALL_THREADS) void route_small_kernel(const half_t
         if (mi < mt) acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mi], b, acc[mi][ni], 0, 0, 0);
     }
   }
-  // D layout of a tile: lane (g, j), register r holds token row 4 g + r, expert column j
+  // D layout of a tile: lane (g, j), register r holds token row 4 g + r, expert column j.
+  // The waves' partial tiles meet in LDS and are summed in a fixed order (wave 0, 1, ...): all
+  // token tiles in one pass when their partial sums fit the buffer together, else tile by tile.
+  const bool one_pass = mt * NT <= PART_TILES;
 #pragma unroll
   for (int mi = 0; mi < MT; ++mi) {
     if (mi >= mt) break;  // uniform
+    const int slot0 = one_pass ? mi * NT : 0;
 #pragma unroll
-    for (int ni = 0; ni < NT; ++ni) s_part[wave][ni][lane] = acc[mi][ni];
+    for (int ni = 0; ni < NT; ++ni) s_part[wave][slot0 + ni][lane] = acc[mi][ni];
+    if (one_pass && mi + 1 < mt) continue;
     __syncthreads();
-    for (int o = tid; o < NT * 256; o += SMALL_THREADS) {
-      const int ni = o >> 8, l = (o & 255) >> 2, r = o & 3;
+    const int mi_first = one_pass ? 0 : mi;
+    const int n_out = (mi - mi_first + 1) * NT * 256;
+    for (int o = tid; o < n_out; o += SMALL_THREADS) {
+      const int slot = o >> 8, l = (o & 255) >> 2, r = o & 3;
+      const int mo = mi_first + slot / NT, ni = slot % NT;
       float sum = 0.0f;
-      for (int w = 0; w < SMALL_WAVES; ++w) sum += reinterpret_cast<const float*>(&s_part[w][ni][l])[r];
-      s_logit[(16 * mi + 4 * (l >> 4) + r) * E + 16 * ni + (l & 15)] = sum;
+#pragma unroll
+      for (int w = 0; w < SMALL_WAVES; ++w) sum += reinterpret_cast<const float*>(&s_part[w][slot][l])[r];
+      s_logit[(16 * mo + 4 * (l >> 4) + r) * E + 16 * ni + (l & 15)] = sum;
     }
     __syncthreads();
   }
