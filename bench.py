@@ -41,8 +41,8 @@ MFMA_F16_PEAK_TFLOPS = 2500.0
 # HBM traffic per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
 # WRITE_SIZE runs of this script, each scaled by what the same counter reads for a 256 MiB
 # device copy in the same run); from the profiles/*_hbm_traffic.txt summaries.  None where no
-# counter run was made.
-MEASURED_TRAFFIC_BYTES = {}
+# counter run was made.  FFN1 of c1 (read + written; profiles/decode_c1_hbm_traffic.txt):
+MEASURED_TRAFFIC_BYTES = {("c1", 4): 39766526, ("c1", 3): 30154587, ("c1", 2): 20456738}
 
 
 def parse():
@@ -52,7 +52,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="c1",
                     choices=("c1", "c2", "c3", "c4_T24_uniform", "c4_T24_zipf", "c4_T4096_uniform", "c4_T4096_zipf",
-                             "n2_e128", "n2_dense"))
+                             "n2_e128", "n2_dense", "c1_T64", "c1_T64_zipf"))
     ap.add_argument("--bits", type=int, default=None, choices=(2, 3, 4, 8, 16),
                     help="bit width of the headline line (default: the workload's own)")
     ap.add_argument("--codec", default="linear", choices=("linear", "log"),

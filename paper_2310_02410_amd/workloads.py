@@ -66,6 +66,10 @@ CONFIGS = {
 EXTRA = {
     "n2_e128": Workload("n2_e128", E=128, d=768, f=3072, T=24, bits=(4,), seed=5, outlier_prob=1e-3),
     "n2_dense": Workload("n2_dense", E=1, d=1024, f=4096, T=24, bits=(4,), seed=6, outlier_prob=1e-3),
+    # the largest batch the decode-sized kernels take (64 tokens), uniform and Zipf(1.1) load
+    "c1_T64": Workload("c1_T64", E=32, d=1024, f=4096, T=64, bits=(4,), seed=7, outlier_prob=1e-3),
+    "c1_T64_zipf": Workload("c1_T64_zipf", E=32, d=1024, f=4096, T=64, bits=(4,), seed=8, outlier_prob=1e-3,
+                            routing="zipf", n_empty=4),
 }
 
 
