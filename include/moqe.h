@@ -96,7 +96,9 @@ enum { MOQE_LAUNCH_AUTO = 0, MOQE_LAUNCH_SEPARATE = 1, MOQE_LAUNCH_FUSED = 2 };
 int moqe_set_launch_mode(int mode);
 
 /* Which dequantize-in-register kernel serves decode-sized batches (a process-wide setting, for
- * tests and comparisons; results are identical): AUTO takes the kernel specialised for batches
+ * tests and comparisons; each kernel is deterministic, both run the same sums in the same order
+ * and differ only in how the last step, gate times output, is rounded to fp16 - by at most one
+ * unit in the last place of a few outputs in ten thousand): AUTO takes the kernel specialised for batches
  * of at most 64 tokens (at most 128 experts, 2- to 4-bit codes) where it applies and the
  * general one elsewhere; GENERAL always takes the general one.  Launch mode FUSED uses the
  * general kernel.  Returns the previous setting, or -1 (nothing changed) for an unknown one. */

@@ -170,3 +170,55 @@ def test_log_scale_layer_shapes_and_modes(bits):
 @pytest.mark.parametrize("bits", (4, 3, 2))
 def test_log_scale_layer_benchmark_shape(bits):
     _log_layer_parity(W.CONFIGS["c1"], bits)
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+def test_decode_kernels_agree(bits):
+    """The kernel built for batches of at most 64 tokens and the general decode kernel run the same
+    arithmetic in the same order (same unpack, same K order, same K-split sums): FFN1's output is
+    identical bit for bit, and the layer output differs at most by how gate x output is rounded to
+    fp16 (one unit in the last place, in a few outputs of ten thousand), as the header says for
+    moqe_set_decode_kernel.  C1 at full size, shapes with other slice lengths and K splits, a
+    residual, 128 experts, and log-scale codes."""
+    cases = [(W.CONFIGS["c1"], False, moqe.CODEC_LINEAR), (W.small(E=4, d=512, f=2048, T=40, seed=21), True, moqe.CODEC_LINEAR),
+             (W.small(E=3, d=768, f=3072, T=21, seed=22), False, moqe.CODEC_LINEAR),
+             (W.small(E=128, d=256, f=512, T=64, seed=23), True, moqe.CODEC_LINEAR),
+             (W.small(E=8, d=128, f=256, T=37, seed=24), False, moqe.CODEC_LOG)]
+    for wl, residual, codec in cases:
+        layer, x = W.make_layer(wl), W.make_tokens(wl)
+        ql = moqe.quantize_layer(dev(layer["w1"]), dev(layer["b1"]), dev(layer["w2"]), dev(layer["b2"]), bits,
+                                 dev(layer["w_gate"]), codec=codec)
+        xd = dev(x)
+        r = moqe.moqe_route(xd, ql.w_gate)
+        h_small = torch.zeros((wl.T, wl.f), dtype=torch.float16, device="cuda")
+        h_general = torch.zeros_like(h_small)
+        old = moqe.moqe_set_decode_kernel(moqe.DECODE_AUTO)
+        try:
+            moqe.moqe_expert_ffn1(ql, xd, r, h_small)
+            y_small = moqe.moqe_expert_ffn(ql, xd, r, residual=xd if residual else None)
+            moqe.moqe_set_decode_kernel(moqe.DECODE_GENERAL)
+            moqe.moqe_expert_ffn1(ql, xd, r, h_general)
+            y_general = moqe.moqe_expert_ffn(ql, xd, r, residual=xd if residual else None)
+        finally:
+            moqe.moqe_set_decode_kernel(old)
+        torch.cuda.synchronize()
+        assert torch.equal(h_small.view(torch.int16), h_general.view(torch.int16)), wl.name
+        a, b = y_small.cpu().numpy(), y_general.cpu().numpy()
+        differ = a.view(np.uint16) != b.view(np.uint16)
+        assert differ.mean() <= 2e-3, f"{wl.name}: {differ.sum()} outputs differ"
+        # neighbours in fp16: the bit patterns of two finite halves of one sign differ by one
+        assert np.all(np.abs(a.view(np.int16).astype(np.int32)[differ] - b.view(np.int16).astype(np.int32)[differ]) == 1), wl.name
+
+
+def test_stream_read_leaves_its_input_alone():
+    """The plain read that bench.py times as the ceiling: runs, writes nothing but (at most) its
+    sink word, rejects sizes that are not whole KiB."""
+    src = torch.arange(0, 3 << 20, dtype=torch.int32, device="cuda")
+    keep = src.clone()
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    L = moqe.lib()
+    for nbytes in (1024, 37 * 1024, src.numel() * 4):
+        assert L.moqe_stream_read(src.data_ptr(), nbytes, sink.data_ptr(), torch.cuda.current_stream().cuda_stream) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(src, keep)
+    assert L.moqe_stream_read(src.data_ptr(), 1000, sink.data_ptr(), None) == 3

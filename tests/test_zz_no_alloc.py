@@ -62,6 +62,33 @@ def test_decode_step_at_full_size_then_smaller():
         assert np.array_equal(ys, ye)
 
 
+def test_single_launch_mode_on_the_library_scratch():
+    """Launch mode FUSED keeps its hand-over state in the scratch from call to call: three calls in a
+    row on the library's array (24, 5, 24 tokens), each equal to the step on a caller's workspace."""
+    wl = W.small("static_fused", E=8, d=512, f=2048, T=24, seed=77)
+    layer, x_all = W.make_layer(wl), W.make_tokens(wl)
+    ql = gpu_quantize_layer(layer, 4)
+    old = moqe.moqe_set_launch_mode(moqe.LAUNCH_FUSED)
+    try:
+        ws = moqe.alloc_workspace(moqe.moqe_layer_workspace_bytes(24, ql.E, ql.d, ql.f), "cuda")
+        for T in (24, 5, 24):
+            x = dev(x_all[:T])
+            y_s, r_s = torch.empty_like(x), moqe.alloc_route(T, ql.E, x.device)[0]
+            moqe.moqe_moe_layer_static(ql, x, y_s, r_s)
+            y_e, r_e = moqe.moqe_moe_layer(ql, x, workspace=ws)
+            torch.cuda.synchronize()
+            assert not moqe.workspace_error(ws)
+            for a, b in zip(route_to_numpy(r_s), route_to_numpy(r_e)):
+                assert np.array_equal(a, b)
+            assert np.array_equal(y_s.cpu().numpy(), y_e.cpu().numpy())
+            idx, gate, _, _ = O.route(x_all[:T], layer["w_gate"])
+            assert np.array_equal(route_to_numpy(r_s)[0], idx)
+            ref = oracle_layer_output(x_all[:T], layer, 4, idx, gate)
+            assert ffn_error(y_s.cpu().numpy(), ref) <= FFN_TOL
+    finally:
+        moqe.moqe_set_launch_mode(old)
+
+
 def test_sizes_beyond_the_array_are_refused():
     wl = W.small("static_big", E=8, d=256, f=4096, T=300, seed=5)
     layer = W.make_layer(wl)
