@@ -90,13 +90,20 @@ __device__ inline uint32_t opaque_vgpr(uint32_t c) {
 }
 
 // ---------------------------------------------------------------------------
-// Wave-level top-1 and sum (the router's argmax and softmax denominator; App. B top-1 gating)
+// Top-1 and softmax denominator of a row of logits (App. B top-1 gating)
 // ---------------------------------------------------------------------------
-// Order of the top-1 comparison: a NaN ranks above every number and ties with another NaN, as
-// in the plain definition "first index of the row maximum" once a NaN is met (non-finite logits
-// are outside the method's domain; what matters is that the index stays in [0, E) and is unique).
-__device__ inline bool logit_above(float a, float b) { return (a > b) || (a != a && b == b); }
-__device__ inline bool logit_same(float a, float b) { return (a == b) || (a != a && b != b); }
+// Logits are compared through an integer key with the order of the values: one integer compare
+// per decision, no branches.  -0 and +0 get the same key; a NaN gets the largest key of all, so
+// it ranks above every number and ties with another NaN, as in the plain definition "first
+// index of the row maximum" once a NaN is met (non-finite logits are outside the method's
+// domain; what matters is that the index stays in [0, E) and is unique).
+__device__ inline int logit_key(float v) {
+  const int u = __builtin_bit_cast(int, v + 0.0f);  // (-0 + 0 = +0)
+  const int k = u ^ ((u >> 31) & 0x7fffffff);
+  return v != v ? 0x7fffffff : k;
+}
+__device__ inline float logit_of_key(int k) { return __builtin_bit_cast(float, k ^ ((k >> 31) & 0x7fffffff)); }
+constexpr int LOGIT_KEY_LOWEST = (int)0x807fffffu;  // the key of -inf
 
 // Cross-lane moves inside a row of 16 lanes, as DPP operands of ordinary vector instructions (no
 // trip through the LDS crossbar, which is what a general shuffle costs): lane ^ 1, lane ^ 2, then
@@ -116,43 +123,110 @@ __device__ inline float readlane_f32(float v, int l) {
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
 }
 
-// All lanes' (value, index) pairs -> the pair every lane agrees on: the largest value, the lowest
-// index among equals (a symmetric rule, so both lanes of a DPP pair end up with the same winner).
-__device__ inline void wave_top1(float best, int bidx, float* best_out, int* idx_out) {
-#define MOQE_PICK_STEP(CTRL)                                                        \
-  {                                                                                 \
-    const float ov = dpp_f32<CTRL>(best);                                           \
-    const int oi = dpp_i32<CTRL>(bidx);                                             \
-    const bool take = logit_above(ov, best) || (logit_same(ov, best) && oi < bidx); \
-    best = take ? ov : best;                                                        \
-    bidx = take ? oi : bidx;                                                        \
-  }
-  MOQE_PICK_STEP(DPP_XOR1)
-  MOQE_PICK_STEP(DPP_XOR2)
-  MOQE_PICK_STEP(DPP_HALF_MIRROR)
-  MOQE_PICK_STEP(DPP_MIRROR)
-#undef MOQE_PICK_STEP
-  float wbest = readlane_f32(best, 0);
-  int widx = __builtin_amdgcn_readlane(bidx, 0);
-#pragma unroll
-  for (int r = 1; r < 4; ++r) {
-    const float ov = readlane_f32(best, 16 * r);
-    const int oi = __builtin_amdgcn_readlane(bidx, 16 * r);
-    const bool take = logit_above(ov, wbest) || (logit_same(ov, wbest) && oi < widx);
-    wbest = take ? ov : wbest;
-    widx = take ? oi : widx;
-  }
-  *best_out = wbest;
-  *idx_out = widx;
+// (key, index) pairs meet: the larger key wins, the lower index among equal keys (a symmetric
+// rule, so both lanes of a DPP pair end up with the same winner).
+__device__ inline void top1_meet(int& key, int& idx, int okey, int oidx) {
+  const bool take = (okey > key) | ((okey == key) & (oidx < idx));
+  key = take ? okey : key;
+  idx = take ? oidx : idx;
 }
-
-// Sum over the 64 lanes in a fixed order (the same in every kernel that computes a gate, so that
-// the gate does not depend on which kernel routed).
-__device__ inline float wave_sum(float sum) {
+// The 16 lanes of a row -> the pair all of them agree on.
+__device__ inline void row16_top1(int& key, int& idx) {
+  top1_meet(key, idx, dpp_i32<DPP_XOR1>(key), dpp_i32<DPP_XOR1>(idx));
+  top1_meet(key, idx, dpp_i32<DPP_XOR2>(key), dpp_i32<DPP_XOR2>(idx));
+  top1_meet(key, idx, dpp_i32<DPP_HALF_MIRROR>(key), dpp_i32<DPP_HALF_MIRROR>(idx));
+  top1_meet(key, idx, dpp_i32<DPP_MIRROR>(key), dpp_i32<DPP_MIRROR>(idx));
+}
+__device__ inline float row16_sum(float sum) {
   sum += dpp_f32<DPP_XOR1>(sum);
   sum += dpp_f32<DPP_XOR2>(sum);
   sum += dpp_f32<DPP_HALF_MIRROR>(sum);
   sum += dpp_f32<DPP_MIRROR>(sum);
-  return (readlane_f32(sum, 0) + readlane_f32(sum, 16)) + (readlane_f32(sum, 32) + readlane_f32(sum, 48));
+  return sum;
 }
 
+// The order in which every router here scans a row of E <= 256 logits: a row of 16 lanes, lane q
+// owning the experts q, q + 16, q + 32, ... (one after the other, ascending), the 16 lanes then
+// meeting in the four DPP steps above.  Top-1 is exact whatever the order; the softmax
+// denominator is a sum of roundings, and with one order everywhere a token gets the same gate
+// from every kernel.  `read(e)` returns logit e of the row; NPL > 0 says at compile time that
+// every lane owns exactly NPL experts (E = 16 NPL).  Every lane of the 16 gets the result.
+// A row without any value above -inf keeps index 0.
+template <int NPL, typename Read>
+__device__ inline void row16_pick(Read read, int q, int E, int* idx_out, float* gate_out) {
+  int key = LOGIT_KEY_LOWEST, idx = 0;
+  float sum = 0.0f;
+  if constexpr (NPL > 0) {
+    float v[NPL];
+#pragma unroll
+    for (int i = 0; i < NPL; ++i) {
+      v[i] = read(q + 16 * i);
+      const int k = logit_key(v[i]);
+      const bool take = k > key;  // ascending: strictly above keeps the lowest index
+      key = take ? k : key;
+      idx = take ? q + 16 * i : idx;
+    }
+    row16_top1(key, idx);
+    const float best = logit_of_key(key);
+#pragma unroll
+    for (int i = 0; i < NPL; ++i) sum += expf(v[i] - best);
+  } else {
+    for (int e = q; e < E; e += 16) {
+      const int k = logit_key(read(e));
+      const bool take = k > key;
+      key = take ? k : key;
+      idx = take ? e : idx;
+    }
+    row16_top1(key, idx);
+    const float best = logit_of_key(key);
+    for (int e = q; e < E; e += 16) sum += expf(read(e) - best);
+  }
+  *idx_out = idx;
+  *gate_out = 1.0f / row16_sum(sum);
+}
+
+// One wave, one row of E logits in LDS or global memory: every lane gets the same (idx, gate).
+// Up to 256 experts in the order above (the wave's four rows of lanes all scan the same row);
+// beyond that, where no second kernel has to agree, the 64 lanes share the row.
+__device__ inline void wave_pick(const float* row, int E, int* idx_out, float* gate_out) {
+  const int lane = lane_id();
+  if (E <= 256) {
+    row16_pick<0>([row](int e) { return row[e]; }, lane & 15, E, idx_out, gate_out);
+    return;
+  }
+  int key = LOGIT_KEY_LOWEST, idx = 0;
+  for (int e = lane; e < E; e += 64) {
+    const int k = logit_key(row[e]);
+    const bool take = k > key;
+    key = take ? k : key;
+    idx = take ? e : idx;
+  }
+  row16_top1(key, idx);
+  int wkey = __builtin_amdgcn_readlane(key, 0), widx = __builtin_amdgcn_readlane(idx, 0);
+#pragma unroll
+  for (int r = 1; r < 4; ++r) top1_meet(wkey, widx, __builtin_amdgcn_readlane(key, 16 * r), __builtin_amdgcn_readlane(idx, 16 * r));
+  const float best = logit_of_key(wkey);
+  float sum = 0.0f;
+  for (int e = lane; e < E; e += 64) sum += expf(row[e] - best);
+  sum = row16_sum(sum);
+  const float total = (readlane_f32(sum, 0) + readlane_f32(sum, 16)) + (readlane_f32(sum, 32) + readlane_f32(sum, 48));
+  *idx_out = widx;
+  *gate_out = 1.0f / total;
+}
+
+// Inclusive prefix sum over the 64 lanes: shifts inside the rows of 16 lanes as DPP operands
+// (lanes a shift would take from outside the row read 0), then the row totals by readlane.
+template <int N>
+__device__ inline int dpp_row_shr(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, 0x110 + N, 0xF, 0xF, true);
+}
+__device__ inline int wave_inclusive_scan(int v) {
+  v += dpp_row_shr<1>(v);
+  v += dpp_row_shr<2>(v);
+  v += dpp_row_shr<4>(v);
+  v += dpp_row_shr<8>(v);
+  const int t0 = __builtin_amdgcn_readlane(v, 15), t1 = __builtin_amdgcn_readlane(v, 31),
+            t2 = __builtin_amdgcn_readlane(v, 47);
+  const int row = lane_id() >> 4;
+  return v + (row == 0 ? 0 : row == 1 ? t0 : row == 2 ? t0 + t1 : t0 + t1 + t2);
+}

@@ -207,23 +207,12 @@ __global__ __launch_bounds__(WG_THREADS, min_waves(BITS, KSTEPS)) void moe_decod
       }
       __syncthreads();
       if (wave == 0) {
-        // wavefront-level argmax (lowest index on ties) and softmax probability
-        const float* row = s_route[WG_WAVES];
-        // (the same comparisons and the same order of additions as the router kernels)
-        float lbest = -INFINITY;
-        int lidx = 0;
-        for (int e = lane; e < E; e += 64) {
-          const float v = row[e];
-          if (logit_above(v, lbest)) { lbest = v; lidx = e; }
-        }
-        float best;
+        // wavefront-level argmax (lowest index on ties) and softmax probability, with the same
+        // comparisons and the same order of additions as the router kernels
         int bidx;
-        wave_top1(lbest, lidx, &best, &bidx);
-        float sum = 0.0f;
-        for (int e = lane; e < E; e += 64) sum += expf(row[e] - best);
-        sum = wave_sum(sum);
+        float g;
+        wave_pick(s_route[WG_WAVES], E, &bidx, &g);
         if (lane == 0) {
-          const float g = 1.0f / sum;
           A.expert_idx[bid] = bidx;
           A.gate[bid] = g;
           // the result other workgroups wait for: two words, each carrying this launch's tag

@@ -65,17 +65,6 @@ constexpr int window_chunks(int nch) {
 }
 constexpr uint32_t NOWHERE = 0x80000000u;  // a buffer offset beyond every descriptor: loads give 0, stores vanish
 
-// Inclusive prefix sum over the 64 lanes.
-__device__ inline int wave_inclusive_scan(int v) {
-  const int lane = lane_id();
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const int o = __shfl_up(v, off, 64);
-    if (lane >= off) v += o;
-  }
-  return v;
-}
-
 __device__ inline int read_lane(int v, int l) { return __builtin_amdgcn_readlane(v, l); }
 __device__ inline float read_lane(float v, int l) {
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));

@@ -16,29 +16,6 @@ constexpr int SCORE_THREADS = 256;
 constexpr int SEG_THREADS = 1024;
 constexpr int SEG_LDS_INTS = 9216;
 
-// Wave-level top-1 over one row of logits held in LDS or global memory.
-// Every lane gets the same (idx, gate).  A row without any value above -inf keeps index 0.
-__device__ inline void wave_pick(const float* row, int E, int* idx_out, float* gate_out) {
-  const int lane = lane_id();
-  float best = -INFINITY;
-  int bidx = 0;
-  for (int e = lane; e < E; e += 64) {
-    float v = row[e];
-    if (logit_above(v, best)) {  // ascending e: strictly above keeps the lowest index
-      best = v;
-      bidx = e;
-    }
-  }
-  float wbest;
-  int widx;
-  wave_top1(best, bidx, &wbest, &widx);
-  float sum = 0.0f;
-  for (int e = lane; e < E; e += 64) sum += expf(row[e] - wbest);
-  const float total = wave_sum(sum);
-  *idx_out = widx;
-  *gate_out = 1.0f / total;
-}
-
 // Block = 256 threads, TB tokens.  Thread (e_l, kp): partial logit of expert
 // e_l over the kp-th slice of d for each of the TB tokens.
 template <int TB>
@@ -319,34 +296,57 @@ __global__ __launch_bounds__(SEG_THREADS) void route_segments_kernel(const int* 
 
 // ---------------------------------------------------------------------------
 // Decode-sized batches (T <= 64): the whole router in ONE workgroup and one launch.
-// The logits are a small MFMA GEMM (token tiles x expert tiles of 16 x 16, 32 rows of d per
-// step) with d split over the 16 waves; the partial tiles are summed through LDS in a fixed
-// order, then each wave picks top-1 / softmax for its tokens and wave 0 builds the dispatch
-// tables.  NT = E / 16 expert tiles, MT = token tiles kept per wave (4, or 2 for 128 experts).
+// One workgroup has one CU's instruction issue (a vector instruction of a wave takes four
+// cycles of its SIMD), and at this size that, not memory, is what the router's phases cost:
+// every phase is laid out for few instructions per wave.
+//   scores  the logits are a small MFMA GEMM (token tiles x expert tiles of 16 x 16, 32 rows of
+//           d per step), d split over the 16 waves; a wave asks for the operands of two steps
+//           at once, so d = 1024 is one round trip to memory;
+//   sum     the waves' partial tiles meet in LDS and are summed in a fixed order, four values
+//           (one MFMA result register quad) per thread;
+//   pick    a token's row of E logits is scanned by 16 neighbouring lanes (E / 16 experts each,
+//           then four DPP steps), four tokens per wave, all waves at once;
+//   tables  wave 0: equal-key masks by ballots, counts, a DPP scan, the stable permutation.
+// NT = E / 16 expert tiles, MT = token tiles kept per wave (4, or 2 for 128 experts).
 // ---------------------------------------------------------------------------
-constexpr int SMALL_THREADS = 1024;
-constexpr int SMALL_WAVES = 16;
+constexpr int small_waves(int nt) { return nt >= 8 ? 8 : 16; }
+
+// NT neighbouring fp16 values of a row of W_g as one load.
+template <int NT>
+struct GateRow {
+  typedef _Float16 type __attribute__((ext_vector_type(NT)));
+  static __device__ inline _Float16 at(const type& v, int i) { return v[i]; }
+};
+template <>
+struct GateRow<1> {
+  typedef _Float16 type;
+  static __device__ inline _Float16 at(const type& v, int) { return v; }
+};
 
 // TABLES = false: the same scoring for any number of tokens (T_total), one workgroup per
 // 16 tokens, top-1 and gate only; route_segments_kernel follows.
 template <int NT, bool TABLES>
-__global__ __launch_bounds__(SMALL_THREADS) void route_small_kernel(const half_t* __restrict__ x,
-                                                                    const half_t* __restrict__ wg, int T_total, int d,
-                                                                    int* __restrict__ expert_idx,
-                                                                    float* __restrict__ gate,
-                                                                    int* __restrict__ seg_offsets,
-                                                                    int* __restrict__ perm) {
+__global__ __launch_bounds__(64 * small_waves(NT)) void route_small_kernel(const half_t* __restrict__ x,
+                                                                           const half_t* __restrict__ wg, int T_total,
+                                                                           int d, int* __restrict__ expert_idx,
+                                                                           float* __restrict__ gate,
+                                                                           int* __restrict__ seg_offsets,
+                                                                           int* __restrict__ perm) {
   constexpr int MT = !TABLES ? 1 : NT >= 8 ? 2 : 4;
   constexpr int E = 16 * NT;
+  constexpr int WAVES = small_waves(NT), THREADS = 64 * WAVES;
   // this workgroup's tokens
   const int t_base = TABLES ? 0 : (int)blockIdx.x * 16 * MT;
   const int T = TABLES ? T_total : min(16 * MT, T_total - t_base);
   x += (int64_t)t_base * d;
   expert_idx += t_base;
   gate += t_base;
-  constexpr int PART_TILES = NT < 4 ? 4 : NT;  // 16 x 16 result tiles the partial-sum buffer holds per wave
-  __shared__ float4_t s_part[SMALL_WAVES][PART_TILES][64];
-  __shared__ float s_logit[MT * 16 * E];
+  // 16 x 16 result tiles the partial-sum buffer holds per wave, token tiles summed per pass
+  constexpr int PART_TILES = MT * NT > 8 ? 8 : MT * NT;
+  constexpr int MT_PASS = PART_TILES / NT;
+  constexpr int LROW = E + 16;  // row of logits; the pad sends neighbouring tokens to different banks
+  __shared__ float4_t s_part[WAVES][PART_TILES][64];
+  __shared__ __align__(16) float s_logit[MT * 16 * LROW];
   __shared__ int s_idx[64];
   __shared__ int s_seg[E + 1];
 
@@ -361,54 +361,94 @@ __global__ __launch_bounds__(SMALL_THREADS) void route_small_kernel(const half_t
 #pragma unroll
     for (int ni = 0; ni < NT; ++ni) acc[mi][ni] = float4_t{0, 0, 0, 0};
 
-  for (int s = wave; s < steps; s += SMALL_WAVES) {
-    const int k0 = s * 32 + 8 * g;  // this lane's 8 rows of d
-    half8_t a[MT];
+  // Lane (g, j) holds, as the A operand, token row j of each token tile (rows past the last
+  // token repeat it: their logits are never looked at) over rows 8 g .. 8 g + 7 of a step, and,
+  // as the B operand of expert tile ni, column j of that tile.  Which experts make up a tile is
+  // free: tile ni takes the experts NT j + ni, so that the NT values a lane needs from one row
+  // of W_g are neighbours and come with one load (eight loads per step whatever E is; one CU's
+  // memory pipeline takes a wave's load every 16 cycles or so whatever its width, and with two
+  // bytes per lane that, not latency, would set the time of this phase).
+  using Row = GateRow<NT>;
+  const half_t* xrow[MT];
+#pragma unroll
+  for (int mi = 0; mi < MT; ++mi) xrow[mi] = x + (int64_t)min(16 * mi + j, T - 1) * d + 8 * g;
+  const half_t* const wcol = wg + (int64_t)(8 * g) * E + NT * j;
+  // Up to 32 experts: two steps per trip, all their operands asked for before the first is
+  // used (a wave without a second step repeats the first and leaves its product out).  More
+  // expert tiles fill the registers with one step's operands.
+  constexpr int PER_TRIP = NT <= 2 ? 2 : 1;
+  for (int s = wave; s < steps; s += PER_TRIP * WAVES) {
+    const bool two = PER_TRIP == 2 && s + WAVES < steps;  // (uniform)
+    const int sb = two ? s + WAVES : s;
+    half8_t a0[MT], a1[PER_TRIP == 2 ? MT : 1];
+    typename Row::type w0[8], w1[PER_TRIP == 2 ? 8 : 1];
 #pragma unroll
     for (int mi = 0; mi < MT; ++mi) {
-      const int t = 16 * mi + j;
-      a[mi] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
-      if (t < T) a[mi] = *(const half8_t*)(x + (int64_t)t * d + k0);
+      a0[mi] = *(const half8_t*)(xrow[mi] + s * 32);
+      if constexpr (PER_TRIP == 2) a1[mi] = *(const half8_t*)(xrow[mi] + sb * 32);
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      w0[q] = *(const typename Row::type*)(wcol + (int64_t)s * 32 * E + q * E);
+      if constexpr (PER_TRIP == 2) w1[q] = *(const typename Row::type*)(wcol + (int64_t)sb * 32 * E + q * E);
     }
 #pragma unroll
     for (int ni = 0; ni < NT; ++ni) {
       half8_t b;
 #pragma unroll
-      for (int q = 0; q < 8; ++q) b[q] = wg[(int64_t)(k0 + q) * E + 16 * ni + j];
+      for (int q = 0; q < 8; ++q) b[q] = Row::at(w0[q], ni);
 #pragma unroll
       for (int mi = 0; mi < MT; ++mi)
-        if (mi < mt) acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mi], b, acc[mi][ni], 0, 0, 0);
+        if (mi < mt) acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0[mi], b, acc[mi][ni], 0, 0, 0);
+    }
+    if constexpr (PER_TRIP == 2) {
+      if (two) {
+#pragma unroll
+        for (int ni = 0; ni < NT; ++ni) {
+          half8_t b;
+#pragma unroll
+          for (int q = 0; q < 8; ++q) b[q] = Row::at(w1[q], ni);
+#pragma unroll
+          for (int mi = 0; mi < MT; ++mi)
+            if (mi < mt) acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1[mi], b, acc[mi][ni], 0, 0, 0);
+        }
+      }
     }
   }
-  // D layout of a tile: lane (g, j), register r holds token row 4 g + r, expert column j.
-  // The waves' partial tiles meet in LDS and are summed in a fixed order (wave 0, 1, ...): all
-  // token tiles in one pass when their partial sums fit the buffer together, else tile by tile.
-  const bool one_pass = mt * NT <= PART_TILES;
+  // D layout of a tile: lane (g, j), register r holds token row 4 g + r, expert NT j + ni.
+  // The waves' partial tiles meet in LDS and are summed in a fixed order (wave 0, 1, ...), as
+  // many token tiles per pass as the buffer holds.
+  for (int m0 = 0; m0 < mt; m0 += MT_PASS) {  // (uniform)
+    if (m0 > 0) __syncthreads();
 #pragma unroll
-  for (int mi = 0; mi < MT; ++mi) {
-    if (mi >= mt) break;  // uniform
-    const int slot0 = one_pass ? mi * NT : 0;
+    for (int mi = 0; mi < MT; ++mi) {
+      if (mi < m0 || mi >= m0 + MT_PASS || mi >= mt) continue;
 #pragma unroll
-    for (int ni = 0; ni < NT; ++ni) s_part[wave][slot0 + ni][lane] = acc[mi][ni];
-    if (one_pass && mi + 1 < mt) continue;
-    __syncthreads();
-    const int mi_first = one_pass ? 0 : mi;
-    const int n_out = (mi - mi_first + 1) * NT * 256;
-    for (int o = tid; o < n_out; o += SMALL_THREADS) {
-      const int slot = o >> 8, l = (o & 255) >> 2, r = o & 3;
-      const int mo = mi_first + slot / NT, ni = slot % NT;
-      float sum = 0.0f;
-#pragma unroll
-      for (int w = 0; w < SMALL_WAVES; ++w) sum += reinterpret_cast<const float*>(&s_part[w][slot][l])[r];
-      s_logit[(16 * mo + 4 * (l >> 4) + r) * E + 16 * ni + (l & 15)] = sum;
+      for (int ni = 0; ni < NT; ++ni) s_part[wave][(mi - m0) * NT + ni][lane] = acc[mi][ni];
     }
     __syncthreads();
+    const int n_out = min(MT_PASS, mt - m0) * NT * 64;
+    for (int o = tid; o < n_out; o += THREADS) {
+      const int slot = o >> 6, l = o & 63;
+      float4_t sum = s_part[0][slot][l];
+#pragma unroll
+      for (int w = 1; w < WAVES; ++w) sum = sum + s_part[w][slot][l];
+      const int mo = m0 + slot / NT, ni = slot % NT;
+      float* const out = &s_logit[(16 * mo + 4 * (l >> 4)) * LROW + NT * (l & 15) + ni];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) out[r * LROW] = sum[r];
+    }
   }
-  for (int t = wave; t < T; t += SMALL_WAVES) {
+  __syncthreads();
+
+  // top-1 and gate: a row of 16 lanes per token, four tokens per wave
+  for (int t0 = 4 * wave; t0 < T; t0 += 4 * WAVES) {  // (uniform)
+    const int t = t0 + g;
+    const float* const row = &s_logit[min(t, T - 1) * LROW];
     int idx;
     float gt;
-    wave_pick(&s_logit[t * E], E, &idx, &gt);
-    if (lane == 0) {
+    row16_pick<NT>([row](int e) { return row[e]; }, j, E, &idx, &gt);
+    if (j == 0 && t < T) {
       expert_idx[t] = idx;
       gate[t] = gt;
       s_idx[t] = idx;
@@ -434,17 +474,13 @@ __global__ __launch_bounds__(SMALL_THREADS) void route_small_kernel(const half_t
     for (int eg = 0; eg < E; eg += 64) {
       const int e = eg + lane;
       const int v = (e < E) ? s_seg[e] : 0;
-      int inc = v;
-      for (int off = 1; off < 64; off <<= 1) {
-        const int o = __shfl_up(inc, off, 64);
-        if (lane >= off) inc += o;
-      }
+      const int inc = wave_inclusive_scan(v);
       __builtin_amdgcn_wave_barrier();
       if (e < E) {
         s_seg[e] = carry + inc - v;
         seg_offsets[e] = carry + inc - v;
       }
-      carry += __shfl(inc, 63, 64);
+      carry += __builtin_amdgcn_readlane(inc, 63);
     }
     if (lane == 0) seg_offsets[E] = T;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -512,10 +548,10 @@ hipError_t moqe_launch_route(const uint16_t* x, const uint16_t* wg, const float*
     const half_t* xh = (const half_t*)x;
     const half_t* wh = (const half_t*)wg;
     switch (E) {
-      case 16: hipLaunchKernelGGL((route_small_kernel<1, true>), dim3(1), dim3(SMALL_THREADS), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
-      case 32: hipLaunchKernelGGL((route_small_kernel<2, true>), dim3(1), dim3(SMALL_THREADS), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
-      case 64: hipLaunchKernelGGL((route_small_kernel<4, true>), dim3(1), dim3(SMALL_THREADS), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
-      default: hipLaunchKernelGGL((route_small_kernel<8, true>), dim3(1), dim3(SMALL_THREADS), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
+      case 16: hipLaunchKernelGGL((route_small_kernel<1, true>), dim3(1), dim3(64 * small_waves(1)), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
+      case 32: hipLaunchKernelGGL((route_small_kernel<2, true>), dim3(1), dim3(64 * small_waves(2)), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
+      case 64: hipLaunchKernelGGL((route_small_kernel<4, true>), dim3(1), dim3(64 * small_waves(4)), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
+      default: hipLaunchKernelGGL((route_small_kernel<8, true>), dim3(1), dim3(64 * small_waves(8)), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
     }
     return hipGetLastError();
   }
@@ -526,10 +562,10 @@ hipError_t moqe_launch_route(const uint16_t* x, const uint16_t* wg, const float*
     const int per_wg = 16;
     const dim3 grid((unsigned)((T + per_wg - 1) / per_wg));
     switch (E) {
-      case 16: hipLaunchKernelGGL((route_small_kernel<1, false>), grid, dim3(SMALL_THREADS), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
-      case 32: hipLaunchKernelGGL((route_small_kernel<2, false>), grid, dim3(SMALL_THREADS), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
-      case 64: hipLaunchKernelGGL((route_small_kernel<4, false>), grid, dim3(SMALL_THREADS), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
-      default: hipLaunchKernelGGL((route_small_kernel<8, false>), grid, dim3(SMALL_THREADS), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
+      case 16: hipLaunchKernelGGL((route_small_kernel<1, false>), grid, dim3(64 * small_waves(1)), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
+      case 32: hipLaunchKernelGGL((route_small_kernel<2, false>), grid, dim3(64 * small_waves(2)), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
+      case 64: hipLaunchKernelGGL((route_small_kernel<4, false>), grid, dim3(64 * small_waves(4)), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
+      default: hipLaunchKernelGGL((route_small_kernel<8, false>), grid, dim3(64 * small_waves(8)), 0, stream, xh, wh, T, d, expert_idx, gate, seg_offsets, perm); break;
     }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
