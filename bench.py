@@ -66,6 +66,8 @@ def parse():
     ap.add_argument("--cpu-steps", type=int, default=None, help="oracle steps timed, the median is reported (default 5; 1 from 512 tokens on)")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches only")
     ap.add_argument("--parts", action="store_true", help="also time each kernel of the step on its own")
+    ap.add_argument("--tiled", default="auto", choices=("auto", "streamed"),
+                    help="which tiled kernel serves many-token segments (moqe_set_tiled_kernel); default: the library's choice")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run three plain device-to-device copies of this size first: under "
                          "rocprofv3 --pmc they give the counter reading of a known amount of traffic")
@@ -112,6 +114,7 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    moqe.moqe_set_tiled_kernel({"auto": moqe.TILED_AUTO, "streamed": moqe.TILED_STREAMED}[args.tiled])
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
     variants = dict(W.CONFIGS)

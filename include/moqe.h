@@ -13,9 +13,9 @@
  *     (moqe_workspace_status apart) never synchronises: each call validates its
  *     arguments on the host, enqueues kernels on `stream` (a hipStream_t passed as
  *     void*, NULL = the null stream) and returns.
- *   - State the library keeps between calls: three process-wide tuning settings
- *     (moqe_set_launch_mode, moqe_set_decode_kernel, moqe_set_prefill_policy; plain
- *     atomics, results do not depend on them), per-device cached device properties,
+ *   - State the library keeps between calls: four process-wide tuning settings
+ *     (moqe_set_launch_mode, moqe_set_decode_kernel, moqe_set_tiled_kernel,
+ *     moqe_set_prefill_policy; plain atomics, results do not depend on them), per-device cached device properties,
  *     and the array behind moqe_moe_layer_static.  Everything else that survives a
  *     call lives in the caller's FFN / layer workspace (see the *_workspace_bytes
  *     functions below).
@@ -104,6 +104,15 @@ int moqe_set_launch_mode(int mode);
  * general kernel.  Returns the previous setting, or -1 (nothing changed) for an unknown one. */
 enum { MOQE_DECODE_AUTO = 0, MOQE_DECODE_GENERAL = 1 };
 int moqe_set_decode_kernel(int which);
+
+/* Which tiled matrix-core kernel serves the expert segments with many tokens (a process-wide
+ * setting, for tests and comparisons; results are within the same tolerance either way): AUTO
+ * keeps a tile's token rows resident in LDS for the whole contraction where they fit (K <= 1024,
+ * a multiple of 256 for int4 and of 512 for int3 / int2; 2- to 4-bit codes, at most 1024 experts,
+ * T*N < 2^30) and stages K in blocks elsewhere; STREAMED always stages K in blocks.  Returns the
+ * previous setting, or -1 (nothing changed) for an unknown one. */
+enum { MOQE_TILED_AUTO = 0, MOQE_TILED_STREAMED = 1 };
+int moqe_set_tiled_kernel(int which);
 
 /* Path choice inside the expert FFN (process-wide, for tuning and tests; results are within
  * the same tolerance either way): in a batch of at least min_batch_tokens tokens, expert

@@ -12,7 +12,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libmoqe.so")
 SOURCES = ("moqe_api.hip", "moqe_quantize.hip", "moqe_route.hip", "moqe_ffn_decode.hip", "moqe_ffn_decode_small.hip",
-           "moqe_ffn_prefill.hip", "moqe_stream_read.hip")
+           "moqe_ffn_prefill.hip", "moqe_ffn_resident.hip", "moqe_stream_read.hip")
 
 
 def hipcc() -> str:

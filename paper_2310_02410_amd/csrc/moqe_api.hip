@@ -50,6 +50,8 @@ std::atomic<int> g_prefill_batch{MOQE_PREFILL_MIN_BATCH_DEFAULT};
 std::atomic<int> g_prefill_all{MOQE_PREFILL_ALL_TILED_DEFAULT};
 // Decode-sized batches take the lean decode kernel where it applies (moqe_set_decode_kernel).
 std::atomic<int> g_small_decode{1};
+// Which tiled kernel serves the many-token segments (moqe_set_tiled_kernel).
+std::atomic<int> g_tiled_kernel{MOQE_TILED_AUTO};
 
 }  // namespace
 
@@ -84,6 +86,11 @@ int moqe_set_prefill_policy(int min_segment_tokens, int min_batch_tokens, int al
 int moqe_set_decode_kernel(int which) {
   if (which != MOQE_DECODE_AUTO && which != MOQE_DECODE_GENERAL) return -1;
   return g_small_decode.exchange(which == MOQE_DECODE_AUTO) ? MOQE_DECODE_AUTO : MOQE_DECODE_GENERAL;
+}
+
+int moqe_set_tiled_kernel(int which) {
+  if (which != MOQE_TILED_AUTO && which != MOQE_TILED_STREAMED) return -1;
+  return g_tiled_kernel.exchange(which);
 }
 
 int moqe_set_launch_mode(int mode) {
@@ -372,6 +379,10 @@ static hipError_t launch_contraction(DecodeArgs& a, int phase, int ksteps, hipSt
   q.seg_offsets = a.seg_offsets;
   q.perm = a.perm;
   q.gate = a.gate;
+  const int tiled = g_tiled_kernel.load();
+  if (tiled != MOQE_TILED_STREAMED && a.E <= 1024 && (int64_t)a.T * p.N < (1ll << 30) &&
+      moqe_resident_supported(a.bits, p.K, p.N))
+    return moqe_launch_resident(q, num_cus(), stream);
   return moqe_launch_prefill(q, num_cus(), stream);
 }
 

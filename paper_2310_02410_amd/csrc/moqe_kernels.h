@@ -88,6 +88,10 @@ struct PrefillArgs {
 };
 bool moqe_prefill_supported(int bits, int64_t K, int64_t N);
 hipError_t moqe_launch_prefill(const PrefillArgs& a, int num_cus, hipStream_t stream);
+// The same contraction with a tile's token rows resident in LDS for the whole K (K <= 1024,
+// 2- to 4-bit codes, T N < 2^30).
+bool moqe_resident_supported(int bits, int64_t K, int64_t N);
+hipError_t moqe_launch_resident(const PrefillArgs& a, int num_cus, hipStream_t stream);
 
 // One contraction of a decode-sized batch (T <= 64, E <= 128, 2- to 4-bit codes): the lean
 // dequantize-in-register kernel, one pair (expert, 4 tokens) per workgroup.

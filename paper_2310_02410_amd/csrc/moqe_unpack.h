@@ -268,6 +268,15 @@ __device__ inline half8_t unpack3_exact(uint32_t dl, uint32_t dh, const C& c) {
                          pk_sub(pk_add(l.z, h.z), 36.0f), pk_sub(pk_add(l.w, h.w), 16.0f));
 }
 
+// int3 with the two planes added and their offsets left in the value (bias_frag<3>): one
+// fragment, hence one MFMA, per step.
+template <int SS, class C>
+__device__ inline half8_t unpack3_sum(uint32_t dl, uint32_t dh, const C& c) {
+  const uint4_t l = __builtin_bit_cast(uint4_t, unpack2<SS & 1>(dl, c));
+  const uint4_t h = __builtin_bit_cast(uint4_t, unpack1x4<SS>(dh, c));
+  return frag_from_words(pk_add(l.x, h.x), pk_add(l.y, h.y), pk_add(l.z, h.z), pk_add(l.w, h.w));
+}
+
 // Constant B fragment holding, per code position, the amount the unpacked value
 // exceeds the signed code: exponent bias(es) + zero point.
 template <int BITS>

@@ -28,7 +28,7 @@ EXPORTS = (
     "moqe_layer_workspace_bytes", "moqe_moe_layer", "moqe_set_launch_mode",
     "moqe_set_prefill_policy", "moqe_quantize_tensor_scale", "moqe_quantize_log", "moqe_dequantize_log",
     "moqe_moe_layer_static", "moqe_set_decode_kernel", "moqe_workspace_status",
-    "moqe_stream_read",
+    "moqe_stream_read", "moqe_set_tiled_kernel",
 )
 
 LAUNCH_AUTO, LAUNCH_SEPARATE, LAUNCH_FUSED = 0, 1, 2
@@ -79,6 +79,8 @@ def lib() -> ctypes.CDLL:
     L.moqe_workspace_status.argtypes = [vp, sz, vp]
     L.moqe_set_decode_kernel.restype = ci
     L.moqe_set_decode_kernel.argtypes = [ci]
+    L.moqe_set_tiled_kernel.restype = ci
+    L.moqe_set_tiled_kernel.argtypes = [ci]
     L.moqe_set_prefill_policy.restype = ci
     L.moqe_set_prefill_policy.argtypes = [ci, ci, ci]
     L.moqe_packed_bytes.restype = sz
@@ -178,6 +180,18 @@ def moqe_set_decode_kernel(which: int) -> int:
     old = lib().moqe_set_decode_kernel(which)
     if old < 0:
         raise ValueError(f"unknown decode kernel choice {which}")
+    return old
+
+
+TILED_AUTO, TILED_STREAMED = 0, 1
+
+
+def moqe_set_tiled_kernel(which: int) -> int:
+    """Process-wide: TILED_AUTO (token rows resident in LDS where a tile's fit, K <= 1024) or
+    TILED_STREAMED (always K staged in blocks); returns the old setting."""
+    old = lib().moqe_set_tiled_kernel(which)
+    if old < 0:
+        raise ValueError(f"unknown tiled kernel choice {which}")
     return old
 
 

@@ -46,6 +46,9 @@ def test_version_and_strings():
     assert L.moqe_set_decode_kernel(5) == -1
     old = L.moqe_set_decode_kernel(moqe.DECODE_GENERAL)
     assert L.moqe_set_decode_kernel(old) == moqe.DECODE_GENERAL
+    assert L.moqe_set_tiled_kernel(2) == -1 and L.moqe_set_tiled_kernel(-1) == -1
+    old = L.moqe_set_tiled_kernel(moqe.TILED_STREAMED)
+    assert old == moqe.TILED_AUTO and L.moqe_set_tiled_kernel(old) == moqe.TILED_STREAMED
     assert L.moqe_workspace_status(None, 4096, None) == 1 and L.moqe_workspace_status(P, 512, None) == 5
     assert L.moqe_stream_read(None, 1024, P, None) == 1 and L.moqe_stream_read(P, 1000, P, None) == 3
     assert L.moqe_stream_read(P, 0, P, None) == 3 and L.moqe_stream_read(P + 8, 1024, P, None) == 4

@@ -25,6 +25,15 @@ def prefill_min():
     moqe.moqe_set_prefill_policy()
 
 
+@pytest.fixture(params=("resident", "streamed"))
+def tiled(request):
+    """Runs a test once per tiled kernel: token rows resident in LDS where a pair's fit (the
+    library's choice), and K staged in blocks throughout."""
+    moqe.moqe_set_tiled_kernel(moqe.TILED_AUTO if request.param == "resident" else moqe.TILED_STREAMED)
+    yield request.param
+    moqe.moqe_set_tiled_kernel(moqe.TILED_AUTO)
+
+
 def _parity(wl, bits, residual=False, forced=None, layer=None):
     layer = W.make_layer(wl) if layer is None else layer
     x = W.make_tokens(wl)
@@ -47,7 +56,7 @@ def _parity(wl, bits, residual=False, forced=None, layer=None):
 
 @pytest.mark.parametrize("bits", (8, 4, 3, 2))
 @pytest.mark.parametrize("T", (1, 37, 150, 700))
-def test_every_segment_through_the_tiled_kernel(prefill_min, bits, T):
+def test_every_segment_through_the_tiled_kernel(prefill_min, tiled, bits, T):
     # threshold 1: also one-token segments take 64-token tiles (ragged in every way);
     # d=256, f=512: one and two K blocks for int2/int3, two and four for int4
     prefill_min(1)
@@ -55,7 +64,7 @@ def test_every_segment_through_the_tiled_kernel(prefill_min, bits, T):
 
 
 @pytest.mark.parametrize("bits", (8, 4, 3, 2))
-def test_tiled_kernel_residual_and_odd_widths(prefill_min, bits):
+def test_tiled_kernel_residual_and_odd_widths(prefill_min, tiled, bits):
     prefill_min(1)
     _parity(W.small(E=4, d=512, f=1024, T=90, seed=81), bits, residual=True)
     _parity(W.small(E=3, d=768, f=256, T=33, seed=83), bits)
@@ -67,7 +76,7 @@ def test_tiled_kernel_residual_and_odd_widths(prefill_min, bits):
 
 @pytest.mark.parametrize("all_tiled", (False, True))
 @pytest.mark.parametrize("bits", (4, 2))
-def test_forced_segment_sizes(bits, all_tiled, prefill_min):
+def test_forced_segment_sizes(bits, all_tiled, prefill_min, tiled):
     """Segments of exactly 4, 5, 63, 64, 65 and 200 tokens, with full and ragged tiles.  With
     the decode kernel kept for segments below 5 tokens the first goes there and the others to
     the tiled kernel; at the defaults this batch has 50 tokens per expert, so all of them,
@@ -177,7 +186,7 @@ def test_threshold_does_not_change_results_beyond_tolerance(prefill_min):
     assert np.abs(outs[1] - outs[2]).max() <= 2 * FFN_TOL * scale
 
 
-def test_config3_full_size():
+def test_config3_full_size(tiled):
     """Config 3: T=1536, Zipf(1.1) load over 32 experts (largest segment several hundred
     tokens, four experts empty), int4; every output compared."""
     wl = W.CONFIGS["c3"]

@@ -1,0 +1,154 @@
+"""GPU parity of the tiled kernel that keeps a pair's token rows resident in LDS (K <= 1024) against
+the oracle, next to the kernel that stages K in blocks: every shape the work split, the staging
+and the unit hand-out distinguish."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import moqe_oracle as O
+from paper_2310_02410_amd import moqe, workloads as W
+from tests.helpers import FFN_TOL, dev, ffn_error, gpu_quantize_layer, make_route, oracle_layer_output
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture
+def all_tiled():
+    """Every segment, however small, takes the tiled kernel; defaults restored afterwards."""
+    moqe.moqe_set_prefill_policy(1, 1, moqe.PREFILL_NEVER)
+    yield
+    moqe.moqe_set_prefill_policy()
+    moqe.moqe_set_tiled_kernel(moqe.TILED_AUTO)
+
+
+def _run(wl, bits, idx, gate, residual=False, codec="linear"):
+    layer, x = W.make_layer(wl), W.make_tokens(wl)
+    xd = dev(x)
+    r = make_route(idx, gate, wl.E)
+    g64 = np.asarray(gate, dtype=np.float64)
+    if codec == "log":
+        ql = moqe.quantize_layer(dev(layer["w1"]), dev(layer["b1"]), dev(layer["w2"]), dev(layer["b2"]), bits,
+                                 dev(layer["w_gate"]), codec=moqe.CODEC_LOG)
+        q1, s1 = O.quantize_log(layer["w1"], bits)
+        q2, s2 = O.quantize_log(layer["w2"], bits)
+        ref = O.expert_ffn(x, idx, g64, O.dequantize_log(q1, s1, bits), layer["b1"], O.dequantize_log(q2, s2, bits),
+                           layer["b2"], residual=x if residual else None)
+    else:
+        ql = gpu_quantize_layer(layer, bits)
+        ref = oracle_layer_output(x, layer, bits, idx, g64, residual=residual)
+    out = {}
+    for name, which in (("resident", moqe.TILED_AUTO), ("streamed", moqe.TILED_STREAMED)):
+        moqe.moqe_set_tiled_kernel(which)
+        y = moqe.moqe_expert_ffn(ql, xd, r, residual=xd if residual else None)
+        torch.cuda.synchronize()
+        out[name] = y.cpu().numpy()
+        err = ffn_error(out[name], ref)
+        assert err <= FFN_TOL, f"{wl.name} {codec} {bits} bits, {name}: max|err|/max|ref| = {err:.3e}"
+    return out, ref
+
+
+def _forced(sizes, seed):
+    idx = np.concatenate([np.full(n, e) for e, n in enumerate(sizes)]).astype(np.int32)
+    rng = np.random.default_rng(seed)
+    rng.shuffle(idx)
+    return idx, rng.uniform(0.2, 1.0, size=idx.size).astype(np.float32)
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+def test_ragged_pairs_of_every_height(all_tiled, bits):
+    """Segments that end in a pair of 1, 2, 3 and 4 token tiles (1, 17, 33, 49 and 64 rows), full
+    pairs in front of some of them, an empty expert; d = 1024 (the largest K that stays resident,
+    four or eight chunks per column tile) and d_ff = 512 (FFN2 resident too, K = 512)."""
+    sizes = (1, 17, 33, 49, 64, 65, 0, 64 + 64 + 3)
+    idx, gate = _forced(sizes, 91)
+    _run(W.small(E=8, d=1024, f=512, T=int(sum(sizes)), seed=91), bits, idx, gate, residual=True)
+
+
+@pytest.mark.parametrize("bits", (4, 2))
+def test_more_pairs_than_workgroups(all_tiled, bits):
+    """A narrow FFN1 (128 channels at int4: four units per pair, half a round; 256 at int2) and
+    20,000 tokens: 300-odd pairs for 256 workgroups, so every workgroup takes up several pairs,
+    some of them ragged."""
+    wl = W.small(E=24, d=512, f=128 if bits == 4 else 256, T=20000, seed=92)
+    rng = np.random.default_rng(92)
+    idx = rng.integers(0, 24, size=wl.T).astype(np.int32)
+    idx[idx == 5] = 6  # an empty expert in the middle
+    gate = rng.uniform(0.2, 1.0, size=wl.T).astype(np.float32)
+    layer, x = W.make_layer(wl), W.make_tokens(wl)
+    xd = dev(x)
+    r = make_route(idx, gate, wl.E)
+    ql = gpu_quantize_layer(layer, bits)
+    moqe.moqe_set_tiled_kernel(moqe.TILED_AUTO)
+    y = moqe.moqe_expert_ffn(ql, xd, r).cpu().numpy()
+    rows = np.random.default_rng(93).choice(wl.T, size=1500, replace=False)
+    perm = np.argsort(idx, kind="stable")
+    offs = np.concatenate([[0], np.cumsum(np.bincount(idx, minlength=wl.E))])
+    ne = np.diff(offs) > 0
+    rows = np.unique(np.concatenate([rows, perm[offs[:-1][ne]], perm[offs[1:][ne] - 1]]))
+    ref = oracle_layer_output(x[rows], layer, bits, idx[rows], gate[rows].astype(np.float64))
+    assert ffn_error(y[rows], ref) <= FFN_TOL
+    moqe.moqe_set_tiled_kernel(moqe.TILED_STREAMED)
+    y2 = moqe.moqe_expert_ffn(ql, xd, r).cpu().numpy().astype(np.float64)
+    assert np.abs(y2 - y).max() <= 2 * FFN_TOL * np.abs(y2).max()
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+def test_window_of_two_chunks_and_partial_rounds(all_tiled, bits):
+    """Column tiles with six chunks (d = 768 at int4) or two (d_ff = 256 at int4, 512 at int3 / int2):
+    a window of two chunks instead of four; and, at int4, d = 128: FFN2 has four units per pair,
+    half a round (FFN1, K = 128, stays with the decode kernel)."""
+    sizes = (40, 130, 7, 64)
+    idx, gate = _forced(sizes, 94)
+    T = int(sum(sizes))
+    if bits == 4:
+        _run(W.small(E=4, d=768, f=256, T=T, seed=94), bits, idx, gate)
+        _run(W.small(E=4, d=128, f=512, T=T, seed=97), bits, idx, gate, residual=True)
+    else:
+        _run(W.small(E=4, d=512, f=512, T=T, seed=94), bits, idx, gate)
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+def test_log_scale_codes_resident(all_tiled, bits):
+    sizes = (70, 3, 50, 0)
+    idx, gate = _forced(sizes, 95)
+    _run(W.small(E=4, d=512, f=1024, T=int(sum(sizes)), seed=95), bits, idx, gate, residual=True, codec="log")
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+def test_offsets_left_in_the_sum_cost_no_accuracy(all_tiled, bits):
+    """The resident kernel leaves a constant per code position in the unpacked weights and takes
+    sum_k a_k c_k out once per pair.  Worst case for that: long K (1024), activations that are all
+    positive and far from zero mean (FFN2 reads h after ReLU; here x itself is shifted to mean 3),
+    so that the constants' sum is thousands of times the signal.  Same bound as everywhere."""
+    wl = W.small(E=4, d=1024, f=1024, T=200, seed=96)
+    layer, x = W.make_layer(wl), W.make_tokens(wl)
+    x = (np.abs(x.astype(np.float32)) + 3.0).astype(np.float16)
+    sizes = (64, 100, 33, 3)
+    idx, gate = _forced(sizes, 96)
+    xd = dev(x)
+    r = make_route(idx, gate, wl.E)
+    ql = gpu_quantize_layer(layer, bits)
+    ref = oracle_layer_output(x, layer, bits, idx, gate.astype(np.float64))
+    moqe.moqe_set_tiled_kernel(moqe.TILED_AUTO)
+    err = ffn_error(moqe.moqe_expert_ffn(ql, xd, r).cpu().numpy(), ref)
+    assert err <= FFN_TOL, f"int{bits}: {err:.3e}"
+
+
+def test_resident_and_streamed_agree_at_the_benchmarked_size(all_tiled):
+    """One layer of the 12-layer int2 stack at 4096 tokens (E = 32, d = 1024, d_ff = 4096): FFN1
+    through both tiled kernels, every element of h within two fp16 units of the other kernel's
+    (they add the same products in different groupings)."""
+    wl = [v for v in W.c4_variants() if v.name == "c4_T4096_uniform"][0]
+    layer, x = W.make_layer(wl), W.make_tokens(wl)
+    ql = gpu_quantize_layer(layer, 2)
+    xd = dev(x)
+    r = moqe.moqe_route(xd, ql.w_gate)
+    hs = []
+    for which in (moqe.TILED_AUTO, moqe.TILED_STREAMED):
+        moqe.moqe_set_tiled_kernel(which)
+        h = torch.empty((wl.T, wl.f), dtype=torch.float16, device="cuda")
+        moqe.moqe_expert_ffn1(ql, xd, r, h)
+        hs.append(h.float().cpu().numpy())
+    scale = np.abs(hs[1]).max()
+    assert np.abs(hs[0] - hs[1]).max() <= 2e-3 * scale
