@@ -313,8 +313,9 @@ def main():
             flops = 2.0 * T * d * f
             res.update(bound="mfma", kernel_us=kern_us, kernel_work=flops, achieved=flops / (kern_us * 1e-6) / 1e12,
                        peak=MFMA_F16_PEAK_TFLOPS, unit="TFLOP/s",
-                       kernel="moe_prefill_kernel<%d,*> (the launches of FFN1 and FFN2, each back to back, "
-                              "averaged)" % kbits(b))
+                       kernel="the tiled kernels (FFN1: moe_resident_kernel<%d,2,8,*,0> where K <= 1024 with %s, else "
+                              "moe_prefill_kernel; FFN2: moe_prefill_kernel<%d,*>; each launched back to back, the "
+                              "two averaged)" % (kbits(b), "--tiled auto", kbits(b)))
         else:
             kern_us = parts["ffn1_back_to_back_us"]
             read_us = time_stream_read(ffn1_bytes)
