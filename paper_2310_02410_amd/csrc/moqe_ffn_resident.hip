@@ -5,13 +5,13 @@
 //
 // Work decomposition
 //   pair = (expert e, tile of 64 of its tokens), found on device from seg_offsets
-//   unit = (pair, group of NT column tiles of 16 channels); round = WAVES consecutive units of
-//          a pair.  A round costs 4 + 3 (token tiles of the pair) - the unpack does not shrink
-//          with a ragged pair, the matrix-core work and the epilogue do -, taking up a pair costs
-//          about a round and a half, and the rounds of the whole launch, in pair-major order,
-//          are cut into one contiguous range of equal cost per workgroup (one workgroup of WAVES
-//          waves per compute unit): every workgroup gets the same work whatever the number of
-//          pairs is, and a range touches as few pairs as possible
+//   unit = (pair, group of NT column tiles of 16 channels).  A unit costs 8 + 10 (token tiles
+//          of the pair) - the unpack does not shrink with a ragged pair, the matrix-core work and
+//          the epilogue do -, taking up a pair costs about eight units of a full pair, and the
+//          units of the whole launch, in pair-major order, are cut into one contiguous range of
+//          equal cost per workgroup (one workgroup of WAVES waves per compute unit): every
+//          workgroup gets the same work whatever the number of pairs is, and a range touches as
+//          few pairs as possible
 //   per pair of its range a workgroup
 //     - stages the pair's 64 x K token rows in LDS ONCE (128 KiB at K = 1024; loads that go from
 //       global memory straight into LDS, a row's 16-byte pieces XOR-swizzled by the row number so
@@ -50,12 +50,15 @@ namespace {
 constexpr int RS_TILE_M = 64;    // tokens per pair
 constexpr int RS_MAX_K = 1024;   // 64 rows x 1024 x 2 bytes = 128 KiB of LDS
 constexpr int RS_MAX_E = 1024;
-// Cost model of the work split, in units in which a round (WAVES units of a pair, 32 K steps
-// per 1024 of K each) costs 4 + 3 (token tiles): the unpack does not shrink with a ragged pair,
-// the matrix-core work and the epilogue do.  Taking up a pair (staging its rows, the offset
-// sums) costs about a round and a half of a full pair, measured.
-constexpr int RS_SWITCH = 24;
-__host__ __device__ constexpr int rs_round_cost(int token_tiles) { return 4 + 3 * token_tiles; }
+// Cost model of the work split, fitted to time stamps of the 4096-token and the 1536-token
+// layers (int2 and int4, uniform and Zipf load): eight units (of two column tiles, 32 K steps per
+// 1024 of K) of a pair with m token tiles take 1.9 / 2.6-3.0 / 3.8-4.2 / 5.2-5.3 us for m = 1 .. 4
+// on a workgroup's eight waves - the unpack does not shrink with a ragged pair, the matrix-core
+// work and the epilogue do - and taking up a pair (staging its rows, the offset sums) about as
+// long as eight units of a full pair.  rs_round_cost: of eight units; RS_SWITCH: of a pair's
+// start, in the same scale.
+constexpr int RS_SWITCH = 44;
+__host__ __device__ constexpr int rs_round_cost(int token_tiles) { return 8 + 10 * token_tiles; }
 
 struct RsPair {
   int e, row0, rows;
@@ -99,7 +102,9 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
 
   const int CT = N >> 4;
   const int NG = (CT + NT - 1) / NT;        // units per pair
-  const int RPP = (NG + WAVES - 1) / WAVES;  // rounds per pair
+  // cost of a unit of a pair with m token tiles, and of taking up a pair
+  auto unit_cost = [](int m) { return rs_round_cost(m) * (NT / 2); };
+  constexpr int SWITCH = RS_SWITCH * WAVES;
   const int Q = K / (32 * SC);              // packed chunks per column tile
   const int NSG = K >> 8;                   // segments of 256 along K
 
@@ -115,8 +120,7 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
         s_seg[e] = s0;
         if (e == E - 1) s_seg[E] = s0 + n;
         if (n >= A.min_tokens)
-          v = (n >> 6) * (RS_SWITCH + RPP * rs_round_cost(4)) +
-              ((n & 63) ? RS_SWITCH + RPP * rs_round_cost(((n & 63) + 15) >> 4) : 0);
+          v = (n >> 6) * (SWITCH + NG * unit_cost(4)) + ((n & 63) ? SWITCH + NG * unit_cost(((n & 63) + 15) >> 4) : 0);
       }
       v = wave_inclusive_scan(v);
       if (e < E) s_cost[e] = carry + v;
@@ -430,8 +434,8 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
     }
   };
 
-  // ---- this workgroup's rounds: those whose first unit of cost lies in [c_lo, c_hi) ----
-  // next_job walks through the pairs that have such rounds, in order.
+  // ---- this workgroup's units: those whose first unit of cost lies in [c_lo, c_hi) ----
+  // next_job walks through the pairs that have such units, in order.
   int it_e = E, it_ti = -1;
   for (int eg = 0; eg < E; eg += 64) {  // the first expert whose cost range ends beyond c_lo
     const bool beyond = eg + lane < E && s_cost[eg + lane] > c_lo;
@@ -449,24 +453,24 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
       const int seg0 = s_seg[it_e], n = s_seg[it_e + 1] - seg0;
       const int full = n >> 6, rem = n & 63;
       const int npairs = full + (rem ? 1 : 0);
-      const int pair_cost = RS_SWITCH + RPP * rs_round_cost(4);
+      const int pair_cost = SWITCH + NG * unit_cost(4);
       if (it_ti < 0) {
         it_ti = c_lo > base ? (c_lo - base) / pair_cost : 0;
         if (it_ti > full) it_ti = full;
       }
       for (; it_ti < npairs; ++it_ti) {
-        const int S = base + it_ti * pair_cost + RS_SWITCH;  // cost at the pair's first round
-        if (S - RS_SWITCH >= c_hi) break;
+        const int S = base + it_ti * pair_cost + SWITCH;  // cost at the pair's first unit
+        if (S - SWITCH >= c_hi) break;
         const int rows = it_ti < full ? RS_TILE_M : rem;
-        const int w = rs_round_cost((rows + 15) >> 4);
-        const int rd0 = c_lo > S ? (c_lo - S + w - 1) / w : 0;
-        int rd1 = c_hi > S ? (c_hi - S + w - 1) / w : 0;
-        if (rd1 > RPP) rd1 = RPP;
-        if (rd0 >= rd1) continue;
+        const int w = unit_cost((rows + 15) >> 4);
+        const int u0 = c_lo > S ? (c_lo - S + w - 1) / w : 0;
+        int u1 = c_hi > S ? (c_hi - S + w - 1) / w : 0;
+        if (u1 > NG) u1 = NG;
+        if (u0 >= u1) continue;
         RsJob jb;
         jb.t = RsPair{uniform_i32(it_e), uniform_i32(seg0 + RS_TILE_M * it_ti), uniform_i32(rows)};
-        jb.g0 = uniform_i32(rd0 * WAVES);
-        jb.g1 = uniform_i32(min(NG, rd1 * WAVES));
+        jb.g0 = uniform_i32(u0);
+        jb.g1 = uniform_i32(u1);
         ++it_ti;
         return jb;
       }
@@ -496,7 +500,8 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
 
 // Two column tiles per unit and 8 waves (two per SIMD, up to 256 registers each) measured
 // fastest: 4 column tiles per unit, or 12 or 16 waves with a window of two chunks, were 5 to 15 %
-// slower on the 4096-token layers.
+// slower on the 4096-token layers (4 column tiles per unit also with the units handed out one by
+// one: 46.7 against 44.6 us, so the LDS reads are not what the loop waits for).
 template <int BITS, int W>
 static void launch_shape(const PrefillArgs& a, int grid, hipStream_t stream) {
   constexpr int NT = 2, WAVES = 8;
