@@ -66,6 +66,8 @@ def parse():
     ap.add_argument("--cpu-steps", type=int, default=None, help="oracle steps timed, the median is reported (default 5; 1 from 512 tokens on)")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches only")
     ap.add_argument("--parts", action="store_true", help="also time each kernel of the step on its own")
+    ap.add_argument("--decode", default="auto", choices=("auto", "general", "rows8", "rows4"),
+                    help="which decode kernel serves batches of at most 64 tokens (moqe_set_decode_kernel)")
     ap.add_argument("--tiled", default="auto", choices=("auto", "streamed"),
                     help="which tiled kernel serves many-token segments (moqe_set_tiled_kernel); default: the library's choice")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
@@ -115,6 +117,8 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     moqe.moqe_set_tiled_kernel({"auto": moqe.TILED_AUTO, "streamed": moqe.TILED_STREAMED}[args.tiled])
+    moqe.moqe_set_decode_kernel({"auto": moqe.DECODE_AUTO, "general": moqe.DECODE_GENERAL, "rows8": moqe.DECODE_ROWS8,
+                                 "rows4": moqe.DECODE_ROWS4}[args.decode])
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
     variants = dict(W.CONFIGS)

@@ -96,13 +96,17 @@ enum { MOQE_LAUNCH_AUTO = 0, MOQE_LAUNCH_SEPARATE = 1, MOQE_LAUNCH_FUSED = 2 };
 int moqe_set_launch_mode(int mode);
 
 /* Which dequantize-in-register kernel serves decode-sized batches (a process-wide setting, for
- * tests and comparisons; each kernel is deterministic, both run the same sums in the same order
+ * tests and comparisons; each kernel is deterministic, all run the same sums in the same order
  * and differ only in how the last step, gate times output, is rounded to fp16 - by at most one
- * unit in the last place of a few outputs in ten thousand): AUTO takes the kernel specialised for batches
- * of at most 64 tokens (at most 128 experts, 2- to 4-bit codes) where it applies and the
- * general one elsewhere; GENERAL always takes the general one.  Launch mode FUSED uses the
- * general kernel.  Returns the previous setting, or -1 (nothing changed) for an unknown one. */
-enum { MOQE_DECODE_AUTO = 0, MOQE_DECODE_GENERAL = 1 };
+ * unit in the last place of a few outputs in ten thousand): AUTO takes the kernel specialised for
+ * batches of at most 64 tokens (at most 128 experts, 2- to 4-bit codes) where it applies and the
+ * general one elsewhere; the specialised kernel works on (expert, 4 of its tokens) up to 32
+ * tokens and on (expert, 8 of its tokens) from 33 tokens on, where experts with more than four
+ * tokens are common and their weights are then streamed once per eight (K = 1024 or 4096 only,
+ * else 4).  GENERAL always takes the general kernel; ROWS8 / ROWS4 are AUTO with 8 / 4 tokens at
+ * every batch size (bit-identical results).  Launch mode FUSED uses the general kernel.  Returns
+ * the previous setting, or -1 (nothing changed) for an unknown one. */
+enum { MOQE_DECODE_AUTO = 0, MOQE_DECODE_GENERAL = 1, MOQE_DECODE_ROWS8 = 2, MOQE_DECODE_ROWS4 = 3 };
 int moqe_set_decode_kernel(int which);
 
 /* Which tiled matrix-core kernel serves the expert segments with many tokens (a process-wide

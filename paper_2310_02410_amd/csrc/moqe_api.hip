@@ -49,7 +49,16 @@ std::atomic<int> g_prefill_min{MOQE_PREFILL_MIN_SEGMENT_DEFAULT};
 std::atomic<int> g_prefill_batch{MOQE_PREFILL_MIN_BATCH_DEFAULT};
 std::atomic<int> g_prefill_all{MOQE_PREFILL_ALL_TILED_DEFAULT};
 // Decode-sized batches take the lean decode kernel where it applies (moqe_set_decode_kernel).
+// 0: general kernel always; 1: the decode-sized kernel where it applies, with pairs of 8 token
+// rows from ROWS8_FROM_TOKENS tokens on; 2: the same with pairs of 8 rows at every size; 3: with
+// pairs of 4 rows at every size
 std::atomic<int> g_small_decode{1};
+// Measured on the benchmark layer (E = 32, d = 1024, f = 4096), per step: pairs of 8 rows against
+// pairs of 4 at 24 tokens 25.5 / 28.2 / 22.9 us against 25.9 / 27.5 / 22.1 (int4 / int3 / int2: the
+// kernels are faster back to back, the step is not), at 64 tokens 33.6 against 35.1 us under
+// uniform and 30.4 against 34.1 us under Zipf load (an expert's weights streamed once per 8
+// instead of once per 4 of its tokens).
+constexpr int ROWS8_FROM_TOKENS = 33;
 // Which tiled kernel serves the many-token segments (moqe_set_tiled_kernel).
 std::atomic<int> g_tiled_kernel{MOQE_TILED_AUTO};
 
@@ -84,8 +93,11 @@ int moqe_set_prefill_policy(int min_segment_tokens, int min_batch_tokens, int al
 }
 
 int moqe_set_decode_kernel(int which) {
-  if (which != MOQE_DECODE_AUTO && which != MOQE_DECODE_GENERAL) return -1;
-  return g_small_decode.exchange(which == MOQE_DECODE_AUTO) ? MOQE_DECODE_AUTO : MOQE_DECODE_GENERAL;
+  if (which != MOQE_DECODE_AUTO && which != MOQE_DECODE_GENERAL && which != MOQE_DECODE_ROWS8 && which != MOQE_DECODE_ROWS4)
+    return -1;
+  const int now = which == MOQE_DECODE_GENERAL ? 0 : which == MOQE_DECODE_ROWS8 ? 2 : which == MOQE_DECODE_ROWS4 ? 3 : 1;
+  const int old = g_small_decode.exchange(now);
+  return old == 0 ? MOQE_DECODE_GENERAL : old == 2 ? MOQE_DECODE_ROWS8 : old == 3 ? MOQE_DECODE_ROWS4 : MOQE_DECODE_AUTO;
 }
 
 int moqe_set_tiled_kernel(int which) {
@@ -340,6 +352,7 @@ static hipError_t launch_contraction(DecodeArgs& a, int phase, int ksteps, hipSt
       s.bits = a.bits;
       s.ksteps = ksteps;
       s.ksplit = p.ksplit;
+      s.rows = (g_small_decode.load() == 2 || (g_small_decode.load() == 1 && a.T >= ROWS8_FROM_TOKENS)) ? 8 : 4;
       s.mode = p.mode;
       s.E = a.E;
       s.T = a.T;

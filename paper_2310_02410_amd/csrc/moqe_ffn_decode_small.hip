@@ -9,9 +9,10 @@
 // around the latencies in front of and behind the weight stream rather than around throughput:
 //   * every wave reads the routing tables itself, with three loads into registers (one round
 //     trip, no LDS staging, no workgroup barrier), and finds its work with ballots;
-//   * a workgroup serves ONE pair (expert, tile of up to 4 of its tokens): the persistent grid
-//     is split into as many equal groups as there are pairs and a group's workgroups share the
-//     pair's column tiles, so a wave needs one set of token rows for all its units;
+//   * a workgroup serves ONE pair (expert, tile of up to 4 - or, from 33 tokens on, 8 - of its
+//     tokens): the persistent grid is split into as many equal groups as there are pairs and a
+//     group's workgroups share the pair's column tiles, so a wave needs one set of token rows
+//     for all its units;
 //   * the token rows ride along with the weights: a CU's (and the memory fabric's) requests are
 //     served in order, so rows asked for on their own arrive behind whatever weights other waves
 //     asked for a moment earlier - measured: microseconds late, with all arithmetic left for the
@@ -33,7 +34,7 @@
 // Work decomposition: unit = (pair, column tile of 16 channels); `R` waves of a workgroup share a
 // unit along K (each owns 32*KS rows, partial sums meet in LDS), 4/R teams per workgroup.  Codes go
 // straight from registers into v_mfma_f32_16x16x32_f16 as the B operand (see moqe_unpack.h), the
-// token rows are the A operand (rows 4..15 of a fragment read a row of zeros).
+// token rows are the A operand (the rows of a fragment beyond the pair's 4 or 8 read a row of zeros).
 #include <type_traits>
 
 #include "moqe_dev.h"
@@ -44,7 +45,6 @@ namespace {
 
 constexpr int WG_THREADS = 256;
 constexpr int WG_WAVES = 4;
-constexpr int TILE_ROWS = 4;
 #ifndef MOQE_SMALL_WG_PER_CU
 #define MOQE_SMALL_WG_PER_CU 3
 #endif
@@ -84,13 +84,18 @@ struct Unit {
   int col;           // column tile
   rsrc_t codes;      // this wave's K-slice of the unit's packed words (empty when inactive)
   uint16_t sc, bi;   // fp16 scale and bias of the lane's channel
-  uint16_t res[TILE_ROWS];  // MODE 1: residual of the lane's channel for the pair's tokens (0 without one)
+  uint16_t res[4];   // MODE 1: residual of the lane's channel for the lane's four rows of the pair (0 without one)
 };
 
 // MODE 0: rows of `a` by token (through perm), out = relu(.) by sorted position (FFN1 -> h)
 // MODE 1: rows of `a` by sorted position, out = gate * (.) (+ residual) by token (FFN2 -> y)
-template <int BITS, int KS, int MODE>
-__global__ __launch_bounds__(WG_THREADS, MIN_WAVES) void moe_decode_small_kernel(SmallDecodeArgs A) {
+// TR: token rows of a pair, 4 or 8.  With 8 an expert's weights are streamed once per eight of
+// its tokens instead of once per four; the parked rows then take twice the LDS, which leaves
+// room for two workgroups per CU instead of three.
+template <int BITS, int KS, int MODE, int TR>
+__global__ __launch_bounds__(WG_THREADS, TR == 4 ? MIN_WAVES : 2) void moe_decode_small_kernel(SmallDecodeArgs A) {
+  constexpr int TILE_ROWS = TR;
+  constexpr int RQ = TR / 4;  // row quads: lanes 16 q .. 16 q + 15 hold the results of rows 4 q .. 4 q + 3
   using S = Shape<BITS, KS>;
   constexpr int WIN = window_chunks(S::NCH);  // chunks in flight
   using Words = WindowWords<BITS, KS, WIN>;
@@ -105,7 +110,7 @@ __global__ __launch_bounds__(WG_THREADS, MIN_WAVES) void moe_decode_small_kernel
   constexpr uint32_t UNIT_BYTES = S::NCH * S::CHUNK_WORDS * 4;
 
   __shared__ uint4_t s_x[WG_WAVES * TILE_ROWS + 1][ROW_PIECES];
-  __shared__ float4_t s_red[2][WG_WAVES][16];
+  __shared__ float4_t s_red[2][WG_WAVES][16 * RQ];
 
   UnpackConsts<BITS> uc;
   uc.init();
@@ -202,11 +207,13 @@ __global__ __launch_bounds__(WG_THREADS, MIN_WAVES) void moe_decode_small_kernel
     u.sc = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(scale_rs, ch, 0, 0);
     u.bi = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(bias_rs, ch, 0, 0);
 #pragma unroll
-    for (int r = 0; r < TILE_ROWS; ++r) {
+    for (int r = 0; r < 4; ++r) {
       u.res[r] = 0;
       if constexpr (MODE == 1) {
-        const uint32_t at = (((uint32_t)tk[r] * (uint32_t)N + (uint32_t)(16 * u.col + j)) * 2u) | unit_nowhere |
-                            (r < rows_valid ? 0u : NOWHERE);
+        int tok = tk[r];
+        if constexpr (RQ == 2) tok = grp == 1 ? tk[4 + r] : tok;
+        const uint32_t at = (((uint32_t)tok * (uint32_t)N + (uint32_t)(16 * u.col + j)) * 2u) | unit_nowhere |
+                            ((grp < RQ && 4 * grp + r < rows_valid) ? 0u : NOWHERE);
         u.res[r] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(res_rs, at, 0, 0);
       }
     }
@@ -225,19 +232,26 @@ __global__ __launch_bounds__(WG_THREADS, MIN_WAVES) void moe_decode_small_kernel
   // the pair does not have and pieces past the block read as zeros
   const rsrc_t a_rs = make_rsrc(A.a, (uint32_t)T * (uint32_t)K * 2u);
   const int rr = lane >> 4, rp = lane & 15;
-  uint32_t row_off;  // byte offset of this lane's piece of block 0
-  {
-    const int tok = rr == 0 ? tk[0] : rr == 1 ? tk[1] : rr == 2 ? tk[2] : tk[3];
-    const uint32_t arow = MODE == 0 ? (uint32_t)tok : (uint32_t)(row0 + rr);
-    row_off = (rr < rows_valid && rp < BLK_PIECES) ? (arow * (uint32_t)K + (uint32_t)ks * (KS * 32) + (uint32_t)rp * 8u) * 2u
-                                                   : NOWHERE;
+  uint32_t row_off[RQ];  // byte offset of this lane's piece of block 0, rows rr and (TR = 8) rr + 4
+#pragma unroll
+  for (int q = 0; q < RQ; ++q) {
+    const int r = rr + 4 * q;
+    int tok = tk[0];
+#pragma unroll
+    for (int i = 1; i < TILE_ROWS; ++i) tok = r == i ? tk[i] : tok;
+    const uint32_t arow = MODE == 0 ? (uint32_t)tok : (uint32_t)(row0 + r);
+    row_off[q] = (r < rows_valid && rp < BLK_PIECES) ? (arow * (uint32_t)K + (uint32_t)ks * (KS * 32) + (uint32_t)rp * 8u) * 2u
+                                                      : NOWHERE;
   }
-  uint4_t rows[WIN * BLK_PER_CHUNK];  // row blocks in flight, slot as for the chunks
+  uint4_t rows[WIN * BLK_PER_CHUNK * RQ];  // row blocks in flight, slot as for the chunks
   auto issue_rows = [&](int ch) {
 #pragma unroll
     for (int bi = 0; bi < BLK_PER_CHUNK; ++bi) {
       const int b = ch * BLK_PER_CHUNK + bi;
-      rows[(ch % WIN) * BLK_PER_CHUNK + bi] = __builtin_amdgcn_raw_buffer_load_b128(a_rs, row_off + (uint32_t)(b * BLK_STEPS * 64), 0, 0);
+#pragma unroll
+      for (int q = 0; q < RQ; ++q)
+        rows[((ch % WIN) * BLK_PER_CHUNK + bi) * RQ + q] =
+            __builtin_amdgcn_raw_buffer_load_b128(a_rs, row_off[q] + (uint32_t)(b * BLK_STEPS * 64), 0, 0);
     }
   };
   // (the scheduling fences keep the requests in this order: the scale and bias, which the first
@@ -259,10 +273,20 @@ __global__ __launch_bounds__(WG_THREADS, MIN_WAVES) void moe_decode_small_kernel
   // the first unit (log-scale codes unpack to their exact values: nothing to remove)
   float4_t corr = {0, 0, 0, 0};
 
-  // gate of the pair's tokens (MODE 1)
-  float g[TILE_ROWS];
+  // The lane's four result rows are rows 4 grp + r of the pair (lanes from 16 RQ on hold none):
+  // their tokens and, MODE 1, gates
+  int tkl[4];
+  float g[4];
 #pragma unroll
-  for (int r = 0; r < TILE_ROWS; ++r) g[r] = MODE == 1 ? read_lane(gt, tk[r] & 63) : 1.0f;
+  for (int r = 0; r < 4; ++r) {
+    tkl[r] = tk[r];
+    if constexpr (RQ == 2) tkl[r] = grp == 1 ? tk[4 + r] : tk[r];
+    g[r] = 1.0f;
+    if constexpr (MODE == 1) {
+      g[r] = read_lane(gt, tk[r] & 63);
+      if constexpr (RQ == 2) g[r] = grp == 1 ? read_lane(gt, tk[4 + r] & 63) : g[r];
+    }
+  }
 
   // Consumes unit `u` chunk by chunk; as soon as a chunk's words are unpacked its slot is
   // refilled with the chunk WIN further on, of this unit or of the next one, `nx`.  The wave's
@@ -284,7 +308,11 @@ __global__ __launch_bounds__(WG_THREADS, MIN_WAVES) void moe_decode_small_kernel
 #pragma unroll
         for (int bi = 0; bi < BLK_PER_CHUNK; ++bi) {
           const int blk = ch * BLK_PER_CHUNK + bi;
-          if (rp < BLK_PIECES) patch[rr][blk * BLK_PIECES + rp] = rows[(ch % WIN) * BLK_PER_CHUNK + bi];
+          if (rp < BLK_PIECES) {
+#pragma unroll
+            for (int q = 0; q < RQ; ++q)
+              patch[rr + 4 * q][blk * BLK_PIECES + rp] = rows[((ch % WIN) * BLK_PER_CHUNK + bi) * RQ + q];
+          }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -338,32 +366,33 @@ __global__ __launch_bounds__(WG_THREADS, MIN_WAVES) void moe_decode_small_kernel
 
   // where the pair's output rows start (bytes), and the top bit for rows the pair does not have
   // and for lanes that hold no result
-  uint32_t out_row[TILE_ROWS], out_row_nowhere[TILE_ROWS];
+  uint32_t out_row[4], out_row_nowhere[4];
 #pragma unroll
-  for (int r = 0; r < TILE_ROWS; ++r) {
-    out_row[r] = (uint32_t)(MODE == 0 ? row0 + r : tk[r]) * (uint32_t)N * 2u;
-    out_row_nowhere[r] = r < rows_valid ? 0u : NOWHERE;
+  for (int r = 0; r < 4; ++r) {
+    out_row[r] = (uint32_t)(MODE == 0 ? row0 + 4 * min(grp, RQ - 1) + r : tkl[r]) * (uint32_t)N * 2u;
+    out_row_nowhere[r] = (grp < RQ && 4 * grp + r < rows_valid) ? 0u : NOWHERE;
   }
-  const uint32_t lane_nowhere = (ks == 0 && lane < 16) ? 0u : NOWHERE;
+  const uint32_t lane_nowhere = (ks == 0 && lane < 16 * RQ) ? 0u : NOWHERE;
 
   int par = 0;
   auto finish_unit = [&](const Unit& u, float4_t part) {
-    // the pair's rows are rows 0..3 of the MFMA tile: lanes 0..15 hold them, one channel each
+    // the pair's rows are rows 0 .. TR - 1 of the MFMA tile: lanes 0 .. 16 RQ - 1 hold them, four
+    // rows of one channel each
     if (R > 1) {  // (uniform; every wave of the workgroup runs the same number of units)
-      if (lane < 16) s_red[par][wave][lane] = part;
+      if (lane < 16 * RQ) s_red[par][wave][lane] = part;
       __syncthreads();
-      if (ks == 0 && lane < 16) {
+      if (ks == 0 && lane < 16 * RQ) {
         for (int q = 1; q < R; ++q) part = part + s_red[par][wave + q][lane];
       }
       par ^= 1;
     }
     const float sc = (float)half_from_bits(u.sc);
     const float bi = (float)half_from_bits(u.bi);
-    // one 2-byte store per row from lanes 0..15 of the team's first wave; everything else is
+    // one 2-byte store per row from the lanes of the team's first wave that hold rows; everything else is
     // sent NOWHERE by or-ing the top bit into the offset (the sums stay below 2^31)
     const uint32_t unit_off = ((uint32_t)(16 * u.col + j) * 2u) | (u.active ? lane_nowhere : NOWHERE);
 #pragma unroll
-    for (int r = 0; r < TILE_ROWS; ++r) {
+    for (int r = 0; r < 4; ++r) {
       float o = fmaf(part[r], sc, bi);
       if constexpr (MODE == 0) {
         o = fmaxf(o, 0.0f);  // ReLU
@@ -390,19 +419,26 @@ __global__ __launch_bounds__(WG_THREADS, MIN_WAVES) void moe_decode_small_kernel
 }
 
 // Workgroups per CU of one instantiation on the current device (asked once per device).
-template <int BITS, int KS, int MODE>
+template <int BITS, int KS, int MODE, int TR>
 int resident_per_cu() {
   static int cache[64];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 1;
   if (cache[dev] == 0) {
+    constexpr int want = TR == 4 ? MIN_WAVES : 2;
     int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, moe_decode_small_kernel<BITS, KS, MODE>, WG_THREADS, 0) != hipSuccess ||
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, moe_decode_small_kernel<BITS, KS, MODE, TR>, WG_THREADS, 0) != hipSuccess ||
         n < 1)
       n = 1;
-    cache[dev] = n > MIN_WAVES ? MIN_WAVES : n;
+    cache[dev] = n > want ? want : n;
   }
   return cache[dev];
+}
+
+template <int BITS, int KS, int MODE, int TR>
+void launch_rows(const SmallDecodeArgs& a, int num_cus, hipStream_t stream) {
+  hipLaunchKernelGGL((moe_decode_small_kernel<BITS, KS, MODE, TR>), dim3(resident_per_cu<BITS, KS, MODE, TR>() * num_cus),
+                     dim3(WG_THREADS), 0, stream, a);
 }
 
 template <int BITS, int KS>
@@ -410,13 +446,16 @@ hipError_t launch_mode(const SmallDecodeArgs& a, int num_cus, hipStream_t stream
   // A persistent grid split evenly over the pairs.  (A grid sized for the largest possible number
   // of pairs with one unit per wave, handed out by the hardware as slots become free, measured
   // 1.5 us slower: every late workgroup pays the table round trip again.)
-  if (a.mode == 0) {
-    hipLaunchKernelGGL((moe_decode_small_kernel<BITS, KS, 0>), dim3(resident_per_cu<BITS, KS, 0>() * num_cus),
-                       dim3(WG_THREADS), 0, stream, a);
-  } else {
-    hipLaunchKernelGGL((moe_decode_small_kernel<BITS, KS, 1>), dim3(resident_per_cu<BITS, KS, 1>() * num_cus),
-                       dim3(WG_THREADS), 0, stream, a);
+  // (pairs of 8 rows: slices of 32 steps only - the sizes the batches that gain from them have)
+  if constexpr (KS == 32) {
+    if (a.rows == 8) {
+      if (a.mode == 0) launch_rows<BITS, KS, 0, 8>(a, num_cus, stream);
+      else launch_rows<BITS, KS, 1, 8>(a, num_cus, stream);
+      return hipGetLastError();
+    }
   }
+  if (a.mode == 0) launch_rows<BITS, KS, 0, 4>(a, num_cus, stream);
+  else launch_rows<BITS, KS, 1, 4>(a, num_cus, stream);
   return hipGetLastError();
 }
 

@@ -97,6 +97,7 @@ hipError_t moqe_launch_resident(const PrefillArgs& a, int num_cus, hipStream_t s
 // dequantize-in-register kernel, one pair (expert, 4 tokens) per workgroup.
 struct SmallDecodeArgs {
   int bits, ksteps, ksplit;  // K = 32 * ksteps * ksplit
+  int rows;                  // token rows of a pair: 4, or 8 (slices of 32 steps only)
   int mode;                  // as in PhaseArgs
   int E, T, N;
   int min_tokens, max_tokens;  // expert segments with min_tokens <= n < max_tokens are handled

@@ -45,7 +45,9 @@ def test_version_and_strings():
         assert L.moqe_status_string(s).decode().startswith(moqe.STATUS_NAMES[s])
     assert L.moqe_set_decode_kernel(5) == -1
     old = L.moqe_set_decode_kernel(moqe.DECODE_GENERAL)
-    assert L.moqe_set_decode_kernel(old) == moqe.DECODE_GENERAL
+    assert L.moqe_set_decode_kernel(moqe.DECODE_ROWS8) == moqe.DECODE_GENERAL
+    assert L.moqe_set_decode_kernel(moqe.DECODE_ROWS4) == moqe.DECODE_ROWS8
+    assert L.moqe_set_decode_kernel(old) == moqe.DECODE_ROWS4
     assert L.moqe_set_tiled_kernel(2) == -1 and L.moqe_set_tiled_kernel(-1) == -1
     old = L.moqe_set_tiled_kernel(moqe.TILED_STREAMED)
     assert old == moqe.TILED_AUTO and L.moqe_set_tiled_kernel(old) == moqe.TILED_STREAMED

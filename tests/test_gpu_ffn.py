@@ -183,7 +183,9 @@ def test_decode_kernels_agree(bits):
     cases = [(W.CONFIGS["c1"], False, moqe.CODEC_LINEAR), (W.small(E=4, d=512, f=2048, T=40, seed=21), True, moqe.CODEC_LINEAR),
              (W.small(E=3, d=768, f=3072, T=21, seed=22), False, moqe.CODEC_LINEAR),
              (W.small(E=128, d=256, f=512, T=64, seed=23), True, moqe.CODEC_LINEAR),
-             (W.small(E=8, d=128, f=256, T=37, seed=24), False, moqe.CODEC_LOG)]
+             (W.small(E=8, d=128, f=256, T=37, seed=24), False, moqe.CODEC_LOG),
+             (W.small(E=8, d=1024, f=4096, T=64, routing="zipf", n_empty=2, seed=25), True, moqe.CODEC_LINEAR),
+             (W.small(E=2, d=1024, f=1024, T=23, seed=26), True, moqe.CODEC_LOG)]
     for wl, residual, codec in cases:
         layer, x = W.make_layer(wl), W.make_tokens(wl)
         ql = moqe.quantize_layer(dev(layer["w1"]), dev(layer["b1"]), dev(layer["w2"]), dev(layer["b2"]), bits,
@@ -199,10 +201,17 @@ def test_decode_kernels_agree(bits):
             moqe.moqe_set_decode_kernel(moqe.DECODE_GENERAL)
             moqe.moqe_expert_ffn1(ql, xd, r, h_general)
             y_general = moqe.moqe_expert_ffn(ql, xd, r, residual=xd if residual else None)
+            # pairs of 8 token rows instead of 4: the same sums per token, so the same bits
+            moqe.moqe_set_decode_kernel(moqe.DECODE_ROWS8)
+            h_rows8 = torch.zeros_like(h_small)
+            moqe.moqe_expert_ffn1(ql, xd, r, h_rows8)
+            y_rows8 = moqe.moqe_expert_ffn(ql, xd, r, residual=xd if residual else None)
         finally:
             moqe.moqe_set_decode_kernel(old)
         torch.cuda.synchronize()
         assert torch.equal(h_small.view(torch.int16), h_general.view(torch.int16)), wl.name
+        assert torch.equal(h_small.view(torch.int16), h_rows8.view(torch.int16)), wl.name
+        assert torch.equal(y_small.view(torch.int16), y_rows8.view(torch.int16)), wl.name
         a, b = y_small.cpu().numpy(), y_general.cpu().numpy()
         differ = a.view(np.uint16) != b.view(np.uint16)
         assert differ.mean() <= 2e-3, f"{wl.name}: {differ.sum()} outputs differ"
