@@ -42,7 +42,7 @@ MFMA_F16_PEAK_TFLOPS = 2500.0
 # WRITE_SIZE runs of this script, each scaled by what the same counter reads for a 256 MiB
 # device copy in the same run); from the profiles/*_hbm_traffic.txt summaries.  None where no
 # counter run was made.  FFN1 of c1 (read + written; profiles/decode_c1_hbm_traffic.txt):
-MEASURED_TRAFFIC_BYTES = {("c1", 4): 39766526, ("c1", 3): 30154587, ("c1", 2): 20456738}
+MEASURED_TRAFFIC_BYTES = {("c1", 4): 39711835, ("c1", 3): 30091706, ("c1", 2): 20388750}
 
 
 def parse():

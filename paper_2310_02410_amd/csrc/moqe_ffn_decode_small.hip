@@ -45,8 +45,13 @@ namespace {
 
 constexpr int WG_THREADS = 256;
 constexpr int WG_WAVES = 4;
+// Workgroups (of 4 waves) per CU.  Measured on the benchmark layer at 24 tokens, FFN1 / FFN2 /
+// whole step: two 8.1 / 8.7 / 24.9 us at int4 (8.8 / 9.4 / 26.8 at int3, 7.1 / 7.3 / 21.8 at int2),
+// three 8.7 / 10.2 / 25.9 (9.6 / 11.3 / 27.5, 7.4 / 8.5 / 22.1), four slower still: eight waves per CU
+// with four chunks in flight each already cover the latency, and every further wave asks for
+// its token rows and first chunks in the same opening burst.
 #ifndef MOQE_SMALL_WG_PER_CU
-#define MOQE_SMALL_WG_PER_CU 3
+#define MOQE_SMALL_WG_PER_CU 2
 #endif
 constexpr int MIN_WAVES = MOQE_SMALL_WG_PER_CU;  // workgroups per CU the register and LDS budgets are sized for
 #ifndef MOQE_SMALL_WINDOW
