@@ -63,8 +63,11 @@ constexpr int MIN_WAVES = MOQE_SMALL_WG_PER_CU;  // workgroups per CU the regist
 // just covers the latency keeps request and arithmetic going side by side.
 constexpr int MAX_WINDOW = MOQE_SMALL_WINDOW;
 // (the window divides the chunks of a unit, so that a chunk's slot is known at compile time)
-constexpr int window_chunks(int nch) {
-  int w = nch < MAX_WINDOW ? nch : MAX_WINDOW;
+// (3-bit codes: a chunk is two loads, 1.5 KiB, and covers 8 steps with two MFMAs each - a window
+// of two measured faster than four: C1 FFN1 8.55 against 8.85 us, FFN2 8.7 against 9.45)
+constexpr int window_chunks(int nch, int field_bits) {
+  const int most = field_bits == 3 ? (MAX_WINDOW < 2 ? MAX_WINDOW : 2) : MAX_WINDOW;
+  int w = nch < most ? nch : most;
   while (nch % w) --w;
   return w;
 }
@@ -102,7 +105,7 @@ __global__ __launch_bounds__(WG_THREADS, TR == 4 ? MIN_WAVES : 2) void moe_decod
   constexpr int TILE_ROWS = TR;
   constexpr int RQ = TR / 4;  // row quads: lanes 16 q .. 16 q + 15 hold the results of rows 4 q .. 4 q + 3
   using S = Shape<BITS, KS>;
-  constexpr int WIN = window_chunks(S::NCH);  // chunks in flight
+  constexpr int WIN = window_chunks(S::NCH, S::FB);  // chunks in flight
   using Words = WindowWords<BITS, KS, WIN>;
   constexpr int PIECES = KS * 4;          // 16-byte pieces of a row slice (8 columns each)
   constexpr int ROW_PIECES = PIECES + 4;  // parked row, padded by 64 bytes against bank conflicts
