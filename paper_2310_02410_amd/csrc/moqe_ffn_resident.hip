@@ -55,10 +55,10 @@ constexpr int RS_MAX_E = 1024;
 // 1024 of K) of a pair with m token tiles take 1.9 / 2.6-3.0 / 3.8-4.2 / 5.2-5.3 us for m = 1 .. 4
 // on a workgroup's eight waves - the unpack does not shrink with a ragged pair, the matrix-core
 // work and the epilogue do - and taking up a pair (staging its rows, the offset sums) about as
-// long as eight units of a full pair.  rs_round_cost: of eight units; RS_SWITCH: of a pair's
-// start, in the same scale.
+// long as eight units of a full pair.  RS_SWITCH: a pair's start, in the scale of
+// rs_cost_of_8_units.
 constexpr int RS_SWITCH = 44;
-__host__ __device__ constexpr int rs_round_cost(int token_tiles) { return 8 + 10 * token_tiles; }
+__host__ __device__ constexpr int rs_cost_of_8_units(int token_tiles) { return 8 + 10 * token_tiles; }
 
 struct RsPair {
   int e, row0, rows;
@@ -72,8 +72,10 @@ struct RsRows {
   uint32_t r0, r1, r2, r3;
 };
 
-// NT: column tiles per unit; WAVES: waves per workgroup (8: two per SIMD, up to 256 registers each); W: packed chunks in flight
-// per wave and column tile (the chunk count of a column tile must be a multiple of W)
+// NT: column tiles per unit; WAVES: waves per workgroup (8: two per SIMD, up to 256 registers
+// each); W: packed chunks in flight per wave and column tile (the chunk count of a column tile
+// must be a multiple of W); MODE 0: FFN1 (rows of `a` by token through perm, ReLU, output by sorted
+// position), MODE 1: FFN2 (rows by sorted position, gate and residual, output by token)
 template <int BITS, int NT, int WAVES, int W, int MODE>
 __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A) {
   constexpr int FB = moqe_field_bits(BITS);  // stored bits per weight
@@ -103,7 +105,7 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
   const int CT = N >> 4;
   const int NG = (CT + NT - 1) / NT;        // units per pair
   // cost of a unit of a pair with m token tiles, and of taking up a pair
-  auto unit_cost = [](int m) { return rs_round_cost(m) * (NT / 2); };
+  auto unit_cost = [](int m) { return rs_cost_of_8_units(m) * (NT / 2); };
   constexpr int SWITCH = RS_SWITCH * WAVES;
   const int Q = K / (32 * SC);              // packed chunks per column tile
   const int NSG = K >> 8;                   // segments of 256 along K
@@ -178,8 +180,52 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
     return RsRows{o[0], o[1], o[2], o[3]};
   };
 
+  // ---- this workgroup's units: those whose first unit of cost lies in [c_lo, c_hi) ----
+  // next_job walks through the pairs that have such units, in order.
+  int it_e = E, it_ti = -1;
+  for (int eg = 0; eg < E; eg += 64) {  // the first expert whose cost range ends beyond c_lo
+    const bool beyond = eg + lane < E && s_cost[eg + lane] > c_lo;
+    const unsigned long long m = __ballot(beyond);
+    if (m) {
+      it_e = uniform_i32(eg + (int)__builtin_ctzll(m));
+      break;
+    }
+  }
+  auto next_job = [&]() -> RsJob {
+    for (; it_e < E; ++it_e, it_ti = -1) {
+      const int base = it_e > 0 ? s_cost[it_e - 1] : 0;
+      if (base >= c_hi) break;
+      if (s_cost[it_e] == base) continue;  // no pairs
+      const int seg0 = s_seg[it_e], n = s_seg[it_e + 1] - seg0;
+      const int full = n >> 6, rem = n & 63;
+      const int npairs = full + (rem ? 1 : 0);
+      const int pair_cost = SWITCH + NG * unit_cost(4);
+      if (it_ti < 0) {
+        it_ti = c_lo > base ? (c_lo - base) / pair_cost : 0;
+        if (it_ti > full) it_ti = full;
+      }
+      for (; it_ti < npairs; ++it_ti) {
+        const int S = base + it_ti * pair_cost + SWITCH;  // cost at the pair's first unit
+        if (S - SWITCH >= c_hi) break;
+        const int rows = it_ti < full ? RS_TILE_M : rem;
+        const int w = unit_cost((rows + 15) >> 4);
+        const int u0 = c_lo > S ? (c_lo - S + w - 1) / w : 0;
+        int u1 = c_hi > S ? (c_hi - S + w - 1) / w : 0;
+        if (u1 > NG) u1 = NG;
+        if (u0 >= u1) continue;
+        RsJob jb;
+        jb.t = RsPair{uniform_i32(it_e), uniform_i32(seg0 + RS_TILE_M * it_ti), uniform_i32(rows)};
+        jb.g0 = uniform_i32(u0);
+        jb.g1 = uniform_i32(u1);
+        ++it_ti;
+        return jb;
+      }
+    }
+    return RsJob{RsPair{0, 0, 1}, 0, 0};
+  };
+
   // The units [g0, g1) of pair t for this workgroup
-  auto run_pair = [&](const RsPair t, const int g0, const int g1, const RsRows rows_off, const RsPair t_next,
+  auto run_pair = [&](const RsPair t, const int g0, const int g1, const RsRows rows_off, RsJob* job_next,
                       RsRows* rows_next, auto MTC) {
     constexpr int MT = decltype(MTC)::value;  // token tiles of 16 the pair has
     const rsrc_t b_rsrc = make_rsrc((const char*)A.codes + (int64_t)t.e * matrix_bytes, (uint32_t)matrix_bytes);
@@ -210,8 +256,9 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
     // ---- stage the pair's token rows ----
     // Load n = 32 sg + rr brings the rows 2 rr and 2 rr + 1 of segment sg (32 pieces each) to
     // s_a[64 n ..]; wave w issues the loads n = w, w + WAVES, ..., so it only ever meets the
-    // row pairs rr = w, w + WAVES, ... < 32: the caller has their offsets in `a` ready (row_offsets).  Row pairs of token tiles the pair does not
-    // have are left out; the rows a ragged tile lacks repeat its last row (never stored).
+    // row pairs rr = w, w + WAVES, ... < 32: the caller has their offsets in `a` ready
+    // (row_offsets).  Row pairs of token tiles the pair does not have are left out; the rows a
+    // ragged tile lacks repeat its last row (never stored).
     {
       const uint32_t rowoff[4] = {rows_off.r0, rows_off.r1, rows_off.r2, rows_off.r3};
       for (int sg = 0; sg < NSG; ++sg) {
@@ -222,9 +269,10 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
         }
       }
     }
-    // the rows the next pair will stage, asked for now: the trip through perm is over long
-    // before that pair is taken up
-    *rows_next = row_offsets(t_next);
+    // the workgroup's next pair and the rows it will stage, found and asked for now: the search
+    // and the trip through perm are over long before that pair is taken up
+    *job_next = next_job();
+    *rows_next = row_offsets(job_next->t);
     // FFN2 writes by token, times the token's gate.  Byte offset of this lane's output rows
     // (T N < 2^31: checked by the caller); rows a ragged tile lacks get an offset beyond the
     // descriptor, so that their stores (and residual loads) touch no memory.
@@ -434,63 +482,19 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
     }
   };
 
-  // ---- this workgroup's units: those whose first unit of cost lies in [c_lo, c_hi) ----
-  // next_job walks through the pairs that have such units, in order.
-  int it_e = E, it_ti = -1;
-  for (int eg = 0; eg < E; eg += 64) {  // the first expert whose cost range ends beyond c_lo
-    const bool beyond = eg + lane < E && s_cost[eg + lane] > c_lo;
-    const unsigned long long m = __ballot(beyond);
-    if (m) {
-      it_e = uniform_i32(eg + (int)__builtin_ctzll(m));
-      break;
-    }
-  }
-  auto next_job = [&]() -> RsJob {
-    for (; it_e < E; ++it_e, it_ti = -1) {
-      const int base = it_e > 0 ? s_cost[it_e - 1] : 0;
-      if (base >= c_hi) break;
-      if (s_cost[it_e] == base) continue;  // no pairs
-      const int seg0 = s_seg[it_e], n = s_seg[it_e + 1] - seg0;
-      const int full = n >> 6, rem = n & 63;
-      const int npairs = full + (rem ? 1 : 0);
-      const int pair_cost = SWITCH + NG * unit_cost(4);
-      if (it_ti < 0) {
-        it_ti = c_lo > base ? (c_lo - base) / pair_cost : 0;
-        if (it_ti > full) it_ti = full;
-      }
-      for (; it_ti < npairs; ++it_ti) {
-        const int S = base + it_ti * pair_cost + SWITCH;  // cost at the pair's first unit
-        if (S - SWITCH >= c_hi) break;
-        const int rows = it_ti < full ? RS_TILE_M : rem;
-        const int w = unit_cost((rows + 15) >> 4);
-        const int u0 = c_lo > S ? (c_lo - S + w - 1) / w : 0;
-        int u1 = c_hi > S ? (c_hi - S + w - 1) / w : 0;
-        if (u1 > NG) u1 = NG;
-        if (u0 >= u1) continue;
-        RsJob jb;
-        jb.t = RsPair{uniform_i32(it_e), uniform_i32(seg0 + RS_TILE_M * it_ti), uniform_i32(rows)};
-        jb.g0 = uniform_i32(u0);
-        jb.g1 = uniform_i32(u1);
-        ++it_ti;
-        return jb;
-      }
-    }
-    return RsJob{RsPair{0, 0, 1}, 0, 0};
-  };
-
   RsJob cur = next_job();
   RsRows cur_rows = row_offsets(cur.t);
   bool first_pair = true;
   while (cur.g0 < cur.g1) {
-    const RsJob nxt = next_job();
+    RsJob nxt;
     RsRows nxt_rows;
     if (!first_pair) __syncthreads();  // every wave is done with the previous pair's rows
     first_pair = false;
     const int mt = (cur.t.rows + 15) >> 4;
-    if (mt == 4) run_pair(cur.t, cur.g0, cur.g1, cur_rows, nxt.t, &nxt_rows, std::integral_constant<int, 4>{});
-    else if (mt == 3) run_pair(cur.t, cur.g0, cur.g1, cur_rows, nxt.t, &nxt_rows, std::integral_constant<int, 3>{});
-    else if (mt == 2) run_pair(cur.t, cur.g0, cur.g1, cur_rows, nxt.t, &nxt_rows, std::integral_constant<int, 2>{});
-    else run_pair(cur.t, cur.g0, cur.g1, cur_rows, nxt.t, &nxt_rows, std::integral_constant<int, 1>{});
+    if (mt == 4) run_pair(cur.t, cur.g0, cur.g1, cur_rows, &nxt, &nxt_rows, std::integral_constant<int, 4>{});
+    else if (mt == 3) run_pair(cur.t, cur.g0, cur.g1, cur_rows, &nxt, &nxt_rows, std::integral_constant<int, 3>{});
+    else if (mt == 2) run_pair(cur.t, cur.g0, cur.g1, cur_rows, &nxt, &nxt_rows, std::integral_constant<int, 2>{});
+    else run_pair(cur.t, cur.g0, cur.g1, cur_rows, &nxt, &nxt_rows, std::integral_constant<int, 1>{});
     cur = nxt;
     cur_rows = nxt_rows;
   }
