@@ -185,7 +185,9 @@ def test_decode_kernels_agree(bits):
              (W.small(E=128, d=256, f=512, T=64, seed=23), True, moqe.CODEC_LINEAR),
              (W.small(E=8, d=128, f=256, T=37, seed=24), False, moqe.CODEC_LOG),
              (W.small(E=8, d=1024, f=4096, T=64, routing="zipf", n_empty=2, seed=25), True, moqe.CODEC_LINEAR),
-             (W.small(E=2, d=1024, f=1024, T=23, seed=26), True, moqe.CODEC_LOG)]
+             (W.small(E=2, d=1024, f=1024, T=23, seed=26), True, moqe.CODEC_LOG),
+             # more than 64 experts (the tables' second half) with slices of 32 steps: pairs of 8 rows apply
+             (W.small(E=72, d=1024, f=1024, T=64, seed=27), False, moqe.CODEC_LINEAR)]
     for wl, residual, codec in cases:
         layer, x = W.make_layer(wl), W.make_tokens(wl)
         ql = moqe.quantize_layer(dev(layer["w1"]), dev(layer["b1"]), dev(layer["w2"]), dev(layer["b2"]), bits,
