@@ -119,22 +119,26 @@ enum { MOQE_TILED_AUTO = 0, MOQE_TILED_STREAMED = 1 };
 int moqe_set_tiled_kernel(int which);
 
 /* Path choice inside the expert FFN (process-wide, for tuning and tests; results are within
- * the same tolerance either way): in a batch of at least min_batch_tokens tokens, expert
- * segments with at least min_segment_tokens tokens are computed by the tiled MFMA kernel (token
- * rows staged in LDS, 64-token tiles), all other segments by the dequantize-in-register decode
- * kernel.  Smaller batches do not launch the tiled kernel at all (a decode step would pay a
- * launch for segments that almost never exist), and batches with at least
- * all_tiled_tokens_per_expert tokens per expert on average (T >= that * E) do not launch the
- * decode kernel: every segment, however small, then takes the tiled kernel (a padded tile
- * for the rare small segment costs less than a launch).  Defaults below; a huge
- * min_batch_tokens switches the tiled kernel off, a huge all_tiled_tokens_per_expert the
- * second rule.  The tiled kernel needs K >= 256 and a multiple of 128 (int8, int4) or 256
- * (int2, int3), T*K*2 < 2^32 and T*N < 2^31; other layers use the decode kernel throughout.
- * Launch mode FUSED uses the decode kernel for everything it chains.
+ * the same tolerance either way).  Batches with at least all_tiled_tokens_per_expert tokens per
+ * expert on average (T >= that * E for 4-bit codes; times 4/3 for 3-bit, 5/3 for 2-bit and 16/3
+ * for 8-bit codes, whose passes over an expert's weights are cheaper or dearer for the decode
+ * kernel while a tile costs the tiled kernel the same) do not launch the decode kernel: every
+ * segment, however small, takes the tiled MFMA kernel (token rows in LDS, 64-token tiles).
+ * Below that, in a batch of at least min_batch_tokens tokens, expert segments with at least
+ * min_segment_tokens tokens are computed by the tiled kernel and all other segments by the
+ * dequantize-in-register decode kernel; smaller batches do not launch the tiled kernel at all.
+ * Defaults below: everything tiled from 3 tokens per expert on, the decode kernel alone below
+ * that - on the benchmark layer (E = 32, d = 1024, f = 4096) the two kernels side by side were
+ * never faster than the better of the two alone (65 to 384 tokens: 65-78 us per step side by
+ * side against 50-57), and the two alone cross at 3 (int4) to 5 (int2) tokens per expert (2.3 at
+ * E = 128).  A huge min_batch_tokens switches the tiled kernel off, a huge
+ * all_tiled_tokens_per_expert the first rule.  The tiled kernel needs K >= 256 and a multiple of
+ * 128 (int8, int4) or 256 (int2, int3), T*K*2 < 2^32 and T*N < 2^31; other layers use the decode
+ * kernel throughout.  Launch mode FUSED uses the decode kernel for everything it chains.
  * Returns 0, or -1 (nothing changed) if a value < 1. */
-#define MOQE_PREFILL_MIN_SEGMENT_DEFAULT 5
+#define MOQE_PREFILL_MIN_SEGMENT_DEFAULT 0x40000000
 #define MOQE_PREFILL_MIN_BATCH_DEFAULT 65
-#define MOQE_PREFILL_ALL_TILED_DEFAULT 16
+#define MOQE_PREFILL_ALL_TILED_DEFAULT 3
 int moqe_set_prefill_policy(int min_segment_tokens, int min_batch_tokens, int all_tiled_tokens_per_expert);
 
 /* Bytes of one packed [K,N] matrix = K*N*bits/8 (Table 2: exactly `bits` bits

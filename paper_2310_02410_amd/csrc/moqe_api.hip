@@ -331,7 +331,12 @@ static hipError_t launch_contraction(DecodeArgs& a, int phase, int ksteps, hipSt
   // many tokens per expert on average, or fp16 weights (which only the tiled kernel takes):
   // everything through the tiled kernel
   const bool tiled_only = a.bits == 16;
-  const int pmin = (tiled_only || (int64_t)a.T >= (int64_t)g_prefill_all.load() * a.E) ? 1 : g_prefill_min.load();
+  // (the tokens per expert from which everything is tiled grow as the codes get narrower: a pass
+  // over an expert's weights by the decode kernel gets cheaper, a tile of the tiled kernel does not)
+  const int fbits = moqe_field_bits(a.bits);
+  const int64_t width_scale = fbits == 2 ? 5 : fbits == 3 ? 4 : fbits == 8 ? 16 : 3;
+  const bool all_tiled = (int64_t)a.T * 3 >= (int64_t)g_prefill_all.load() * width_scale * a.E;
+  const int pmin = (tiled_only || all_tiled) ? 1 : g_prefill_min.load();
   // (the tiled kernel addresses its input rows with 32-bit byte offsets and its output rows with
   // 32-bit element offsets)
   const bool split = a.T >= pmin && (tiled_only || a.T >= g_prefill_batch.load()) &&

@@ -197,7 +197,7 @@ def moqe_set_tiled_kernel(which: int) -> int:
     return old
 
 
-PREFILL_MIN_SEGMENT_DEFAULT, PREFILL_MIN_BATCH_DEFAULT, PREFILL_ALL_TILED_DEFAULT = 5, 65, 16
+PREFILL_MIN_SEGMENT_DEFAULT, PREFILL_MIN_BATCH_DEFAULT, PREFILL_ALL_TILED_DEFAULT = 0x40000000, 65, 3
 PREFILL_NEVER = 2**31 - 1  # as all_tiled_tokens_per_expert: keep the decode kernel for small segments
 
 

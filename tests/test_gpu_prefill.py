@@ -78,14 +78,14 @@ def test_tiled_kernel_residual_and_odd_widths(prefill_min, tiled, bits):
 @pytest.mark.parametrize("bits", (4, 2))
 def test_forced_segment_sizes(bits, all_tiled, prefill_min, tiled):
     """Segments of exactly 4, 5, 63, 64, 65 and 200 tokens, with full and ragged tiles.  With
-    the decode kernel kept for segments below 5 tokens the first goes there and the others to
-    the tiled kernel; at the defaults this batch has 50 tokens per expert, so all of them,
-    the 4-token one included, take the tiled kernel and no decode kernel is launched."""
+    the decode kernel kept for segments below 5 tokens (thresholds 5, 65, never) the first goes
+    there and the others to the tiled kernel; at the defaults this batch has 50 tokens per expert,
+    so all of them, the 4-token one included, take the tiled kernel and no decode kernel is
+    launched."""
     if all_tiled:
         moqe.moqe_set_prefill_policy()
     else:
-        moqe.moqe_set_prefill_policy(moqe.PREFILL_MIN_SEGMENT_DEFAULT, moqe.PREFILL_MIN_BATCH_DEFAULT,
-                                     moqe.PREFILL_NEVER)
+        moqe.moqe_set_prefill_policy(5, 65, moqe.PREFILL_NEVER)
     wl = W.small(E=8, d=256, f=512, T=4 + 5 + 63 + 64 + 65 + 200, seed=84)
     sizes = (4, 5, 63, 64, 65, 200, 0, 0)
     idx = np.concatenate([np.full(n, e) for e, n in enumerate(sizes)])
@@ -162,9 +162,11 @@ def test_batch_beyond_the_tiled_kernels_offsets():
     assert ffn_error(y[torch.from_numpy(rows).cuda()].cpu().numpy(), ref) <= FFN_TOL
 
 
-def test_mixed_paths_under_zipf_load():
-    """Zipf load at the default thresholds: large segments go to the tiled kernel, small ones
-    to the decode kernel, some experts stay empty; both kernels write disjoint rows of h and y."""
+def test_mixed_paths_under_zipf_load(prefill_min):
+    """Zipf load with both kernels side by side (segments from 5 tokens on tiled, the rest by the
+    decode kernel; the defaults would tile everything here): some experts stay empty; both
+    kernels write disjoint rows of h and y."""
+    moqe.moqe_set_prefill_policy(5, 65, moqe.PREFILL_NEVER)
     wl = W.small(E=16, d=256, f=512, T=200, routing="zipf", n_empty=3, seed=85)
     for bits in (8, 4, 3, 2):
         counts = _parity(wl, bits, residual=True)
