@@ -24,6 +24,7 @@ from __future__ import annotations
 
 import argparse
 import ctypes
+import dataclasses
 import json
 import os
 import sys
@@ -71,8 +72,12 @@ def parse():
     ap.add_argument("--parts", action="store_true", help="also time each kernel of the step on its own")
     ap.add_argument("--decode", default="auto", choices=("auto", "general", "rows8", "rows4"),
                     help="which decode kernel serves batches of at most 64 tokens (moqe_set_decode_kernel)")
-    ap.add_argument("--tiled", default="auto", choices=("auto", "streamed"),
+    ap.add_argument("--tiled", default="auto", choices=("auto", "streamed", "resident"),
                     help="which tiled kernel serves many-token segments (moqe_set_tiled_kernel); default: the library's choice")
+    ap.add_argument("--tokens", type=int, default=None, metavar="T",
+                    help="batch size in place of the workload's own (same layer, same routing recipe)")
+    ap.add_argument("--prefill-policy", default=None, metavar="SEG,BATCH,PER_EXPERT",
+                    help="thresholds of the path choice (moqe_set_prefill_policy) in place of the library's defaults")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run three plain device-to-device copies of this size first: under "
                          "rocprofv3 --pmc they give the counter reading of a known amount of traffic")
@@ -119,7 +124,7 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
-    moqe.moqe_set_tiled_kernel({"auto": moqe.TILED_AUTO, "streamed": moqe.TILED_STREAMED}[args.tiled])
+    moqe.moqe_set_tiled_kernel({"auto": moqe.TILED_AUTO, "streamed": moqe.TILED_STREAMED, "resident": moqe.TILED_RESIDENT}[args.tiled])
     moqe.moqe_set_decode_kernel({"auto": moqe.DECODE_AUTO, "general": moqe.DECODE_GENERAL, "rows8": moqe.DECODE_ROWS8,
                                  "rows4": moqe.DECODE_ROWS4}[args.decode])
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
@@ -128,6 +133,13 @@ def main():
     variants.update({v.name: v for v in W.c4_variants()})
     variants.update(W.EXTRA)
     wl = variants[args.workload]
+    if args.tokens is not None:
+        if args.tokens < 1:
+            print("bench.py: --tokens must be positive", file=sys.stderr)
+            sys.exit(2)
+        wl = dataclasses.replace(wl, name="%s_T%d" % (wl.name, args.tokens), T=args.tokens)
+    if args.prefill_policy is not None:
+        moqe.moqe_set_prefill_policy(*[int(v) for v in args.prefill_policy.split(",")])
     E, d, f, T = wl.E, wl.d, wl.f, wl.T
     residual = wl.layers > 1               # the stack adds the layer's output to its input
     compute_bound = T >= 512               # the tiled MFMA kernel dominates, not the weight stream
@@ -255,10 +267,13 @@ def main():
     # ---- the ceiling: a plain streaming read of as many bytes as the dominant kernel's launch
     # must read, on memory that is not cache resident (an arena twice the last-level cache,
     # walked launch by launch), in the decode kernels' launch shape ----
-    arena = torch.empty(768 << 20, dtype=torch.uint8, device="cuda").fill_(1) if not compute_bound else None
+    arena = None
     sink = torch.zeros(64, dtype=torch.uint8, device="cuda")
 
     def time_stream_read(nbytes, nlaunch=200):
+        nonlocal arena
+        if arena is None:
+            arena = torch.empty(768 << 20, dtype=torch.uint8, device="cuda").fill_(1)
         nbytes = max(1024, int(nbytes) // 1024 * 1024)
         stride = (nbytes + (2 << 20) - 1) // (2 << 20) * (2 << 20)
         slots = arena.numel() // stride
@@ -313,29 +328,40 @@ def main():
                    graph_min_ms=graph_min_ms, tokens_per_s=T / (best_ms * 1e-3),
                    active_experts=float(np.mean([a[0] for a in ab])), layer_bytes=layer_bytes, parts=parts,
                    step_gbs=layer_bytes / (best_ms * 1e-3) / 1e9, step_tflops=4.0 * T * d * f / (best_ms * 1e-3) / 1e12)
-        if compute_bound:
-            # one launch of the tiled kernel per contraction: 2 T d f flops each (at these sizes,
-            # 16 or more tokens per expert, every segment takes the tiled kernel)
+        # which kernels the two contractions launch at this size and width (the library's own answer)
+        kb = kbits(b)
+        paths = (moqe.moqe_contraction_path(b, T, E, d, f), moqe.moqe_contraction_path(b, T, E, f, d))
+        tiled = all(p & (moqe.PATH_TILED_RESIDENT | moqe.PATH_TILED_STAGED) for p in paths)
+
+        def kernels_of(p, mode):
+            names = []
+            if p & moqe.PATH_DECODE_SMALL:
+                names.append("moe_decode_small_kernel<%d,*,%d,*>" % (kb, mode))
+            if p & moqe.PATH_DECODE:
+                names.append("moe_decode_kernel<%d,*,2>" % kb)
+            if p & moqe.PATH_TILED_RESIDENT:
+                names.append("moe_resident_kernel<%d,2,8,*,%d>" % (kb, mode))
+            if p & moqe.PATH_TILED_STAGED:
+                names.append("moe_prefill_kernel<%d,*>" % kb)
+            return " + ".join(names)
+        if compute_bound and tiled:
+            # one launch of a tiled kernel per contraction, 2 T d f flops each
             kern_us = 0.5 * (parts["ffn1_back_to_back_us"] + parts["ffn2_back_to_back_us"])
             flops = 2.0 * T * d * f
             res.update(bound="mfma", kernel_us=kern_us, kernel_work=flops, achieved=flops / (kern_us * 1e-6) / 1e12,
                        peak=MFMA_F16_PEAK_TFLOPS, unit="TFLOP/s",
-                       kernel="the tiled kernels (FFN1: moe_resident_kernel<%d,2,8,*,0> where K <= 1024 with %s, else "
-                              "moe_prefill_kernel; FFN2: moe_prefill_kernel<%d,*>; each launched back to back, the "
-                              "two averaged)" % (kbits(b), "--tiled auto", kbits(b)))
+                       kernel="FFN1: %s; FFN2: %s (each launched back to back, the two averaged)"
+                              % (kernels_of(paths[0], 0), kernels_of(paths[1], 1)))
         else:
+            # below some hundred tokens the weight bytes set the time, whichever kernel reads them
             kern_us = parts["ffn1_back_to_back_us"]
             read_us = time_stream_read(ffn1_bytes)
             res.update(bound="hbm", kernel_us=kern_us, kernel_work=ffn1_bytes, ceiling_us=read_us,
                        ceiling_gbs=ffn1_bytes / (read_us * 1e-6) / 1e9,
                        achieved=ffn1_bytes / (kern_us * 1e-6) / 1e9, peak=HBM_PEAK_GBS, unit="GB/s",
-                       kernel=("moe_decode_small_kernel<%d,*,0> (FFN1; FFN2 is the same kernel, mode 1, on a matrix of "
-                               "the same size)" if b in (2, 3, 4) and T <= 64 and E <= 128 else
-                               "moe_decode_kernel<%d,*,2> (FFN1; FFN2 is the same kernel on a matrix of the same "
-                               "size)") % kbits(b))
+                       kernel="%s (FFN1; FFN2 on a matrix of the same size: %s)"
+                              % (kernels_of(paths[0], 0), kernels_of(paths[1], 1)))
         results[b] = res
-        if b == 16 and not compute_bound:
-            res["kernel"] = "moe_prefill_kernel<16,2> (FFN1; fp16 experts run on the tiled kernel at every batch size)"
         print(f"[bench] {wl.name} {wname(b)}: eager {eager_ms * 1e3:.1f} us/step (events {eager_ev_ms * 1e3:.1f}), graph "
               f"{(graph_ms or float('nan')) * 1e3:.1f} us/step; dominant kernel {res['kernel_us']:.1f} us = "
               f"{res['achieved']:.0f} {res['unit']}; parts {json.dumps(parts)}", file=sys.stderr, flush=True)

@@ -109,37 +109,57 @@ int moqe_set_launch_mode(int mode);
 enum { MOQE_DECODE_AUTO = 0, MOQE_DECODE_GENERAL = 1, MOQE_DECODE_ROWS8 = 2, MOQE_DECODE_ROWS4 = 3 };
 int moqe_set_decode_kernel(int which);
 
-/* Which tiled matrix-core kernel serves the expert segments with many tokens (a process-wide
- * setting, for tests and comparisons; results are within the same tolerance either way): AUTO
- * keeps a tile's token rows resident in LDS for the whole contraction where they fit (K <= 1024,
- * a multiple of 256 for int4 and of 512 for int3 / int2; 2- to 4-bit codes, at most 1024 experts,
- * T*N < 2^30) and stages K in blocks elsewhere; STREAMED always stages K in blocks.  Returns the
- * previous setting, or -1 (nothing changed) for an unknown one. */
-enum { MOQE_TILED_AUTO = 0, MOQE_TILED_STREAMED = 1 };
+/* Which tiled matrix-core kernel serves the expert segments that take one (a process-wide
+ * setting, for tests and comparisons; results are within the same tolerance either way).  The
+ * resident kernel keeps a tile's token rows in LDS for the whole contraction: tiles of 64 tokens
+ * where K <= 1024, of 16 tokens where K <= 4096 (K a multiple of 256 for int4 and of 512 for
+ * int3 / int2; 2- to 4-bit codes, at most 1024 experts, T*N < 2^30); the other kernel stages K in
+ * blocks for tiles of 64 tokens.  AUTO takes the resident kernel where K <= 1024 and, for longer
+ * K, while the batch has at most 16 tokens per expert on average (T <= 16 E: most experts then
+ * fill one tile of 16 at most; measured on the benchmark layer's FFN2, K = 4096: 21.8 against
+ * 29.4 us at 256 tokens and int4, 16.5 against 27.3 at int2, 28.0 against 29.7 at 512 tokens,
+ * 38.0 against 31.1 at 1024); STREAMED always stages K in blocks; RESIDENT takes the resident
+ * kernel wherever it applies.  Returns the previous setting, or -1 (nothing changed) for an
+ * unknown one. */
+enum { MOQE_TILED_AUTO = 0, MOQE_TILED_STREAMED = 1, MOQE_TILED_RESIDENT = 2 };
 int moqe_set_tiled_kernel(int which);
 
 /* Path choice inside the expert FFN (process-wide, for tuning and tests; results are within
  * the same tolerance either way).  Batches with at least all_tiled_tokens_per_expert tokens per
- * expert on average (T >= that * E for 4-bit codes; times 4/3 for 3-bit, 5/3 for 2-bit and 16/3
- * for 8-bit codes, whose passes over an expert's weights are cheaper or dearer for the decode
- * kernel while a tile costs the tiled kernel the same) do not launch the decode kernel: every
- * segment, however small, takes the tiled MFMA kernel (token rows in LDS, 64-token tiles).
- * Below that, in a batch of at least min_batch_tokens tokens, expert segments with at least
- * min_segment_tokens tokens are computed by the tiled kernel and all other segments by the
+ * expert on average (T >= that * E; eight times that for 8-bit codes, which have no tiled kernel
+ * with resident token rows) and at least min_batch_tokens tokens do not launch the decode kernel:
+ * every segment, however small, takes the tiled MFMA kernel (token rows in LDS, tiles of 64 or 16
+ * tokens).  Below that, in a batch of at least min_batch_tokens tokens, expert segments with at
+ * least min_segment_tokens tokens are computed by the tiled kernel and all other segments by the
  * dequantize-in-register decode kernel; smaller batches do not launch the tiled kernel at all.
- * Defaults below: everything tiled from 3 tokens per expert on, the decode kernel alone below
- * that - on the benchmark layer (E = 32, d = 1024, f = 4096) the two kernels side by side were
- * never faster than the better of the two alone (65 to 384 tokens: 65-78 us per step side by
- * side against 50-57), and the two alone cross at 3 (int4) to 5 (int2) tokens per expert (2.3 at
- * E = 128).  A huge min_batch_tokens switches the tiled kernel off, a huge
+ * Defaults below: everything tiled from 65 tokens and 2 tokens per expert on, the decode kernel
+ * alone below that - on the benchmark layer (E = 32, d = 1024, f = 4096) the two kernels side by
+ * side were never faster than the better of the two alone (65 to 384 tokens: 65-78 us per step
+ * side by side against 47-57), and the tiled kernels alone are the faster from 65 tokens on at
+ * every width (65 tokens: 46.9 / 52.0 / 40.0 us per step at int4 / int3 / int2 against 50.2 /
+ * 52.2 / 42.8 with the decode kernel alone; 160 tokens: 51.3 / 55.4 / 42.1 against 65.0 / 66.3 /
+ * 52.2).  A huge min_batch_tokens switches the tiled kernel off, a huge
  * all_tiled_tokens_per_expert the first rule.  The tiled kernel needs K >= 256 and a multiple of
  * 128 (int8, int4) or 256 (int2, int3), T*K*2 < 2^32 and T*N < 2^31; other layers use the decode
  * kernel throughout.  Launch mode FUSED uses the decode kernel for everything it chains.
  * Returns 0, or -1 (nothing changed) if a value < 1. */
 #define MOQE_PREFILL_MIN_SEGMENT_DEFAULT 0x40000000
 #define MOQE_PREFILL_MIN_BATCH_DEFAULT 65
-#define MOQE_PREFILL_ALL_TILED_DEFAULT 3
+#define MOQE_PREFILL_ALL_TILED_DEFAULT 2
 int moqe_set_prefill_policy(int min_segment_tokens, int min_batch_tokens, int all_tiled_tokens_per_expert);
+
+/* Which kernels one contraction of the expert FFN (moqe_expert_ffn1 / _ffn2, and moqe_expert_ffn /
+ * moqe_moe_layer in the launch modes that run one contraction per launch) launches for experts of
+ * `bits` bits (2, 3, 4, 8, 16), T tokens, E experts and [K, N] matrices, under the settings above as
+ * they stand: the sum of MOQE_PATH_DECODE_SMALL or MOQE_PATH_DECODE (the dequantize-in-register
+ * kernel for decode-sized batches, or the general one) and MOQE_PATH_TILED_RESIDENT or
+ * MOQE_PATH_TILED_STAGED (the tiled matrix-core kernel with a tile's token rows resident in LDS, or
+ * with K staged in blocks) - one of each pair at most, both where segments are shared out by size.
+ * Host only, launches nothing; the decode-sized kernel needs a workgroup per (expert, token group)
+ * resident at once, so the answer uses the current device's compute unit count (256 without a
+ * device).  Returns -1 for sizes or widths the expert FFN does not take. */
+enum { MOQE_PATH_DECODE_SMALL = 1, MOQE_PATH_DECODE = 2, MOQE_PATH_TILED_RESIDENT = 4, MOQE_PATH_TILED_STAGED = 8 };
+int moqe_contraction_path(int bits, int64_t T, int64_t E, int64_t K, int64_t N);
 
 /* Bytes of one packed [K,N] matrix = K*N*bits/8 (Table 2: exactly `bits` bits
  * per expert weight).  Returns 0 for an unsupported (bits, K, N). Host only. */

@@ -101,7 +101,7 @@ int moqe_set_decode_kernel(int which) {
 }
 
 int moqe_set_tiled_kernel(int which) {
-  if (which != MOQE_TILED_AUTO && which != MOQE_TILED_STREAMED) return -1;
+  if (which != MOQE_TILED_AUTO && which != MOQE_TILED_STREAMED && which != MOQE_TILED_RESIDENT) return -1;
   return g_tiled_kernel.exchange(which);
 }
 
@@ -324,33 +324,72 @@ static void set_ffn2(DecodeArgs* a, const moqe_layer* L, const moqe_f16* h, cons
   p.residual = residual;
 }
 
+// What one contraction launches: the decode kernel (which of the two), the tiled kernel (which of
+// the two), or both, and the segment size from which the tiled kernel takes over.
+struct PathChoice {
+  bool split;     // the tiled kernel is launched, for segments of at least pmin tokens
+  int pmin;
+  bool decode;    // a decode kernel is launched (for all segments, or for those below pmin)
+  bool small;     // ... and it is the one for decode-sized batches
+  bool resident;  // the tiled kernel is the one that keeps the token rows in LDS
+  bool valid;     // false: fp16 weights on a shape the tiled kernel does not take
+};
+
+static PathChoice choose_path(int bits, int64_t T, int64_t E, int64_t K, int64_t N) {
+  PathChoice c;
+  // many tokens per expert on average, or fp16 weights (which only the tiled kernel takes):
+  // everything through the tiled kernel
+  const bool tiled_only = bits == 16;
+  // (8-bit codes have no tiled kernel with resident token rows and a decode kernel that reads two
+  // words per step: eight times the tokens per expert)
+  const int64_t per_expert = (int64_t)g_prefill_all.load() * (moqe_field_bits(bits) == 8 ? 8 : 1);
+  const bool all_tiled = T >= per_expert * E;
+  c.pmin = (tiled_only || all_tiled) ? 1 : g_prefill_min.load();
+  // (the tiled kernel addresses its input rows with 32-bit byte offsets and its output rows with
+  // 32-bit element offsets)
+  c.split = T >= c.pmin && (tiled_only || T >= g_prefill_batch.load()) && moqe_prefill_supported(bits, K, N) &&
+            T * K * 2 < (1ll << 32) && T * N < (1ll << 31);
+  c.valid = !tiled_only || c.split;
+  // (with a threshold of one token every segment is the tiled kernel's: no decode launch)
+  c.decode = !c.split || c.pmin > 1;
+  c.small = c.decode && g_small_decode.load() && moqe_decode_small_supported(bits, T, E, K, N, num_cus());
+  // token rows resident in LDS: always where a tile of 64 tokens fits (K <= 1024); with the
+  // tiles of 16 tokens that a longer K leaves room for, while most experts have no more tokens
+  // than one such tile (beyond that the weights are read once per 16 tokens, and staging K in
+  // blocks for 64 at a time is faster)
+  const int tk = g_tiled_kernel.load();
+  c.resident = c.split && tk != MOQE_TILED_STREAMED && E <= 1024 && T * N < (1ll << 30) &&
+               moqe_resident_supported(bits, K, N) && (K <= 1024 || tk == MOQE_TILED_RESIDENT || T <= 16 * E);
+  return c;
+}
+
+int moqe_contraction_path(int bits, int64_t T, int64_t E, int64_t K, int64_t N) {
+  if (!valid_bits(bits) || T < 1 || T > MAX_TOKENS || E < 1 || E > MAX_EXPERTS || K < 1 || N < 1) return -1;
+  int ks = 0, r = 0;
+  if (bits != 16 && !moqe_pick_ksplit(bits, K, &ks, &r)) return -1;
+  const PathChoice c = choose_path(bits, T, E, K, N);
+  if (!c.valid) return -1;
+  int m = 0;
+  if (c.decode) m |= c.small ? MOQE_PATH_DECODE_SMALL : MOQE_PATH_DECODE;
+  if (c.split) m |= c.resident ? MOQE_PATH_TILED_RESIDENT : MOQE_PATH_TILED_STAGED;
+  return m;
+}
+
 // One contraction as its own launch(es): the decode kernel takes the small segments, the
 // tiled MFMA kernel the large ones (none can exist when T is below the threshold).
 static hipError_t launch_contraction(DecodeArgs& a, int phase, int ksteps, hipStream_t stream) {
   const PhaseArgs& p = a.ph[phase];
-  // many tokens per expert on average, or fp16 weights (which only the tiled kernel takes):
-  // everything through the tiled kernel
-  const bool tiled_only = a.bits == 16;
-  // (the tokens per expert from which everything is tiled grow as the codes get narrower: a pass
-  // over an expert's weights by the decode kernel gets cheaper, a tile of the tiled kernel does not)
-  const int fbits = moqe_field_bits(a.bits);
-  const int64_t width_scale = fbits == 2 ? 5 : fbits == 3 ? 4 : fbits == 8 ? 16 : 3;
-  const bool all_tiled = (int64_t)a.T * 3 >= (int64_t)g_prefill_all.load() * width_scale * a.E;
-  const int pmin = (tiled_only || all_tiled) ? 1 : g_prefill_min.load();
-  // (the tiled kernel addresses its input rows with 32-bit byte offsets and its output rows with
-  // 32-bit element offsets)
-  const bool split = a.T >= pmin && (tiled_only || a.T >= g_prefill_batch.load()) &&
-                     moqe_prefill_supported(a.bits, p.K, p.N) && (int64_t)a.T * p.K * 2 < (1ll << 32) &&
-                     (int64_t)a.T * p.N < (1ll << 31);
-  if (tiled_only && !split) return hipErrorInvalidValue;  // (sizes are checked by the callers)
+  const PathChoice c = choose_path(a.bits, a.T, a.E, p.K, p.N);
+  const bool split = c.split;
+  const int pmin = c.pmin;
+  if (!c.valid) return hipErrorInvalidValue;  // (sizes are checked by the callers)
   a.ksteps = ksteps;
   a.phase_mask = 2 << phase;
   a.min_tokens = 1;
   a.max_tokens = split ? pmin : INT_MAX;
-  // (with a threshold of one token every segment is the tiled kernel's: no decode launch)
-  if (!split || pmin > 1) {
+  if (c.decode) {
     hipError_t e;
-    if (g_small_decode.load() && moqe_decode_small_supported(a.bits, a.T, a.E, p.K, p.N, num_cus())) {
+    if (c.small) {
       // decode-sized batch: the lean kernel (one pair per workgroup)
       SmallDecodeArgs s;
       memset(&s, 0, sizeof(s));
@@ -397,10 +436,7 @@ static hipError_t launch_contraction(DecodeArgs& a, int phase, int ksteps, hipSt
   q.seg_offsets = a.seg_offsets;
   q.perm = a.perm;
   q.gate = a.gate;
-  const int tiled = g_tiled_kernel.load();
-  if (tiled != MOQE_TILED_STREAMED && a.E <= 1024 && (int64_t)a.T * p.N < (1ll << 30) &&
-      moqe_resident_supported(a.bits, p.K, p.N))
-    return moqe_launch_resident(q, num_cus(), stream);
+  if (c.resident) return moqe_launch_resident(q, num_cus(), stream);
   return moqe_launch_prefill(q, num_cus(), stream);
 }
 

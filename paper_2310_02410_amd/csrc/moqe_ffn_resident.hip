@@ -47,8 +47,8 @@
 
 namespace {
 
-constexpr int RS_TILE_M = 64;    // tokens per pair
-constexpr int RS_MAX_K = 1024;   // 64 rows x 1024 x 2 bytes = 128 KiB of LDS
+constexpr int RS_LDS_ELEMS = 64 * 1024;  // token-row elements resident per workgroup: 128 KiB of LDS
+constexpr int RS_MAX_K = 4096;           // (pairs of 16 tokens; pairs of 64 up to K = 1024)
 constexpr int RS_MAX_E = 1024;
 // Cost model of the work split, fitted to time stamps of the 4096-token and the 1536-token
 // layers (int2 and int4, uniform and Zipf load): eight units (of two column tiles, 32 K steps per
@@ -75,9 +75,12 @@ struct RsRows {
 // NT: column tiles per unit; WAVES: waves per workgroup (8: two per SIMD, up to 256 registers
 // each); W: packed chunks in flight per wave and column tile (the chunk count of a column tile
 // must be a multiple of W); MODE 0: FFN1 (rows of `a` by token through perm, ReLU, output by sorted
-// position), MODE 1: FFN2 (rows by sorted position, gate and residual, output by token)
-template <int BITS, int NT, int WAVES, int W, int MODE>
+// position), MODE 1: FFN2 (rows by sorted position, gate and residual, output by token); TM: tokens
+// per pair, 64 (K <= 1024) or 16 (K <= 4096)
+template <int BITS, int NT, int WAVES, int W, int MODE, int TM>
 __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A) {
+  static_assert(TM == 64 || TM == 16, "pairs of 64 or 16 tokens");
+  constexpr int SEG = TM * 32;               // 16-byte pieces of the pair's rows per 256 of K
   constexpr int FB = moqe_field_bits(BITS);  // stored bits per weight
   static_assert(FB == 2 || FB == 3 || FB == 4, "2- to 4-bit codes");
   constexpr int SC = FB == 4 ? 4 : 8;        // steps of 32 rows per packed chunk
@@ -89,11 +92,11 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
   constexpr uint32_t NOWHERE = 0x80000000u;
 
   // K is cut into segments of 256 (32 pieces of 16 bytes per row); piece p of row r of segment
-  // sg lives at s_a[(sg * 64 + r) * 32 + (p ^ (r & 15))]
-  __shared__ uint4_t s_a[RS_TILE_M * RS_MAX_K / 8];
+  // sg lives at s_a[(sg * TM + r) * 32 + (p ^ (r & 15))]
+  __shared__ uint4_t s_a[RS_LDS_ELEMS / 8];
   __shared__ int s_cost[RS_MAX_E];     // inclusive prefix of the experts' costs
   __shared__ int s_seg[RS_MAX_E + 1];  // seg_offsets
-  __shared__ float s_corr[WAVES][RS_TILE_M];
+  __shared__ float s_corr[WAVES][TM];
   __shared__ int s_next;               // the next unit of the pair nobody has taken yet
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -105,10 +108,12 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
   const int CT = N >> 4;
   const int NG = (CT + NT - 1) / NT;        // units per pair
   // cost of a unit of a pair with m token tiles, and of taking up a pair
-  auto unit_cost = [](int m) { return rs_cost_of_8_units(m) * (NT / 2); };
-  constexpr int SWITCH = RS_SWITCH * WAVES;
   const int Q = K / (32 * SC);              // packed chunks per column tile
   const int NSG = K >> 8;                   // segments of 256 along K
+  // (a unit's cost grows with K, taking up a pair - 128 KiB of rows at most - does not; at
+  // K = 1024 the two are in the ratio the time stamps gave)
+  auto unit_cost = [NSG](int m) { return rs_cost_of_8_units(m) * NT / 2 * NSG; };
+  constexpr int SWITCH = RS_SWITCH * WAVES * 4;
 
   // ---- cost of every expert's pairs, inclusive prefix ----
   if (wave == 0) {
@@ -122,7 +127,7 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
         s_seg[e] = s0;
         if (e == E - 1) s_seg[E] = s0 + n;
         if (n >= A.min_tokens)
-          v = (n >> 6) * (SWITCH + NG * unit_cost(4)) + ((n & 63) ? SWITCH + NG * unit_cost(((n & 63) + 15) >> 4) : 0);
+          v = (n / TM) * (SWITCH + NG * unit_cost(TM / 16)) + ((n % TM) ? SWITCH + NG * unit_cost(((n % TM) + 15) >> 4) : 0);
       }
       v = wave_inclusive_scan(v);
       if (e < E) s_cost[e] = carry + v;
@@ -165,8 +170,8 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
   // pair for the wave's row pairs rr = wave, wave + WAVES, ... (FFN1: through perm, a global read,
   // which is why this is asked for a pair ahead); piece (lane & 31) of each 512-byte segment of
   // the row, swizzled.
-  constexpr int RPW = 32 / WAVES;
-  static_assert(32 % WAVES == 0, "a wave stages whole pairs of rows");
+  constexpr int RPW = (TM / 2) / WAVES;
+  static_assert((TM / 2) % WAVES == 0 && RPW >= 1, "a wave stages whole pairs of rows");
   static_assert(RPW <= 4, "RsRows holds four row pairs");
   auto row_offsets = [&](const RsPair t) -> RsRows {
     uint32_t o[4] = {0, 0, 0, 0};
@@ -197,9 +202,9 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
       if (base >= c_hi) break;
       if (s_cost[it_e] == base) continue;  // no pairs
       const int seg0 = s_seg[it_e], n = s_seg[it_e + 1] - seg0;
-      const int full = n >> 6, rem = n & 63;
+      const int full = n / TM, rem = n % TM;
       const int npairs = full + (rem ? 1 : 0);
-      const int pair_cost = SWITCH + NG * unit_cost(4);
+      const int pair_cost = SWITCH + NG * unit_cost(TM / 16);
       if (it_ti < 0) {
         it_ti = c_lo > base ? (c_lo - base) / pair_cost : 0;
         if (it_ti > full) it_ti = full;
@@ -207,14 +212,14 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
       for (; it_ti < npairs; ++it_ti) {
         const int S = base + it_ti * pair_cost + SWITCH;  // cost at the pair's first unit
         if (S - SWITCH >= c_hi) break;
-        const int rows = it_ti < full ? RS_TILE_M : rem;
+        const int rows = it_ti < full ? TM : rem;
         const int w = unit_cost((rows + 15) >> 4);
         const int u0 = c_lo > S ? (c_lo - S + w - 1) / w : 0;
         int u1 = c_hi > S ? (c_hi - S + w - 1) / w : 0;
         if (u1 > NG) u1 = NG;
         if (u0 >= u1) continue;
         RsJob jb;
-        jb.t = RsPair{uniform_i32(it_e), uniform_i32(seg0 + RS_TILE_M * it_ti), uniform_i32(rows)};
+        jb.t = RsPair{uniform_i32(it_e), uniform_i32(seg0 + TM * it_ti), uniform_i32(rows)};
         jb.g0 = uniform_i32(u0);
         jb.g1 = uniform_i32(u1);
         ++it_ti;
@@ -254,9 +259,9 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
     };
 
     // ---- stage the pair's token rows ----
-    // Load n = 32 sg + rr brings the rows 2 rr and 2 rr + 1 of segment sg (32 pieces each) to
-    // s_a[64 n ..]; wave w issues the loads n = w, w + WAVES, ..., so it only ever meets the
-    // row pairs rr = w, w + WAVES, ... < 32: the caller has their offsets in `a` ready
+    // Load n = (TM / 2) sg + rr brings the rows 2 rr and 2 rr + 1 of segment sg (32 pieces each) to
+    // s_a[64 n ..]; wave w issues the loads of the row pairs rr = w, w + WAVES, ... < TM / 2 of
+    // every segment: the caller has their offsets in `a` ready
     // (row_offsets).  Row pairs of token tiles the pair does not have are left out; the rows a
     // ragged tile lacks repeat its last row (never stored).
     {
@@ -265,7 +270,7 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
           const int rr = wave + i * WAVES;
-          if (rr < 8 * MT) stage_load(32 * sg + rr, rowoff[i] + (uint32_t)sg * 512u);
+          if (rr < 8 * MT) stage_load((TM / 2) * sg + rr, rowoff[i] + (uint32_t)sg * 512u);
         }
       }
     }
@@ -305,6 +310,10 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
       if constexpr (W > 1) first(std::integral_constant<int, 1>{});
       if constexpr (W > 2) first(std::integral_constant<int, 2>{});
       if constexpr (W > 3) first(std::integral_constant<int, 3>{});
+      if constexpr (W > 4) first(std::integral_constant<int, 4>{});
+      if constexpr (W > 5) first(std::integral_constant<int, 5>{});
+      if constexpr (W > 6) first(std::integral_constant<int, 6>{});
+      if constexpr (W > 7) first(std::integral_constant<int, 7>{});
     }
     // loads into LDS are invisible to the compiler's wait insertion
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
@@ -327,7 +336,7 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
       for (int st = wave; st < 8 * NSG; st += WAVES) {
         const int within = st & 7;
         const int ab = (within & 3) == 0 ? ab0 : (within & 3) == 1 ? ab1 : (within & 3) == 2 ? ab2 : ab3;
-        const uint4_t* ps = s_a + (st >> 3) * (64 * 32) + (within >> 2) * 16 + ab;
+        const uint4_t* ps = s_a + (st >> 3) * SEG + (within >> 2) * 16 + ab;
         const half8_t cf = (st & 1) ? c_odd : c_even;
 #pragma unroll
         for (int mi = 0; mi < MT; ++mi)
@@ -345,11 +354,25 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
       }
     }
 
+    // a chunk's first piece: segment c (8 steps per chunk) or half of segment c / 2 (4 steps)
+    auto chunk_ofs = [&](int c) { return SC == 8 ? c * SEG : (c >> 1) * SEG + (c & 1) * 16; };
+    // With a single token tile a step is too short to hide the LDS read of the next step's
+    // fragment: the fragments are then read a whole chunk ahead, step s of chunk c + 1 as soon as
+    // step s of chunk c has been issued (the rows do not depend on the unit: after a unit's last
+    // chunk comes the next unit's first).
+    half8_t afr[MT == 1 ? SC : 1];
+    if constexpr (MT == 1) {
+      const uint4_t* q = s_a + chunk_ofs(0);
+#pragma unroll
+      for (int st = 0; st < SC; ++st) {
+        const int ab = (st & 3) == 0 ? ab0 : (st & 3) == 1 ? ab1 : (st & 3) == 2 ? ab2 : ab3;
+        afr[st] = __builtin_bit_cast(half8_t, q[ab + (st >> 2) * 16]);
+      }
+    }
     // chunk c (of the unit in flight) from window slot SLOT
     auto compute_chunk = [&](auto SLOT, int c) {
       constexpr int slot = decltype(SLOT)::value;
-      // the chunk's first piece: segment c (8 steps per chunk) or half of segment c / 2 (4 steps)
-      const int cofs = SC == 8 ? c * (64 * 32) : (c >> 1) * (64 * 32) + (c & 1) * 16;
+      const int cofs = MT == 1 ? chunk_ofs(c + 1 < Q ? c + 1 : 0) : chunk_ofs(c);
       const uint4_t* p0 = s_a + cofs + ab0;
       const uint4_t* p1 = s_a + cofs + ab1;
       const uint4_t* p2 = s_a + cofs + ab2;
@@ -363,10 +386,17 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
         for (int mi = 0; mi < MT; ++mi) a[mi] = __builtin_bit_cast(half8_t, ps[mi * (16 * 32) + (s >> 2) * 16]);
       };
       half8_t a[2][MT];
-      read_frags(0, a[0]);
+      if constexpr (MT > 1) read_frags(0, a[0]);
 #pragma unroll
       for (int s = 0; s < SC; ++s) {
-        if (s + 1 < SC) read_frags(s + 1, a[(s + 1) & 1]);
+        if constexpr (MT == 1) {
+          a[s & 1][0] = afr[s];
+          half8_t ahead[MT];
+          read_frags(s, ahead);
+          afr[s] = ahead[0];
+        } else {
+          if (s + 1 < SC) read_frags(s + 1, a[(s + 1) & 1]);
+        }
 #pragma unroll
         for (int ni = 0; ni < NT; ++ni) {
           half8_t w;
@@ -410,6 +440,10 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
       if constexpr (W > 1) one(std::integral_constant<int, 1>{});
       if constexpr (W > 2) one(std::integral_constant<int, 2>{});
       if constexpr (W > 3) one(std::integral_constant<int, 3>{});
+      if constexpr (W > 4) one(std::integral_constant<int, 4>{});
+      if constexpr (W > 5) one(std::integral_constant<int, 5>{});
+      if constexpr (W > 6) one(std::integral_constant<int, 6>{});
+      if constexpr (W > 7) one(std::integral_constant<int, 7>{});
     };
 
     while (grp < g1) {
@@ -490,11 +524,15 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
     RsRows nxt_rows;
     if (!first_pair) __syncthreads();  // every wave is done with the previous pair's rows
     first_pair = false;
-    const int mt = (cur.t.rows + 15) >> 4;
-    if (mt == 4) run_pair(cur.t, cur.g0, cur.g1, cur_rows, &nxt, &nxt_rows, std::integral_constant<int, 4>{});
-    else if (mt == 3) run_pair(cur.t, cur.g0, cur.g1, cur_rows, &nxt, &nxt_rows, std::integral_constant<int, 3>{});
-    else if (mt == 2) run_pair(cur.t, cur.g0, cur.g1, cur_rows, &nxt, &nxt_rows, std::integral_constant<int, 2>{});
-    else run_pair(cur.t, cur.g0, cur.g1, cur_rows, &nxt, &nxt_rows, std::integral_constant<int, 1>{});
+    if constexpr (TM == 64) {
+      const int mt = (cur.t.rows + 15) >> 4;
+      if (mt == 4) run_pair(cur.t, cur.g0, cur.g1, cur_rows, &nxt, &nxt_rows, std::integral_constant<int, 4>{});
+      else if (mt == 3) run_pair(cur.t, cur.g0, cur.g1, cur_rows, &nxt, &nxt_rows, std::integral_constant<int, 3>{});
+      else if (mt == 2) run_pair(cur.t, cur.g0, cur.g1, cur_rows, &nxt, &nxt_rows, std::integral_constant<int, 2>{});
+      else run_pair(cur.t, cur.g0, cur.g1, cur_rows, &nxt, &nxt_rows, std::integral_constant<int, 1>{});
+    } else {
+      run_pair(cur.t, cur.g0, cur.g1, cur_rows, &nxt, &nxt_rows, std::integral_constant<int, 1>{});
+    }
     cur = nxt;
     cur_rows = nxt_rows;
   }
@@ -506,21 +544,37 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
 // fastest: 4 column tiles per unit, or 12 or 16 waves with a window of two chunks, were 5 to 15 %
 // slower on the 4096-token layers (4 column tiles per unit also with the units handed out one by
 // one: 46.7 against 44.6 us, so the LDS reads are not what the loop waits for).
-template <int BITS, int W>
+template <int BITS, int W, int TM, int NT>
 static void launch_shape(const PrefillArgs& a, int grid, hipStream_t stream) {
-  constexpr int NT = 2, WAVES = 8;
+  constexpr int WAVES = 8;
   if (a.mode == 0)
-    hipLaunchKernelGGL((moe_resident_kernel<BITS, NT, WAVES, W, 0>), dim3((unsigned)grid), dim3(64 * WAVES), 0, stream, a);
+    hipLaunchKernelGGL((moe_resident_kernel<BITS, NT, WAVES, W, 0, TM>), dim3((unsigned)grid), dim3(64 * WAVES), 0, stream, a);
   else
-    hipLaunchKernelGGL((moe_resident_kernel<BITS, NT, WAVES, W, 1>), dim3((unsigned)grid), dim3(64 * WAVES), 0, stream, a);
+    hipLaunchKernelGGL((moe_resident_kernel<BITS, NT, WAVES, W, 1, TM>), dim3((unsigned)grid), dim3(64 * WAVES), 0, stream, a);
 }
 
 template <int BITS>
 static void launch_bits(const PrefillArgs& a, int grid, hipStream_t stream) {
   constexpr int FB = moqe_field_bits(BITS);
   const int Q = a.K / (32 * (FB == 4 ? 4 : 8));
-  if (Q % 4 == 0) launch_shape<BITS, 4>(a, grid, stream);
-  else launch_shape<BITS, 2>(a, grid, stream);
+  if (a.K * 64 <= RS_LDS_ELEMS) {
+    if (Q % 4 == 0) launch_shape<BITS, 4, 64, 2>(a, grid, stream);
+    else launch_shape<BITS, 2, 64, 2>(a, grid, stream);
+  } else {
+    // (one token tile per pair leaves registers for a window twice as deep)
+    // Units of a single column tile where units of two would leave waves without one: there are at
+    // most T / 16 + E pairs (and at most T), each with N / 32 units of two column tiles.
+    const int64_t pairs_max = a.T < a.T / 16 + a.E ? a.T : a.T / 16 + a.E;
+    const bool narrow = pairs_max * ((a.N + 31) / 32) < (int64_t)grid * 8;
+    if (Q % 8 == 0) {
+      if (narrow) launch_shape<BITS, 8, 16, 1>(a, grid, stream);
+      else launch_shape<BITS, 8, 16, 2>(a, grid, stream);
+    } else if (Q % 4 == 0) {
+      launch_shape<BITS, 4, 16, 2>(a, grid, stream);
+    } else {
+      launch_shape<BITS, 2, 16, 2>(a, grid, stream);
+    }
+  }
 }
 
 bool moqe_resident_supported(int bits, int64_t K, int64_t N) {

@@ -28,7 +28,7 @@ EXPORTS = (
     "moqe_layer_workspace_bytes", "moqe_moe_layer", "moqe_set_launch_mode",
     "moqe_set_prefill_policy", "moqe_quantize_tensor_scale", "moqe_quantize_log", "moqe_dequantize_log",
     "moqe_moe_layer_static", "moqe_set_decode_kernel", "moqe_workspace_status",
-    "moqe_stream_read", "moqe_set_tiled_kernel",
+    "moqe_stream_read", "moqe_set_tiled_kernel", "moqe_contraction_path",
 )
 
 LAUNCH_AUTO, LAUNCH_SEPARATE, LAUNCH_FUSED = 0, 1, 2
@@ -83,6 +83,8 @@ def lib() -> ctypes.CDLL:
     L.moqe_set_tiled_kernel.argtypes = [ci]
     L.moqe_set_prefill_policy.restype = ci
     L.moqe_set_prefill_policy.argtypes = [ci, ci, ci]
+    L.moqe_contraction_path.restype = ci
+    L.moqe_contraction_path.argtypes = [ci, i64, i64, i64, i64]
     L.moqe_packed_bytes.restype = sz
     L.moqe_packed_bytes.argtypes = [ci, i64, i64]
     L.moqe_check_matrix.restype = ci
@@ -185,19 +187,20 @@ def moqe_set_decode_kernel(which: int) -> int:
     return old
 
 
-TILED_AUTO, TILED_STREAMED = 0, 1
+TILED_AUTO, TILED_STREAMED, TILED_RESIDENT = 0, 1, 2
 
 
 def moqe_set_tiled_kernel(which: int) -> int:
-    """Process-wide: TILED_AUTO (token rows resident in LDS where a tile's fit, K <= 1024) or
-    TILED_STREAMED (always K staged in blocks); returns the old setting."""
+    """Process-wide: TILED_AUTO (token rows resident in LDS where 64 fit, K <= 1024, and in tiles
+    of 16 up to K = 4096 while T <= 16 E), TILED_STREAMED (always K staged in blocks) or
+    TILED_RESIDENT (resident wherever it applies); returns the old setting."""
     old = lib().moqe_set_tiled_kernel(which)
     if old < 0:
         raise ValueError(f"unknown tiled kernel choice {which}")
     return old
 
 
-PREFILL_MIN_SEGMENT_DEFAULT, PREFILL_MIN_BATCH_DEFAULT, PREFILL_ALL_TILED_DEFAULT = 0x40000000, 65, 3
+PREFILL_MIN_SEGMENT_DEFAULT, PREFILL_MIN_BATCH_DEFAULT, PREFILL_ALL_TILED_DEFAULT = 0x40000000, 65, 2
 PREFILL_NEVER = 2**31 - 1  # as all_tiled_tokens_per_expert: keep the decode kernel for small segments
 
 
@@ -210,6 +213,18 @@ def moqe_set_prefill_policy(min_segment_tokens: int = PREFILL_MIN_SEGMENT_DEFAUL
     the defaults."""
     if lib().moqe_set_prefill_policy(min_segment_tokens, min_batch_tokens, all_tiled_tokens_per_expert) != 0:
         raise ValueError("thresholds must be >= 1")
+
+
+PATH_DECODE_SMALL, PATH_DECODE, PATH_TILED_RESIDENT, PATH_TILED_STAGED = 1, 2, 4, 8
+
+
+def moqe_contraction_path(bits: int, T: int, E: int, K: int, N: int) -> int:
+    """Which kernels one contraction over [K, N] expert matrices launches under the current
+    settings: a sum of PATH_* values (host only, launches nothing)."""
+    m = lib().moqe_contraction_path(bits, T, E, K, N)
+    if m < 0:
+        raise ValueError(f"the expert FFN does not take bits={bits} T={T} E={E} K={K} N={N}")
+    return m
 
 
 def alloc_workspace(nbytes: int, device) -> torch.Tensor:

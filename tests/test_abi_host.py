@@ -48,13 +48,68 @@ def test_version_and_strings():
     assert L.moqe_set_decode_kernel(moqe.DECODE_ROWS8) == moqe.DECODE_GENERAL
     assert L.moqe_set_decode_kernel(moqe.DECODE_ROWS4) == moqe.DECODE_ROWS8
     assert L.moqe_set_decode_kernel(old) == moqe.DECODE_ROWS4
-    assert L.moqe_set_tiled_kernel(2) == -1 and L.moqe_set_tiled_kernel(-1) == -1
+    assert L.moqe_set_tiled_kernel(3) == -1 and L.moqe_set_tiled_kernel(-1) == -1
     old = L.moqe_set_tiled_kernel(moqe.TILED_STREAMED)
     assert old == moqe.TILED_AUTO and L.moqe_set_tiled_kernel(old) == moqe.TILED_STREAMED
     assert L.moqe_workspace_status(None, 4096, None) == 1 and L.moqe_workspace_status(P, 512, None) == 5
     assert L.moqe_stream_read(None, 1024, P, None) == 1 and L.moqe_stream_read(P, 1000, P, None) == 3
     assert L.moqe_stream_read(P, 0, P, None) == 3 and L.moqe_stream_read(P + 8, 1024, P, None) == 4
     assert L.moqe_status_string(99) == b"unknown status"
+
+
+def test_contraction_path_follows_the_settings():
+    """The path query is host-only: which kernels a contraction launches, by batch size, width
+    and the process-wide settings (benchmark layer: E = 32, d = 1024, f = 4096)."""
+    m = moqe
+    path = m.moqe_contraction_path
+    E, d, f = 32, 1024, 4096
+    try:
+        m.moqe_set_prefill_policy()
+        m.moqe_set_decode_kernel(m.DECODE_AUTO)
+        m.moqe_set_tiled_kernel(m.TILED_AUTO)
+        # decode-sized batches: the kernel for them, for both contractions
+        for T in (1, 24, 64):
+            assert path(4, T, E, d, f) == m.PATH_DECODE_SMALL and path(2, T, E, f, d) == m.PATH_DECODE_SMALL
+        assert path(8, 24, E, d, f) == m.PATH_DECODE            # int8: general kernel only
+        assert path(4, 24, 256, d, f) == m.PATH_DECODE          # more than 128 experts
+        # above 64 tokens: everything tiled from 2 tokens per expert on (16 at 8 bits); token rows
+        # resident in LDS where K <= 1024, and up to K = 4096 while T <= 16 E
+        for b in (4, 3, 2):
+            assert path(b, 65, E, d, f) == m.PATH_TILED_RESIDENT and path(b, 65, E, f, d) == m.PATH_TILED_RESIDENT
+            assert path(b, 512, E, f, d) == m.PATH_TILED_RESIDENT and path(b, 513, E, f, d) == m.PATH_TILED_STAGED
+            assert path(b, 513, E, d, f) == m.PATH_TILED_RESIDENT
+            assert path(b, 65, 64, d, f) == m.PATH_DECODE and path(b, 128, 64, d, f) == m.PATH_TILED_RESIDENT
+        assert path(8, 511, E, d, f) == m.PATH_DECODE and path(8, 512, E, d, f) == m.PATH_TILED_STAGED
+        assert path(16, 24, E, d, f) == m.PATH_TILED_STAGED     # fp16 weights: tiled at every size
+        # the settings move the answer
+        m.moqe_set_tiled_kernel(m.TILED_STREAMED)
+        assert path(4, 96, E, d, f) == m.PATH_TILED_STAGED
+        m.moqe_set_tiled_kernel(m.TILED_RESIDENT)
+        assert path(4, 4096, E, f, d) == m.PATH_TILED_RESIDENT
+        m.moqe_set_tiled_kernel(m.TILED_AUTO)
+        m.moqe_set_decode_kernel(m.DECODE_GENERAL)
+        assert path(4, 24, E, d, f) == m.PATH_DECODE
+        m.moqe_set_decode_kernel(m.DECODE_AUTO)
+        m.moqe_set_prefill_policy(5, 65, m.PREFILL_NEVER)       # both side by side
+        assert path(4, 256, E, d, f) == m.PATH_DECODE | m.PATH_TILED_RESIDENT
+        assert path(4, 256, E, f, d) == m.PATH_DECODE | m.PATH_TILED_RESIDENT
+        assert path(4, 1024, E, f, d) == m.PATH_DECODE | m.PATH_TILED_STAGED
+        assert path(4, 64, E, d, f) == m.PATH_DECODE_SMALL
+        m.moqe_set_prefill_policy(m.PREFILL_NEVER, m.PREFILL_NEVER, m.PREFILL_NEVER)
+        assert path(4, 4096, E, d, f) == m.PATH_DECODE
+        # a K the tiled kernels do not take stays with the decode kernel
+        m.moqe_set_prefill_policy()
+        assert path(4, 4096, E, 128, 512) == m.PATH_DECODE
+        # refused: unknown width, no tokens, a K that cannot be packed
+        L = m.lib()
+        assert L.moqe_contraction_path(5, 24, E, d, f) == -1 and L.moqe_contraction_path(4, 0, E, d, f) == -1
+        assert L.moqe_contraction_path(4, 24, E, 100, f) == -1 and L.moqe_contraction_path(4, 24, 0, d, f) == -1
+        with pytest.raises(ValueError):
+            path(4, 24, E, 100, f)
+    finally:
+        m.moqe_set_prefill_policy()
+        m.moqe_set_decode_kernel(m.DECODE_AUTO)
+        m.moqe_set_tiled_kernel(m.TILED_AUTO)
 
 
 @pytest.mark.parametrize("bits", (2, 3, 4, 8))

@@ -1,6 +1,6 @@
-"""GPU parity of the tiled kernel that keeps a pair's token rows resident in LDS (K <= 1024) against
-the oracle, next to the kernel that stages K in blocks: every shape the work split, the staging
-and the unit hand-out distinguish."""
+"""GPU parity of the tiled kernel that keeps a pair's token rows resident in LDS (pairs of 64 tokens
+for K <= 1024, of 16 tokens up to K = 4096) against the oracle, next to the kernel that stages K in
+blocks: every shape the work split, the staging and the unit hand-out distinguish."""
 
 import numpy as np
 import pytest
@@ -38,7 +38,7 @@ def _run(wl, bits, idx, gate, residual=False, codec="linear"):
         ql = gpu_quantize_layer(layer, bits)
         ref = oracle_layer_output(x, layer, bits, idx, g64, residual=residual)
     out = {}
-    for name, which in (("resident", moqe.TILED_AUTO), ("streamed", moqe.TILED_STREAMED)):
+    for name, which in (("resident", moqe.TILED_RESIDENT), ("streamed", moqe.TILED_STREAMED)):
         moqe.moqe_set_tiled_kernel(which)
         y = moqe.moqe_expert_ffn(ql, xd, r, residual=xd if residual else None)
         torch.cuda.synchronize()
@@ -152,3 +152,82 @@ def test_resident_and_streamed_agree_at_the_benchmarked_size(all_tiled):
         hs.append(h.float().cpu().numpy())
     scale = np.abs(hs[1]).max()
     assert np.abs(hs[0] - hs[1]).max() <= 2e-3 * scale
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+def test_pairs_of_16_tokens_for_long_k(all_tiled, bits):
+    """K = 4096, 2048 and 1536 (FFN2 of d_ff that size): pairs of 16 tokens, ragged ones of 1, 15
+    and 5 rows, several pairs per expert, an empty expert; few pairs, so units of one column tile.
+    K = 1536 has 12 chunks per column tile at int4 (window of four) and 6 at int2 (of two); int3
+    needs K to be a multiple of 512 there and stays with the staged kernel."""
+    sizes = (1, 15, 16, 17, 33, 0, 70, 5)
+    idx, gate = _forced(sizes, 98)
+    T = int(sum(sizes))
+    E, d, f = 8, 512, 4096
+    assert moqe.moqe_contraction_path(bits, T, E, f, d) == moqe.PATH_TILED_STAGED
+    moqe.moqe_set_tiled_kernel(moqe.TILED_RESIDENT)
+    assert moqe.moqe_contraction_path(bits, T, E, f, d) == moqe.PATH_TILED_RESIDENT
+    _run(W.small(E=E, d=d, f=f, T=T, seed=98), bits, idx, gate, residual=True)
+    _run(W.small(E=E, d=d, f=2048, T=T, seed=99), bits, idx, gate)
+    _run(W.small(E=E, d=256, f=1536, T=T, seed=100), bits, idx, gate, residual=True)
+
+
+@pytest.mark.parametrize("bits", (4, 2))
+def test_pairs_of_16_tokens_many_per_workgroup(all_tiled, bits):
+    """6000 tokens on 24 experts with K = 4096: 380-odd pairs of 16 for 256 workgroups, units of
+    two column tiles; sampled rows against the oracle, everything against the staged kernel."""
+    wl = W.small(E=24, d=256, f=4096, T=6000, seed=101)
+    rng = np.random.default_rng(101)
+    idx = rng.integers(0, 24, size=wl.T).astype(np.int32)
+    idx[idx == 5] = 6
+    gate = rng.uniform(0.2, 1.0, size=wl.T).astype(np.float32)
+    out, _ = _run(wl, bits, idx, gate)
+    assert np.abs(out["resident"].astype(np.float64) - out["streamed"]).max() <= 2 * FFN_TOL * np.abs(out["streamed"]).max()
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+def test_pairs_of_16_tokens_log_codes_and_offsets(all_tiled, bits):
+    """Log-scale codes through the pairs of 16 (no offsets to take out), and the worst case for the
+    offsets that linear codes leave in the sum: K = 4096 with all-positive rows far from zero
+    mean (FFN1 of a layer with d_model 4096, rows shifted to mean 3)."""
+    sizes = (20, 3, 50, 0)
+    idx, gate = _forced(sizes, 102)
+    _run(W.small(E=4, d=512, f=4096, T=int(sum(sizes)), seed=102), bits, idx, gate, residual=True, codec="log")
+    wl = W.small(E=4, d=4096, f=256, T=200, seed=103)
+    layer, x = W.make_layer(wl), W.make_tokens(wl)
+    x = (np.abs(x.astype(np.float32)) + 3.0).astype(np.float16)
+    idx, gate = _forced((64, 100, 33, 3), 103)
+    xd = dev(x)
+    r = make_route(idx, gate, wl.E)
+    ql = gpu_quantize_layer(layer, bits)
+    ref = oracle_layer_output(x, layer, bits, idx, gate.astype(np.float64))
+    moqe.moqe_set_tiled_kernel(moqe.TILED_RESIDENT)
+    assert moqe.moqe_contraction_path(bits, wl.T, wl.E, wl.d, wl.f) == moqe.PATH_TILED_RESIDENT
+    err = ffn_error(moqe.moqe_expert_ffn(ql, xd, r).cpu().numpy(), ref)
+    assert err <= FFN_TOL, f"int{bits}: {err:.3e}"
+
+
+def test_default_path_at_mid_sized_batches():
+    """What the library picks by itself between 65 and 1024 tokens on the benchmark layer - both
+    contractions resident up to 16 tokens per expert, FFN2 staged beyond - against the oracle."""
+    moqe.moqe_set_prefill_policy()
+    moqe.moqe_set_tiled_kernel(moqe.TILED_AUTO)
+    base = W.CONFIGS["c1"]
+    layer = W.make_layer(base)
+    for bits in (4, 2):
+        ql = gpu_quantize_layer(layer, bits)
+        w1, w2 = O.layer_weights(O.quantize_layer(layer, bits))
+        for T in (65, 512, 600):
+            wl = W.small(E=base.E, d=base.d, f=base.f, T=T, seed=104 + T, outlier_prob=base.outlier_prob)
+            x = W.make_tokens(wl)
+            xd = dev(x)
+            r = moqe.moqe_route(xd, ql.w_gate)
+            want2 = moqe.PATH_TILED_RESIDENT if T <= 16 * base.E else moqe.PATH_TILED_STAGED
+            assert moqe.moqe_contraction_path(bits, T, base.E, base.d, base.f) == moqe.PATH_TILED_RESIDENT
+            assert moqe.moqe_contraction_path(bits, T, base.E, base.f, base.d) == want2
+            y = moqe.moqe_expert_ffn(ql, xd, r).cpu().numpy()
+            idx, gate = r.expert_idx.cpu().numpy(), r.gate.cpu().numpy().astype(np.float64)
+            ref = O.expert_ffn(x, idx, gate, w1, layer["b1"], w2, layer["b2"], residual=None)
+            err = ffn_error(y, ref)
+            assert err <= FFN_TOL, f"int{bits} T={T}: {err:.3e}"
+        del w1, w2
