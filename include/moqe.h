@@ -99,13 +99,17 @@ int moqe_set_launch_mode(int mode);
  * tests and comparisons; each kernel is deterministic, all run the same sums in the same order
  * and differ only in how the last step, gate times output, is rounded to fp16 - by at most one
  * unit in the last place of a few outputs in ten thousand): AUTO takes the kernel specialised for
- * batches of at most 64 tokens (at most 128 experts, 2- to 4-bit codes) where it applies and the
- * general one elsewhere; the specialised kernel works on (expert, 4 of its tokens) up to 32
- * tokens and on (expert, 8 of its tokens) from 33 tokens on, where experts with more than four
- * tokens are common and their weights are then streamed once per eight (K = 1024 or 4096 only,
- * else 4).  GENERAL always takes the general kernel; ROWS8 / ROWS4 are AUTO with 8 / 4 tokens at
- * every batch size (bit-identical results).  Launch mode FUSED uses the general kernel.  Returns
- * the previous setting, or -1 (nothing changed) for an unknown one. */
+ * decode-sized batches (at most 128 experts, 2- to 4-bit codes) where it applies and the general
+ * one elsewhere; the specialised kernel works on (expert, 4 of its tokens) up to 32 tokens and on
+ * (expert, 8 of its tokens) from 33 tokens on, where experts with more than four tokens are
+ * common and their weights are then streamed once per eight (K = 1024 or 4096 only, else 4).  It
+ * takes batches of up to 64 tokens, and in groups of 8 up to 128 (measured on the benchmark
+ * layer at 128 tokens: 41.6 us per step at int4 and 36.1 at int2, against 51.4 and 42.7 through
+ * the tiled kernels); from 65 tokens on only while moqe_set_prefill_policy's min_segment_tokens
+ * is at least its default, i.e. no segments are asked onto the tiled kernel explicitly.
+ * GENERAL always takes the general kernel; ROWS8 / ROWS4 are AUTO with 8 / 4 tokens at every
+ * batch size (bit-identical results; ROWS4 ends at 64 tokens).  Launch mode FUSED uses the
+ * general kernel.  Returns the previous setting, or -1 (nothing changed) for an unknown one. */
 enum { MOQE_DECODE_AUTO = 0, MOQE_DECODE_GENERAL = 1, MOQE_DECODE_ROWS8 = 2, MOQE_DECODE_ROWS4 = 3 };
 int moqe_set_decode_kernel(int which);
 
@@ -132,8 +136,9 @@ int moqe_set_tiled_kernel(int which);
  * tokens).  Below that, in a batch of at least min_batch_tokens tokens, expert segments with at
  * least min_segment_tokens tokens are computed by the tiled kernel and all other segments by the
  * dequantize-in-register decode kernel; smaller batches do not launch the tiled kernel at all.
- * Defaults below: everything tiled from 65 tokens and 2 tokens per expert on, the decode kernel
- * alone below that - on the benchmark layer (E = 32, d = 1024, f = 4096) the two kernels side by
+ * Defaults below: everything tiled from 65 tokens (129 where the kernel for decode-sized batches
+ * applies, see moqe_set_decode_kernel) and 2 tokens per expert on, the decode kernel alone below
+ * that - on the benchmark layer (E = 32, d = 1024, f = 4096) the two kernels side by
  * side were never faster than the better of the two alone (65 to 384 tokens: 65-78 us per step
  * side by side against 47-57), and the tiled kernels alone are the faster from 65 tokens on at
  * every width (65 tokens: 46.9 / 52.0 / 40.0 us per step at int4 / int3 / int2 against 50.2 /

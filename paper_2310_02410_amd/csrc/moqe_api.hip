@@ -331,6 +331,7 @@ struct PathChoice {
   int pmin;
   bool decode;    // a decode kernel is launched (for all segments, or for those below pmin)
   bool small;     // ... and it is the one for decode-sized batches
+  int rows;       // ... which works on (expert, this many of its tokens): 4 or 8
   bool resident;  // the tiled kernel is the one that keeps the token rows in LDS
   bool valid;     // false: fp16 weights on a shape the tiled kernel does not take
 };
@@ -349,10 +350,17 @@ static PathChoice choose_path(int bits, int64_t T, int64_t E, int64_t K, int64_t
   // 32-bit element offsets)
   c.split = T >= c.pmin && (tiled_only || T >= g_prefill_batch.load()) && moqe_prefill_supported(bits, K, N) &&
             T * K * 2 < (1ll << 32) && T * N < (1ll << 31);
+  // The decode-sized kernel, where it applies, keeps batches of up to 128 tokens to itself (in
+  // pairs of 8 rows an expert's weights are still streamed about once there) unless segments are
+  // asked onto the tiled kernel explicitly.
+  const int sd = g_small_decode.load();
+  c.rows = (sd == 2 || (sd == 1 && T >= ROWS8_FROM_TOKENS)) ? 8 : 4;
+  const bool small_ok = sd && bits != 16 && moqe_decode_small_supported(bits, T, E, K, N, num_cus(), c.rows);
+  if (small_ok && g_prefill_min.load() >= MOQE_PREFILL_MIN_SEGMENT_DEFAULT) c.split = false;
   c.valid = !tiled_only || c.split;
   // (with a threshold of one token every segment is the tiled kernel's: no decode launch)
   c.decode = !c.split || c.pmin > 1;
-  c.small = c.decode && g_small_decode.load() && moqe_decode_small_supported(bits, T, E, K, N, num_cus());
+  c.small = c.decode && small_ok;
   // token rows resident in LDS: always where a tile of 64 tokens fits (K <= 1024); with the
   // tiles of 16 tokens that a longer K leaves room for, while most experts have no more tokens
   // than one such tile (beyond that the weights are read once per 16 tokens, and staging K in
@@ -396,7 +404,7 @@ static hipError_t launch_contraction(DecodeArgs& a, int phase, int ksteps, hipSt
       s.bits = a.bits;
       s.ksteps = ksteps;
       s.ksplit = p.ksplit;
-      s.rows = (g_small_decode.load() == 2 || (g_small_decode.load() == 1 && a.T >= ROWS8_FROM_TOKENS)) ? 8 : 4;
+      s.rows = c.rows;
       s.mode = p.mode;
       s.E = a.E;
       s.T = a.T;

@@ -100,8 +100,10 @@ struct Unit {
 // TR: token rows of a pair, 4 or 8.  With 8 an expert's weights are streamed once per eight of
 // its tokens instead of once per four; the parked rows then take twice the LDS, which leaves
 // room for two workgroups per CU instead of three.
-template <int BITS, int KS, int MODE, int TR>
+// XT: tokens the routing tables in registers cover, 64 (one register per table) or 128 (two).
+template <int BITS, int KS, int MODE, int TR, int XT = 64>
 __global__ __launch_bounds__(WG_THREADS, TR == 4 ? MIN_WAVES : 2) void moe_decode_small_kernel(SmallDecodeArgs A) {
+  static_assert(XT == 64 || XT == 128, "one or two registers per routing table");
   constexpr int TILE_ROWS = TR;
   constexpr int RQ = TR / 4;  // row quads: lanes 16 q .. 16 q + 15 hold the results of rows 4 q .. 4 q + 3
   using S = Shape<BITS, KS>;
@@ -140,9 +142,14 @@ __global__ __launch_bounds__(WG_THREADS, TR == 4 ? MIN_WAVES : 2) void moe_decod
   int s2 = (int)__builtin_amdgcn_raw_buffer_load_b32(seg_rs, l4 + 256u, 0, 0);
   int s3 = (int)__builtin_amdgcn_raw_buffer_load_b32(seg_rs, l4 + 260u, 0, 0);
   int pm = (int)__builtin_amdgcn_raw_buffer_load_b32(tok_rs, l4, 0, 0);
-  float gt = 0.0f;
-  if constexpr (MODE == 1)
-    gt = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(make_rsrc(A.gate, (uint32_t)T * 4u), l4, 0, 0));
+  int pm_hi = 0;  // (XT = 128: tokens 64 .. 127; past the batch the descriptor gives zeros)
+  if constexpr (XT == 128) pm_hi = (int)__builtin_amdgcn_raw_buffer_load_b32(tok_rs, l4 + 256u, 0, 0);
+  float gt = 0.0f, gt_hi = 0.0f;
+  if constexpr (MODE == 1) {
+    const rsrc_t gate_rs = make_rsrc(A.gate, (uint32_t)T * 4u);
+    gt = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(gate_rs, l4, 0, 0));
+    if constexpr (XT == 128) gt_hi = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(gate_rs, l4 + 256u, 0, 0));
+  }
   // the zero row, while the tables travel (every wave writes the same zeros and reads only after
   // its own writes)
   {
@@ -157,6 +164,7 @@ __global__ __launch_bounds__(WG_THREADS, TR == 4 ? MIN_WAVES : 2) void moe_decod
   const int n0 = lane < E ? min(max(s1 - s0, 0), T - s0) : 0;
   const int n1 = lane + 64 < E ? min(max(s3 - s2, 0), T - s2) : 0;
   pm = min(max(pm, 0), T - 1);
+  pm_hi = min(max(pm_hi, 0), T - 1);
 
   // ---- token tiles per expert, their prefix, the pair this workgroup serves ----
   const int t0 = (n0 >= A.min_tokens && n0 < A.max_tokens) ? (n0 + TILE_ROWS - 1) / TILE_ROWS : 0;
@@ -186,7 +194,12 @@ __global__ __launch_bounds__(WG_THREADS, TR == 4 ? MIN_WAVES : 2) void moe_decod
   const int rows_valid = min(TILE_ROWS, n_e - TILE_ROWS * m);
   int tk[TILE_ROWS];  // the pair's tokens
 #pragma unroll
-  for (int r = 0; r < TILE_ROWS; ++r) tk[r] = read_lane(pm, (row0 + r) & 63);
+  for (int r = 0; r < TILE_ROWS; ++r) {
+    // (rows past the pair's last one may read any lane: their token is never used)
+    const int pos = row0 + r;
+    tk[r] = read_lane(pm, pos & 63);
+    if constexpr (XT == 128) tk[r] = (pos & 64) ? read_lane(pm_hi, pos & 63) : tk[r];
+  }
 
   // ---- this workgroup's column tiles, this wave's place in it ----
   const int CT = N >> 4;
@@ -291,8 +304,13 @@ __global__ __launch_bounds__(WG_THREADS, TR == 4 ? MIN_WAVES : 2) void moe_decod
     if constexpr (RQ == 2) tkl[r] = grp == 1 ? tk[4 + r] : tk[r];
     g[r] = 1.0f;
     if constexpr (MODE == 1) {
-      g[r] = read_lane(gt, tk[r] & 63);
-      if constexpr (RQ == 2) g[r] = grp == 1 ? read_lane(gt, tk[4 + r] & 63) : g[r];
+      auto gate_of = [&](int tok) {  // (tok is uniform)
+        float v = read_lane(gt, tok & 63);
+        if constexpr (XT == 128) v = (tok & 64) ? read_lane(gt_hi, tok & 63) : v;
+        return v;
+      };
+      g[r] = gate_of(tk[r]);
+      if constexpr (RQ == 2) g[r] = grp == 1 ? gate_of(tk[4 + r]) : g[r];
     }
   }
 
@@ -427,7 +445,7 @@ __global__ __launch_bounds__(WG_THREADS, TR == 4 ? MIN_WAVES : 2) void moe_decod
 }
 
 // Workgroups per CU of one instantiation on the current device (asked once per device).
-template <int BITS, int KS, int MODE, int TR>
+template <int BITS, int KS, int MODE, int TR, int XT>
 int resident_per_cu() {
   static int cache[64];
   int dev = 0;
@@ -435,7 +453,7 @@ int resident_per_cu() {
   if (cache[dev] == 0) {
     constexpr int want = TR == 4 ? MIN_WAVES : 2;
     int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, moe_decode_small_kernel<BITS, KS, MODE, TR>, WG_THREADS, 0) != hipSuccess ||
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, moe_decode_small_kernel<BITS, KS, MODE, TR, XT>, WG_THREADS, 0) != hipSuccess ||
         n < 1)
       n = 1;
     cache[dev] = n > want ? want : n;
@@ -443,9 +461,9 @@ int resident_per_cu() {
   return cache[dev];
 }
 
-template <int BITS, int KS, int MODE, int TR>
+template <int BITS, int KS, int MODE, int TR, int XT = 64>
 void launch_rows(const SmallDecodeArgs& a, int num_cus, hipStream_t stream) {
-  hipLaunchKernelGGL((moe_decode_small_kernel<BITS, KS, MODE, TR>), dim3(resident_per_cu<BITS, KS, MODE, TR>() * num_cus),
+  hipLaunchKernelGGL((moe_decode_small_kernel<BITS, KS, MODE, TR, XT>), dim3(resident_per_cu<BITS, KS, MODE, TR, XT>() * num_cus),
                      dim3(WG_THREADS), 0, stream, a);
 }
 
@@ -456,12 +474,18 @@ hipError_t launch_mode(const SmallDecodeArgs& a, int num_cus, hipStream_t stream
   // 1.5 us slower: every late workgroup pays the table round trip again.)
   // (pairs of 8 rows: slices of 32 steps only - the sizes the batches that gain from them have)
   if constexpr (KS == 32) {
+    if (a.rows == 8 && a.T > 64) {
+      if (a.mode == 0) launch_rows<BITS, KS, 0, 8, 128>(a, num_cus, stream);
+      else launch_rows<BITS, KS, 1, 8, 128>(a, num_cus, stream);
+      return hipGetLastError();
+    }
     if (a.rows == 8) {
       if (a.mode == 0) launch_rows<BITS, KS, 0, 8>(a, num_cus, stream);
       else launch_rows<BITS, KS, 1, 8>(a, num_cus, stream);
       return hipGetLastError();
     }
   }
+  if (a.T > 64) return hipErrorInvalidValue;  // (65 to 128 tokens: pairs of 8 rows only)
   if (a.mode == 0) launch_rows<BITS, KS, 0, 4>(a, num_cus, stream);
   else launch_rows<BITS, KS, 1, 4>(a, num_cus, stream);
   return hipGetLastError();
@@ -484,15 +508,17 @@ hipError_t launch_bits(const SmallDecodeArgs& a, int num_cus, hipStream_t stream
 
 }  // namespace
 
-bool moqe_decode_small_supported(int bits, int64_t T, int64_t E, int64_t K, int64_t N, int grid_min) {
+bool moqe_decode_small_supported(int bits, int64_t T, int64_t E, int64_t K, int64_t N, int grid_min, int rows) {
   const int fb = moqe_field_bits(bits);
   if (fb != 2 && fb != 3 && fb != 4) return false;
   // (every pair needs a workgroup of its own, and there are at most T pairs)
-  if (T < 1 || T > 64 || T > grid_min || E < 1 || E > 128) return false;
+  if (T < 1 || T > 128 || T > grid_min || E < 1 || E > 128) return false;
   // rows and outputs are addressed with 32-bit byte offsets inside their buffers
   if (T * K * 2 >= (1ll << 31) || T * N * 2 >= (1ll << 31)) return false;
   int ks = 0, r = 0;
-  return moqe_pick_ksplit(bits > 100 ? fb : bits, K, &ks, &r);
+  if (!moqe_pick_ksplit(bits > 100 ? fb : bits, K, &ks, &r)) return false;
+  // (65 to 128 tokens: in pairs of 8 rows, which exist for wave slices of 32 steps)
+  return T <= 64 || (rows == 8 && ks == 32);
 }
 
 hipError_t moqe_launch_decode_small(const SmallDecodeArgs& a, int num_cus, hipStream_t stream) {

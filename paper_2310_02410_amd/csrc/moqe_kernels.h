@@ -113,7 +113,7 @@ struct SmallDecodeArgs {
 };
 // (bits as the kernels are instantiated: 2, 3, 4 or MOQE_LOG2..4; grid_min = workgroups the
 // launch will have at least: one per CU)
-bool moqe_decode_small_supported(int bits, int64_t T, int64_t E, int64_t K, int64_t N, int grid_min);
+bool moqe_decode_small_supported(int bits, int64_t T, int64_t E, int64_t K, int64_t N, int grid_min, int rows);
 hipError_t moqe_launch_decode_small(const SmallDecodeArgs& a, int num_cus, hipStream_t stream);
 
 // Dequantize-in-register path for few tokens per expert (tiles of 4 tokens), any batch size.

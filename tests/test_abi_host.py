@@ -72,31 +72,42 @@ def test_contraction_path_follows_the_settings():
             assert path(4, T, E, d, f) == m.PATH_DECODE_SMALL and path(2, T, E, f, d) == m.PATH_DECODE_SMALL
         assert path(8, 24, E, d, f) == m.PATH_DECODE            # int8: general kernel only
         assert path(4, 24, 256, d, f) == m.PATH_DECODE          # more than 128 experts
-        # above 64 tokens: everything tiled from 2 tokens per expert on (16 at 8 bits); token rows
-        # resident in LDS where K <= 1024, and up to K = 4096 while T <= 16 E
+        # 65 to 128 tokens: still the decode-sized kernel where its pairs of 8 rows apply (wave
+        # slices of 32 steps: K = 1024 or 4096); above, or where they do not, everything tiled from
+        # 2 tokens per expert on (16 at 8 bits); token rows resident in LDS where K <= 1024, and
+        # up to K = 4096 while T <= 16 E
         for b in (4, 3, 2):
-            assert path(b, 65, E, d, f) == m.PATH_TILED_RESIDENT and path(b, 65, E, f, d) == m.PATH_TILED_RESIDENT
+            assert path(b, 65, E, d, f) == m.PATH_DECODE_SMALL and path(b, 128, E, f, d) == m.PATH_DECODE_SMALL
+            assert path(b, 129, E, d, f) == m.PATH_TILED_RESIDENT and path(b, 129, E, f, d) == m.PATH_TILED_RESIDENT
+            assert path(b, 100, E, 3072, 768) == m.PATH_TILED_RESIDENT
+            assert path(b, 100, E, 768, 3072) == (m.PATH_TILED_RESIDENT if b == 4 else m.PATH_TILED_STAGED)
+            assert path(b, 100, 256, d, f) == m.PATH_DECODE and path(b, 512, 256, d, f) == m.PATH_TILED_RESIDENT
             assert path(b, 512, E, f, d) == m.PATH_TILED_RESIDENT and path(b, 513, E, f, d) == m.PATH_TILED_STAGED
             assert path(b, 513, E, d, f) == m.PATH_TILED_RESIDENT
-            assert path(b, 65, 64, d, f) == m.PATH_DECODE and path(b, 128, 64, d, f) == m.PATH_TILED_RESIDENT
+            assert path(b, 129, 80, d, f) == m.PATH_DECODE and path(b, 160, 80, d, f) == m.PATH_TILED_RESIDENT
         assert path(8, 511, E, d, f) == m.PATH_DECODE and path(8, 512, E, d, f) == m.PATH_TILED_STAGED
         assert path(16, 24, E, d, f) == m.PATH_TILED_STAGED     # fp16 weights: tiled at every size
         # the settings move the answer
         m.moqe_set_tiled_kernel(m.TILED_STREAMED)
-        assert path(4, 96, E, d, f) == m.PATH_TILED_STAGED
+        assert path(4, 196, E, d, f) == m.PATH_TILED_STAGED
         m.moqe_set_tiled_kernel(m.TILED_RESIDENT)
         assert path(4, 4096, E, f, d) == m.PATH_TILED_RESIDENT
         m.moqe_set_tiled_kernel(m.TILED_AUTO)
         m.moqe_set_decode_kernel(m.DECODE_GENERAL)
-        assert path(4, 24, E, d, f) == m.PATH_DECODE
+        assert path(4, 24, E, d, f) == m.PATH_DECODE and path(4, 100, E, d, f) == m.PATH_TILED_RESIDENT
+        m.moqe_set_decode_kernel(m.DECODE_ROWS4)    # pairs of 4 rows stop at 64 tokens
+        assert path(4, 64, E, d, f) == m.PATH_DECODE_SMALL and path(4, 100, E, d, f) == m.PATH_TILED_RESIDENT
         m.moqe_set_decode_kernel(m.DECODE_AUTO)
         m.moqe_set_prefill_policy(5, 65, m.PREFILL_NEVER)       # both side by side
+        assert path(4, 100, E, d, f) == m.PATH_DECODE_SMALL | m.PATH_TILED_RESIDENT
         assert path(4, 256, E, d, f) == m.PATH_DECODE | m.PATH_TILED_RESIDENT
         assert path(4, 256, E, f, d) == m.PATH_DECODE | m.PATH_TILED_RESIDENT
         assert path(4, 1024, E, f, d) == m.PATH_DECODE | m.PATH_TILED_STAGED
         assert path(4, 64, E, d, f) == m.PATH_DECODE_SMALL
         m.moqe_set_prefill_policy(m.PREFILL_NEVER, m.PREFILL_NEVER, m.PREFILL_NEVER)
-        assert path(4, 4096, E, d, f) == m.PATH_DECODE
+        assert path(4, 4096, E, d, f) == m.PATH_DECODE and path(4, 128, E, d, f) == m.PATH_DECODE_SMALL
+        m.moqe_set_prefill_policy(1, 1, m.PREFILL_NEVER)        # every segment tiled, at any size
+        assert path(4, 24, E, d, f) == m.PATH_TILED_RESIDENT and path(4, 100, E, f, d) == m.PATH_TILED_RESIDENT
         # a K the tiled kernels do not take stays with the decode kernel
         m.moqe_set_prefill_policy()
         assert path(4, 4096, E, 128, 512) == m.PATH_DECODE

@@ -221,6 +221,56 @@ def test_decode_kernels_agree(bits):
         assert np.all(np.abs(a.view(np.int16).astype(np.int32)[differ] - b.view(np.int16).astype(np.int32)[differ]) == 1), wl.name
 
 
+@pytest.mark.parametrize("bits", (4, 3, 2))
+def test_decode_sized_kernel_from_65_to_128_tokens(bits):
+    """Batches of 65 to 128 tokens stay with the decode-sized kernel where its pairs of 8 rows
+    apply (K = 1024 or 4096): the routing tables then take two registers per lane.  Same
+    arithmetic as the general decode kernel (FFN1 bit for bit, the layer output up to the last
+    rounding), and the oracle's result: the first size, the last, a skewed load, more than 64
+    experts, and one expert with every token but one (16 pairs, tokens from both halves of the
+    tables in one pair's rows)."""
+    cases = [(W.small(E=8, d=1024, f=4096, T=65, seed=31), False, False),
+             (W.small(E=8, d=1024, f=4096, T=128, seed=32), True, False),
+             (W.small(E=8, d=1024, f=4096, T=100, routing="zipf", n_empty=2, seed=33), True, False),
+             (W.small(E=72, d=1024, f=1024, T=128, seed=34), False, False),
+             (W.small(E=4, d=1024, f=1024, T=127, seed=35), True, True)]
+    for wl, residual, one_expert in cases:
+        layer, x = W.make_layer(wl), W.make_tokens(wl)
+        ql = gpu_quantize_layer(layer, bits)
+        xd = dev(x)
+        if one_expert:
+            idx = np.full(wl.T, 2, np.int32)
+            idx[-1] = 0
+            r = make_route(idx, np.random.default_rng(5).uniform(0.2, 1.0, wl.T).astype(np.float32), wl.E)
+        else:
+            r = moqe.moqe_route(xd, ql.w_gate)
+        outs = {}
+        old = moqe.moqe_set_decode_kernel(moqe.DECODE_AUTO)
+        moqe.moqe_set_prefill_policy(moqe.PREFILL_NEVER, moqe.PREFILL_NEVER, moqe.PREFILL_NEVER)  # no tiled kernel
+        try:
+            for name, which, want in (("small", moqe.DECODE_AUTO, moqe.PATH_DECODE_SMALL),
+                                      ("general", moqe.DECODE_GENERAL, moqe.PATH_DECODE)):
+                moqe.moqe_set_decode_kernel(which)
+                assert moqe.moqe_contraction_path(bits, wl.T, wl.E, wl.d, wl.f) == want
+                assert moqe.moqe_contraction_path(bits, wl.T, wl.E, wl.f, wl.d) == want
+                h = torch.zeros((wl.T, wl.f), dtype=torch.float16, device="cuda")
+                moqe.moqe_expert_ffn1(ql, xd, r, h)
+                outs[name] = (h, moqe.moqe_expert_ffn(ql, xd, r, residual=xd if residual else None))
+        finally:
+            moqe.moqe_set_decode_kernel(old)
+            moqe.moqe_set_prefill_policy()
+        torch.cuda.synchronize()
+        assert torch.equal(outs["small"][0].view(torch.int16), outs["general"][0].view(torch.int16)), wl.name
+        a, b = outs["small"][1].cpu().numpy(), outs["general"][1].cpu().numpy()
+        differ = a.view(np.uint16) != b.view(np.uint16)
+        assert differ.mean() <= 2e-3, f"{wl.name}: {differ.sum()} outputs differ"
+        assert np.all(np.abs(a.view(np.int16).astype(np.int32)[differ] - b.view(np.int16).astype(np.int32)[differ]) == 1), wl.name
+        if wl.E <= 8:
+            idx, gate = r.expert_idx.cpu().numpy(), r.gate.cpu().numpy().astype(np.float64)
+            ref = oracle_layer_output(x, layer, bits, idx, gate, residual=residual)
+            assert ffn_error(a, ref) <= FFN_TOL, wl.name
+
+
 def test_stream_read_leaves_its_input_alone():
     """The plain read that bench.py times as the ceiling: runs, writes nothing but (at most) its
     sink word, rejects sizes that are not whole KiB."""

@@ -208,8 +208,9 @@ def test_pairs_of_16_tokens_log_codes_and_offsets(all_tiled, bits):
 
 
 def test_default_path_at_mid_sized_batches():
-    """What the library picks by itself between 65 and 1024 tokens on the benchmark layer - both
-    contractions resident up to 16 tokens per expert, FFN2 staged beyond - against the oracle."""
+    """What the library picks by itself between 65 and 1024 tokens on the benchmark layer - the
+    decode-sized kernel up to 128 tokens, then both contractions on the resident kernel up to 16
+    tokens per expert, FFN2 staged beyond - against the oracle."""
     moqe.moqe_set_prefill_policy()
     moqe.moqe_set_tiled_kernel(moqe.TILED_AUTO)
     base = W.CONFIGS["c1"]
@@ -217,13 +218,14 @@ def test_default_path_at_mid_sized_batches():
     for bits in (4, 2):
         ql = gpu_quantize_layer(layer, bits)
         w1, w2 = O.layer_weights(O.quantize_layer(layer, bits))
-        for T in (65, 512, 600):
+        for T in (128, 129, 512, 600):
             wl = W.small(E=base.E, d=base.d, f=base.f, T=T, seed=104 + T, outlier_prob=base.outlier_prob)
             x = W.make_tokens(wl)
             xd = dev(x)
             r = moqe.moqe_route(xd, ql.w_gate)
-            want2 = moqe.PATH_TILED_RESIDENT if T <= 16 * base.E else moqe.PATH_TILED_STAGED
-            assert moqe.moqe_contraction_path(bits, T, base.E, base.d, base.f) == moqe.PATH_TILED_RESIDENT
+            want1 = moqe.PATH_DECODE_SMALL if T <= 128 else moqe.PATH_TILED_RESIDENT
+            want2 = want1 if T <= 16 * base.E else moqe.PATH_TILED_STAGED
+            assert moqe.moqe_contraction_path(bits, T, base.E, base.d, base.f) == want1
             assert moqe.moqe_contraction_path(bits, T, base.E, base.f, base.d) == want2
             y = moqe.moqe_expert_ffn(ql, xd, r).cpu().numpy()
             idx, gate = r.expert_idx.cpu().numpy(), r.gate.cpu().numpy().astype(np.float64)
