@@ -1,5 +1,6 @@
-// One expert contraction of a decode-sized batch (at most 64 tokens, at most 128 experts) as a
-// fused dequantize-in-register grouped GEMM, bound by the packed weight bytes it reads:
+// One expert contraction of a decode-sized batch (at most 64 tokens - 128 in pairs of 8 - and at
+// most 128 experts) as a fused dequantize-in-register grouped GEMM, bound by the packed weight
+// bytes it reads:
 //
 //   out[rows of expert e, n] = epilogue( sum_k a[row, k] * (Q_e[k, n] * s_e[n]) + b_e[n] )
 // (paper Sec. 2.1 two-layer FFN, App. A dequantization A' = Q s; the per-channel scale
@@ -7,8 +8,9 @@
 //
 // A step of this size moves a few tens of MB and lasts microseconds, so the kernel is built
 // around the latencies in front of and behind the weight stream rather than around throughput:
-//   * every wave reads the routing tables itself, with three loads into registers (one round
-//     trip, no LDS staging, no workgroup barrier), and finds its work with ballots;
+//   * every wave reads the routing tables itself, with a few loads into registers (one round
+//     trip, no LDS staging, no workgroup barrier: lane t holds token t, and token t + 64 in the
+//     instantiations for 65 to 128 tokens), and finds its work with ballots;
 //   * a workgroup serves ONE pair (expert, tile of up to 4 - or, from 33 tokens on, 8 - of its
 //     tokens): the persistent grid is split into as many equal groups as there are pairs and a
 //     group's workgroups share the pair's column tiles, so a wave needs one set of token rows

@@ -1,19 +1,20 @@
 // Expert FFN contraction for segments with many tokens when a tile's token rows fit in LDS
-// whole: K <= 1024 (FFN1 of the paper's layers: Sec. 2.1 two-layer FFN, App. A A' = Q s).
+// whole: 64 tokens where K <= 1024 (FFN1 of the paper's layers), 16 tokens where K <= 4096
+// (their FFN2) - Sec. 2.1 two-layer FFN, App. A A' = Q s.
 //
 //   out[rows of expert e, n] = epilogue( sum_k a[row, k] * (Q_e[k, n] * s_e[n]) + b_e[n] )
 //
 // Work decomposition
-//   pair = (expert e, tile of 64 of its tokens), found on device from seg_offsets
+//   pair = (expert e, tile of TM = 64 or 16 of its tokens), found on device from seg_offsets
 //   unit = (pair, group of NT column tiles of 16 channels).  A unit costs 8 + 10 (token tiles
 //          of the pair) - the unpack does not shrink with a ragged pair, the matrix-core work and
-//          the epilogue do -, taking up a pair costs about eight units of a full pair, and the
-//          units of the whole launch, in pair-major order, are cut into one contiguous range of
-//          equal cost per workgroup (one workgroup of WAVES waves per compute unit): every
-//          workgroup gets the same work whatever the number of pairs is, and a range touches as
-//          few pairs as possible
+//          the epilogue do -, taking up a pair costs about eight units of a full pair of 64 at
+//          K = 1024, and the units of the whole launch, in pair-major order, are cut into one
+//          contiguous range of equal cost per workgroup (one workgroup of WAVES waves per compute
+//          unit): every workgroup gets the same work whatever the number of pairs is, and a range
+//          touches as few pairs as possible
 //   per pair of its range a workgroup
-//     - stages the pair's 64 x K token rows in LDS ONCE (128 KiB at K = 1024; loads that go from
+//     - stages the pair's TM x K token rows in LDS ONCE (128 KiB at most; loads that go from
 //       global memory straight into LDS, a row's 16-byte pieces XOR-swizzled by the row number so
 //       that the fragment reads are conflict-free without padding), one barrier; the row numbers
 //       (FFN1: through perm) were asked for while the pair before was being worked on;
@@ -27,18 +28,26 @@
 //       first operand, tokens as second, fp32 accumulate); the window runs on across the end of
 //       a unit, so a unit's first chunks arrive during the previous unit's epilogue.
 //   Token tiles a ragged pair does not have are neither staged nor multiplied (the loop is
-//   instantiated for 1 to 4 token tiles).
+//   instantiated for 1 to 4 token tiles).  With one token tile a step is two MFMAs and too short
+//   to hide an LDS read: the fragments are then read a whole chunk ahead.
+//   Pairs of 16 tokens read an expert's weights once per 16 of its tokens instead of once per 64:
+//   they serve batches with few tokens per expert (most experts fill one such pair at most),
+//   where staging K in blocks costs a barrier every 128 rows of K for a tile that is mostly
+//   padding; launches with so few pairs that units of two column tiles would leave waves idle use
+//   units of one.
 //   Unpack: linear codes become (code + a constant per position in the step) with the unpack
 //   of the decode kernels (moqe_unpack.h), a packed subtract per register less than the exact
 //   one; sum_k a[token, k] c[k] does not depend on the channel, is computed once per pair on
-//   the matrix cores and is what the accumulators start from (negated).  With K <= 1024 the
-//   constants (at most 132 per weight) cost no accuracy that shows against the fp16 rounding
-//   of the outputs.  The loop issues 2.5 vector instructions per MFMA; a vector instruction
-//   takes the SIMD's issue port for 4 cycles, an MFMA for 8 of its 16, so at 8 MFMAs and 12 to
-//   20 vector instructions a step the matrix cores, not the issue port, bound the loop.
-// Compared with staging K in blocks through LDS (moqe_ffn_prefill.hip, which serves K > 1024)
-// the token rows are fetched once per pair and workgroup instead of once per block of output
-// channels, and the main loop has no barrier and no wait that the compiler cannot see.
+//   the matrix cores and is what the accumulators start from (negated).  The constants (at most
+//   132 per weight) cost no accuracy that shows against the fp16 rounding of the outputs, also
+//   over K = 4096 of all-positive rows (tested).  With four token tiles the loop issues 2.5 vector
+//   instructions per MFMA; a vector instruction takes the SIMD's issue port for 4 cycles, an MFMA
+//   for 8 of its 16, so at 8 MFMAs and 12 to 20 vector instructions a step the matrix cores, not
+//   the issue port, bound the loop.
+// Compared with staging K in blocks through LDS (moqe_ffn_prefill.hip, which serves longer K and
+// K > 1024 at many tokens per expert) the token rows are fetched once per pair and workgroup
+// instead of once per block of output channels, and the main loop has no barrier and no wait
+// that the compiler cannot see.
 #include "moqe_dev.h"
 #include "moqe_kernels.h"
 #include "moqe_unpack.h"
@@ -541,9 +550,9 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
 }  // namespace
 
 // Two column tiles per unit and 8 waves (two per SIMD, up to 256 registers each) measured
-// fastest: 4 column tiles per unit, or 12 or 16 waves with a window of two chunks, were 5 to 15 %
-// slower on the 4096-token layers (4 column tiles per unit also with the units handed out one by
-// one: 46.7 against 44.6 us, so the LDS reads are not what the loop waits for).
+// fastest for pairs of 64: 4 column tiles per unit, or 12 or 16 waves with a window of two chunks,
+// were 5 to 15 % slower on the 4096-token layers (4 column tiles per unit also with the units
+// handed out one by one: 46.7 against 44.6 us, so the LDS reads are not what the loop waits for).
 template <int BITS, int W, int TM, int NT>
 static void launch_shape(const PrefillArgs& a, int grid, hipStream_t stream) {
   constexpr int WAVES = 8;
