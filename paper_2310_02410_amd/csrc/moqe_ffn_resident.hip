@@ -105,7 +105,13 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
   __shared__ uint4_t s_a[RS_LDS_ELEMS / 8];
   __shared__ int s_cost[RS_MAX_E];     // inclusive prefix of the experts' costs
   __shared__ int s_seg[RS_MAX_E + 1];  // seg_offsets
-  __shared__ float s_corr[WAVES][TM];
+  // The constants' share of the K-sums is taken out per slab of 512 along K where K can exceed
+  // 1024 (one slab for the whole K otherwise), so that the running sums never carry more than one
+  // slab's share.
+  constexpr int NSLAB = TM == 64 ? 1 : 8;
+  constexpr int SLAB_STEPS = TM == 64 ? 32 : 16;  // steps of 32 rows per slab
+  constexpr int CPS = SLAB_STEPS / SC;            // packed chunks per slab
+  __shared__ float s_corr[WAVES][NSLAB][TM];
   __shared__ int s_next;               // the next unit of the pair nobody has taken yet
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -334,32 +340,46 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
     // sum): it does not depend on the channel.
     // Every wave multiplies the steps wave, wave + WAVES, ... of the pair's rows with the
     // constants, the partial sums meet in LDS and are added in a fixed order.
-    float corr[MT];
+    // Over a long K of all-positive rows that sum is thousands of times the signal and its fp32
+    // rounding would show: it is taken out slab by slab (512 of K each), the accumulators start
+    // at minus the first slab's sum and the next slab's is subtracted when its first chunk is due.
+    float corr[MT][NSLAB];
 #pragma unroll
-    for (int mi = 0; mi < MT; ++mi) corr[mi] = 0.0f;
+    for (int mi = 0; mi < MT; ++mi)
+#pragma unroll
+      for (int sl = 0; sl < NSLAB; ++sl) corr[mi][sl] = 0.0f;
     if constexpr (!moqe_is_log(BITS)) {
-      float4_t cacc[MT];
-#pragma unroll
-      for (int mi = 0; mi < MT; ++mi) cacc[mi] = float4_t{0, 0, 0, 0};
+      float4_t cacc[MT][NSLAB];
       const half8_t c_even = bias_frag<BITS>(0), c_odd = bias_frag<BITS>(1);
-      for (int st = wave; st < 8 * NSG; st += WAVES) {
-        const int within = st & 7;
-        const int ab = (within & 3) == 0 ? ab0 : (within & 3) == 1 ? ab1 : (within & 3) == 2 ? ab2 : ab3;
-        const uint4_t* ps = s_a + (st >> 3) * SEG + (within >> 2) * 16 + ab;
-        const half8_t cf = (st & 1) ? c_odd : c_even;
 #pragma unroll
-        for (int mi = 0; mi < MT; ++mi)
-          cacc[mi] = __builtin_amdgcn_mfma_f32_16x16x32_f16(cf, __builtin_bit_cast(half8_t, ps[mi * (16 * 32)]), cacc[mi], 0, 0, 0);
+      for (int sl = 0; sl < NSLAB; ++sl) {
+#pragma unroll
+        for (int mi = 0; mi < MT; ++mi) cacc[mi][sl] = float4_t{0, 0, 0, 0};
+        const int st_end = min(SLAB_STEPS * (sl + 1), 8 * NSG);
+        for (int st = SLAB_STEPS * sl + wave; st < st_end; st += WAVES) {
+          const int within = st & 7;
+          const int ab = (within & 3) == 0 ? ab0 : (within & 3) == 1 ? ab1 : (within & 3) == 2 ? ab2 : ab3;
+          const uint4_t* ps = s_a + (st >> 3) * SEG + (within >> 2) * 16 + ab;
+          const half8_t cf = (st & 1) ? c_odd : c_even;
+#pragma unroll
+          for (int mi = 0; mi < MT; ++mi)
+            cacc[mi][sl] = __builtin_amdgcn_mfma_f32_16x16x32_f16(cf, __builtin_bit_cast(half8_t, ps[mi * (16 * 32)]), cacc[mi][sl], 0, 0, 0);
+        }
       }
       if (g == 0) {
 #pragma unroll
-        for (int mi = 0; mi < MT; ++mi) s_corr[wave][16 * mi + j] = cacc[mi][0];
+        for (int mi = 0; mi < MT; ++mi)
+#pragma unroll
+          for (int sl = 0; sl < NSLAB; ++sl) s_corr[wave][sl][16 * mi + j] = cacc[mi][sl][0];
       }
       __syncthreads();
 #pragma unroll
       for (int mi = 0; mi < MT; ++mi) {
 #pragma unroll
-        for (int w = 0; w < WAVES; ++w) corr[mi] += s_corr[w][16 * mi + j];
+        for (int sl = 0; sl < NSLAB; ++sl) {
+#pragma unroll
+          for (int w = 0; w < WAVES; ++w) corr[mi][sl] += s_corr[w][sl][16 * mi + j];
+        }
       }
     }
 
@@ -386,6 +406,25 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
       const uint4_t* p1 = s_a + cofs + ab1;
       const uint4_t* p2 = s_a + cofs + ab2;
       const uint4_t* p3 = s_a + cofs + ab3;
+      if constexpr (NSLAB > 1 && !moqe_is_log(BITS)) {
+        // The first chunk of a further slab: its offset sum goes out now.  No branch (behind one
+        // the compiler waits for every load in flight, which empties the window): where the
+        // window is a multiple of a slab's chunks the slot says whether this chunk starts a slab,
+        // elsewhere a select does; slab 0's sum is what the accumulators started from.
+        constexpr bool by_slot = (W % CPS) == 0;
+        if constexpr (!by_slot || (slot % CPS) == 0) {
+          const int sl = c / CPS;
+          const bool starts = by_slot || (c & (CPS - 1)) == 0;
+#pragma unroll
+          for (int mi = 0; mi < MT; ++mi) {
+            float cs = 0.0f;
+#pragma unroll
+            for (int q = 1; q < NSLAB; ++q) cs = (starts && sl == q) ? corr[mi][q] : cs;
+#pragma unroll
+            for (int ni = 0; ni < NT; ++ni) acc[mi][ni] -= float4_t{cs, cs, cs, cs};
+          }
+        }
+      }
       // the fragments of step s + 1 are read while step s is multiplied; nothing moves across
       // a step's end (without the fence the scheduler hoists a whole chunk's fragment reads to
       // its start, which costs more registers than there are)
@@ -474,7 +513,7 @@ __global__ __launch_bounds__(64 * WAVES) void moe_resident_kernel(PrefillArgs A)
 #pragma unroll
       for (int mi = 0; mi < MT; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < NT; ++ni) acc[mi][ni] = float4_t{-corr[mi], -corr[mi], -corr[mi], -corr[mi]};
+        for (int ni = 0; ni < NT; ++ni) acc[mi][ni] = float4_t{-corr[mi][0], -corr[mi][0], -corr[mi][0], -corr[mi][0]};
 
       for (int cq = 0; cq < Q - W; cq += W) window(cq, std::false_type{});
       window(Q - W, std::true_type{});

@@ -233,3 +233,15 @@ def test_default_path_at_mid_sized_batches():
             err = ffn_error(y, ref)
             assert err <= FFN_TOL, f"int{bits} T={T}: {err:.3e}"
         del w1, w2
+
+
+def test_offset_sums_go_out_slab_by_slab():
+    """FFN2 reads h after ReLU: all-positive rows over K = 4096, so the constants the unpack leaves
+    in the sum add up to thousands of times the signal, and taken out in one piece their fp32
+    rounding showed (2.3e-3 of the largest output on this case, int2, against the bound's 2e-3).
+    The pairs of 16 tokens take them out per 512 of K: the error is back at the exact unpack's."""
+    from tests.test_gpu_random_sweep import run_mid_case
+    case = (2, 0, 4, 1024, 4096, 128, False, False, moqe.TILED_RESIDENT, (5, 65, moqe.PREFILL_NEVER), 209828)
+    assert moqe.moqe_contraction_path(2, 128, 4, 4096, 1024) == moqe.PATH_DECODE_SMALL  # (default thresholds)
+    err = run_mid_case(case)
+    assert err <= 1e-3, f"{err:.3e}"
