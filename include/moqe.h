@@ -120,9 +120,9 @@ int moqe_set_decode_kernel(int which);
  * int3 / int2; 2- to 4-bit codes, at most 1024 experts, T*N < 2^30); the other kernel stages K in
  * blocks for tiles of 64 tokens.  AUTO takes the resident kernel where K <= 1024 and, for longer
  * K, while the batch has at most 16 tokens per expert on average (T <= 16 E: most experts then
- * fill one tile of 16 at most; measured on the benchmark layer's FFN2, K = 4096: 21.8 against
- * 29.4 us at 256 tokens and int4, 16.5 against 27.3 at int2, 28.0 against 29.7 at 512 tokens,
- * 38.0 against 31.1 at 1024); STREAMED always stages K in blocks; RESIDENT takes the resident
+ * fill one tile of 16 at most; measured on the benchmark layer's FFN2, K = 4096: 22.3 against
+ * 29.4 us at 256 tokens and int4, 17.4 against 27.3 at int2, 24.4 against 29.7 at 512 tokens,
+ * 38 against 31 at 1024); STREAMED always stages K in blocks; RESIDENT takes the resident
  * kernel wherever it applies.  Returns the previous setting, or -1 (nothing changed) for an
  * unknown one. */
 enum { MOQE_TILED_AUTO = 0, MOQE_TILED_STREAMED = 1, MOQE_TILED_RESIDENT = 2 };
