@@ -45,7 +45,7 @@ MFMA_F16_PEAK_TFLOPS = 2500.0
 # counter run was made.  FFN1 of c1 (read + written; profiles/decode_c1_hbm_traffic.txt); for the
 # many-token workloads the mean of the FFN1 and the FFN2 launch, as their time is reported
 # (profiles/prefill_c3_int4.txt, profiles/prefill_c4_T4096_int2.txt):
-MEASURED_TRAFFIC_BYTES = {("c1", 4): 39711835, ("c1", 3): 30091706, ("c1", 2): 20388750,
+MEASURED_TRAFFIC_BYTES = {("c1", 4): 39711835, ("c1", 3): 30099886, ("c1", 2): 20402059,
                           ("c3", 4): 84020000, ("c4_T4096_uniform", 2): 100735000}
 
 
