@@ -139,7 +139,14 @@ def main():
             sys.exit(2)
         wl = dataclasses.replace(wl, name="%s_T%d" % (wl.name, args.tokens), T=args.tokens)
     if args.prefill_policy is not None:
-        moqe.moqe_set_prefill_policy(*[int(v) for v in args.prefill_policy.split(",")])
+        try:
+            thresholds = [int(v) for v in args.prefill_policy.split(",")]
+            if len(thresholds) != 3:
+                raise ValueError
+            moqe.moqe_set_prefill_policy(*thresholds)
+        except ValueError:
+            print("bench.py: --prefill-policy takes three integers >= 1, e.g. 5,65,16", file=sys.stderr)
+            sys.exit(2)
     E, d, f, T = wl.E, wl.d, wl.f, wl.T
     residual = wl.layers > 1               # the stack adds the layer's output to its input
     compute_bound = T >= 512               # the tiled MFMA kernel dominates, not the weight stream

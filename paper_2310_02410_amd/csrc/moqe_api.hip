@@ -356,7 +356,7 @@ static PathChoice choose_path(int bits, int64_t T, int64_t E, int64_t K, int64_t
   const int sd = g_small_decode.load();
   c.rows = (sd == 2 || (sd == 1 && T >= ROWS8_FROM_TOKENS)) ? 8 : 4;
   const bool small_ok = sd && bits != 16 && moqe_decode_small_supported(bits, T, E, K, N, num_cus(), c.rows);
-  if (small_ok && g_prefill_min.load() >= MOQE_PREFILL_MIN_SEGMENT_DEFAULT) c.split = false;
+  if (small_ok && T > 64 && g_prefill_min.load() >= MOQE_PREFILL_MIN_SEGMENT_DEFAULT) c.split = false;
   c.valid = !tiled_only || c.split;
   // (with a threshold of one token every segment is the tiled kernel's: no decode launch)
   c.decode = !c.split || c.pmin > 1;

@@ -106,6 +106,9 @@ def test_contraction_path_follows_the_settings():
         assert path(4, 64, E, d, f) == m.PATH_DECODE_SMALL
         m.moqe_set_prefill_policy(m.PREFILL_NEVER, m.PREFILL_NEVER, m.PREFILL_NEVER)
         assert path(4, 4096, E, d, f) == m.PATH_DECODE and path(4, 128, E, d, f) == m.PATH_DECODE_SMALL
+        m.moqe_set_prefill_policy(m.PREFILL_MIN_SEGMENT_DEFAULT, 1, 1)   # everything tiled from one token per expert on
+        assert path(4, 48, E, d, f) == m.PATH_TILED_RESIDENT and path(4, 24, E, d, f) == m.PATH_DECODE_SMALL
+        assert path(4, 100, E, d, f) == m.PATH_DECODE_SMALL     # (the decode-sized kernel keeps 65 to 128 tokens)
         m.moqe_set_prefill_policy(1, 1, m.PREFILL_NEVER)        # every segment tiled, at any size
         assert path(4, 24, E, d, f) == m.PATH_TILED_RESIDENT and path(4, 100, E, f, d) == m.PATH_TILED_RESIDENT
         # a K the tiled kernels do not take stays with the decode kernel
