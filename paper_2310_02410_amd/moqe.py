@@ -177,8 +177,9 @@ DECODE_AUTO, DECODE_GENERAL, DECODE_ROWS8, DECODE_ROWS4 = 0, 1, 2, 3
 
 
 def moqe_set_decode_kernel(which: int) -> int:
-    """Process-wide: DECODE_AUTO (the kernel specialised for batches of at most 64 tokens where it
-    applies; pairs of 4 token rows up to 32 tokens, of 8 from 33 on), DECODE_GENERAL (always the
+    """Process-wide: DECODE_AUTO (the kernel specialised for decode-sized batches where it applies:
+    pairs of 4 token rows up to 32 tokens, of 8 from 33 on, up to 64 tokens and, in pairs of 8, up
+    to 128), DECODE_GENERAL (always the
     general decode kernel), DECODE_ROWS8 / DECODE_ROWS4 (AUTO with 8 / 4 rows at every size);
     returns the old setting."""
     old = lib().moqe_set_decode_kernel(which)
